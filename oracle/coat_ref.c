@@ -1,0 +1,245 @@
+/*
+ * coat_ref.c -- CPU oracle for COAT's FP8-state AdamW step (arxiv 2410.19313).
+ *
+ * TEST INFRASTRUCTURE ONLY: called by tests/, the smoke check and the bench's
+ * cpu_baseline leg.  Plain C, fp64 inner math, one loop nest per definition, no blocking
+ * or fusion beyond "one group at a time".  Nothing here is shared with the HIP path.
+ *
+ * Parity pins: every function below is pinned by tests that need no GPU (E4M3 codec by
+ * brute force over all 256 codes and by a library cast; the quantizer by the k == 1
+ * special case, the range identity R_f(X) = R_X^k, oddness and scale invariance; the step
+ * by its G == 1 reduction to a library AdamW and by a hand-worked two-element case).
+ */
+#include "coat_ref.h"
+
+#include <math.h>
+#include <stddef.h>
+#include <stdlib.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Sec. 3: largest finite E4M3 magnitude.  Sec. 4.1: R_E4M3 = 448 * 512. */
+#define E4M3_MAX 448.0
+#define LOG2_R_E4M3 17.807354922057606 /* log2(229376) */
+
+int coat_ref_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* ---- E4M3 codec (OCP 8-bit floating point, E4M3 variant; Sec. 3 cites it) ---------- */
+
+double coat_ref_e4m3_decode(uint8_t code) {
+  int s = code >> 7, e = (code >> 3) & 15, m = code & 7;
+  double v;
+  if (e == 15 && m == 7) return NAN;             /* the only non-finite pattern */
+  if (e == 0) v = ldexp((double)m / 8.0, -6);    /* subnormal: 2^-6 * m/8 */
+  else        v = ldexp(1.0 + (double)m / 8.0, e - 7);
+  return s ? -v : v;
+}
+
+uint8_t coat_ref_e4m3_encode(double q) {
+  uint8_t sign = signbit(q) ? 0x80 : 0x00;
+  double a = fabs(q);
+  int e, mant, code;
+  if (isnan(q)) return 0x7F;
+  if (a > E4M3_MAX) a = E4M3_MAX;                /* saturate, never emit NaN for a number */
+  if (a < ldexp(1.0, -6)) {
+    /* subnormal spacing is 2^-9; rint() is round-half-even in the default mode.  A
+     * result of 8 is the code of the smallest normal number, 2^-6. */
+    code = (int)rint(a * 512.0);
+  } else {
+    int ex;
+    (void)frexp(a, &ex);                         /* a = f * 2^ex, f in [0.5, 1) */
+    e = ex - 1;                                  /* a = (1 + frac) * 2^e */
+    mant = (int)rint((ldexp(a, -e) - 1.0) * 8.0);
+    if (mant == 8) { mant = 0; e += 1; }         /* mantissa carry */
+    code = ((e + 7) << 3) | mant;
+    if (code > 0x7E) code = 0x7E;
+  }
+  return (uint8_t)(sign | code);
+}
+
+/* ---- per-group quantizer with dynamic range expansion (Sec. 3, Sec. 4) ------------- */
+
+static void resolve_k_bounds(float* k_min, float* k_max) {
+  if (*k_min == 0.0f && *k_max == 0.0f) { *k_min = 0.0625f; *k_max = 1024.0f; }
+}
+
+static void quant_one_group(const float* x, uint64_t len, uint32_t flags,
+                            float k_min, float k_max,
+                            uint8_t* q, float* scale_out, float* k_out) {
+  double amax = 0.0, amin = INFINITY;
+  float scale, k = 1.0f;
+  double a, kd;
+  uint64_t i;
+
+  /* Definition 1, with the minimum taken over the non-zero magnitudes. */
+  for (i = 0; i < len; ++i) {
+    double ax = fabs((double)x[i]);
+    if (ax > amax) amax = ax;
+    if (ax > 0.0 && ax < amin) amin = ax;
+  }
+  if (amax == 0.0) {                             /* nothing but zeros (or NaNs) */
+    for (i = 0; i < len; ++i)
+      q[i] = isnan(x[i]) ? 0x7F : (signbit(x[i]) ? 0x80 : 0x00);
+    *scale_out = 0.0f;
+    *k_out = 1.0f;
+    return;
+  }
+  scale = (float)(amax / E4M3_MAX);              /* S_X of Sec. 3, kept in fp32 */
+  if ((flags & COAT_REF_FLAG_EXPAND) && amax != amin) {
+    /* optimal k of Sec. 4.2: R_X^k = R_E4M3 */
+    kd = LOG2_R_E4M3 / log2(amax / amin);
+    if (kd < (double)k_min) kd = (double)k_min;
+    if (kd > (double)k_max) kd = (double)k_max;
+    k = (float)kd;
+  }
+  /* Quantize with the STORED scale and k so that Q and DQ agree.  The expanded group is
+   * f(x / a) with a = 448 * scale ~= amax, whose largest element is 1, so the plain
+   * quantizer's scale is 1/448 and the value to round is 448 * (|x|/a)^k. */
+  a = E4M3_MAX * (double)scale;
+  kd = (double)k;
+  for (i = 0; i < len; ++i) {
+    double xv = (double)x[i], mag;
+    if (xv == 0.0) { q[i] = signbit(x[i]) ? 0x80 : 0x00; continue; }
+    mag = E4M3_MAX * pow(fabs(xv) / a, kd);
+    if (mag > E4M3_MAX) mag = E4M3_MAX;
+    q[i] = coat_ref_e4m3_encode(copysign(mag, xv));
+  }
+  *scale_out = scale;
+  *k_out = k;
+}
+
+static void dequant_one_group(const uint8_t* q, float scale, float k, uint64_t len,
+                              double* x) {
+  double a = E4M3_MAX * (double)scale, inv_k = 1.0 / (double)k;
+  uint64_t i;
+  for (i = 0; i < len; ++i) {
+    double c = coat_ref_e4m3_decode(q[i]);
+    if (c == 0.0) { x[i] = c; continue; }        /* f(0) = 0, sign of zero kept */
+    x[i] = copysign(a * pow(fabs(c) / E4M3_MAX, inv_k), c);
+  }
+}
+
+void coat_ref_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags,
+                          float k_min, float k_max,
+                          uint8_t* q, float* scale, float* k) {
+  int64_t ng, gi;
+  if (!x || !q || !scale || !k || G < 1 || n == 0) return;
+  resolve_k_bounds(&k_min, &k_max);
+  ng = (int64_t)((n + (uint64_t)G - 1) / (uint64_t)G);
+#pragma omp parallel for schedule(static)
+  for (gi = 0; gi < ng; ++gi) {
+    uint64_t lo = (uint64_t)gi * (uint64_t)G;
+    uint64_t len = (n - lo < (uint64_t)G) ? n - lo : (uint64_t)G;
+    quant_one_group(x + lo, len, flags, k_min, k_max, q + lo, scale + gi, k + gi);
+  }
+}
+
+void coat_ref_dequant_group_f64(const uint8_t* q, const float* scale, const float* k,
+                                uint64_t n, int32_t G, double* x) {
+  int64_t ng, gi;
+  if (!x || !q || !scale || !k || G < 1 || n == 0) return;
+  ng = (int64_t)((n + (uint64_t)G - 1) / (uint64_t)G);
+#pragma omp parallel for schedule(static)
+  for (gi = 0; gi < ng; ++gi) {
+    uint64_t lo = (uint64_t)gi * (uint64_t)G;
+    uint64_t len = (n - lo < (uint64_t)G) ? n - lo : (uint64_t)G;
+    dequant_one_group(q + lo, scale[gi], k[gi], len, x + lo);
+  }
+}
+
+void coat_ref_dequant_group(const uint8_t* q, const float* scale, const float* k,
+                            uint64_t n, int32_t G, float* x) {
+  int64_t ng, gi;
+  if (!x || !q || !scale || !k || G < 1 || n == 0) return;
+  ng = (int64_t)((n + (uint64_t)G - 1) / (uint64_t)G);
+#pragma omp parallel for schedule(static)
+  for (gi = 0; gi < ng; ++gi) {
+    uint64_t lo = (uint64_t)gi * (uint64_t)G, i;
+    uint64_t len = (n - lo < (uint64_t)G) ? n - lo : (uint64_t)G;
+    double* tmp = (double*)malloc(len * sizeof(double));
+    if (!tmp) continue;
+    dequant_one_group(q + lo, scale[gi], k[gi], len, tmp);
+    for (i = 0; i < len; ++i) x[lo + i] = (float)tmp[i];
+    free(tmp);
+  }
+}
+
+/* ---- the fused step (Appendix A; update rule of Sec. 3, Eq. 1) ---------------------- */
+
+static double bf16_to_double(uint16_t bits) {
+  union { uint32_t u; float f; } cvt;
+  cvt.u = (uint32_t)bits << 16;                  /* bf16 is the top half of an fp32 */
+  return (double)cvt.f;
+}
+
+int coat_ref_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
+                            uint8_t* m_q, float* m_scale, float* m_k,
+                            uint8_t* v_q, float* v_scale, float* v_k,
+                            uint64_t n, const coat_ref_hparams* hp) {
+  double lr, b1, b2, eps, wd, bc1, bc2;
+  float k_min, k_max;
+  int32_t G;
+  int64_t ng, gi;
+  int failed = 0;
+
+  if (!hp) return -1;
+  if (n == 0) return 0;
+  if (!w || !grad_bf16 || !m_q || !m_scale || !m_k || !v_q || !v_scale || !v_k) return -1;
+  G = hp->group_size;
+  if (G < 1 || hp->step < 1) return -1;
+
+  lr = hp->lr; b1 = hp->beta1; b2 = hp->beta2; eps = hp->eps; wd = hp->weight_decay;
+  bc1 = 1.0 - pow(b1, (double)hp->step);         /* 1 - beta1^t */
+  bc2 = 1.0 - pow(b2, (double)hp->step);         /* 1 - beta2^t */
+  k_min = hp->k_min; k_max = hp->k_max;
+  resolve_k_bounds(&k_min, &k_max);
+  ng = (int64_t)((n + (uint64_t)G - 1) / (uint64_t)G);
+
+#pragma omp parallel for schedule(static)
+  for (gi = 0; gi < ng; ++gi) {
+    uint64_t lo = (uint64_t)gi * (uint64_t)G, i;
+    uint64_t len = (n - lo < (uint64_t)G) ? n - lo : (uint64_t)G;
+    double* m = (double*)malloc(2 * len * sizeof(double));
+    float* mt = (float*)malloc(2 * len * sizeof(float));
+    double* v;
+    float* vt;
+    if (!m || !mt) {
+      free(m); free(mt);
+#pragma omp atomic write
+      failed = 1;
+      continue;
+    }
+    v = m + len; vt = mt + len;
+
+    /* m_{t-1} = DQ(m^q), v_{t-1} = DQ(v^q), each followed by the inverse expansion */
+    dequant_one_group(m_q + lo, m_scale[gi], m_k[gi], len, m);
+    dequant_one_group(v_q + lo, v_scale[gi], v_k[gi], len, v);
+
+    for (i = 0; i < len; ++i) {
+      double g = bf16_to_double(grad_bf16[lo + i]);
+      double wi = (double)w[lo + i];
+      double m_t = b1 * m[i] + (1.0 - b1) * g;
+      double v_t = b2 * v[i] + (1.0 - b2) * g * g;
+      double m_hat = m_t / bc1;
+      double v_hat = v_t / bc2;
+      /* the weight sees the new moments BEFORE they are quantized */
+      w[lo + i] = (float)(wi - lr * (m_hat / (sqrt(v_hat) + eps) + wd * wi));
+      mt[i] = (float)m_t;                        /* moments live in fp32 before Q */
+      vt[i] = (float)v_t;
+    }
+
+    /* m^q_t, S = Q(m_t);  v^q_t, S = Q(v_t) */
+    quant_one_group(mt, len, hp->flags, k_min, k_max, m_q + lo, m_scale + gi, m_k + gi);
+    quant_one_group(vt, len, hp->flags, k_min, k_max, v_q + lo, v_scale + gi, v_k + gi);
+    free(m); free(mt);
+  }
+  return failed ? -1 : 0;
+}

@@ -1,0 +1,78 @@
+/*
+ * coat_ref.h -- CPU oracle for the FP8-state AdamW step of COAT (arxiv 2410.19313).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This library is the slow, plain definition the GPU path is
+ * checked against.  Only tests, the smoke check and the bench's cpu_baseline leg may call
+ * it; the product path never does.  It shares no code, header, table or constant
+ * generator with the HIP implementation.
+ *
+ * All pointers are HOST pointers.  Inner arithmetic is fp64 (libm); values are rounded
+ * to fp32 exactly where the state the method keeps is fp32 (w, scale, k, and the new
+ * moments just before they are quantized).
+ *
+ * Parity pins (tests/, run without a GPU) cover every function here; none is unpinned.
+ */
+#ifndef COAT_REF_H
+#define COAT_REF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Hyper-parameters of one AdamW step (paper Sec. 3, Eq. 1 and the symbols below it). */
+typedef struct {
+  float    lr;            /* eta */
+  float    beta1, beta2;  /* betas */
+  float    eps;           /* epsilon, added to sqrt(v_hat) */
+  float    weight_decay;  /* lambda, decoupled: enters as eta*lambda*w */
+  int32_t  step;          /* t >= 1; bias corrections are 1 - beta^t */
+  int32_t  group_size;    /* G >= 1: every G consecutive elements form a group (Sec. 3) */
+  uint32_t flags;         /* bit 0: dynamic range expansion on (off => k == 1) */
+  float    k_min, k_max;  /* clamp applied to k; both 0 => defaults 2^-4 and 2^10 */
+} coat_ref_hparams;
+
+#define COAT_REF_FLAG_EXPAND 1u
+
+/* OCP FP8 E4M3 ("FN"): 1-4-3 bits, bias 7, no infinity, 0x7F/0xFF are NaN, largest
+ * finite 448 and smallest positive 2^-9 (the two constants Sec. 3 prints). */
+double  coat_ref_e4m3_decode(uint8_t code);
+/* Round-to-nearest, ties to even mantissa; |q| > 448 saturates to +-448; NaN -> 0x7F. */
+uint8_t coat_ref_e4m3_encode(double q);
+
+/* Quantize n fp32 values in groups of G (last group may be short).
+ * Per group (Sec. 3 quantizer, Sec. 4.1 Definition 1, Sec. 4.2):
+ *   amax = max|x|, amin = min over NON-ZERO |x|, scale = fl32(amax/448),
+ *   k = fl32(clamp(log2(448*512) / log2(amax/amin))) if expansion is on and amax != amin,
+ *   else 1;  code = E4M3(sign(x) * 448 * (|x| / (448*scale))^k).
+ * All-zero group: scale 0, k 1, codes 0.  scale and k have ceil(n/G) entries. */
+void coat_ref_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags,
+                          float k_min, float k_max,
+                          uint8_t* q, float* scale, float* k);
+
+/* Inverse: x = sign(c) * (448*scale) * (|c|/448)^(1/k), c = decode(code)  (Sec. 4.2,
+ * inverse expansion applied after the plain dequantizer of Sec. 3). */
+void coat_ref_dequant_group(const uint8_t* q, const float* scale, const float* k,
+                            uint64_t n, int32_t G, float* x);
+
+/* Same as coat_ref_dequant_group but keeps the fp64 result (used inside the step). */
+void coat_ref_dequant_group_f64(const uint8_t* q, const float* scale, const float* k,
+                                uint64_t n, int32_t G, double* x);
+
+/* One fused optimizer step (Appendix A): dequantize m, v; update m, v, w; requantize.
+ * w: fp32 master weights (in place).  grad_bf16: raw bf16 bit patterns.
+ * m_q/v_q: E4M3 codes (in place).  *_scale, *_k: per-group metadata (in place).
+ * Returns 0, or -1 on an invalid argument (NULL, G < 1, step < 1). */
+int coat_ref_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
+                            uint8_t* m_q, float* m_scale, float* m_k,
+                            uint8_t* v_q, float* v_scale, float* v_k,
+                            uint64_t n, const coat_ref_hparams* hp);
+
+/* Number of threads the step will use (OpenMP max threads; 1 when built without it). */
+int coat_ref_num_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
