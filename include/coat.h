@@ -1,0 +1,103 @@
+/*
+ * coat.h -- C ABI of the MI355X (gfx950) implementation of COAT's FP8-state AdamW step
+ * (arxiv 2410.19313: Sec. 3 "Preliminaries", Sec. 4 "Dynamic range expansion",
+ * Appendix A "Details about optimizer states quantization").
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is caller-owned DEVICE memory on the current HIP device.  The
+ *     library allocates nothing, keeps no state between calls and frees nothing.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work on that stream; the caller synchronizes.
+ *   - A tensor is a flat buffer of n elements.  Every G consecutive elements form one
+ *     quantization group (Sec. 3, optimizer state quantization); the last group is short
+ *     when n % G != 0.  Per-group arrays have ceil(n/G) entries.
+ *   - Base pointers must be 16-byte aligned.  n is 64-bit (the 7B and 13B parameter sets
+ *     exceed 2^32 elements).
+ *   - Return value: COAT_OK (0) or a negative COAT_ERR_* code.  Arguments are validated on
+ *     the host before anything is launched, so a failing call has touched no memory.
+ *     n == 0 is a successful no-op.  No exception or abort crosses this boundary.
+ *   - FP8 format: OCP E4M3 (1-4-3 bits, bias 7, max 448, min subnormal 2^-9, no infinity;
+ *     0x7F/0xFF are NaN and are never produced from finite inputs).
+ */
+#ifndef COAT_H
+#define COAT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define COAT_OK            0
+#define COAT_ERR_NULL     -1  /* a required pointer is NULL */
+#define COAT_ERR_ALIGN    -2  /* a base pointer is not 16-byte aligned */
+#define COAT_ERR_GROUP    -3  /* group size not one of 32, 64, 128, 256, 512 */
+#define COAT_ERR_STEP     -4  /* step < 1 */
+#define COAT_ERR_HPARAM   -5  /* non-finite or out-of-domain hyper-parameter */
+#define COAT_ERR_LAUNCH   -6  /* the HIP runtime refused the launch */
+#define COAT_ERR_SIZE     -7  /* n exceeds what the launch geometry supports */
+
+#define COAT_FLAG_EXPAND  1u  /* bit 0: dynamic range expansion on (off => k == 1) */
+
+/* Hyper-parameters of one step: symbols of Sec. 3, Eq. (1). */
+typedef struct {
+  float    lr;            /* eta > 0 or 0 */
+  float    beta1, beta2;  /* in [0, 1) */
+  float    eps;           /* epsilon >= 0, added to sqrt(v_hat) */
+  float    weight_decay;  /* lambda, decoupled: enters as eta * lambda * w */
+  int32_t  step;          /* t >= 1; bias corrections 1 - beta^t are formed on the host in fp64 */
+  int32_t  group_size;    /* G in {32, 64, 128, 256, 512} */
+  uint32_t flags;         /* COAT_FLAG_* */
+  float    k_min, k_max;  /* clamp applied to the expansion exponent k; 0,0 => 2^-4 and 2^10 */
+} coat_adamw_hparams;
+
+/*
+ * One fused optimizer step over a flat parameter buffer (Appendix A; kernel structure of
+ * Appendix F.4 re-designed for 64-wide wavefronts):
+ *   m = DQ(m_q), v = DQ(v_q) with the inverse expansion |.|^(1/k) (Sec. 4.2);
+ *   m_t = beta1 m + (1-beta1) g,  v_t = beta2 v + (1-beta2) g^2           (Sec. 3);
+ *   w  <- w - lr * ( (m_t/(1-beta1^t)) / (sqrt(v_t/(1-beta2^t)) + eps) + weight_decay * w )  (Eq. 1),
+ *        computed from the new moments BEFORE they are quantized;
+ *   per group and per moment: amax, amin over non-zero magnitudes (Definition 1),
+ *   scale = amax/448, k = log2(448*512)/log2(amax/amin) clamped to [k_min, k_max],
+ *   code = E4M3_rne( sign(x) * 448 * (|x| / (448*scale))^k ).
+ *
+ * w          [n]   fp32 master weights, updated in place.
+ * grad_bf16  [n]   bf16 gradients (raw 16-bit patterns), read only.
+ * m_q, v_q   [n]   E4M3 codes of the first and second moment, updated in place.
+ * m_scale, m_k, v_scale, v_k  [ceil(n/G)]  fp32 per-group scale and exponent, in place.
+ * The valid start state (m0 = v0 = 0) is: all codes 0, scale 0, k 1.
+ * Gradients that are NaN/Inf poison their own element of w and their own group's
+ * moments; other groups are unaffected.  Moments that are fp32-subnormal are flushed.
+ */
+int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
+                        uint8_t* m_q, float* m_scale, float* m_k,
+                        uint8_t* v_q, float* v_scale, float* v_k,
+                        uint64_t n, const coat_adamw_hparams* hp, void* hip_stream);
+
+/*
+ * Per-group quantizer with dynamic range expansion (Sec. 3 quantizer Q applied to f(X),
+ * Sec. 4.2): the second half of the step on its own.
+ * x [n] fp32 in;  q [n] codes, scale/k [ceil(n/G)] out.  All-zero group: scale 0, k 1.
+ */
+int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags,
+                     float k_min, float k_max,
+                     uint8_t* q, float* scale, float* k, void* hip_stream);
+
+/*
+ * Dequantizer followed by the inverse expansion (Sec. 3 DQ, Sec. 4.2 f^-1): the first half
+ * of the step on its own.  x = sign(c) * (448*scale) * (|c|/448)^(1/k), c = decode(code).
+ */
+int coat_dequant_group(const uint8_t* q, const float* scale, const float* k,
+                       uint64_t n, int32_t G, float* x, void* hip_stream);
+
+/* Human-readable text for a return code (static storage, never NULL). */
+const char* coat_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int coat_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

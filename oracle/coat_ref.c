@@ -108,7 +108,9 @@ static void quant_one_group(const float* x, uint64_t len, uint32_t flags,
   for (i = 0; i < len; ++i) {
     double xv = (double)x[i], mag;
     if (xv == 0.0) { q[i] = signbit(x[i]) ? 0x80 : 0x00; continue; }
-    mag = E4M3_MAX * pow(fabs(xv) / a, kd);
+    /* Appendix A keeps the optimizer arithmetic in FP32: the number handed to the E4M3
+     * rounding is an fp32 value (with k == 1 it is the fp32 quotient x / S_X of Sec. 3). */
+    mag = (double)(float)(E4M3_MAX * pow(fabs(xv) / a, kd));
     if (mag > E4M3_MAX) mag = E4M3_MAX;
     q[i] = coat_ref_e4m3_encode(copysign(mag, xv));
   }

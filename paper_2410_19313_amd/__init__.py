@@ -1,0 +1,8 @@
+"""MI355X-native FP8-state AdamW step of COAT (arxiv 2410.19313): HIP kernels behind a C ABI
+(include/coat.h) and this thin binding."""
+from .binding import (CoatError, HParams, FLAG_EXPAND, SUPPORTED_GROUP_SIZES, EXPORTS,
+                      make_hparams, n_groups, strerror, lib,
+                      coat_fp8_adamw_step, coat_quant_group, coat_dequant_group)
+
+__all__ = ["CoatError", "HParams", "FLAG_EXPAND", "SUPPORTED_GROUP_SIZES", "EXPORTS", "make_hparams",
+           "n_groups", "strerror", "lib", "coat_fp8_adamw_step", "coat_quant_group", "coat_dequant_group"]

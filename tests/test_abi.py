@@ -1,0 +1,86 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+include/coat.h declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def coat():
+    import paper_2410_19313_amd as C
+    from paper_2410_19313_amd import build
+    if build.is_stale():
+        build.build()
+    return C
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "coat.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(coat_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(coat):
+    names = declared_symbols()
+    assert set(names) == set(coat.EXPORTS)
+    L = coat.lib()
+    for name in names:
+        assert getattr(L, name) is not None
+    assert coat.lib().coat_version() >= 100
+
+
+def test_error_codes_have_text(coat):
+    for code in range(0, -8, -1):
+        assert coat.strerror(code) and "unknown" not in coat.strerror(code)
+    assert "unknown" in coat.strerror(-99)
+
+
+def test_step_rejects_bad_arguments_before_launch(coat):
+    L = coat.lib()
+    ok = 0x1000                                       # a fake, aligned, never dereferenced address
+
+    def call(hp, ptrs=None, n=4096):
+        p = [ctypes.c_void_p(ok)] * 8 if ptrs is None else [ctypes.c_void_p(x) for x in ptrs]
+        return L.coat_fp8_adamw_step(*p, n, ctypes.byref(hp) if hp is not None else None, None)
+
+    assert call(None) == -1
+    assert call(coat.make_hparams(group_size=100)) == -3
+    assert call(coat.make_hparams(group_size=16)) == -3
+    assert call(coat.make_hparams(step=0)) == -4
+    assert call(coat.make_hparams(lr=float("nan"))) == -5
+    assert call(coat.make_hparams(beta1=1.0)) == -5
+    assert call(coat.make_hparams(beta2=-0.1)) == -5
+    assert call(coat.make_hparams(eps=-1.0)) == -5
+    assert call(coat.make_hparams(lr=float("inf"))) == -5
+    assert call(coat.make_hparams(k_min=4.0, k_max=2.0)) == -5
+    assert call(coat.make_hparams(), ptrs=[ok, ok, 0, ok, ok, ok, ok, ok]) == -1
+    assert call(coat.make_hparams(), ptrs=[ok + 4, ok, ok, ok, ok, ok, ok, ok]) == -2
+    assert call(coat.make_hparams(), ptrs=[ok, ok, ok, ok, ok, ok + 8, ok, ok]) == -2
+    assert call(coat.make_hparams(), n=1 << 50) == -7
+    assert call(coat.make_hparams(), ptrs=[0] * 8, n=0) == 0      # empty input: successful no-op
+
+
+def test_quant_dequant_reject_bad_arguments(coat):
+    L = coat.lib()
+    ok = ctypes.c_void_p(0x1000)
+    bad = ctypes.c_void_p(0x1004)
+    assert L.coat_quant_group(ok, 1024, 48, 1, 0.0, 0.0, ok, ok, ok, None) == -3
+    assert L.coat_quant_group(None, 1024, 128, 1, 0.0, 0.0, ok, ok, ok, None) == -1
+    assert L.coat_quant_group(ok, 1024, 128, 1, 0.0, 0.0, bad, ok, ok, None) == -2
+    assert L.coat_quant_group(ok, 1024, 128, 1, 2.0, 1.0, ok, ok, ok, None) == -5
+    assert L.coat_quant_group(None, 0, 128, 1, 0.0, 0.0, None, None, None, None) == 0
+    assert L.coat_dequant_group(ok, ok, ok, 1024, 7, ok, None) == -3
+    assert L.coat_dequant_group(ok, None, ok, 1024, 128, ok, None) == -1
+    assert L.coat_dequant_group(ok, ok, bad, 1024, 128, ok, None) == -2
+    assert L.coat_dequant_group(None, None, None, 0, 128, None, None) == 0
+
+
+def test_binding_refuses_host_tensors(coat):
+    import torch
+    x = torch.zeros(1024)
+    with pytest.raises(TypeError):
+        coat.coat_quant_group(x, 128)

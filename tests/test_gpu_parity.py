@@ -1,0 +1,378 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on identical seeded inputs.  Multi-step cases run in lock-step: at every step both sides
+start from the oracle's state, so that an allowed one-step code difference at a rounding tie
+cannot grow into a weight difference at the next step."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+from parity import EPS_DQ_M, assert_codes, assert_k, assert_scale, assert_w, eps_dq_v, k_tolerance
+
+pytestmark = pytest.mark.gpu
+
+HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+GROUPS = [32, 64, 128, 256, 512]
+
+
+@pytest.fixture(scope="module")
+def coat():
+    import paper_2410_19313_amd as C
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    C.lib()
+    return C
+
+
+def dev(a):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    return t.cuda()
+
+
+def dev_bf16(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def gpu_step(coat, w, g_bits, st, G, step, expand=True, **over):
+    kw = dict(HP)
+    kw.update(over)
+    hp = coat.make_hparams(step=step, group_size=G, expand=expand, **kw)
+    tw, tg = dev(w), dev_bf16(g_bits)
+    ts = {k: dev(v) for k, v in st.items()}
+    coat.coat_fp8_adamw_step(tw, tg, ts["m_q"], ts["m_scale"], ts["m_k"], ts["v_q"], ts["v_scale"], ts["v_k"], hp)
+    torch.cuda.synchronize()
+    return tw.cpu().numpy(), {k: v.cpu().numpy() for k, v in ts.items()}, tg
+
+
+def ref_step(ref, w, g_bits, st, G, step, expand=True, **over):
+    kw = dict(HP)
+    kw.update(over)
+    hp = ref.make_hparams(step=step, group_size=G, expand=expand, **kw)
+    w = w.copy()
+    st = {k: v.copy() for k, v in st.items()}
+    assert ref.fp8_adamw_step(w, g_bits, st["m_q"], st["m_scale"], st["m_k"],
+                              st["v_q"], st["v_scale"], st["v_k"], hp) == 0
+    return w, st
+
+
+def new_moments(ref, st_old, g_bits, G, hp_over):
+    """The fp64 new moments of the reference side and the bound dx on how far the fp32 side's
+    moments may be from them (see parity.py).  Used for tolerances only, never as expected values."""
+    kw = dict(HP)
+    kw.update(hp_over)
+    b1, b2 = float(np.float32(kw["beta1"])), float(np.float32(kw["beta2"]))
+    n = st_old["m_q"].size
+    m_old = ref.dequant_group(st_old["m_q"], st_old["m_scale"], st_old["m_k"], G, f64=True)
+    v_old = ref.dequant_group(st_old["v_q"], st_old["v_scale"], st_old["v_k"], G, f64=True)
+    g = S.bf16_bits_to_f32(g_bits).astype(np.float64)
+    m_t = b1 * m_old + (1 - b1) * g
+    v_t = b2 * v_old + (1 - b2) * g * g
+    dm = EPS_DQ_M * b1 * np.abs(m_old) + 2.0 ** -22 * np.abs(m_t)
+    dv = np.repeat(eps_dq_v(st_old["v_k"].astype(np.float64)), G)[:n] * b2 * v_old + 2.0 ** -22 * v_t
+    return m_t, dm, v_t, dv
+
+
+def check_step(ref, tag, w_g, st_g, w_r, st_r, st_old, g_bits, G, expand=True, extra_w_tol=None, **over):
+    """st_old: the state both sides started from (it conditions the tolerances)."""
+    k_min = over.get("k_min", 0.0) or 0.0625
+    k_max = over.get("k_max", 0.0) or 1024.0
+    assert_w(w_g, w_r, tag + " w", extra_w_tol)
+    assert_scale(st_g["m_scale"], st_r["m_scale"], tag + " m scale")
+    assert_scale(st_g["v_scale"], st_r["v_scale"], tag + " v scale")
+    m_t, dm, v_t, dv = new_moments(ref, st_old, g_bits, G, over)
+    stats = {}
+    for name, x, dx in (("m", m_t, dm), ("v", v_t, dv)):
+        tol, cl = k_tolerance(st_r[name + "_k"], x, dx, G, k_min, k_max)
+        if not expand:
+            tol = np.full_like(tol, 1e-6)            # k is 1 on both sides
+        in_bar = assert_k(st_g[name + "_k"], st_r[name + "_k"], tol, cl, tag + " %s k" % name)
+        n_bad, bad_regular, n_irregular = assert_codes(
+            ref, st_g[name + "_q"], st_r[name + "_q"], x, dx, st_r[name + "_scale"], st_r[name + "_k"], tol, G,
+            tag + " %s codes" % name)
+        stats[name] = dict(bad=n_bad, bad_regular=bad_regular, irregular=n_irregular, k_in_bar=in_bar)
+    assert np.all(st_g["v_q"] < 0x80), tag + ": a second-moment code carries a sign"
+    return stats
+
+
+def lockstep(coat, ref, n, G, grads_fn, steps, seed, expand=True, state=None, **over):
+    w = S.weights(n, seed)
+    st = state if state is not None else S.zero_state(n, G)
+    total_bad = 0
+    for t in range(1, steps + 1):
+        g = grads_fn(t)
+        w_g, st_g, _ = gpu_step(coat, w, g, st, G, t, expand, **over)
+        st_old = st
+        w, st = ref_step(ref, w, g, st, G, t, expand, **over)
+        stats = check_step(ref, "n=%d G=%d step %d" % (n, G, t), w_g, st_g, w, st, st_old, g, G, expand, **over)
+        total_bad += stats["m"]["bad_regular"] + stats["v"]["bad_regular"]
+    # over the whole run the match rate must hold too
+    assert total_bad <= max(2, int(1e-4 * 2 * n * steps)), total_bad
+    return total_bad
+
+
+def update_error_model(ref, st, g, G, t):
+    """Extra weight tolerance for states that come from no optimizer trajectory (random codes,
+    scales and exponents): there |m| / sqrt(v) reaches 1e5, the update dwarfs the weight and the
+    fp32 error of the update itself shows.  For u = (lr/bc1) m_t / (sqrt(v_t/bc2) + eps) the
+    dequantized m carries EPS_DQ_M, the dequantized v eps_dq_v (halved by the square root), the
+    remaining operations a few ulp."""
+    from parity import EPS_DQ_M, eps_dq_v
+    n = st["m_q"].size
+    b1, b2, lr, eps = (float(np.float32(HP[k])) for k in ("beta1", "beta2", "lr", "eps"))
+    m_old = np.abs(ref.dequant_group(st["m_q"], st["m_scale"], st["m_k"], G, f64=True))
+    v_old = ref.dequant_group(st["v_q"], st["v_scale"], st["v_k"], G, f64=True)
+    gf = S.bf16_bits_to_f32(g).astype(np.float64)
+    denom = np.sqrt((b2 * v_old + (1 - b2) * gf * gf) / (1 - b2 ** t)) + eps
+    u_scale = lr / (1 - b1 ** t) * (b1 * m_old + (1 - b1) * np.abs(gf)) / denom
+    ev = np.repeat(eps_dq_v(st["v_k"].astype(np.float64)), G)[:n]
+    return u_scale * (EPS_DQ_M + 0.5 * ev + 6 * 2.0 ** -24)
+
+
+# --- dequantizer -------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("G", GROUPS)
+def test_dequant_every_code(coat, ref, G):
+    # every code byte under a spread of exponents and scales; n spans several chunks + a tail
+    n = 5 * 1024 + 3 * G + 5
+    rng = np.random.default_rng(G)
+    q = (np.arange(n) % 256).astype(np.uint8)
+    rng.shuffle(q)
+    ng = (n + G - 1) // G
+    scale = np.exp(rng.uniform(np.log(1e-14), np.log(1e-2), ng)).astype(np.float32)
+    k = np.exp(rng.uniform(np.log(0.3), np.log(40.0), ng)).astype(np.float32)
+    k[::5] = 1.0
+    x_g = coat.coat_dequant_group(dev(q), dev(scale), dev(k), G).cpu().numpy()
+    x_r = ref.dequant_group(q, scale, k, G, f64=True)
+    nan = (q & 0x7F) == 0x7F
+    assert np.all(np.isnan(x_g[nan]))
+    ok = ~nan
+    # x = a * exp2(L / k), L = log2|c/448| in [-17.81, 0].  fp32 error model: L (table) and 1/k are
+    # each rounded, their product is rounded (3 * 2^-24 relative on the exponent, i.e. an absolute
+    # exponent error of |L/k| * 3 * 2^-24 and a relative error of ln2 times that on x), the hardware
+    # exp2 is good to ~1.5 ulp and two more roundings follow (448*scale and the final product).
+    L = np.log2(np.maximum(np.abs(np.array([ref.e4m3_decode(int(c) & 0x7F) for c in range(256)])), 1e-300) / 448.0)
+    expo = np.abs(L[q]) / np.repeat(k.astype(np.float64), G)[:n]
+    tol = (expo * 3 * 2.0 ** -24 * np.log(2.0) + 4 * 2.0 ** -24) * 1.25
+    err = np.abs(x_g[ok] - x_r[ok]) / np.abs(np.where(x_r[ok] == 0, 1.0, x_r[ok]))
+    assert np.all(err <= tol[ok]), float((err / tol[ok]).max())
+    assert np.array_equal(np.signbit(x_g[ok]), np.signbit(x_r[ok]))
+    assert np.all(x_g[(q & 0x7F) == 0] == 0)
+    # the standalone dequantizer uses the compensated exponent: a few ulp whatever the exponent
+    assert np.all(err <= 8 * 2.0 ** -24), float(err.max())
+
+
+# --- quantizer ---------------------------------------------------------------------------------
+
+def quant_inputs(kind, n, seed):
+    rng = np.random.default_rng(seed)
+    if kind == "normal":
+        return (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    if kind == "square":
+        return ((rng.standard_normal(n) * 1e-3) ** 2).astype(np.float32)
+    if kind == "lognormal":
+        return (1e-3 * np.exp(2 * rng.standard_normal(n)) * rng.choice([-1.0, 1.0], n)).astype(np.float32)
+    if kind == "zeros_mixed":
+        x = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        x[rng.random(n) < 0.3] = 0.0
+        x[: min(n, 700)] = 0.0                       # whole groups of zeros
+        return x
+    raise ValueError(kind)
+
+
+def check_quant(ref, tag, x, G, gpu, expect, expand):
+    """Standalone quantizer: both sides see the same fp32 inputs, so dx = 0 and the stated bar
+    applies as it stands (k: 1e-6, widened only by 1/ln R for groups narrower than e)."""
+    (q_g, s_g, k_g), (q_r, s_r, k_r) = gpu, expect
+    zero = np.zeros(x.size)
+    tol, cl = k_tolerance(k_r, x, zero, G)
+    if not expand:
+        tol = np.full_like(tol, 1e-6)
+    assert_scale(s_g, s_r, tag)
+    assert_k(k_g, k_r, tol, cl, tag)
+    assert_codes(ref, q_g, q_r, x, zero, s_r, k_r, tol, G, tag)
+
+
+@pytest.mark.parametrize("G", GROUPS)
+@pytest.mark.parametrize("kind", ["normal", "square", "lognormal", "zeros_mixed"])
+@pytest.mark.parametrize("expand", [True, False])
+def test_quant_parity(coat, ref, G, kind, expand):
+    n = 37 * 1024 + 2 * G + 17
+    x = quant_inputs(kind, n, seed=G + len(kind))
+    q_g, s_g, k_g = (t.cpu().numpy() for t in coat.coat_quant_group(dev(x), G, expand=expand))
+    q_r, s_r, k_r = ref.quant_group(x, G, expand=expand)
+    tag = "quant %s G=%d expand=%s" % (kind, G, expand)
+    check_quant(ref, tag, x, G, (q_g, s_g, k_g), (q_r, s_r, k_r), expand)
+    if kind == "square":
+        assert np.all(q_g < 0x80)
+
+
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 127, 128, 129, 1023, 1024, 1025, 4096 + 511])
+def test_quant_small_and_ragged_sizes(coat, ref, n):
+    x = quant_inputs("normal", n, seed=n)
+    q_g, s_g, k_g = (t.cpu().numpy() for t in coat.coat_quant_group(dev(x), 128))
+    q_r, s_r, k_r = ref.quant_group(x, 128)
+    check_quant(ref, "n=%d" % n, x, 128, (q_g, s_g, k_g), (q_r, s_r, k_r), True)
+
+
+def test_quant_roundtrip_through_dequant(coat, ref):
+    n, G = 64 * 1024, 128
+    x = quant_inputs("normal", n, seed=3)
+    q, s, k = coat.coat_quant_group(dev(x), G)
+    xh = coat.coat_dequant_group(q, s, k, G).cpu().numpy()
+    rel = np.abs(xh / x - 1.0)
+    assert np.median(rel) < 2.0 ** -5 and np.all(np.sign(xh) == np.sign(x))
+
+
+def test_quant_does_not_touch_neighbours(coat):
+    # outputs are written only inside [0, n): canaries around every buffer survive
+    n, G, pad = 3 * 1024 + 77, 128, 256
+    x = dev(quant_inputs("normal", n, 5))
+    ng = (n + G - 1) // G
+    qbuf = torch.full((n + 2 * pad,), 0xAB, dtype=torch.uint8, device="cuda")
+    sbuf = torch.full((ng + 2 * pad,), -7.0, dtype=torch.float32, device="cuda")
+    kbuf = torch.full((ng + 2 * pad,), -7.0, dtype=torch.float32, device="cuda")
+    coat.coat_quant_group(x, G, out=(qbuf[pad:pad + n], sbuf[pad:pad + ng], kbuf[pad:pad + ng]))
+    torch.cuda.synchronize()
+    assert torch.all(qbuf[:pad] == 0xAB) and torch.all(qbuf[pad + n:] == 0xAB)
+    assert torch.all(sbuf[:pad] == -7.0) and torch.all(sbuf[pad + ng:] == -7.0)
+    assert torch.all(kbuf[:pad] == -7.0) and torch.all(kbuf[pad + ng:] == -7.0)
+
+
+# --- the fused step ------------------------------------------------------------------------------
+
+def test_step_cfg1_ten_steps(coat, ref):
+    # 1024 x 1024 master weight, grads ~ N(0, 1e-3), G = 128, ten steps, seed 0
+    n = S.workload_numel("cfg1")
+    lockstep(coat, ref, n, 128, lambda t: S.grads_normal(n, 0, t), steps=10, seed=0)
+
+
+@pytest.mark.parametrize("G", GROUPS)
+def test_step_outlier_groups_ragged(coat, ref, G):
+    n = 300 * 1024 + 5 * G + 9
+    lockstep(coat, ref, n, G, lambda t: S.grads_normal(n, 1, t, G=G, outlier_frac=0.01), steps=4, seed=1)
+
+
+@pytest.mark.parametrize("G", [32, 128, 512])
+def test_step_lognormal_grads(coat, ref, G):
+    n = 256 * 1024
+    lockstep(coat, ref, n, G, lambda t: S.grads_lognormal(n, 2, t), steps=4, seed=2)
+
+
+@pytest.mark.parametrize("G", GROUPS)
+def test_step_from_arbitrary_state(coat, ref, G):
+    n = 128 * 1024 + G + 3
+    st = S.random_state(n, G, seed=4)
+    w = S.weights(n, 4)
+    g = S.grads_normal(n, 4, 1, G=G, outlier_frac=0.02)
+    t = 7
+    w_g, st_g, _ = gpu_step(coat, w, g, st, G, t)
+    w_r, st_r = ref_step(ref, w, g, st, G, t)
+    extra = update_error_model(ref, st, g, G, t)
+    check_step(ref, "random state G=%d" % G, w_g, st_g, w_r, st_r, st, g, G, extra_w_tol=extra)
+
+
+def test_step_expansion_off(coat, ref):
+    n = 64 * 1024 + 50
+    lockstep(coat, ref, n, 128, lambda t: S.grads_normal(n, 5, t), steps=3, seed=5, expand=False)
+
+
+def test_step_other_hyperparameters(coat, ref):
+    n = 64 * 1024
+    lockstep(coat, ref, n, 128, lambda t: S.grads_normal(n, 6, t), steps=3, seed=6,
+             lr=1e-3, beta1=0.8, beta2=0.999, eps=1e-6, weight_decay=0.0)
+    lockstep(coat, ref, n, 64, lambda t: S.grads_normal(n, 7, t), steps=2, seed=7, k_min=1.0, k_max=8.0)
+
+
+@pytest.mark.parametrize("n", [1, 31, 128, 1000, 1024, 1025, 2048 + 127])
+def test_step_tiny_sizes(coat, ref, n):
+    lockstep(coat, ref, n, 128, lambda t: S.grads_normal(n, 8, t), steps=2, seed=8)
+
+
+def test_step_zero_gradients_and_zero_groups(coat, ref):
+    n, G = 8 * 1024, 128
+    def grads(t):
+        g = S.grads_normal(n, 9, t)
+        g[: 3 * G] = 0                               # groups that never receive a gradient
+        g[5 * G: 6 * G: 2] = 0                       # zeros mixed into a live group
+        g[7 * G] = 0x8000                            # a negative zero
+        return g
+    lockstep(coat, ref, n, G, grads, steps=3, seed=9)
+
+
+def test_step_does_not_touch_gradients_or_neighbours(coat, ref):
+    n, G, pad = 5 * 1024 + 200, 128, 512
+    ng = (n + G - 1) // G
+    w = S.weights(n, 10)
+    g = S.grads_normal(n, 10, 1)
+    st = S.random_state(n, G, seed=10)
+    wbuf = torch.full((n + 2 * pad,), 3.0, dtype=torch.float32, device="cuda")
+    wbuf[pad:pad + n] = dev(w)
+    bufs = {}
+    for name, arr in st.items():
+        fill = 0xAB if arr.dtype == np.uint8 else -7.0
+        b = torch.full((arr.size + 2 * pad,), fill, dtype=torch.from_numpy(arr).dtype, device="cuda")
+        b[pad:pad + arr.size] = dev(arr)
+        bufs[name] = b
+    tg = dev_bf16(g)
+    hp = coat.make_hparams(step=3, group_size=G, **HP)
+    view = lambda name: bufs[name][pad:pad + st[name].size]
+    coat.coat_fp8_adamw_step(wbuf[pad:pad + n], tg, view("m_q"), view("m_scale"), view("m_k"),
+                             view("v_q"), view("v_scale"), view("v_k"), hp)
+    torch.cuda.synchronize()
+    assert torch.all(wbuf[:pad] == 3.0) and torch.all(wbuf[pad + n:] == 3.0)
+    for name, arr in st.items():
+        fill = 0xAB if arr.dtype == np.uint8 else -7.0
+        assert torch.all(bufs[name][:pad] == fill) and torch.all(bufs[name][pad + arr.size:] == fill), name
+    assert np.array_equal(tg.view(torch.int16).cpu().numpy().view(np.uint16), g)
+    w_r, st_r = ref_step(ref, w, g, st, G, 3)
+    check_step(ref, "padded", wbuf[pad:pad + n].cpu().numpy(), {k: view(k).cpu().numpy() for k in st}, w_r, st_r,
+               st, g, G, extra_w_tol=update_error_model(ref, st, g, G, 3))
+
+
+def test_step_is_deterministic_and_reloadable(coat):
+    n, G = 64 * 1024, 128
+    w = S.weights(n, 11)
+    grads = [S.grads_normal(n, 11, t) for t in (1, 2, 3)]
+
+    def run(split):
+        tw = dev(w)
+        ts = {k: dev(v) for k, v in S.zero_state(n, G).items()}
+        for t, g in enumerate(grads, start=1):
+            if split and t == 3:                       # save -> load -> continue
+                tw = dev(tw.cpu().numpy())
+                ts = {k: dev(v.cpu().numpy()) for k, v in ts.items()}
+            hp = coat.make_hparams(step=t, group_size=G, **HP)
+            coat.coat_fp8_adamw_step(tw, dev_bf16(g), ts["m_q"], ts["m_scale"], ts["m_k"],
+                                     ts["v_q"], ts["v_scale"], ts["v_k"], hp)
+        torch.cuda.synchronize()
+        return tw.cpu().numpy(), {k: v.cpu().numpy() for k, v in ts.items()}
+
+    w_a, s_a = run(False)
+    w_b, s_b = run(True)
+    assert np.array_equal(w_a, w_b)
+    for k in s_a:
+        assert np.array_equal(s_a[k], s_b[k]), k
+
+
+def test_non_finite_gradient_stays_in_its_group(coat, ref):
+    n, G = 4 * 1024, 128
+    w = S.weights(n, 12)
+    st = S.random_state(n, G, seed=12)
+    g = S.grads_normal(n, 12, 1)
+    g_bad = g.copy()
+    g_bad[5 * G + 3] = 0x7FC0                          # NaN
+    g_bad[9 * G + 100] = 0x7F80                        # +Inf
+    w_a, st_a, _ = gpu_step(coat, w, g, st, G, 2)
+    w_b, st_b, _ = gpu_step(coat, w, g_bad, st, G, 2)
+    keep = np.ones(n, bool)
+    keep[5 * G:6 * G] = False
+    keep[9 * G:10 * G] = False
+    assert np.array_equal(w_a[keep], w_b[keep])
+    assert np.array_equal(st_a["m_q"][keep], st_b["m_q"][keep]) and np.array_equal(st_a["v_q"][keep], st_b["v_q"][keep])
+    gk = np.ones(n // G, bool)
+    gk[[5, 9]] = False
+    for name in ("m_scale", "m_k", "v_scale", "v_k"):
+        assert np.array_equal(st_a[name][gk], st_b[name][gk]), name
+    assert not np.isfinite(w_b[5 * G + 3])
+    # inside a poisoned group the other weights are still the clean result
+    rest = np.arange(5 * G, 6 * G) != 5 * G + 3
+    assert np.array_equal(w_a[5 * G:6 * G][rest], w_b[5 * G:6 * G][rest])

@@ -51,7 +51,8 @@ def test_expansion_off_is_plain_per_group_quantizer(ref, G):
     amax = np.abs(xg).max(1)
     assert np.array_equal(s, (amax / 448.0).astype(np.float32))       # S_X = max|X| / 448
     assert np.all(k == 1.0)
-    scaled = (xg / s.astype(np.float64)[:, None]).reshape(-1)          # X / S_X
+    scaled = (xg / s.astype(np.float64)[:, None]).reshape(-1)          # X / S_X ...
+    scaled = scaled.astype(np.float32).astype(np.float64)              # ... as an fp32 number (Appendix A)
     assert np.array_equal(q, nearest_codes(scaled))
     # library cast of the same quotient (fp32 quotient; skip the rare double-rounding ties)
     lib = torch.from_numpy(scaled.astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
