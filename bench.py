@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused FP8-state AdamW step on one MI355X.
+
+A "step" is one pass of the whole hot path (dequantize + inverse expansion, moment and weight
+update, group statistics, exponent and scale, expansion + requantization) over one flat
+parameter buffer with every input resident in HBM.  The default workload is the full
+Llama-2-7B-sized parameter set (6.74e9 fp32 master weights, bf16 gradients, E4M3 moments with
+group size 128).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--group-size 128]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+
+
+def bytes_per_param(G: int) -> float:
+    """Algorithmic HBM bytes per parameter per step: read w 4 + g 2 + m_q 1 + v_q 1 and write
+    w 4 + m_q 1 + v_q 1, plus 4 fp32 metadata words per group read and written."""
+    return 14.0 + 32.0 / G
+
+
+def read_profile_traffic(workload: str, G: int):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "coat_fp8_adamw_step_%s_G%d_pmc.txt" % (workload, G))
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(G: int, sample_params: int, steps: int):
+    """The CPU oracle, as it stands, timed on this host on a bounded sample of the workload."""
+    import numpy as np
+    import synth_inputs as S
+    from oracle import coat_ref as R
+    n = sample_params
+    w = S.weights(n, seed=0)
+    st = S.zero_state(n, G)
+    grads = [S.grads_normal(n, 0, t, G=G, outlier_frac=0.01) for t in range(1, steps + 2)]
+    # step 1 starts from the all-zero state (cheaper: nothing to dequantize); it is not timed
+    R.fp8_adamw_step(w, grads[0], st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"],
+                     R.make_hparams(step=1, group_size=G, **HP))
+    t0 = time.perf_counter()
+    for t in range(2, steps + 2):
+        R.fp8_adamw_step(w, grads[t - 1], st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"],
+                         R.make_hparams(step=t, group_size=G, **HP))
+    dt = time.perf_counter() - t0
+    assert np.all(np.isfinite(w))
+    return dict(value=n * steps / dt, unit="params/s", cores=R.num_threads(), kind="oracle",
+                sample="first %d parameters of the workload, %d steps after one untimed step, %.1f s" % (n, steps, dt))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg5"])
+    ap.add_argument("--group-size", type=int, default=128)
+    ap.add_argument("--grads", default="normal", choices=["normal", "lognormal"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 27)
+    ap.add_argument("--cpu-steps", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the step needs no communication; a sharded run is "
+                 "the same kernel on n/P elements per GPU). Use --gpus 1.")
+
+    import torch
+    import paper_2410_19313_amd as C
+    import synth_inputs as S
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; there is no CPU path to time")
+    C.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    G = args.group_size
+    n = S.workload_numel(args.workload)
+    assert n % G == 0
+
+    gen = S.torch_generator(dev, 0)
+    w = S.torch_weights(n, dev, gen)
+    st = S.torch_zero_state(n, G, dev)
+    mask = S.torch_outlier_group_mask(n // G, dev, gen, 0.01)
+    # two gradient buffers, alternated, so that consecutive steps do not see identical input
+    if args.grads == "normal":
+        grads = [S.torch_grads_normal(n, dev, gen, G=G, outlier_mask=mask) for _ in range(2)]
+    else:
+        grads = [S.torch_grads_lognormal(n, dev, gen) for _ in range(2)]
+    del mask
+    torch.cuda.synchronize()
+
+    def step(t):
+        hp = C.make_hparams(step=t, group_size=G, **HP)
+        C.coat_fp8_adamw_step(w, grads[t & 1], st["m_q"], st["m_scale"], st["m_k"],
+                              st["v_q"], st["v_scale"], st["v_k"], hp)
+
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        step(t)
+    torch.cuda.synchronize()
+
+    # HIP events on the stream the kernel is launched on (torch's current stream)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        t += 1
+        ev[i][0].record()
+        step(t)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    launch_ms = [a.elapsed_time(b) for a, b in ev]
+    avg_launch_s = sum(launch_ms) / len(launch_ms) / 1e3
+
+    finite = bool(torch.isfinite(w[:: max(1, n // (1 << 20))]).all().item())
+    if not finite:
+        sys.exit("bench.py: non-finite weights after the timed steps")
+
+    ms_per_step = wall / args.steps * 1e3
+    value = n * args.steps / wall
+    algo_bytes = bytes_per_param(G) * n
+    achieved = algo_bytes / avg_launch_s / 1e9
+    out = {
+        "metric": "params updated/sec, FP8-state AdamW (E4M3 m/v, per-group scale + dynamic range expansion)",
+        "value": value,
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s, %d params, G=%d, grads %s" % (
+            args.workload, {"cfg1": "one 1024x1024 weight", "cfg2": "one Llama-2-7B decoder layer",
+                            "cfg3": "full Llama-2-7B-sized parameter set", "cfg5": "full Llama-2-13B-sized parameter set"}[
+                args.workload], n, G, args.grads),
+            "params": n, "group_size": G, "hbm_gbs": achieved, "hbm_frac_of_peak": achieved / HBM_PEAK_GBS},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_profile_traffic(args.workload, G),
+                     "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_ms": avg_launch_s * 1e3,
+                     "kernel": "adamw_step_kernel<%d, expand>" % G},
+    }
+    # free the device buffers before the host-side baseline allocates its own arrays
+    del w, st, grads
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(G, min(args.cpu_sample, n), args.cpu_steps)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -21,7 +21,10 @@ namespace {
 
 constexpr int kWave = 64;                 // lanes per wavefront
 constexpr int kEPL = 16;                  // consecutive elements owned by one lane
-constexpr int kWavesPerBlock = 4;
+#ifndef COAT_WPB
+#define COAT_WPB 4
+#endif
+constexpr int kWavesPerBlock = COAT_WPB;
 constexpr int kBlock = kWave * kWavesPerBlock;
 constexpr int kChunk = kWave * kEPL;      // elements one wavefront handles per iteration
 
@@ -180,13 +183,29 @@ __device__ __forceinline__ float group_allreduce(float x) {
   return x;
 }
 
+// Compile-time streaming hints (bit mask): 1 load codes, 2 store codes, 4 load gradients,
+// 8 load weights, 16 store weights.  A set bit issues the access as non-temporal.
+#ifndef COAT_NT
+#define COAT_NT 31
+#endif
+template <int BIT, typename T>
+__device__ __forceinline__ T ldg(const T* p) {
+  if constexpr ((COAT_NT & BIT) != 0) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <int BIT, typename T>
+__device__ __forceinline__ void stg(T* p, T v) {
+  if constexpr ((COAT_NT & BIT) != 0) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
 template <bool GUARD>
 __device__ __forceinline__ void load_f32x16(const float* p, uint64_t base, uint64_t n, float (&x)[kEPL]) {
   if constexpr (!GUARD) {
     const f32x4* q = reinterpret_cast<const f32x4*>(p + base);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      f32x4 t = q[j];
+      f32x4 t = ldg<8>(q + j);
       x[4 * j + 0] = t.x; x[4 * j + 1] = t.y; x[4 * j + 2] = t.z; x[4 * j + 3] = t.w;
     }
   } else {
@@ -202,7 +221,7 @@ __device__ __forceinline__ void store_f32x16(float* p, uint64_t base, uint64_t n
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       f32x4 t = {x[4 * j + 0], x[4 * j + 1], x[4 * j + 2], x[4 * j + 3]};
-      q[j] = t;
+      stg<16>(q + j, t);
     }
   } else {
 #pragma unroll
@@ -218,7 +237,7 @@ __device__ __forceinline__ void load_bf16x16(const uint16_t* p, uint64_t base, u
     const u32x4* q = reinterpret_cast<const u32x4*>(p + base);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      u32x4 t = q[j];
+      u32x4 t = ldg<4>(q + j);
       x[8 * j + 0] = as_f32(t.x << 16); x[8 * j + 1] = as_f32(t.x & 0xffff0000u);
       x[8 * j + 2] = as_f32(t.y << 16); x[8 * j + 3] = as_f32(t.y & 0xffff0000u);
       x[8 * j + 4] = as_f32(t.z << 16); x[8 * j + 5] = as_f32(t.z & 0xffff0000u);
@@ -235,7 +254,7 @@ __device__ __forceinline__ void load_bf16x16(const uint16_t* p, uint64_t base, u
 template <bool GUARD>
 __device__ __forceinline__ void load_codes16(const uint8_t* p, uint64_t base, uint64_t n, uint32_t (&c)[4]) {
   if constexpr (!GUARD) {
-    u32x4 t = *reinterpret_cast<const u32x4*>(p + base);
+    u32x4 t = ldg<1>(reinterpret_cast<const u32x4*>(p + base));
     c[0] = t.x; c[1] = t.y; c[2] = t.z; c[3] = t.w;
   } else {
 #pragma unroll
@@ -253,13 +272,26 @@ template <bool GUARD>
 __device__ __forceinline__ void store_codes16(uint8_t* p, uint64_t base, uint64_t n, const uint32_t (&c)[4]) {
   if constexpr (!GUARD) {
     u32x4 t = {c[0], c[1], c[2], c[3]};
-    *reinterpret_cast<u32x4*>(p + base) = t;
+    stg<2>(reinterpret_cast<u32x4*>(p + base), t);
   } else {
 #pragma unroll
     for (int e = 0; e < kEPL; ++e)
       if (base + e < n) p[base + e] = static_cast<uint8_t>(c[e >> 2] >> (8 * (e & 3)));
   }
 }
+
+// ---------------------------------------------------------------------------------------
+// LDS staging: HBM likes every load/store instruction of a wavefront to cover one contiguous
+// span (and to be issued as a streaming access), the arithmetic wants every lane to own 16
+// consecutive elements.  A 4 KiB (fp32) / 2 KiB (bf16) per-wavefront LDS tile converts between
+// the two: rows of 64 x 16 B on the memory side, 64 B (32 B) per lane on the register side.
+// 16-byte slot s lives at s ^ ((s >> 3) & 7), which makes both access patterns conflict free.
+// A wavefront only ever touches its own tile and LDS executes one wavefront's accesses in
+// order, so no barrier is needed.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int swz(int s) { return s ^ ((s >> 3) & 7); }
+
+struct StageTiles { f32x4* w; u32x4* g; };
 
 __device__ __forceinline__ void fill_lut(Log2Entry* lut) {
   // 256 entries so that the whole code byte indexes it (the sign bit is ignored)
@@ -391,38 +423,30 @@ __device__ __forceinline__ void quantize16(const float (&x)[kEPL], const GroupQu
 // the fused step: one chunk of 1024 elements per wavefront iteration
 // ---------------------------------------------------------------------------------------
 
-template <int G, bool EXPAND, bool GUARD>
-__device__ __forceinline__ void step_chunk(const StepArgs& a, const Log2Entry* lut, uint64_t chunk, int lane) {
+// Per-group metadata of one chunk as one lane sees it (its own group's words).
+struct GroupMeta { float m_scale, m_k, v_scale, v_k; };
+
+// The arithmetic of the step on one lane's 16 elements, registers in, registers out:
+// w (in/out), g, codes (in/out), metadata (in/out).  Cross-lane traffic: the group reductions.
+template <int G, bool EXPAND>
+__device__ __forceinline__ void step_core(const StepArgs& a, const Log2Entry* lut, float (&w)[kEPL],
+                                          const float (&g)[kEPL], uint32_t (&mc)[4], uint32_t (&vc)[4],
+                                          GroupMeta& meta) {
   constexpr int LPG = G / kEPL;                      // lanes per group
-  const uint64_t base = chunk * kChunk + static_cast<uint64_t>(lane) * kEPL;
-  const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
-  const bool gvalid = !GUARD || gidx < a.n_groups;
-
-  float w[kEPL], g[kEPL];
-  uint32_t mc[4], vc[4];
-  load_f32x16<GUARD>(a.w, base, a.n, w);
-  load_bf16x16<GUARD>(a.g, base, a.n, g);
-  load_codes16<GUARD>(a.mq, base, a.n, mc);
-  load_codes16<GUARD>(a.vq, base, a.n, vc);
-  const float m_scale = gvalid ? a.ms[gidx] : 0.0f;
-  const float v_scale = gvalid ? a.vs[gidx] : 0.0f;
-
   float m[kEPL], v[kEPL];
   float m_fac, v_fac;                                // beta * (magnitude of the decoded unit)
   if constexpr (EXPAND) {
     // m = (448 scale) * |c/448|^(1/k)
-    const float m_k = gvalid ? a.mk[gidx] : 1.0f;
-    const float v_k = gvalid ? a.vk[gidx] : 1.0f;
-    inverse_expand16<true, true>(lut, mc, m_k, rcp_refined(m_k), m);
-    inverse_expand16<false, false>(lut, vc, v_k, rcp_refined(v_k), v);
-    m_fac = a.beta1 * (kE4M3Max * m_scale);
-    v_fac = a.beta2 * (kE4M3Max * v_scale);
+    inverse_expand16<true, true>(lut, mc, meta.m_k, rcp_refined(meta.m_k), m);
+    inverse_expand16<false, false>(lut, vc, meta.v_k, rcp_refined(meta.v_k), v);
+    m_fac = a.beta1 * (kE4M3Max * meta.m_scale);
+    v_fac = a.beta2 * (kE4M3Max * meta.v_scale);
   } else {
     // plain dequantizer: m = scale * c (k is 1 in this mode and is not read)
     decode16<true>(mc, m);
     decode16<false>(vc, v);
-    m_fac = a.beta1 * m_scale;
-    v_fac = a.beta2 * v_scale;
+    m_fac = a.beta1 * meta.m_scale;
+    v_fac = a.beta2 * meta.v_scale;
   }
 
 #pragma unroll
@@ -438,7 +462,6 @@ __device__ __forceinline__ void step_chunk(const StepArgs& a, const Log2Entry* l
     m[e] = m_t;
     v[e] = v_t;
   }
-  store_f32x16<GUARD>(a.w, base, a.n, w);
 
   float m_max, m_min, v_max, v_min;
   lane_extremes(m, m_max, m_min);
@@ -449,34 +472,149 @@ __device__ __forceinline__ void step_chunk(const StepArgs& a, const Log2Entry* l
   v_min = group_allreduce<LPG, false>(v_min);
   const GroupQuant qm = group_quant_params<EXPAND>(m_max, m_min, a.k_min, a.k_max);
   const GroupQuant qv = group_quant_params<EXPAND>(v_max, v_min, a.k_min, a.k_max);
-
   quantize16<EXPAND, true>(m, qm, mc);
   quantize16<EXPAND, false>(v, qv, vc);
-  store_codes16<GUARD>(a.mq, base, a.n, mc);
-  store_codes16<GUARD>(a.vq, base, a.n, vc);
-  if (gvalid && (lane % LPG) == 0) {
-    a.ms[gidx] = qm.scale; a.mk[gidx] = qm.k;
-    a.vs[gidx] = qv.scale; a.vk[gidx] = qv.k;
+  meta.m_scale = qm.scale; meta.m_k = qm.k;
+  meta.v_scale = qv.scale; meta.v_k = qv.k;
+}
+
+// What one lane fetches for one full chunk, still in the layout of the memory side: weight and
+// gradient rows (row j of the chunk, 16 bytes at lane), its own 16 code bytes, its group's words.
+struct RawChunk {
+  f32x4 w[4];
+  u32x4 g[2];
+  u32x4 mc, vc;
+  GroupMeta meta;
+};
+
+template <int G, bool EXPAND>
+__device__ __forceinline__ void issue_loads(const StepArgs& a, uint64_t chunk, int lane, RawChunk& r) {
+  constexpr int LPG = G / kEPL;
+  const uint64_t cb = chunk * kChunk;
+  const uint64_t base = cb + static_cast<uint64_t>(lane) * kEPL;
+  const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
+  const f32x4* wq = reinterpret_cast<const f32x4*>(a.w + cb);
+  const u32x4* gq = reinterpret_cast<const u32x4*>(a.g + cb);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) r.w[j] = ldg<8>(wq + 64 * j + lane);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) r.g[j] = ldg<4>(gq + 64 * j + lane);
+  r.mc = ldg<1>(reinterpret_cast<const u32x4*>(a.mq + base));
+  r.vc = ldg<1>(reinterpret_cast<const u32x4*>(a.vq + base));
+  r.meta.m_scale = a.ms[gidx];
+  r.meta.v_scale = a.vs[gidx];
+  if constexpr (EXPAND) { r.meta.m_k = a.mk[gidx]; r.meta.v_k = a.vk[gidx]; }
+  else { r.meta.m_k = 1.0f; r.meta.v_k = 1.0f; }
+}
+
+// One full chunk: rows -> lane layout through the LDS tiles, the arithmetic, and back out.
+template <int G, bool EXPAND>
+__device__ __forceinline__ void process_chunk(const StepArgs& a, const Log2Entry* lut, const StageTiles& tiles,
+                                              uint64_t chunk, int lane, RawChunk& r) {
+  constexpr int LPG = G / kEPL;
+  const uint64_t cb = chunk * kChunk;
+  const uint64_t base = cb + static_cast<uint64_t>(lane) * kEPL;
+  const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
+
+  float w[kEPL], g[kEPL];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) tiles.w[swz(64 * j + lane)] = r.w[j];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) tiles.g[swz(64 * j + lane)] = r.g[j];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f32x4 t = tiles.w[swz(4 * lane + i)];
+    w[4 * i + 0] = t.x; w[4 * i + 1] = t.y; w[4 * i + 2] = t.z; w[4 * i + 3] = t.w;
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const u32x4 t = tiles.g[swz(2 * lane + j)];
+    g[8 * j + 0] = as_f32(t.x << 16); g[8 * j + 1] = as_f32(t.x & 0xffff0000u);
+    g[8 * j + 2] = as_f32(t.y << 16); g[8 * j + 3] = as_f32(t.y & 0xffff0000u);
+    g[8 * j + 4] = as_f32(t.z << 16); g[8 * j + 5] = as_f32(t.z & 0xffff0000u);
+    g[8 * j + 6] = as_f32(t.w << 16); g[8 * j + 7] = as_f32(t.w & 0xffff0000u);
+  }
+  uint32_t mc[4] = {r.mc.x, r.mc.y, r.mc.z, r.mc.w};
+  uint32_t vc[4] = {r.vc.x, r.vc.y, r.vc.z, r.vc.w};
+  GroupMeta meta = r.meta;
+
+  step_core<G, EXPAND>(a, lut, w, g, mc, vc, meta);
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f32x4 t = {w[4 * i + 0], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]};
+    tiles.w[swz(4 * lane + i)] = t;
+  }
+  f32x4* wq = reinterpret_cast<f32x4*>(a.w + cb);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) stg<16>(wq + 64 * j + lane, tiles.w[swz(64 * j + lane)]);
+  const u32x4 mo = {mc[0], mc[1], mc[2], mc[3]}, vo = {vc[0], vc[1], vc[2], vc[3]};
+  stg<2>(reinterpret_cast<u32x4*>(a.mq + base), mo);
+  stg<2>(reinterpret_cast<u32x4*>(a.vq + base), vo);
+  if ((lane % LPG) == 0) {
+    a.ms[gidx] = meta.m_scale; a.mk[gidx] = meta.m_k;
+    a.vs[gidx] = meta.v_scale; a.vk[gidx] = meta.v_k;
   }
 }
 
+// Persistent, software-pipelined main kernel: wavefront q of the launch handles chunks q, q + Q,
+// q + 2Q, ... (Q = wavefronts in the grid) and fetches chunk i+1 while it computes chunk i, so
+// that few resident wavefronts keep both the memory system and the VALU busy.  The first chunk's
+// loads are issued before the block fills its lookup table.
 template <int G, bool EXPAND>
 __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
   __shared__ Log2Entry lut[256];
-  fill_lut(lut);
+  __shared__ f32x4 tile_w[kWavesPerBlock * 256];
+  __shared__ u32x4 tile_g[kWavesPerBlock * 128];
   const int lane = threadIdx.x & (kWave - 1);
-  const uint64_t wave = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+  const int wv = threadIdx.x >> 6;
+  const StageTiles tiles = {tile_w + wv * 256, tile_g + wv * 128};
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
-  for (uint64_t chunk = wave; chunk < a.n_full; chunk += stride)
-    step_chunk<G, EXPAND, false>(a, lut, chunk, lane);
+  uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv;
+
+  RawChunk cur, nxt;
+  if (chunk < a.n_full) issue_loads<G, EXPAND>(a, chunk, lane, cur);
+  fill_lut(lut);
+  while (chunk < a.n_full) {
+    const uint64_t next = chunk + stride;
+    if (next < a.n_full) issue_loads<G, EXPAND>(a, next, lane, nxt);
+    process_chunk<G, EXPAND>(a, lut, tiles, chunk, lane, cur);
+    cur = nxt;
+    chunk = next;
+  }
 }
 
-// the ragged last chunk (n % 1024 elements): one wavefront, element-wise guarded accesses
+// The ragged last chunk (n % 1024 elements): one wavefront, element-wise guarded accesses
+// straight into the lane layout.
 template <int G, bool EXPAND>
 __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
   __shared__ Log2Entry lut[256];
   fill_lut(lut);
-  step_chunk<G, EXPAND, true>(a, lut, a.n_full, threadIdx.x);
+  constexpr int LPG = G / kEPL;
+  const int lane = threadIdx.x;
+  const uint64_t chunk = a.n_full;
+  const uint64_t base = chunk * kChunk + static_cast<uint64_t>(lane) * kEPL;
+  const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
+  const bool gvalid = gidx < a.n_groups;
+  float w[kEPL], g[kEPL];
+  uint32_t mc[4], vc[4];
+  load_f32x16<true>(a.w, base, a.n, w);
+  load_bf16x16<true>(a.g, base, a.n, g);
+  load_codes16<true>(a.mq, base, a.n, mc);
+  load_codes16<true>(a.vq, base, a.n, vc);
+  GroupMeta meta;
+  meta.m_scale = gvalid ? a.ms[gidx] : 0.0f;
+  meta.v_scale = gvalid ? a.vs[gidx] : 0.0f;
+  meta.m_k = (EXPAND && gvalid) ? a.mk[gidx] : 1.0f;
+  meta.v_k = (EXPAND && gvalid) ? a.vk[gidx] : 1.0f;
+  step_core<G, EXPAND>(a, lut, w, g, mc, vc, meta);
+  store_f32x16<true>(a.w, base, a.n, w);
+  store_codes16<true>(a.mq, base, a.n, mc);
+  store_codes16<true>(a.vq, base, a.n, vc);
+  if (gvalid && (lane % LPG) == 0) {
+    a.ms[gidx] = meta.m_scale; a.mk[gidx] = meta.m_k;
+    a.vs[gidx] = meta.v_scale; a.vk[gidx] = meta.v_k;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -558,20 +696,20 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 bool finite_f(float x) { return x == x && x - x == 0.0f; }
 bool group_ok(int32_t G) { return G == 32 || G == 64 || G == 128 || G == 256 || G == 512; }
 
-// Blocks for a grid-stride launch over n_full chunks: enough to cover every chunk once, capped
-// at a multiple of the CU count so that the lookup table is loaded a bounded number of times.
+#ifdef COAT_TUNING
+int g_tune_cap_mult = 0;      // blocks per CU cap; 0 = one wavefront per chunk (no loop)
+int g_tune_lds_pad = 0;       // extra dynamic LDS bytes per block (limits occupancy)
+#endif
+
+// Blocks of the main launch.  One chunk per wavefront measured best (the hardware dispatcher then
+// walks memory in address order and few bytes are in flight per CU); the kernels still loop,
+// which covers buffers with more chunks than a grid can hold blocks.
 unsigned grid_for(uint64_t n_full) {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-      cus = v;
-    else
-      cus = 256;
-  }
   const uint64_t need = (n_full + kWavesPerBlock - 1) / kWavesPerBlock;
-  const uint64_t cap = static_cast<uint64_t>(cus) * 64;
+  uint64_t cap = 1ull << 30;
+#ifdef COAT_TUNING
+  if (g_tune_cap_mult > 0) cap = 256ull * static_cast<uint64_t>(g_tune_cap_mult);
+#endif
   return static_cast<unsigned>(need < cap ? need : cap);
 }
 
@@ -587,9 +725,17 @@ bool resolve_k_bounds(float& k_min, float& k_max) {
 int launch_status() { return hipGetLastError() == hipSuccess ? COAT_OK : COAT_ERR_LAUNCH; }
 
 template <int G, bool EXPAND>
-int launch_step(const StepArgs& a, hipStream_t s) {
+int launch_step(const StepArgs& a0, hipStream_t s) {
+  StepArgs a = a0;
   if (a.n_full) {
-    hipLaunchKernelGGL((adamw_step_kernel<G, EXPAND>), dim3(grid_for(a.n_full)), dim3(kBlock), 0, s, a);
+    const unsigned grid = grid_for(a.n_full);
+    size_t lds = 0;
+#ifdef COAT_TUNING
+    lds = static_cast<size_t>(g_tune_lds_pad);
+    if (lds) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&adamw_step_kernel<G, EXPAND>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+#endif
+    hipLaunchKernelGGL((adamw_step_kernel<G, EXPAND>), dim3(grid), dim3(kBlock), lds, s, a);
     if (int rc = launch_status()) return rc;
   }
   if (a.n > a.n_full * kChunk) {
@@ -748,5 +894,12 @@ const char* coat_strerror(int code) {
 }
 
 int coat_version(void) { return 100; }
+
+#ifdef COAT_TUNING
+// development builds only: launch-shape knobs for sweeps
+void coat_tune_set(int cap_mult, int lds_pad, int unused) {
+  g_tune_cap_mult = cap_mult; g_tune_lds_pad = lds_pad; (void)unused;
+}
+#endif
 
 }  // extern "C"
