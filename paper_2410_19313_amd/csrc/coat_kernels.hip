@@ -30,6 +30,7 @@ constexpr int kChunk = kWave * kEPL;      // elements one wavefront handles per 
 
 constexpr float kE4M3Max = 448.0f;
 constexpr float kLog2Range = 17.807354922057606f;   // log2(448 * 512), Sec. 4.1
+constexpr float kLog2E4M3Max = 8.807354922057604f;  // log2(448)
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -146,14 +147,6 @@ __device__ __forceinline__ float hw_log2(float x) { return __builtin_amdgcn_logf
 __device__ __forceinline__ float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float hw_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ __forceinline__ float hw_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
-
-// a / b: hardware reciprocal plus one correction step (per-group use only)
-__device__ __forceinline__ float div_refined(float a, float b) {
-  float r = hw_rcp(b);
-  float q = a * r;
-  float e = __builtin_fmaf(-b, q, a);
-  return __builtin_fmaf(e, r, q);
-}
 
 __device__ __forceinline__ float rcp_refined(float b) {
   float r = hw_rcp(b);
@@ -360,8 +353,10 @@ __device__ __forceinline__ GroupQuant group_quant_params(float amax, float amin,
   s = __builtin_fmaf(__builtin_fmaf(-kE4M3Max, s, amax), inv448, s);
   float k = 1.0f;
   if constexpr (EXPAND) {
-    const float ratio = div_refined(amax, amin);     // R_X
-    float kk = div_refined(kLog2Range, hw_log2(ratio));
+    // two hardware reciprocals (1 ulp each) are enough here: k moves by ~2 ulp
+    // (the max keeps a ratio that rounds below 1 from turning the huge k negative)
+    const float ratio = __builtin_fmaxf(amax * hw_rcp(amin), 1.0f);   // R_X
+    float kk = kLog2Range * hw_rcp(hw_log2(ratio));
     kk = __builtin_amdgcn_fmed3f(kk, k_min, k_max);
     k = (amax != amin) ? kk : 1.0f;
   }
@@ -407,8 +402,9 @@ __device__ __forceinline__ void quantize16(const float (&x)[kEPL], const GroupQu
     for (int b = 0; b < 4; ++b) {
       const float xv = x[4 * d + b];
       if constexpr (EXPAND) {
-        const float t = hw_log2(__builtin_fabsf(xv) * gq.inv_a) * gq.k;   // log2 0 = -inf -> exp2 = 0
-        const float m = hw_exp2(t) * kE4M3Max;
+        // 448 r^k = exp2(k log2 r + log2 448): one fma, rounded once at magnitude <= 9
+        // (log2 0 = -inf, so a zero stays zero)
+        const float m = hw_exp2(__builtin_fmaf(hw_log2(__builtin_fabsf(xv) * gq.inv_a), gq.k, kLog2E4M3Max));
         q[b] = SIGNED ? as_f32(as_u32(m) | (as_u32(xv) & 0x80000000u)) : m;
       } else {
         q[b] = gq.inv_a != 0.0f ? xv / gq.scale : 0.0f;    // IEEE division: correctly rounded

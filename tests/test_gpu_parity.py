@@ -376,3 +376,23 @@ def test_non_finite_gradient_stays_in_its_group(coat, ref):
     # inside a poisoned group the other weights are still the clean result
     rest = np.arange(5 * G, 6 * G) != 5 * G + 3
     assert np.array_equal(w_a[5 * G:6 * G][rest], w_b[5 * G:6 * G][rest])
+
+
+def test_quant_nearly_constant_groups(coat, ref):
+    # groups whose range is a few ulp: k sits on its upper clamp on both sides
+    n, G = 4 * 1024, 128
+    rng = np.random.default_rng(21)
+    base = np.float32(3.0e-4)
+    x = np.full(n, base, np.float32)
+    ulps = rng.integers(0, 3, n).astype(np.int32)
+    x = (x.view(np.int32) + ulps).view(np.float32) * rng.choice([-1.0, 1.0], n).astype(np.float32)
+    x[:G] = base                                     # one exactly constant group: k = 1
+    q_g, s_g, k_g = (t.cpu().numpy() for t in coat.coat_quant_group(dev(x), G))
+    q_r, s_r, k_r = ref.quant_group(x, G)
+    assert k_r[0] == 1.0 and k_g[0] == 1.0
+    assert np.all(k_r[1:] == 1024.0) and np.all(k_g[1:] == 1024.0)
+    assert_scale(s_g, s_r, "tight groups")
+    # with k = 1024 a 1-ulp difference of x moves the value by 1.2e-4: codes stay within a step
+    n_bad = int(np.sum(q_g != q_r))
+    assert np.all(np.abs((q_g & 0x7F).astype(int) - (q_r & 0x7F).astype(int)) <= 1)
+    assert n_bad <= n // 100
