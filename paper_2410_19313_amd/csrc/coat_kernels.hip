@@ -115,10 +115,15 @@ struct StepArgs {
   uint64_t n;            // elements
   uint64_t n_full;       // number of full kChunk-sized chunks
   uint64_t n_groups;     // ceil(n / G)
-  float beta1, one_minus_beta1, beta2, one_minus_beta2;
-  float neg_lr_over_bc1; // -lr / (1 - beta1^t)
+  // The kernel carries the new moments divided by (1 - beta): m' = m_t / (1 - beta1) =
+  // (beta1/(1-beta1)) m + g is ONE fma (rounded once, which matters where the two terms cancel),
+  // v' = v_t / (1 - beta2) = (beta2/(1-beta2)) v + g*g one mul and one fma.  The factors are
+  // folded into the constants below and into the per-group scale.
+  float beta1_ratio, beta2_ratio;        // beta / (1 - beta)
+  float one_minus_beta1, one_minus_beta2;
+  float neg_lr_m;        // -lr * (1 - beta1) / (1 - beta1^t)
   float neg_lr_wd;       // -lr * weight_decay
-  float rsqrt_bc2;       // 1 / sqrt(1 - beta2^t)
+  float denom_scale;     // sqrt((1 - beta2) / (1 - beta2^t))
   float eps;
   float k_min, k_max;
   uint32_t expand;
@@ -147,12 +152,6 @@ __device__ __forceinline__ float hw_log2(float x) { return __builtin_amdgcn_logf
 __device__ __forceinline__ float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float hw_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ __forceinline__ float hw_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
-
-__device__ __forceinline__ float rcp_refined(float b) {
-  float r = hw_rcp(b);
-  float e = __builtin_fmaf(-b, r, 1.0f);
-  return __builtin_fmaf(e, r, r);
-}
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_mov(float x) {
@@ -278,11 +277,14 @@ __device__ __forceinline__ void store_codes16(uint8_t* p, uint64_t base, uint64_
 // span (and to be issued as a streaming access), the arithmetic wants every lane to own 16
 // consecutive elements.  A 4 KiB (fp32) / 2 KiB (bf16) per-wavefront LDS tile converts between
 // the two: rows of 64 x 16 B on the memory side, 64 B (32 B) per lane on the register side.
-// 16-byte slot s lives at s ^ ((s >> 3) & 7), which makes both access patterns conflict free.
-// A wavefront only ever touches its own tile and LDS executes one wavefront's accesses in
-// order, so no barrier is needed.
+// 16-byte slot s lives at s + (s >> 3) (one pad slot after every eight), which makes both access
+// patterns conflict free and keeps every address of a lane a constant offset from one of two
+// per-lane bases: row side 72 j + lane + (lane >> 3), lane side 4 lane + (lane >> 1) + i (fp32)
+// or 2 lane + (lane >> 2) + j (bf16).  A wavefront only ever touches its own tile and LDS
+// executes one wavefront's accesses in order, so no barrier is needed.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ int swz(int s) { return s ^ ((s >> 3) & 7); }
+constexpr int kTileSlotsW = 256 + 32;   // fp32 tile: 1024 elements + padding, in 16-byte slots
+constexpr int kTileSlotsG = 128 + 16;   // bf16 tile
 
 struct StageTiles { f32x4* w; u32x4* g; };
 
@@ -345,12 +347,16 @@ struct GroupQuant { float scale, k, inv_a; };
 // EXPAND: inv_a = 1/(448 scale), the reciprocal of the magnitude the top code stands for.
 // !EXPAND: k = 1 and inv_a = 1/scale, so that the value to round is simply x / scale (Sec. 3).
 template <bool EXPAND>
-__device__ __forceinline__ GroupQuant group_quant_params(float amax, float amin, float k_min, float k_max) {
+__device__ __forceinline__ GroupQuant group_quant_params(float amax, float amin, float k_min, float k_max,
+                                                         float unit = 1.0f) {
+  // The values reduced over are x / unit (unit = 1 - beta inside the step, 1 otherwise): the
+  // stored scale refers to x, the reciprocal returned refers to the values as they are held.
   GroupQuant r;
   // amax / 448, correctly rounded: multiply by the rounded reciprocal, then one residual step
   constexpr float inv448 = 1.0f / 448.0f;
-  float s = amax * inv448;
-  s = __builtin_fmaf(__builtin_fmaf(-kE4M3Max, s, amax), inv448, s);
+  const float ax = amax * unit;
+  float s = ax * inv448;
+  s = __builtin_fmaf(__builtin_fmaf(-kE4M3Max, s, ax), inv448, s);
   float k = 1.0f;
   if constexpr (EXPAND) {
     // two hardware reciprocals (1 ulp each) are enough here: k moves by ~2 ulp
@@ -360,7 +366,7 @@ __device__ __forceinline__ GroupQuant group_quant_params(float amax, float amin,
     kk = __builtin_amdgcn_fmed3f(kk, k_min, k_max);
     k = (amax != amin) ? kk : 1.0f;
   }
-  const float inv_a = rcp_refined(EXPAND ? kE4M3Max * s : s);
+  const float inv_a = unit * hw_rcp(EXPAND ? kE4M3Max * s : s);
   const bool empty = !(amax > 0.0f);                 // all zero: scale 0, k 1, every code 0
   r.scale = empty ? 0.0f : s;
   r.k = empty ? 1.0f : k;
@@ -394,7 +400,8 @@ __device__ __forceinline__ void lane_extremes(const float (&x)[kEPL], float& ama
 //            plain quantizer of Sec. 3 kept as a baseline; it is not tuned)
 // SIGNED = false (second moment, never negative) skips the sign transfer.
 template <bool EXPAND, bool SIGNED>
-__device__ __forceinline__ void quantize16(const float (&x)[kEPL], const GroupQuant& gq, uint32_t (&c)[4]) {
+__device__ __forceinline__ void quantize16(const float (&x)[kEPL], const GroupQuant& gq, uint32_t (&c)[4],
+                                           float unit = 1.0f) {
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
     float q[4];
@@ -407,7 +414,7 @@ __device__ __forceinline__ void quantize16(const float (&x)[kEPL], const GroupQu
         const float m = hw_exp2(__builtin_fmaf(hw_log2(__builtin_fabsf(xv) * gq.inv_a), gq.k, kLog2E4M3Max));
         q[b] = SIGNED ? as_f32(as_u32(m) | (as_u32(xv) & 0x80000000u)) : m;
       } else {
-        q[b] = gq.inv_a != 0.0f ? xv / gq.scale : 0.0f;    // IEEE division: correctly rounded
+        q[b] = gq.inv_a != 0.0f ? (xv * unit) / gq.scale : 0.0f;   // IEEE division: correctly rounded
       }
     }
     uint32_t p = __builtin_amdgcn_cvt_pk_fp8_f32(q[0], q[1], 0u, false);
@@ -430,30 +437,31 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const Log2Entry* lu
                                           GroupMeta& meta) {
   constexpr int LPG = G / kEPL;                      // lanes per group
   float m[kEPL], v[kEPL];
-  float m_fac, v_fac;                                // beta * (magnitude of the decoded unit)
+  float m_fac, v_fac;                                // beta/(1-beta) * (magnitude of the decoded unit)
   if constexpr (EXPAND) {
-    // m = (448 scale) * |c/448|^(1/k)
-    inverse_expand16<true, true>(lut, mc, meta.m_k, rcp_refined(meta.m_k), m);
-    inverse_expand16<false, false>(lut, vc, meta.v_k, rcp_refined(meta.v_k), v);
-    m_fac = a.beta1 * (kE4M3Max * meta.m_scale);
-    v_fac = a.beta2 * (kE4M3Max * meta.v_scale);
+    // m = (448 scale) * |c/448|^(1/k).  A plain hardware reciprocal of k is enough: the
+    // compensated path recovers its error, the other one is modelled with it.
+    inverse_expand16<true, true>(lut, mc, meta.m_k, hw_rcp(meta.m_k), m);
+    inverse_expand16<false, false>(lut, vc, meta.v_k, hw_rcp(meta.v_k), v);
+    m_fac = a.beta1_ratio * (kE4M3Max * meta.m_scale);
+    v_fac = a.beta2_ratio * (kE4M3Max * meta.v_scale);
   } else {
     // plain dequantizer: m = scale * c (k is 1 in this mode and is not read)
     decode16<true>(mc, m);
     decode16<false>(vc, v);
-    m_fac = a.beta1 * meta.m_scale;
-    v_fac = a.beta2 * meta.v_scale;
+    m_fac = a.beta1_ratio * meta.m_scale;
+    v_fac = a.beta2_ratio * meta.v_scale;
   }
 
 #pragma unroll
   for (int e = 0; e < kEPL; ++e) {
     const float ge = g[e];
-    const float m_t = __builtin_fmaf(m[e], m_fac, a.one_minus_beta1 * ge);          // Sec. 3
-    const float v_t = __builtin_fmaf(v[e], v_fac, (a.one_minus_beta2 * ge) * ge);
-    // Eq. (1) with the unquantized new moments; sqrt(v_t / bc2) = sqrt(v_t) * bc2^-1/2
-    const float denom = __builtin_fmaf(hw_sqrt(v_t), a.rsqrt_bc2, a.eps);
+    const float m_t = __builtin_fmaf(m[e], m_fac, ge);              // m_t / (1 - beta1), Sec. 3
+    const float v_t = __builtin_fmaf(ge, ge, v[e] * v_fac);         // v_t / (1 - beta2)
+    // Eq. (1) with the unquantized new moments; sqrt(v_t / bc2) = sqrt(v') * sqrt((1-beta2)/bc2)
+    const float denom = __builtin_fmaf(hw_sqrt(v_t), a.denom_scale, a.eps);
     const float upd = m_t * hw_rcp(denom);
-    const float wt = __builtin_fmaf(upd, a.neg_lr_over_bc1, w[e]);
+    const float wt = __builtin_fmaf(upd, a.neg_lr_m, w[e]);
     w[e] = __builtin_fmaf(w[e], a.neg_lr_wd, wt);
     m[e] = m_t;
     v[e] = v_t;
@@ -466,10 +474,10 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const Log2Entry* lu
   m_min = group_allreduce<LPG, false>(m_min);
   v_max = group_allreduce<LPG, true>(v_max);
   v_min = group_allreduce<LPG, false>(v_min);
-  const GroupQuant qm = group_quant_params<EXPAND>(m_max, m_min, a.k_min, a.k_max);
-  const GroupQuant qv = group_quant_params<EXPAND>(v_max, v_min, a.k_min, a.k_max);
-  quantize16<EXPAND, true>(m, qm, mc);
-  quantize16<EXPAND, false>(v, qv, vc);
+  const GroupQuant qm = group_quant_params<EXPAND>(m_max, m_min, a.k_min, a.k_max, a.one_minus_beta1);
+  const GroupQuant qv = group_quant_params<EXPAND>(v_max, v_min, a.k_min, a.k_max, a.one_minus_beta2);
+  quantize16<EXPAND, true>(m, qm, mc, a.one_minus_beta1);
+  quantize16<EXPAND, false>(v, qv, vc, a.one_minus_beta2);
   meta.m_scale = qm.scale; meta.m_k = qm.k;
   meta.v_scale = qv.scale; meta.v_k = qv.k;
 }
@@ -486,20 +494,23 @@ struct RawChunk {
 template <int G, bool EXPAND>
 __device__ __forceinline__ void issue_loads(const StepArgs& a, uint64_t chunk, int lane, RawChunk& r) {
   constexpr int LPG = G / kEPL;
+  // chunk is uniform over the wavefront: the array bases below are scalar, lanes add 32-bit offsets
   const uint64_t cb = chunk * kChunk;
-  const uint64_t base = cb + static_cast<uint64_t>(lane) * kEPL;
-  const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
+  const uint64_t gb = chunk * (kChunk / G);
   const f32x4* wq = reinterpret_cast<const f32x4*>(a.w + cb);
   const u32x4* gq = reinterpret_cast<const u32x4*>(a.g + cb);
+  const u32x4* mq = reinterpret_cast<const u32x4*>(a.mq + cb);
+  const u32x4* vq = reinterpret_cast<const u32x4*>(a.vq + cb);
+  const int gl = lane / LPG;
 #pragma unroll
   for (int j = 0; j < 4; ++j) r.w[j] = ldg<8>(wq + 64 * j + lane);
 #pragma unroll
   for (int j = 0; j < 2; ++j) r.g[j] = ldg<4>(gq + 64 * j + lane);
-  r.mc = ldg<1>(reinterpret_cast<const u32x4*>(a.mq + base));
-  r.vc = ldg<1>(reinterpret_cast<const u32x4*>(a.vq + base));
-  r.meta.m_scale = a.ms[gidx];
-  r.meta.v_scale = a.vs[gidx];
-  if constexpr (EXPAND) { r.meta.m_k = a.mk[gidx]; r.meta.v_k = a.vk[gidx]; }
+  r.mc = ldg<1>(mq + lane);
+  r.vc = ldg<1>(vq + lane);
+  r.meta.m_scale = a.ms[gb + gl];
+  r.meta.v_scale = a.vs[gb + gl];
+  if constexpr (EXPAND) { r.meta.m_k = a.mk[gb + gl]; r.meta.v_k = a.vk[gb + gl]; }
   else { r.meta.m_k = 1.0f; r.meta.v_k = 1.0f; }
 }
 
@@ -509,22 +520,25 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const Log2Entry
                                               uint64_t chunk, int lane, RawChunk& r) {
   constexpr int LPG = G / kEPL;
   const uint64_t cb = chunk * kChunk;
-  const uint64_t base = cb + static_cast<uint64_t>(lane) * kEPL;
-  const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
+  const uint64_t gb = chunk * (kChunk / G);
+  f32x4* const w_row = tiles.w + lane + (lane >> 3);          // + 72 j
+  f32x4* const w_own = tiles.w + 4 * lane + (lane >> 1);      // + i
+  u32x4* const g_row = tiles.g + lane + (lane >> 3);          // + 72 j
+  u32x4* const g_own = tiles.g + 2 * lane + (lane >> 2);      // + j
 
   float w[kEPL], g[kEPL];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) tiles.w[swz(64 * j + lane)] = r.w[j];
+  for (int j = 0; j < 4; ++j) w_row[72 * j] = r.w[j];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) tiles.g[swz(64 * j + lane)] = r.g[j];
+  for (int j = 0; j < 2; ++j) g_row[72 * j] = r.g[j];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const f32x4 t = tiles.w[swz(4 * lane + i)];
+    const f32x4 t = w_own[i];
     w[4 * i + 0] = t.x; w[4 * i + 1] = t.y; w[4 * i + 2] = t.z; w[4 * i + 3] = t.w;
   }
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const u32x4 t = tiles.g[swz(2 * lane + j)];
+    const u32x4 t = g_own[j];
     g[8 * j + 0] = as_f32(t.x << 16); g[8 * j + 1] = as_f32(t.x & 0xffff0000u);
     g[8 * j + 2] = as_f32(t.y << 16); g[8 * j + 3] = as_f32(t.y & 0xffff0000u);
     g[8 * j + 4] = as_f32(t.z << 16); g[8 * j + 5] = as_f32(t.z & 0xffff0000u);
@@ -539,44 +553,43 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const Log2Entry
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const f32x4 t = {w[4 * i + 0], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]};
-    tiles.w[swz(4 * lane + i)] = t;
+    w_own[i] = t;
   }
   f32x4* wq = reinterpret_cast<f32x4*>(a.w + cb);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) stg<16>(wq + 64 * j + lane, tiles.w[swz(64 * j + lane)]);
+  for (int j = 0; j < 4; ++j) stg<16>(wq + 64 * j + lane, w_row[72 * j]);
   const u32x4 mo = {mc[0], mc[1], mc[2], mc[3]}, vo = {vc[0], vc[1], vc[2], vc[3]};
-  stg<2>(reinterpret_cast<u32x4*>(a.mq + base), mo);
-  stg<2>(reinterpret_cast<u32x4*>(a.vq + base), vo);
+  stg<2>(reinterpret_cast<u32x4*>(a.mq + cb) + lane, mo);
+  stg<2>(reinterpret_cast<u32x4*>(a.vq + cb) + lane, vo);
   if ((lane % LPG) == 0) {
-    a.ms[gidx] = meta.m_scale; a.mk[gidx] = meta.m_k;
-    a.vs[gidx] = meta.v_scale; a.vk[gidx] = meta.v_k;
+    const int gl = lane / LPG;
+    a.ms[gb + gl] = meta.m_scale; a.mk[gb + gl] = meta.m_k;
+    a.vs[gb + gl] = meta.v_scale; a.vk[gb + gl] = meta.v_k;
   }
 }
 
-// Persistent, software-pipelined main kernel: wavefront q of the launch handles chunks q, q + Q,
-// q + 2Q, ... (Q = wavefronts in the grid) and fetches chunk i+1 while it computes chunk i, so
-// that few resident wavefronts keep both the memory system and the VALU busy.  The first chunk's
-// loads are issued before the block fills its lookup table.
+// Main kernel: one chunk per wavefront (the loop only runs again for buffers with more chunks
+// than the grid has wavefronts).  The first chunk's loads are issued before the block fills its
+// lookup table, so the table's latency hides behind them.
 template <int G, bool EXPAND>
 __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
   __shared__ Log2Entry lut[256];
-  __shared__ f32x4 tile_w[kWavesPerBlock * 256];
-  __shared__ u32x4 tile_g[kWavesPerBlock * 128];
+  __shared__ f32x4 tile_w[kWavesPerBlock * kTileSlotsW];
+  __shared__ u32x4 tile_g[kWavesPerBlock * kTileSlotsG];
   const int lane = threadIdx.x & (kWave - 1);
-  const int wv = threadIdx.x >> 6;
-  const StageTiles tiles = {tile_w + wv * 256, tile_g + wv * 128};
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wavefront-uniform
+  const StageTiles tiles = {tile_w + wv * kTileSlotsW, tile_g + wv * kTileSlotsG};
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
   uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv;
 
-  RawChunk cur, nxt;
-  if (chunk < a.n_full) issue_loads<G, EXPAND>(a, chunk, lane, cur);
-  fill_lut(lut);
-  while (chunk < a.n_full) {
-    const uint64_t next = chunk + stride;
-    if (next < a.n_full) issue_loads<G, EXPAND>(a, next, lane, nxt);
-    process_chunk<G, EXPAND>(a, lut, tiles, chunk, lane, cur);
-    cur = nxt;
-    chunk = next;
+  RawChunk r;
+  const bool have = chunk < a.n_full;
+  if (have) issue_loads<G, EXPAND>(a, chunk, lane, r);
+  fill_lut(lut);                                     // every wavefront of the block reaches this
+  if (have) process_chunk<G, EXPAND>(a, lut, tiles, chunk, lane, r);
+  for (chunk += stride; chunk < a.n_full; chunk += stride) {
+    issue_loads<G, EXPAND>(a, chunk, lane, r);
+    process_chunk<G, EXPAND>(a, lut, tiles, chunk, lane, r);
   }
 }
 
@@ -661,7 +674,7 @@ __device__ __forceinline__ void dequant_chunk(const DequantArgs& a, const Log2En
   load_codes16<GUARD>(a.q, base, a.n, c);
   const float amag = kE4M3Max * (gvalid ? a.scale[gidx] : 0.0f);
   const float k = gvalid ? a.k[gidx] : 1.0f;
-  inverse_expand16<true, true>(lut, c, k, rcp_refined(k), x);
+  inverse_expand16<true, true>(lut, c, k, hw_rcp(k), x);
 #pragma unroll
   for (int e = 0; e < kEPL; ++e) x[e] *= amag;
   store_f32x16<GUARD>(a.x, base, a.n, x);
@@ -833,11 +846,14 @@ int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float
   a.w = w; a.g = grad_bf16; a.mq = m_q; a.ms = m_scale; a.mk = m_k; a.vq = v_q; a.vs = v_scale; a.vk = v_k;
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(hp->group_size) - 1) / static_cast<uint64_t>(hp->group_size);
-  a.beta1 = hp->beta1; a.one_minus_beta1 = 1.0f - hp->beta1;
-  a.beta2 = hp->beta2; a.one_minus_beta2 = 1.0f - hp->beta2;
-  a.neg_lr_over_bc1 = static_cast<float>(-static_cast<double>(hp->lr) / bc1);
+  a.one_minus_beta1 = 1.0f - hp->beta1;               // exact (Sterbenz) for beta >= 0.5
+  a.one_minus_beta2 = 1.0f - hp->beta2;
+  const double omb1 = a.one_minus_beta1, omb2 = a.one_minus_beta2;
+  a.beta1_ratio = static_cast<float>(b1 / omb1);
+  a.beta2_ratio = static_cast<float>(b2 / omb2);
+  a.neg_lr_m = static_cast<float>(-static_cast<double>(hp->lr) * omb1 / bc1);
   a.neg_lr_wd = static_cast<float>(-static_cast<double>(hp->lr) * static_cast<double>(hp->weight_decay));
-  a.rsqrt_bc2 = static_cast<float>(1.0 / __builtin_sqrt(bc2));
+  a.denom_scale = static_cast<float>(__builtin_sqrt(omb2 / bc2));
   a.eps = hp->eps;
   a.k_min = k_min; a.k_max = k_max;
   a.expand = (hp->flags & COAT_FLAG_EXPAND) ? 1u : 0u;
