@@ -65,6 +65,45 @@ def cpu_baseline(G: int, sample_params: int, steps: int):
                 sample="first %d parameters of the workload, %d steps after one untimed step, %.1f s" % (n, steps, dt))
 
 
+def bench_half(args, C, S, torch, dev, gen, n, G):
+    """coat_quant_group / coat_dequant_group alone: 5 + 8/G algorithmic bytes per element each
+    (fp32 in + code and metadata out, or the reverse)."""
+    x = S.torch_weights(n, dev, gen, sigma=1e-3)
+    out = (torch.empty(n, dtype=torch.uint8, device=dev), torch.empty(n // G, dtype=torch.float32, device=dev),
+           torch.empty(n // G, dtype=torch.float32, device=dev))
+    C.coat_quant_group(x, G, out=out)
+    y = torch.empty_like(x)
+
+    def run():
+        if args.op == "quant":
+            C.coat_quant_group(x, G, out=out)
+        else:
+            C.coat_dequant_group(out[0], out[1], out[2], G, out=y)
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    avg_s = e0.elapsed_time(e1) / args.steps / 1e3
+    algo = (5.0 + 8.0 / G) * n
+    print(json.dumps({
+        "metric": "elements/sec, coat_%s_group (E4M3, per-group scale + dynamic range expansion)" % args.op,
+        "value": n * args.steps / wall, "unit": "elements/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d elements, G=%d" % (args.workload, n, G)},
+        "roofline": {"bound": "hbm", "achieved": algo / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": algo / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "%s_kernel<%d>" % (args.op, G)}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +115,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27)
     ap.add_argument("--cpu-steps", type=int, default=12)
+    ap.add_argument("--op", default="step", choices=["step", "quant", "dequant"],
+                    help="step: the fused optimizer step (the metric); quant / dequant: its two halves alone")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (scales the rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -107,6 +148,9 @@ def main():
     assert n % G == 0
 
     gen = S.torch_generator(dev, 0)
+    if args.op != "step":
+        bench_half(args, C, S, torch, dev, gen, n, G)
+        return
     w = S.torch_weights(n, dev, gen)
     st = S.torch_zero_state(n, G, dev)
     mask = S.torch_outlier_group_mask(n // G, dev, gen, 0.01)

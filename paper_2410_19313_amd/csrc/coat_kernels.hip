@@ -288,6 +288,34 @@ constexpr int kTileSlotsG = 128 + 16;   // bf16 tile
 
 struct StageTiles { f32x4* w; u32x4* g; };
 
+// rows (memory side) -> 16 consecutive fp32 per lane, through the wavefront's fp32 tile
+__device__ __forceinline__ void tile_rows_to_lanes(f32x4* tile, int lane, const f32x4 (&rows)[4], float (&x)[kEPL]) {
+  f32x4* const row = tile + lane + (lane >> 3);          // + 72 j
+  const f32x4* const own = tile + 4 * lane + (lane >> 1);  // + i
+#pragma unroll
+  for (int j = 0; j < 4; ++j) row[72 * j] = rows[j];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f32x4 t = own[i];
+    x[4 * i + 0] = t.x; x[4 * i + 1] = t.y; x[4 * i + 2] = t.z; x[4 * i + 3] = t.w;
+  }
+}
+
+// 16 consecutive fp32 per lane -> rows, written straight to memory (p: start of the chunk)
+template <int NT_BIT>
+__device__ __forceinline__ void tile_lanes_to_rows_store(f32x4* tile, int lane, const float (&x)[kEPL], float* p) {
+  const f32x4* const row = tile + lane + (lane >> 3);
+  f32x4* const own = tile + 4 * lane + (lane >> 1);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f32x4 t = {x[4 * i + 0], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]};
+    own[i] = t;
+  }
+  f32x4* q = reinterpret_cast<f32x4*>(p);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) stg<NT_BIT>(q + 64 * j + lane, row[72 * j]);
+}
+
 __device__ __forceinline__ void fill_lut(Log2Entry* lut) {
   // 256 entries so that the whole code byte indexes it (the sign bit is ignored)
   for (int i = threadIdx.x; i < 256; i += blockDim.x) lut[i] = kLog2CodeOverMax[i & 127];
@@ -521,21 +549,13 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const Log2Entry
   constexpr int LPG = G / kEPL;
   const uint64_t cb = chunk * kChunk;
   const uint64_t gb = chunk * (kChunk / G);
-  f32x4* const w_row = tiles.w + lane + (lane >> 3);          // + 72 j
-  f32x4* const w_own = tiles.w + 4 * lane + (lane >> 1);      // + i
   u32x4* const g_row = tiles.g + lane + (lane >> 3);          // + 72 j
   u32x4* const g_own = tiles.g + 2 * lane + (lane >> 2);      // + j
 
   float w[kEPL], g[kEPL];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) w_row[72 * j] = r.w[j];
-#pragma unroll
   for (int j = 0; j < 2; ++j) g_row[72 * j] = r.g[j];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const f32x4 t = w_own[i];
-    w[4 * i + 0] = t.x; w[4 * i + 1] = t.y; w[4 * i + 2] = t.z; w[4 * i + 3] = t.w;
-  }
+  tile_rows_to_lanes(tiles.w, lane, r.w, w);
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const u32x4 t = g_own[j];
@@ -550,14 +570,7 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const Log2Entry
 
   step_core<G, EXPAND>(a, lut, w, g, mc, vc, meta);
 
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const f32x4 t = {w[4 * i + 0], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]};
-    w_own[i] = t;
-  }
-  f32x4* wq = reinterpret_cast<f32x4*>(a.w + cb);
-#pragma unroll
-  for (int j = 0; j < 4; ++j) stg<16>(wq + 64 * j + lane, w_row[72 * j]);
+  tile_lanes_to_rows_store<16>(tiles.w, lane, w, a.w + cb);
   const u32x4 mo = {mc[0], mc[1], mc[2], mc[3]}, vo = {vc[0], vc[1], vc[2], vc[3]};
   stg<2>(reinterpret_cast<u32x4*>(a.mq + cb) + lane, mo);
   stg<2>(reinterpret_cast<u32x4*>(a.vq + cb) + lane, vo);
@@ -630,71 +643,99 @@ __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
 // standalone quantizer / dequantizer (the two halves of the step)
 // ---------------------------------------------------------------------------------------
 
-template <int G, bool EXPAND, bool GUARD>
-__device__ __forceinline__ void quant_chunk(const QuantArgs& a, uint64_t chunk, int lane) {
+// quantize one lane's 16 values (cross-lane: the group reductions) and hand back codes + metadata
+template <int G, bool EXPAND>
+__device__ __forceinline__ GroupQuant quant_core(const QuantArgs& a, const float (&x)[kEPL], uint32_t (&c)[4]) {
   constexpr int LPG = G / kEPL;
-  const uint64_t base = chunk * kChunk + static_cast<uint64_t>(lane) * kEPL;
-  const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
-  const bool gvalid = !GUARD || gidx < a.n_groups;
-  float x[kEPL];
-  uint32_t c[4];
-  load_f32x16<GUARD>(a.x, base, a.n, x);
   float hi, lo;
   lane_extremes(x, hi, lo);
   hi = group_allreduce<LPG, true>(hi);
   lo = group_allreduce<LPG, false>(lo);
   const GroupQuant q = group_quant_params<EXPAND>(hi, lo, a.k_min, a.k_max);
   quantize16<EXPAND, true>(x, q, c);
-  store_codes16<GUARD>(a.q, base, a.n, c);
-  if (gvalid && (lane % LPG) == 0) { a.scale[gidx] = q.scale; a.k[gidx] = q.k; }
+  return q;
 }
 
+// full chunks: coalesced streaming row loads of x staged through the LDS tile, one chunk per wavefront
 template <int G, bool EXPAND>
 __global__ __launch_bounds__(kBlock) void quant_kernel(QuantArgs a) {
+  __shared__ f32x4 tile_x[kWavesPerBlock * kTileSlotsW];
+  constexpr int LPG = G / kEPL;
   const int lane = threadIdx.x & (kWave - 1);
-  const uint64_t wave = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
-  for (uint64_t chunk = wave; chunk < a.n_full; chunk += stride) quant_chunk<G, EXPAND, false>(a, chunk, lane);
+  for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
+    const uint64_t cb = chunk * kChunk, gb = chunk * (kChunk / G);
+    const f32x4* xq = reinterpret_cast<const f32x4*>(a.x + cb);
+    f32x4 rows[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) rows[j] = ldg<8>(xq + 64 * j + lane);
+    float x[kEPL];
+    uint32_t c[4];
+    tile_rows_to_lanes(tile_x + wv * kTileSlotsW, lane, rows, x);
+    const GroupQuant q = quant_core<G, EXPAND>(a, x, c);
+    const u32x4 co = {c[0], c[1], c[2], c[3]};
+    stg<2>(reinterpret_cast<u32x4*>(a.q + cb) + lane, co);
+    if ((lane % LPG) == 0) { a.scale[gb + lane / LPG] = q.scale; a.k[gb + lane / LPG] = q.k; }
+  }
 }
 
+// the ragged last chunk: one wavefront, element-wise guarded accesses
 template <int G, bool EXPAND>
 __global__ __launch_bounds__(kWave) void quant_tail_kernel(QuantArgs a) {
-  quant_chunk<G, EXPAND, true>(a, a.n_full, threadIdx.x);
-}
-
-template <int G, bool GUARD>
-__device__ __forceinline__ void dequant_chunk(const DequantArgs& a, const Log2Entry* lut, uint64_t chunk,
-                                              int lane) {
   constexpr int LPG = G / kEPL;
-  const uint64_t base = chunk * kChunk + static_cast<uint64_t>(lane) * kEPL;
-  const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
-  const bool gvalid = !GUARD || gidx < a.n_groups;
-  uint32_t c[4];
+  const int lane = threadIdx.x;
+  const uint64_t base = a.n_full * kChunk + static_cast<uint64_t>(lane) * kEPL;
+  const uint64_t gidx = a.n_full * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
   float x[kEPL];
-  load_codes16<GUARD>(a.q, base, a.n, c);
-  const float amag = kE4M3Max * (gvalid ? a.scale[gidx] : 0.0f);
-  const float k = gvalid ? a.k[gidx] : 1.0f;
-  inverse_expand16<true, true>(lut, c, k, hw_rcp(k), x);
-#pragma unroll
-  for (int e = 0; e < kEPL; ++e) x[e] *= amag;
-  store_f32x16<GUARD>(a.x, base, a.n, x);
+  uint32_t c[4];
+  load_f32x16<true>(a.x, base, a.n, x);
+  const GroupQuant q = quant_core<G, EXPAND>(a, x, c);
+  store_codes16<true>(a.q, base, a.n, c);
+  if (gidx < a.n_groups && (lane % LPG) == 0) { a.scale[gidx] = q.scale; a.k[gidx] = q.k; }
 }
 
 template <int G>
 __global__ __launch_bounds__(kBlock) void dequant_kernel(DequantArgs a) {
   __shared__ Log2Entry lut[256];
+  __shared__ f32x4 tile_x[kWavesPerBlock * kTileSlotsW];
   fill_lut(lut);
+  constexpr int LPG = G / kEPL;
   const int lane = threadIdx.x & (kWave - 1);
-  const uint64_t wave = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
-  for (uint64_t chunk = wave; chunk < a.n_full; chunk += stride) dequant_chunk<G, false>(a, lut, chunk, lane);
+  for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
+    const uint64_t cb = chunk * kChunk, gb = chunk * (kChunk / G);
+    const u32x4 ci = ldg<1>(reinterpret_cast<const u32x4*>(a.q + cb) + lane);
+    const float amag = kE4M3Max * a.scale[gb + lane / LPG];
+    const float k = a.k[gb + lane / LPG];
+    const uint32_t c[4] = {ci.x, ci.y, ci.z, ci.w};
+    float x[kEPL];
+    inverse_expand16<true, true>(lut, c, k, hw_rcp(k), x);
+#pragma unroll
+    for (int e = 0; e < kEPL; ++e) x[e] *= amag;
+    tile_lanes_to_rows_store<16>(tile_x + wv * kTileSlotsW, lane, x, a.x + cb);
+  }
 }
 
 template <int G>
 __global__ __launch_bounds__(kWave) void dequant_tail_kernel(DequantArgs a) {
   __shared__ Log2Entry lut[256];
   fill_lut(lut);
-  dequant_chunk<G, true>(a, lut, a.n_full, threadIdx.x);
+  constexpr int LPG = G / kEPL;
+  const int lane = threadIdx.x;
+  const uint64_t base = a.n_full * kChunk + static_cast<uint64_t>(lane) * kEPL;
+  const uint64_t gidx = a.n_full * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
+  const bool gvalid = gidx < a.n_groups;
+  uint32_t c[4];
+  float x[kEPL];
+  load_codes16<true>(a.q, base, a.n, c);
+  const float amag = kE4M3Max * (gvalid ? a.scale[gidx] : 0.0f);
+  const float k = gvalid ? a.k[gidx] : 1.0f;
+  inverse_expand16<true, true>(lut, c, k, hw_rcp(k), x);
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) x[e] *= amag;
+  store_f32x16<true>(a.x, base, a.n, x);
 }
 
 // ---------------------------------------------------------------------------------------
