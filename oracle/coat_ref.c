@@ -23,6 +23,18 @@
 /* Sec. 3: largest finite E4M3 magnitude.  Sec. 4.1: R_E4M3 = 448 * 512. */
 #define E4M3_MAX 448.0
 #define LOG2_R_E4M3 17.807354922057606 /* log2(229376) */
+/* Sec. 3: E5M2 spans 2^-16 .. 57344, so R_E5M2 = 57344 * 65536. */
+#define E5M2_MAX 57344.0
+#define LOG2_R_E5M2 31.807354922057606 /* log2(3758096384) */
+
+typedef struct { double fmax, log2_range; int e5m2; } fmt_t;
+static fmt_t fmt_of(int e5m2) {
+  fmt_t f;
+  f.e5m2 = e5m2;
+  f.fmax = e5m2 ? E5M2_MAX : E4M3_MAX;
+  f.log2_range = e5m2 ? LOG2_R_E5M2 : LOG2_R_E4M3;
+  return f;
+}
 
 int coat_ref_num_threads(void) {
 #ifdef _OPENMP
@@ -65,13 +77,47 @@ uint8_t coat_ref_e4m3_encode(double q) {
   return (uint8_t)(sign | code);
 }
 
+/* ---- E5M2 codec (OCP 8-bit floating point, E5M2 variant: IEEE-like, with infinities) -- */
+
+double coat_ref_e5m2_decode(uint8_t code) {
+  int s = code >> 7, e = (code >> 2) & 31, m = code & 3;
+  double v;
+  if (e == 31) v = m ? NAN : INFINITY;
+  else if (e == 0) v = ldexp((double)m / 4.0, -14);  /* subnormal: 2^-14 * m/4 */
+  else v = ldexp(1.0 + (double)m / 4.0, e - 15);
+  return s ? -v : v;
+}
+
+uint8_t coat_ref_e5m2_encode(double q) {
+  uint8_t sign = signbit(q) ? 0x80 : 0x00;
+  double a = fabs(q);
+  int e, mant, code;
+  if (isnan(q)) return 0x7F;
+  if (a > E5M2_MAX) a = E5M2_MAX;                /* saturate to the largest finite value */
+  if (a < ldexp(1.0, -14)) {
+    code = (int)rint(a * 65536.0);               /* subnormal spacing 2^-16; 4 = smallest normal */
+  } else {
+    int ex;
+    (void)frexp(a, &ex);
+    e = ex - 1;
+    mant = (int)rint((ldexp(a, -e) - 1.0) * 4.0);
+    if (mant == 4) { mant = 0; e += 1; }
+    code = ((e + 15) << 2) | mant;
+    if (code > 0x7B) code = 0x7B;
+  }
+  return (uint8_t)(sign | code);
+}
+
+static double fmt_decode(fmt_t f, uint8_t c) { return f.e5m2 ? coat_ref_e5m2_decode(c) : coat_ref_e4m3_decode(c); }
+static uint8_t fmt_encode(fmt_t f, double q) { return f.e5m2 ? coat_ref_e5m2_encode(q) : coat_ref_e4m3_encode(q); }
+
 /* ---- per-group quantizer with dynamic range expansion (Sec. 3, Sec. 4) ------------- */
 
 static void resolve_k_bounds(float* k_min, float* k_max) {
   if (*k_min == 0.0f && *k_max == 0.0f) { *k_min = 0.0625f; *k_max = 1024.0f; }
 }
 
-static void quant_one_group(const float* x, uint64_t len, uint32_t flags,
+static void quant_one_group(const float* x, uint64_t len, int expand, fmt_t f,
                             float k_min, float k_max,
                             uint8_t* q, float* scale_out, float* k_out) {
   double amax = 0.0, amin = INFINITY;
@@ -92,40 +138,40 @@ static void quant_one_group(const float* x, uint64_t len, uint32_t flags,
     *k_out = 1.0f;
     return;
   }
-  scale = (float)(amax / E4M3_MAX);              /* S_X of Sec. 3, kept in fp32 */
-  if ((flags & COAT_REF_FLAG_EXPAND) && amax != amin) {
-    /* optimal k of Sec. 4.2: R_X^k = R_E4M3 */
-    kd = LOG2_R_E4M3 / log2(amax / amin);
+  scale = (float)(amax / f.fmax);                /* S_X of Sec. 3, kept in fp32 */
+  if (expand && amax != amin) {
+    /* optimal k of Sec. 4.2: R_X^k = R_format */
+    kd = f.log2_range / log2(amax / amin);
     if (kd < (double)k_min) kd = (double)k_min;
     if (kd > (double)k_max) kd = (double)k_max;
     k = (float)kd;
   }
   /* Quantize with the STORED scale and k so that Q and DQ agree.  The expanded group is
-   * f(x / a) with a = 448 * scale ~= amax, whose largest element is 1, so the plain
-   * quantizer's scale is 1/448 and the value to round is 448 * (|x|/a)^k. */
-  a = E4M3_MAX * (double)scale;
+   * f(x / a) with a = fmax * scale ~= amax, whose largest element is 1, so the plain
+   * quantizer's scale is 1/fmax and the value to round is fmax * (|x|/a)^k. */
+  a = f.fmax * (double)scale;
   kd = (double)k;
   for (i = 0; i < len; ++i) {
     double xv = (double)x[i], mag;
     if (xv == 0.0) { q[i] = signbit(x[i]) ? 0x80 : 0x00; continue; }
     /* Appendix A keeps the optimizer arithmetic in FP32: the number handed to the E4M3
      * rounding is an fp32 value (with k == 1 it is the fp32 quotient x / S_X of Sec. 3). */
-    mag = (double)(float)(E4M3_MAX * pow(fabs(xv) / a, kd));
-    if (mag > E4M3_MAX) mag = E4M3_MAX;
-    q[i] = coat_ref_e4m3_encode(copysign(mag, xv));
+    mag = (double)(float)(f.fmax * pow(fabs(xv) / a, kd));
+    if (mag > f.fmax) mag = f.fmax;
+    q[i] = fmt_encode(f, copysign(mag, xv));
   }
   *scale_out = scale;
   *k_out = k;
 }
 
-static void dequant_one_group(const uint8_t* q, float scale, float k, uint64_t len,
+static void dequant_one_group(const uint8_t* q, float scale, float k, fmt_t f, uint64_t len,
                               double* x) {
-  double a = E4M3_MAX * (double)scale, inv_k = 1.0 / (double)k;
+  double a = f.fmax * (double)scale, inv_k = 1.0 / (double)k;
   uint64_t i;
   for (i = 0; i < len; ++i) {
-    double c = coat_ref_e4m3_decode(q[i]);
+    double c = fmt_decode(f, q[i]);
     if (c == 0.0) { x[i] = c; continue; }        /* f(0) = 0, sign of zero kept */
-    x[i] = copysign(a * pow(fabs(c) / E4M3_MAX, inv_k), c);
+    x[i] = copysign(a * pow(fabs(c) / f.fmax, inv_k), c);
   }
 }
 
@@ -140,12 +186,13 @@ void coat_ref_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags,
   for (gi = 0; gi < ng; ++gi) {
     uint64_t lo = (uint64_t)gi * (uint64_t)G;
     uint64_t len = (n - lo < (uint64_t)G) ? n - lo : (uint64_t)G;
-    quant_one_group(x + lo, len, flags, k_min, k_max, q + lo, scale + gi, k + gi);
+    quant_one_group(x + lo, len, (flags & COAT_REF_FLAG_EXPAND) != 0, fmt_of((flags & COAT_REF_FLAG_E5M2) != 0),
+                    k_min, k_max, q + lo, scale + gi, k + gi);
   }
 }
 
 void coat_ref_dequant_group_f64(const uint8_t* q, const float* scale, const float* k,
-                                uint64_t n, int32_t G, double* x) {
+                                uint64_t n, int32_t G, uint32_t flags, double* x) {
   int64_t ng, gi;
   if (!x || !q || !scale || !k || G < 1 || n == 0) return;
   ng = (int64_t)((n + (uint64_t)G - 1) / (uint64_t)G);
@@ -153,12 +200,12 @@ void coat_ref_dequant_group_f64(const uint8_t* q, const float* scale, const floa
   for (gi = 0; gi < ng; ++gi) {
     uint64_t lo = (uint64_t)gi * (uint64_t)G;
     uint64_t len = (n - lo < (uint64_t)G) ? n - lo : (uint64_t)G;
-    dequant_one_group(q + lo, scale[gi], k[gi], len, x + lo);
+    dequant_one_group(q + lo, scale[gi], k[gi], fmt_of((flags & COAT_REF_FLAG_E5M2) != 0), len, x + lo);
   }
 }
 
 void coat_ref_dequant_group(const uint8_t* q, const float* scale, const float* k,
-                            uint64_t n, int32_t G, float* x) {
+                            uint64_t n, int32_t G, uint32_t flags, float* x) {
   int64_t ng, gi;
   if (!x || !q || !scale || !k || G < 1 || n == 0) return;
   ng = (int64_t)((n + (uint64_t)G - 1) / (uint64_t)G);
@@ -168,7 +215,7 @@ void coat_ref_dequant_group(const uint8_t* q, const float* scale, const float* k
     uint64_t len = (n - lo < (uint64_t)G) ? n - lo : (uint64_t)G;
     double* tmp = (double*)malloc(len * sizeof(double));
     if (!tmp) continue;
-    dequant_one_group(q + lo, scale[gi], k[gi], len, tmp);
+    dequant_one_group(q + lo, scale[gi], k[gi], fmt_of((flags & COAT_REF_FLAG_E5M2) != 0), len, tmp);
     for (i = 0; i < len; ++i) x[lo + i] = (float)tmp[i];
     free(tmp);
   }
@@ -190,7 +237,8 @@ int coat_ref_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
   float k_min, k_max;
   int32_t G;
   int64_t ng, gi;
-  int failed = 0;
+  int failed = 0, expand_m, expand_v;
+  fmt_t fm, fv;
 
   if (!hp) return -1;
   if (n == 0) return 0;
@@ -204,6 +252,11 @@ int coat_ref_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
   k_min = hp->k_min; k_max = hp->k_max;
   resolve_k_bounds(&k_min, &k_max);
   ng = (int64_t)((n + (uint64_t)G - 1) / (uint64_t)G);
+  /* per-moment format and expansion switch: the 4 x 4 grid of Table 1 */
+  fm = fmt_of((hp->flags & COAT_REF_FLAG_M_E5M2) != 0);
+  fv = fmt_of((hp->flags & COAT_REF_FLAG_V_E5M2) != 0);
+  expand_m = (hp->flags & COAT_REF_FLAG_EXPAND) && !(hp->flags & COAT_REF_FLAG_M_PLAIN);
+  expand_v = (hp->flags & COAT_REF_FLAG_EXPAND) && !(hp->flags & COAT_REF_FLAG_V_PLAIN);
 
 #pragma omp parallel for schedule(static)
   for (gi = 0; gi < ng; ++gi) {
@@ -222,8 +275,8 @@ int coat_ref_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
     v = m + len; vt = mt + len;
 
     /* m_{t-1} = DQ(m^q), v_{t-1} = DQ(v^q), each followed by the inverse expansion */
-    dequant_one_group(m_q + lo, m_scale[gi], m_k[gi], len, m);
-    dequant_one_group(v_q + lo, v_scale[gi], v_k[gi], len, v);
+    dequant_one_group(m_q + lo, m_scale[gi], m_k[gi], fm, len, m);
+    dequant_one_group(v_q + lo, v_scale[gi], v_k[gi], fv, len, v);
 
     for (i = 0; i < len; ++i) {
       double g = bf16_to_double(grad_bf16[lo + i]);
@@ -239,8 +292,8 @@ int coat_ref_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
     }
 
     /* m^q_t, S = Q(m_t);  v^q_t, S = Q(v_t) */
-    quant_one_group(mt, len, hp->flags, k_min, k_max, m_q + lo, m_scale + gi, m_k + gi);
-    quant_one_group(vt, len, hp->flags, k_min, k_max, v_q + lo, v_scale + gi, v_k + gi);
+    quant_one_group(mt, len, expand_m, fm, k_min, k_max, m_q + lo, m_scale + gi, m_k + gi);
+    quant_one_group(vt, len, expand_v, fv, k_min, k_max, v_q + lo, v_scale + gi, v_k + gi);
     free(m); free(mt);
   }
   return failed ? -1 : 0;

@@ -29,11 +29,16 @@ typedef struct {
   float    weight_decay;  /* lambda, decoupled: enters as eta*lambda*w */
   int32_t  step;          /* t >= 1; bias corrections are 1 - beta^t */
   int32_t  group_size;    /* G >= 1: every G consecutive elements form a group (Sec. 3) */
-  uint32_t flags;         /* bit 0: dynamic range expansion on (off => k == 1) */
+  uint32_t flags;         /* COAT_REF_FLAG_*: expansion and, per moment, format / plain */
   float    k_min, k_max;  /* clamp applied to k; both 0 => defaults 2^-4 and 2^10 */
 } coat_ref_hparams;
 
-#define COAT_REF_FLAG_EXPAND 1u
+#define COAT_REF_FLAG_EXPAND  1u   /* dynamic range expansion on (off => k == 1) */
+#define COAT_REF_FLAG_M_E5M2  2u   /* first moment stored as E5M2 instead of E4M3 */
+#define COAT_REF_FLAG_E5M2    2u   /* the same bit for the standalone quantizer / dequantizer */
+#define COAT_REF_FLAG_V_E5M2  4u   /* second moment stored as E5M2 */
+#define COAT_REF_FLAG_M_PLAIN 8u   /* first moment: plain quantizer even when EXPAND is set */
+#define COAT_REF_FLAG_V_PLAIN 16u  /* second moment: plain quantizer even when EXPAND is set */
 
 /* OCP FP8 E4M3 ("FN"): 1-4-3 bits, bias 7, no infinity, 0x7F/0xFF are NaN, largest
  * finite 448 and smallest positive 2^-9 (the two constants Sec. 3 prints). */
@@ -41,24 +46,31 @@ double  coat_ref_e4m3_decode(uint8_t code);
 /* Round-to-nearest, ties to even mantissa; |q| > 448 saturates to +-448; NaN -> 0x7F. */
 uint8_t coat_ref_e4m3_encode(double q);
 
+/* OCP FP8 E5M2: 1-5-2 bits, bias 15, IEEE-like (0x7C is infinity, 0x7D..0x7F NaN), largest
+ * finite 57344 and smallest positive 2^-16 (Sec. 3).  Encode saturates to +-57344. */
+double  coat_ref_e5m2_decode(uint8_t code);
+uint8_t coat_ref_e5m2_encode(double q);
+
 /* Quantize n fp32 values in groups of G (last group may be short).
  * Per group (Sec. 3 quantizer, Sec. 4.1 Definition 1, Sec. 4.2):
  *   amax = max|x|, amin = min over NON-ZERO |x|, scale = fl32(amax/448),
  *   k = fl32(clamp(log2(448*512) / log2(amax/amin))) if expansion is on and amax != amin,
  *   else 1;  code = E4M3(sign(x) * 448 * (|x| / (448*scale))^k).
- * All-zero group: scale 0, k 1, codes 0.  scale and k have ceil(n/G) entries. */
+ * All-zero group: scale 0, k 1, codes 0.  scale and k have ceil(n/G) entries.
+ * With COAT_REF_FLAG_E5M2 the format constants are 57344 and 57344*65536 (Table 1's E5M2 rows). */
 void coat_ref_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags,
                           float k_min, float k_max,
                           uint8_t* q, float* scale, float* k);
 
 /* Inverse: x = sign(c) * (448*scale) * (|c|/448)^(1/k), c = decode(code)  (Sec. 4.2,
- * inverse expansion applied after the plain dequantizer of Sec. 3). */
+ * inverse expansion applied after the plain dequantizer of Sec. 3).  flags: only
+ * COAT_REF_FLAG_E5M2 is read (57344 then replaces 448). */
 void coat_ref_dequant_group(const uint8_t* q, const float* scale, const float* k,
-                            uint64_t n, int32_t G, float* x);
+                            uint64_t n, int32_t G, uint32_t flags, float* x);
 
 /* Same as coat_ref_dequant_group but keeps the fp64 result (used inside the step). */
 void coat_ref_dequant_group_f64(const uint8_t* q, const float* scale, const float* k,
-                                uint64_t n, int32_t G, double* x);
+                                uint64_t n, int32_t G, uint32_t flags, double* x);
 
 /* One fused optimizer step (Appendix A): dequantize m, v; update m, v, w; requantize.
  * w: fp32 master weights (in place).  grad_bf16: raw bf16 bit patterns.

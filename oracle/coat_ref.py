@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "coat_ref.c")
 _LIB = os.path.join(_HERE, "libcoat_ref.so")
 
-FLAG_EXPAND = 1
+FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN = 1, 2, 2, 4, 8, 16
 
 
 class HParams(ctypes.Structure):
@@ -70,9 +70,15 @@ def lib():
         L.coat_ref_quant_group.argtypes = [f32p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32,
                                            ctypes.c_float, ctypes.c_float, u8p, f32p, f32p]
         L.coat_ref_dequant_group.restype = None
-        L.coat_ref_dequant_group.argtypes = [u8p, f32p, f32p, ctypes.c_uint64, ctypes.c_int32, f32p]
+        L.coat_ref_dequant_group.argtypes = [u8p, f32p, f32p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32, f32p]
         L.coat_ref_dequant_group_f64.restype = None
-        L.coat_ref_dequant_group_f64.argtypes = [u8p, f32p, f32p, ctypes.c_uint64, ctypes.c_int32, f64p]
+        L.coat_ref_dequant_group_f64.argtypes = [u8p, f32p, f32p, ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32, f64p]
+        for name in ("coat_ref_e5m2_decode", "coat_ref_e5m2_encode"):
+            getattr(L, name)
+        L.coat_ref_e5m2_decode.restype = ctypes.c_double
+        L.coat_ref_e5m2_decode.argtypes = [ctypes.c_uint8]
+        L.coat_ref_e5m2_encode.restype = ctypes.c_uint8
+        L.coat_ref_e5m2_encode.argtypes = [ctypes.c_double]
         L.coat_ref_fp8_adamw_step.restype = ctypes.c_int
         L.coat_ref_fp8_adamw_step.argtypes = [f32p, u16p, u8p, f32p, f32p, u8p, f32p, f32p,
                                               ctypes.c_uint64, ctypes.POINTER(HParams)]
@@ -103,7 +109,16 @@ def e4m3_encode(q: float) -> int:
     return int(lib().coat_ref_e4m3_encode(float(q)))
 
 
-def quant_group(x: np.ndarray, G: int, expand: bool = True, k_min: float = 0.0, k_max: float = 0.0):
+def e5m2_decode(code: int) -> float:
+    return float(lib().coat_ref_e5m2_decode(int(code) & 0xFF))
+
+
+def e5m2_encode(q: float) -> int:
+    return int(lib().coat_ref_e5m2_encode(float(q)))
+
+
+def quant_group(x: np.ndarray, G: int, expand: bool = True, k_min: float = 0.0, k_max: float = 0.0,
+                e5m2: bool = False):
     """x: fp32 array (flattened).  Returns (codes u8 [n], scale f32 [ng], k f32 [ng])."""
     x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
     n = x.size
@@ -113,14 +128,16 @@ def quant_group(x: np.ndarray, G: int, expand: bool = True, k_min: float = 0.0, 
     k = np.ones(ng, dtype=np.float32)
     if n:
         lib().coat_ref_quant_group(_ptr(x, np.float32, ctypes.c_float), n, G,
-                                   FLAG_EXPAND if expand else 0, k_min, k_max,
+                                   (FLAG_EXPAND if expand else 0) | (FLAG_E5M2 if e5m2 else 0), k_min, k_max,
                                    _ptr(q, np.uint8, ctypes.c_uint8),
                                    _ptr(scale, np.float32, ctypes.c_float),
                                    _ptr(k, np.float32, ctypes.c_float))
     return q, scale, k
 
 
-def dequant_group(q: np.ndarray, scale: np.ndarray, k: np.ndarray, G: int, f64: bool = False):
+def dequant_group(q: np.ndarray, scale: np.ndarray, k: np.ndarray, G: int, f64: bool = False,
+                  e5m2: bool = False):
+    flags = FLAG_E5M2 if e5m2 else 0
     q = np.ascontiguousarray(q, dtype=np.uint8).reshape(-1)
     scale = np.ascontiguousarray(scale, dtype=np.float32).reshape(-1)
     k = np.ascontiguousarray(k, dtype=np.float32).reshape(-1)
@@ -131,22 +148,28 @@ def dequant_group(q: np.ndarray, scale: np.ndarray, k: np.ndarray, G: int, f64: 
         if n:
             lib().coat_ref_dequant_group_f64(_ptr(q, np.uint8, ctypes.c_uint8),
                                              _ptr(scale, np.float32, ctypes.c_float),
-                                             _ptr(k, np.float32, ctypes.c_float), n, G,
+                                             _ptr(k, np.float32, ctypes.c_float), n, G, flags,
                                              _ptr(x, np.float64, ctypes.c_double))
         return x
     x = np.zeros(n, dtype=np.float32)
     if n:
         lib().coat_ref_dequant_group(_ptr(q, np.uint8, ctypes.c_uint8),
                                      _ptr(scale, np.float32, ctypes.c_float),
-                                     _ptr(k, np.float32, ctypes.c_float), n, G,
+                                     _ptr(k, np.float32, ctypes.c_float), n, G, flags,
                                      _ptr(x, np.float32, ctypes.c_float))
     return x
 
 
+def step_flags(expand=True, m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False) -> int:
+    return ((FLAG_EXPAND if expand else 0) | (FLAG_M_E5M2 if m_e5m2 else 0) | (FLAG_V_E5M2 if v_e5m2 else 0)
+            | (FLAG_M_PLAIN if m_plain else 0) | (FLAG_V_PLAIN if v_plain else 0))
+
+
 def make_hparams(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1,
-                 group_size=128, expand=True, k_min=0.0, k_max=0.0) -> HParams:
+                 group_size=128, expand=True, k_min=0.0, k_max=0.0,
+                 m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False) -> HParams:
     return HParams(lr, beta1, beta2, eps, weight_decay, int(step), int(group_size),
-                   FLAG_EXPAND if expand else 0, k_min, k_max)
+                   step_flags(expand, m_e5m2, v_e5m2, m_plain, v_plain), k_min, k_max)
 
 
 def fp8_adamw_step(w, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, hp: HParams) -> int:

@@ -1,0 +1,158 @@
+"""Pins for the oracle's E5M2 codec and for the per-moment format / expansion grid of the
+paper's Table 1 (first and second moment each in {E4M3, E4M3+Expand, E5M2, E5M2+Expand}).
+No GPU needed."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+from test_oracle_codec import golden
+
+HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+GRID = list(itertools.product([False, True], [False, True], [False, True], [False, True]))  # m_e5m2, m_plain, v_e5m2, v_plain
+
+
+def lib_table():
+    return torch.arange(256, dtype=torch.uint8).view(torch.float8_e5m2).to(torch.float64).numpy()
+
+
+def test_e5m2_decode_constants_and_library(ref):
+    g = golden()
+    tab = lib_table()
+    finite_pos = []
+    for c in range(256):
+        d = ref.e5m2_decode(c)
+        if math.isnan(tab[c]):
+            assert math.isnan(d)
+        else:
+            assert d == tab[c] and math.copysign(1.0, d) == (-1.0 if c & 0x80 else 1.0)
+            if 0 < c < 0x7C:
+                finite_pos.append(d)
+    assert min(finite_pos) == g["delta_min_e5m2"] == 2.0 ** -16
+    assert max(finite_pos) == g["delta_max_e5m2"] == 57344.0
+    assert ref.e5m2_decode(0x7C) == math.inf and ref.e5m2_decode(0xFC) == -math.inf
+    # bit fields: 1-5-2, bias 15, subnormals at exponent field 0
+    for c in range(0, 0x7C):
+        e, m = (c >> 2) & 31, c & 3
+        assert ref.e5m2_decode(c) == ((m / 4.0) * 2.0 ** -14 if e == 0 else (1 + m / 4.0) * 2.0 ** (e - 15))
+
+
+def test_e5m2_encode_brute_force_midpoints_saturation(ref):
+    vals = [ref.e5m2_decode(c) for c in range(0, 0x7C)]
+    for c in range(0, 0x7C):
+        assert ref.e5m2_encode(vals[c]) == c and ref.e5m2_encode(-vals[c]) == (c | 0x80 if c else 0x80)
+    for c in range(0, 0x7B):
+        mid = (vals[c] + vals[c + 1]) / 2.0
+        even = c if c % 2 == 0 else c + 1
+        assert ref.e5m2_encode(mid) == even
+        assert ref.e5m2_encode(math.nextafter(mid, 0.0)) == c
+        assert ref.e5m2_encode(math.nextafter(mid, 1e9)) == c + 1
+    for q in (57344.0, 60000.0, 61440.0, 1e9, math.inf):
+        assert ref.e5m2_encode(q) == 0x7B and ref.e5m2_encode(-q) == 0xFB
+    assert ref.e5m2_encode(float("nan")) & 0x7F > 0x7C
+    rng = np.random.default_rng(0)
+    xs = np.exp(rng.uniform(np.log(2.0 ** -18), np.log(57344.0), 3000)) * rng.choice([-1.0, 1.0], 3000)
+    tab = np.array(vals)
+    for q in xs:
+        d = np.abs(tab - abs(q))
+        best = np.flatnonzero(d == d.min())
+        want = best[0] if len(best) == 1 or best[0] % 2 == 0 else best[1]
+        assert ref.e5m2_encode(float(q)) == (want | (0x80 if q < 0 else 0))
+
+
+def test_e5m2_encode_vs_library_cast(ref):
+    rng = np.random.default_rng(1)
+    xs = (np.exp(rng.uniform(np.log(2.0 ** -17), np.log(57344.0), 100000)) * rng.choice([-1.0, 1.0], 100000)).astype(np.float32)
+    lib = torch.from_numpy(xs).to(torch.float8_e5m2).view(torch.uint8).numpy()
+    mine = np.array([ref.e5m2_encode(float(x)) for x in xs], dtype=np.uint8)
+    assert np.array_equal(mine, lib)
+
+
+@pytest.mark.parametrize("G", [2, 128])
+def test_e5m2_quantizer_plain_and_range_identity(ref, G):
+    x = (np.random.default_rng(2).standard_normal(64 * G) * 1e-3).astype(np.float32)
+    tab = lib_table()
+    # plain: S = max|X| / 57344, X_fp8 = round(X / S)   (Sec. 3 with the E5M2 maximum)
+    q, s, k = ref.quant_group(x, G, expand=False, e5m2=True)
+    ax = np.abs(x.astype(np.float64)).reshape(-1, G)
+    assert np.array_equal(s, (ax.max(1) / 57344.0).astype(np.float32)) and np.all(k == 1)
+    scaled = (x.astype(np.float64).reshape(-1, G) / s.astype(np.float64)[:, None]).reshape(-1).astype(np.float32)
+    lib = torch.from_numpy(scaled).to(torch.float8_e5m2).view(torch.uint8).numpy()
+    assert np.array_equal(q, lib)
+    xh = ref.dequant_group(q, s, k, G, f64=True, e5m2=True)
+    assert np.allclose(xh, tab[q] * np.repeat(s.astype(np.float64), G), rtol=1e-12)
+    # expanded: (R_X)^k = R_E5M2 = 57344 * 65536; max -> 57344, min -> 2^-16
+    q, s, k = ref.quant_group(x, G, e5m2=True)
+    mag = np.abs(tab[q]).reshape(-1, G)
+    rows = np.arange(mag.shape[0])
+    free = k < 1024.0
+    assert np.all(mag[rows, ax.argmax(1)] == 57344.0)
+    assert np.all(mag[rows, ax.argmin(1)][free] == 2.0 ** -16)
+    assert np.allclose(((ax.max(1) / ax.min(1)) ** k.astype(np.float64))[free], 57344.0 * 65536.0, rtol=4e-5)
+    xh = ref.dequant_group(q, s, k, G, f64=True, e5m2=True)
+    assert np.all(np.sign(xh) == np.sign(x))
+    # oddness and scale invariance hold for this format too
+    q2, s2, k2 = ref.quant_group(np.ldexp(-x, 5), G, e5m2=True)
+    assert np.array_equal(q2, q ^ 0x80) and np.array_equal(k2, k) and np.array_equal(s2, np.ldexp(s, 5))
+
+
+@pytest.mark.parametrize("m_e5m2,m_plain,v_e5m2,v_plain", GRID)
+def test_step_grid_is_dequant_update_quant(ref, m_e5m2, m_plain, v_e5m2, v_plain):
+    # every cell of Table 1's grid: the step equals the separately pinned dequantizer / quantizer of
+    # each moment's own format and expansion switch around the AdamW update written here in fp64
+    n, G, t = 8 * 128 + 50, 128, 4
+    w0 = S.weights(n, seed=3)
+    g_bits = S.grads_normal(n, seed=3, step=t, outlier_frac=0.1, G=G)
+    # a start state valid for the chosen formats: quantize synthetic moments with the oracle's quantizer
+    rng = np.random.default_rng(5)
+    m0 = (rng.standard_normal(n) * 2e-4).astype(np.float32)
+    v0 = ((rng.standard_normal(n) * 1e-3) ** 2 * 0.3).astype(np.float32)
+    mq, ms, mk = ref.quant_group(m0, G, expand=not m_plain, e5m2=m_e5m2)
+    vq, vs, vk = ref.quant_group(v0, G, expand=not v_plain, e5m2=v_e5m2)
+    st = dict(m_q=mq.copy(), m_scale=ms.copy(), m_k=mk.copy(), v_q=vq.copy(), v_scale=vs.copy(), v_k=vk.copy())
+    w = w0.copy()
+    hp = ref.make_hparams(step=t, group_size=G, m_e5m2=m_e5m2, v_e5m2=v_e5m2, m_plain=m_plain, v_plain=v_plain, **HP)
+    assert ref.fp8_adamw_step(w, g_bits, st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"], hp) == 0
+    m = ref.dequant_group(mq, ms, mk, G, f64=True, e5m2=m_e5m2)
+    v = ref.dequant_group(vq, vs, vk, G, f64=True, e5m2=v_e5m2)
+    g = S.bf16_bits_to_f32(g_bits).astype(np.float64)
+    b1, b2, lr, eps, wd = (float(np.float32(HP[k_])) for k_ in ("beta1", "beta2", "lr", "eps", "weight_decay"))
+    m_t = b1 * m + (1 - b1) * g
+    v_t = b2 * v + (1 - b2) * g * g
+    w_exp = w0 - lr * ((m_t / (1 - b1 ** t)) / (np.sqrt(v_t / (1 - b2 ** t)) + eps) + wd * w0)
+    assert np.array_equal(w, w_exp.astype(np.float32))
+    mq2, ms2, mk2 = ref.quant_group(m_t.astype(np.float32), G, expand=not m_plain, e5m2=m_e5m2)
+    vq2, vs2, vk2 = ref.quant_group(v_t.astype(np.float32), G, expand=not v_plain, e5m2=v_e5m2)
+    assert np.array_equal(st["m_q"], mq2) and np.array_equal(st["m_scale"], ms2) and np.array_equal(st["m_k"], mk2)
+    assert np.array_equal(st["v_q"], vq2) and np.array_equal(st["v_scale"], vs2) and np.array_equal(st["v_k"], vk2)
+    if m_plain:
+        assert np.all(mk2 == 1)
+    if v_plain:
+        assert np.all(vk2 == 1)
+
+
+def test_table1_directions_on_synthetic_moments(ref):
+    # Table 1 reports the MSE of m / sqrt(v) for the 4 x 4 grid on the paper's real optimizer states
+    # (values: parity unpinned).  On synthetic moments with the small dynamic ranges Sec. 4.1
+    # describes, the directions it shows are checked: expansion lowers the error for either format
+    # and either moment, and without expansion E4M3 beats E5M2 for the first moment.
+    rng = np.random.default_rng(7)
+    n, G = 256 * 128, 128
+    m = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    v = (1e-6 * np.exp(rng.uniform(0, math.log(8.0), n))).astype(np.float32)
+    exact = m.astype(np.float64) / np.sqrt(v.astype(np.float64))
+
+    def mse(m_e5m2, m_plain, v_e5m2, v_plain):
+        mh = ref.dequant_group(*ref.quant_group(m, G, expand=not m_plain, e5m2=m_e5m2), G, f64=True, e5m2=m_e5m2)
+        vh = ref.dequant_group(*ref.quant_group(v, G, expand=not v_plain, e5m2=v_e5m2), G, f64=True, e5m2=v_e5m2)
+        return float(np.mean((mh / np.sqrt(vh) - exact) ** 2))
+
+    for fm, fv in itertools.product([False, True], repeat=2):
+        assert mse(fm, False, fv, False) < mse(fm, True, fv, True)          # both expanded < both plain
+        assert mse(fm, False, fv, True) < mse(fm, True, fv, True)           # expanding m alone helps
+        assert mse(fm, True, fv, False) < mse(fm, True, fv, True)           # expanding v alone helps
+    assert mse(False, True, False, True) < mse(True, True, False, True)     # plain: E4M3 m beats E5M2 m
+    assert mse(False, False, False, False) < mse(False, True, False, True) / 1.3
