@@ -117,6 +117,10 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=12)
     ap.add_argument("--op", default="step", choices=["step", "quant", "dequant"],
                     help="step: the fused optimizer step (the metric); quant / dequant: its two halves alone")
+    ap.add_argument("--m-e5m2", action="store_true", help="first moment in E5M2 (a cell of the paper's Table 1)")
+    ap.add_argument("--v-e5m2", action="store_true", help="second moment in E5M2")
+    ap.add_argument("--m-plain", action="store_true", help="first moment without dynamic range expansion")
+    ap.add_argument("--v-plain", action="store_true", help="second moment without dynamic range expansion")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (scales the rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -163,7 +167,8 @@ def main():
     torch.cuda.synchronize()
 
     def step(t):
-        hp = C.make_hparams(step=t, group_size=G, **HP)
+        hp = C.make_hparams(step=t, group_size=G, m_e5m2=args.m_e5m2, v_e5m2=args.v_e5m2,
+                            m_plain=args.m_plain, v_plain=args.v_plain, **HP)
         C.coat_fp8_adamw_step(w, grads[t & 1], st["m_q"], st["m_scale"], st["m_k"],
                               st["v_q"], st["v_scale"], st["v_k"], hp)
 
@@ -190,6 +195,7 @@ def main():
     if not finite:
         sys.exit("bench.py: non-finite weights after the timed steps")
 
+    generic = args.m_e5m2 or args.v_e5m2 or args.m_plain or args.v_plain
     ms_per_step = wall / args.steps * 1e3
     value = n * args.steps / wall
     algo_bytes = bytes_per_param(G) * n
@@ -210,12 +216,15 @@ def main():
         "config": {"workload": "%s: %s, %d params, G=%d, grads %s" % (
             args.workload, {"cfg1": "one 1024x1024 weight", "cfg2": "one Llama-2-7B decoder layer",
                             "cfg3": "full Llama-2-7B-sized parameter set", "cfg5": "full Llama-2-13B-sized parameter set"}[
-                args.workload], n, G, args.grads),
+                args.workload], n, G, args.grads) + (
+                    ", m %s%s, v %s%s" % ("E5M2" if args.m_e5m2 else "E4M3", "" if args.m_plain else "+expand",
+                                            "E5M2" if args.v_e5m2 else "E4M3", "" if args.v_plain else "+expand")
+                    if generic else ""),
             "params": n, "group_size": G, "hbm_gbs": achieved, "hbm_frac_of_peak": achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_profile_traffic(args.workload, G),
                      "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_ms": avg_launch_s * 1e3,
-                     "kernel": "adamw_step_kernel<%d, expand>" % G},
+                     "kernel": "adamw_step_kernel<%d, %s>" % (G, "generic" if generic else "default")},
     }
     # free the device buffers before the host-side baseline allocates its own arrays
     del w, st, grads

@@ -16,8 +16,10 @@
  *   - Return value: COAT_OK (0) or a negative COAT_ERR_* code.  Arguments are validated on
  *     the host before anything is launched, so a failing call has touched no memory.
  *     n == 0 is a successful no-op.  No exception or abort crosses this boundary.
- *   - FP8 format: OCP E4M3 (1-4-3 bits, bias 7, max 448, min subnormal 2^-9, no infinity;
- *     0x7F/0xFF are NaN and are never produced from finite inputs).
+ *   - FP8 formats: OCP E4M3 (1-4-3 bits, bias 7, max 448, min subnormal 2^-9, no infinity;
+ *     0x7F/0xFF are NaN) by default, OCP E5M2 (1-5-2 bits, bias 15, max 57344, min subnormal
+ *     2^-16, 0x7C infinity) per moment on request.  Non-finite codes are never produced from
+ *     finite inputs.
  */
 #ifndef COAT_H
 #define COAT_H
@@ -33,11 +35,19 @@ extern "C" {
 #define COAT_ERR_ALIGN    -2  /* a base pointer is not 16-byte aligned */
 #define COAT_ERR_GROUP    -3  /* group size not one of 32, 64, 128, 256, 512 */
 #define COAT_ERR_STEP     -4  /* step < 1 */
-#define COAT_ERR_HPARAM   -5  /* non-finite or out-of-domain hyper-parameter */
+#define COAT_ERR_HPARAM   -5  /* non-finite or out-of-domain hyper-parameter, unknown flag bit */
 #define COAT_ERR_LAUNCH   -6  /* the HIP runtime refused the launch */
 #define COAT_ERR_SIZE     -7  /* n exceeds what the launch geometry supports */
 
-#define COAT_FLAG_EXPAND  1u  /* bit 0: dynamic range expansion on (off => k == 1) */
+/* Flags.  The per-moment bits select a cell of the paper's Table 1 (each moment stored as E4M3 or
+ * E5M2, with or without the expansion); the default (COAT_FLAG_EXPAND alone) is the method as
+ * the paper runs it and has its own tuned kernel. */
+#define COAT_FLAG_EXPAND   1u  /* dynamic range expansion on (off => k == 1 for both moments) */
+#define COAT_FLAG_M_E5M2   2u  /* first moment stored as OCP E5M2 instead of E4M3 */
+#define COAT_FLAG_E5M2     2u  /* the same bit, for coat_quant_group / coat_dequant_group */
+#define COAT_FLAG_V_E5M2   4u  /* second moment stored as OCP E5M2 */
+#define COAT_FLAG_M_PLAIN  8u  /* first moment without expansion even when COAT_FLAG_EXPAND is set */
+#define COAT_FLAG_V_PLAIN 16u  /* second moment without expansion even when COAT_FLAG_EXPAND is set */
 
 /* Hyper-parameters of one step: symbols of Sec. 3, Eq. (1). */
 typedef struct {
@@ -48,7 +58,8 @@ typedef struct {
   int32_t  step;          /* t >= 1; bias corrections 1 - beta^t are formed on the host in fp64 */
   int32_t  group_size;    /* G in {32, 64, 128, 256, 512} */
   uint32_t flags;         /* COAT_FLAG_* */
-  float    k_min, k_max;  /* clamp applied to the expansion exponent k; 0,0 => 2^-4 and 2^10 */
+  float    k_min, k_max;  /* clamp applied to the expansion exponent k; 0,0 => 2^-4 and 2^10;
+                             otherwise 2^-6 <= k_min <= k_max <= 2^16 */
 } coat_adamw_hparams;
 
 /*
@@ -66,6 +77,9 @@ typedef struct {
  * grad_bf16  [n]   bf16 gradients (raw 16-bit patterns), read only.
  * m_q, v_q   [n]   E4M3 codes of the first and second moment, updated in place.
  * m_scale, m_k, v_scale, v_k  [ceil(n/G)]  fp32 per-group scale and exponent, in place.
+ * With COAT_FLAG_*_E5M2 the constants 448 and 448*512 become 57344 and 57344*65536 for that
+ * moment; a moment stored without expansion uses the plain quantizer of Sec. 3 (code =
+ * round(x/scale), x = scale*code), writes k = 1 and does not read k.
  * The valid start state (m0 = v0 = 0) is: all codes 0, scale 0, k 1.
  * Gradients that are NaN/Inf poison their own element of w and their own group's
  * moments; other groups are unaffected.  Moments that are fp32-subnormal are flushed.
@@ -79,6 +93,7 @@ int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
  * Per-group quantizer with dynamic range expansion (Sec. 3 quantizer Q applied to f(X),
  * Sec. 4.2): the second half of the step on its own.
  * x [n] fp32 in;  q [n] codes, scale/k [ceil(n/G)] out.  All-zero group: scale 0, k 1.
+ * flags: COAT_FLAG_EXPAND, COAT_FLAG_E5M2.
  */
 int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags,
                      float k_min, float k_max,
@@ -87,9 +102,12 @@ int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags,
 /*
  * Dequantizer followed by the inverse expansion (Sec. 3 DQ, Sec. 4.2 f^-1): the first half
  * of the step on its own.  x = sign(c) * (448*scale) * (|c|/448)^(1/k), c = decode(code).
+ * The stored k is always honoured (it is 1 for codes written without expansion).
+ * flags: COAT_FLAG_E5M2 selects the format (57344 replaces 448); COAT_FLAG_EXPAND is accepted
+ * and ignored.
  */
 int coat_dequant_group(const uint8_t* q, const float* scale, const float* k,
-                       uint64_t n, int32_t G, float* x, void* hip_stream);
+                       uint64_t n, int32_t G, uint32_t flags, float* x, void* hip_stream);
 
 /* Human-readable text for a return code (static storage, never NULL). */
 const char* coat_strerror(int code);

@@ -1,8 +1,10 @@
 """MI355X-native FP8-state AdamW step of COAT (arxiv 2410.19313): HIP kernels behind a C ABI
 (include/coat.h) and this thin binding."""
-from .binding import (CoatError, HParams, FLAG_EXPAND, SUPPORTED_GROUP_SIZES, EXPORTS,
+from .binding import (CoatError, HParams, FLAG_EXPAND, FLAG_E5M2, FLAG_M_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN,
+                      step_flags, SUPPORTED_GROUP_SIZES, EXPORTS,
                       make_hparams, n_groups, strerror, lib,
                       coat_fp8_adamw_step, coat_quant_group, coat_dequant_group)
 
-__all__ = ["CoatError", "HParams", "FLAG_EXPAND", "SUPPORTED_GROUP_SIZES", "EXPORTS", "make_hparams",
+__all__ = ["CoatError", "HParams", "FLAG_EXPAND", "FLAG_E5M2", "FLAG_M_E5M2", "FLAG_V_E5M2", "FLAG_M_PLAIN",
+           "FLAG_V_PLAIN", "step_flags", "SUPPORTED_GROUP_SIZES", "EXPORTS", "make_hparams",
            "n_groups", "strerror", "lib", "coat_fp8_adamw_step", "coat_quant_group", "coat_dequant_group"]

@@ -12,7 +12,7 @@ import os
 
 from . import build as _build
 
-FLAG_EXPAND = 1
+FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN = 1, 2, 2, 4, 8, 16
 SUPPORTED_GROUP_SIZES = (32, 64, 128, 256, 512)
 
 EXPORTS = ("coat_fp8_adamw_step", "coat_quant_group", "coat_dequant_group", "coat_strerror", "coat_version")
@@ -41,10 +41,16 @@ class HParams(ctypes.Structure):
     ]
 
 
+def step_flags(expand=True, m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False) -> int:
+    return ((FLAG_EXPAND if expand else 0) | (FLAG_M_E5M2 if m_e5m2 else 0) | (FLAG_V_E5M2 if v_e5m2 else 0)
+            | (FLAG_M_PLAIN if m_plain else 0) | (FLAG_V_PLAIN if v_plain else 0))
+
+
 def make_hparams(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1,
-                 group_size=128, expand=True, k_min=0.0, k_max=0.0) -> HParams:
+                 group_size=128, expand=True, k_min=0.0, k_max=0.0,
+                 m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False) -> HParams:
     return HParams(lr, beta1, beta2, eps, weight_decay, int(step), int(group_size),
-                   FLAG_EXPAND if expand else 0, k_min, k_max)
+                   step_flags(expand, m_e5m2, v_e5m2, m_plain, v_plain), k_min, k_max)
 
 
 _lib = None
@@ -65,7 +71,7 @@ def lib():
         L.coat_quant_group.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32,
                                        ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
         L.coat_dequant_group.restype = ctypes.c_int
-        L.coat_dequant_group.argtypes = [vp, vp, vp, ctypes.c_uint64, ctypes.c_int32, vp, vp]
+        L.coat_dequant_group.argtypes = [vp, vp, vp, ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32, vp, vp]
         L.coat_strerror.restype = ctypes.c_char_p
         L.coat_strerror.argtypes = [ctypes.c_int]
         L.coat_version.restype = ctypes.c_int
@@ -119,7 +125,7 @@ def coat_fp8_adamw_step(w, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, hp: 
 
 
 def coat_quant_group(x, G: int, expand: bool = True, k_min: float = 0.0, k_max: float = 0.0,
-                     out=None):
+                     out=None, e5m2: bool = False):
     """x fp32 [n] -> (codes uint8 [n], scale fp32 [ng], k fp32 [ng]) written on the device."""
     import torch
     n = x.numel()
@@ -129,14 +135,15 @@ def coat_quant_group(x, G: int, expand: bool = True, k_min: float = 0.0, k_max: 
                torch.empty(ng, dtype=torch.float32, device=x.device),
                torch.empty(ng, dtype=torch.float32, device=x.device))
     q, scale, k = out
-    _check(lib().coat_quant_group(_dev_ptr(x, torch.float32), n, G, FLAG_EXPAND if expand else 0,
+    _check(lib().coat_quant_group(_dev_ptr(x, torch.float32), n, G,
+                                  (FLAG_EXPAND if expand else 0) | (FLAG_E5M2 if e5m2 else 0),
                                   k_min, k_max, _dev_ptr(q, torch.uint8, n),
                                   _dev_ptr(scale, torch.float32, ng), _dev_ptr(k, torch.float32, ng),
                                   _stream()))
     return q, scale, k
 
 
-def coat_dequant_group(q, scale, k, G: int, out=None):
+def coat_dequant_group(q, scale, k, G: int, out=None, e5m2: bool = False):
     """codes uint8 [n] + per-group scale, k -> fp32 [n] on the device."""
     import torch
     n = q.numel()
@@ -144,6 +151,6 @@ def coat_dequant_group(q, scale, k, G: int, out=None):
     if out is None:
         out = torch.empty(n, dtype=torch.float32, device=q.device)
     _check(lib().coat_dequant_group(_dev_ptr(q, torch.uint8), _dev_ptr(scale, torch.float32, ng),
-                                    _dev_ptr(k, torch.float32, ng), n, G,
+                                    _dev_ptr(k, torch.float32, ng), n, G, FLAG_E5M2 if e5m2 else 0,
                                     _dev_ptr(out, torch.float32, n), _stream()))
     return out

@@ -1,17 +1,20 @@
 // coat_kernels.hip -- gfx950 kernels and C ABI of the FP8-state AdamW step of COAT
 // (arxiv 2410.19313: Sec. 3 quantizer and update rule, Sec. 4.2 dynamic range expansion,
-// Appendix A step order).  Hand-written for CDNA4: 64-wide wavefronts, every lane owns 16
-// consecutive elements (16-byte loads of the code bytes, 32 B of bf16 gradient, 64 B of fp32
-// weight), a quantization group of G elements is G/16 adjacent lanes and its max/min are
-// DPP butterflies inside the wavefront.  No LDS traffic except a 1 KiB lookup table, no
-// atomics, no inter-wave communication: each group is owned by exactly one wavefront.
+// Appendix A step order, Table 1 format grid).  Hand-written for CDNA4:
+//   * 64-wide wavefronts; every lane owns 16 consecutive elements, a quantization group of G
+//     elements is G/16 adjacent lanes and its max/min are DPP butterflies inside the wavefront;
+//   * every global load/store instruction of a wavefront covers one contiguous 1 KiB row and is
+//     issued as a streaming access; per-wavefront LDS tiles convert between those rows and the
+//     16-elements-per-lane layout the arithmetic wants;
+//   * no atomics, no inter-wave communication: each group is owned by exactly one wavefront.
 //
-// Arithmetic layout (fp32 throughout; transcendental ops are the hardware log2/exp2):
-//   inverse expansion  |c/448|^(1/k) = exp2( log2|c/448| * (1/k) ), log2|c/448| from a table
-//                      of the 127 code magnitudes;
-//   expansion          448 * (|x|/a)^k = 448 * exp2( k * log2(|x| * (1/a)) ), the logarithm
-//                      is taken of the RATIO so that its magnitude stays below 17.81;
-//   conversion         native fp32 -> OCP E4M3 pack instruction (round to nearest even).
+// Arithmetic (fp32 throughout; transcendentals are the hardware log2/exp2/rcp/sqrt), with fmax
+// the largest finite value of the moment's FP8 format (448 for E4M3, 57344 for E5M2):
+//   inverse expansion  |c/fmax|^(1/k) = exp2( log2|c/fmax| * (1/k) ), the logarithm from a table
+//                      of the 127 code magnitudes (compensated for the first moment);
+//   expansion          fmax * (|x|/a)^k = exp2( k * log2(|x| * (1/a)) + log2 fmax ), the logarithm
+//                      taken of the RATIO so that its magnitude stays below log2(range)/k;
+//   conversion         native fp32 -> OCP FP8 pack instructions (round to nearest even).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -28,84 +31,40 @@ constexpr int kWavesPerBlock = COAT_WPB;
 constexpr int kBlock = kWave * kWavesPerBlock;
 constexpr int kChunk = kWave * kEPL;      // elements one wavefront handles per iteration
 
-constexpr float kE4M3Max = 448.0f;
-constexpr float kLog2Range = 17.807354922057606f;   // log2(448 * 512), Sec. 4.1
-constexpr float kLog2E4M3Max = 8.807354922057604f;  // log2(448)
-
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// log2(|decode(c)| / 448) for the 128 magnitude codes of OCP E4M3 as an unevaluated sum
-// hi + lo of two fp32 numbers (hi = the fp32 nearest to the logarithm, lo = what is left).
-// Code 0 is zero: a huge negative finite logarithm makes exp2 return exactly 0 for every
-// admissible exponent k while keeping the correction terms finite.  Code 0x7F is NaN.
-struct Log2Entry { float hi, lo; };
-__device__ const Log2Entry kLog2CodeOverMax[128] = {
-    {-1.0e30f, 0.0f}, {-0x1.1ceaecp+4f, -0x1.fd501p-21f},
-    {-0x1.0ceaecp+4f, -0x1.fd501p-21f}, {-0x1.038eecp+4f, 0x1.49ef6ap-21f},
-    {-0x1.f9d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.ef889ep+3f, 0x1.44b3e8p-24f},
-    {-0x1.e71dd6p+3f, -0x1.6c212cp-22f}, {-0x1.ep+3f, 0x0.0p+0f},
-    {-0x1.d9d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.d465d4p+3f, 0x1.225dcap-22f},
-    {-0x1.cf889ep+3f, 0x1.44b3e8p-24f}, {-0x1.cb223p+3f, -0x1.a6d376p-26f},
-    {-0x1.c71dd6p+3f, -0x1.6c212cp-22f}, {-0x1.c36bdap+3f, 0x1.21eefp-22f},
-    {-0x1.cp+3f, 0x0.0p+0f}, {-0x1.bcd09ap+3f, -0x1.20541p-22f},
-    {-0x1.b9d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.b465d4p+3f, 0x1.225dcap-22f},
-    {-0x1.af889ep+3f, 0x1.44b3e8p-24f}, {-0x1.ab223p+3f, -0x1.a6d376p-26f},
-    {-0x1.a71dd6p+3f, -0x1.6c212cp-22f}, {-0x1.a36bdap+3f, 0x1.21eefp-22f},
-    {-0x1.ap+3f, 0x0.0p+0f}, {-0x1.9cd09ap+3f, -0x1.20541p-22f},
-    {-0x1.99d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.9465d4p+3f, 0x1.225dcap-22f},
-    {-0x1.8f889ep+3f, 0x1.44b3e8p-24f}, {-0x1.8b223p+3f, -0x1.a6d376p-26f},
-    {-0x1.871dd6p+3f, -0x1.6c212cp-22f}, {-0x1.836bdap+3f, 0x1.21eefp-22f},
-    {-0x1.8p+3f, 0x0.0p+0f}, {-0x1.7cd09ap+3f, -0x1.20541p-22f},
-    {-0x1.79d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.7465d4p+3f, 0x1.225dcap-22f},
-    {-0x1.6f889ep+3f, 0x1.44b3e8p-24f}, {-0x1.6b223p+3f, -0x1.a6d376p-26f},
-    {-0x1.671dd6p+3f, -0x1.6c212cp-22f}, {-0x1.636bdap+3f, 0x1.21eefp-22f},
-    {-0x1.6p+3f, 0x0.0p+0f}, {-0x1.5cd09ap+3f, -0x1.20541p-22f},
-    {-0x1.59d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.5465d4p+3f, 0x1.225dcap-22f},
-    {-0x1.4f889ep+3f, 0x1.44b3e8p-24f}, {-0x1.4b223p+3f, -0x1.a6d376p-26f},
-    {-0x1.471dd6p+3f, -0x1.6c212cp-22f}, {-0x1.436bdap+3f, 0x1.21eefp-22f},
-    {-0x1.4p+3f, 0x0.0p+0f}, {-0x1.3cd09ap+3f, -0x1.20541p-22f},
-    {-0x1.39d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.3465d4p+3f, 0x1.225dcap-22f},
-    {-0x1.2f889ep+3f, 0x1.44b3e8p-24f}, {-0x1.2b223p+3f, -0x1.a6d376p-26f},
-    {-0x1.271dd6p+3f, -0x1.6c212cp-22f}, {-0x1.236bdap+3f, 0x1.21eefp-22f},
-    {-0x1.2p+3f, 0x0.0p+0f}, {-0x1.1cd09ap+3f, -0x1.20541p-22f},
-    {-0x1.19d5dap+3f, 0x1.57f7a6p-28f}, {-0x1.1465d4p+3f, 0x1.225dcap-22f},
-    {-0x1.0f889ep+3f, 0x1.44b3e8p-24f}, {-0x1.0b223p+3f, -0x1.a6d376p-26f},
-    {-0x1.071dd6p+3f, -0x1.6c212cp-22f}, {-0x1.036bdap+3f, 0x1.21eefp-22f},
-    {-0x1.0p+3f, 0x0.0p+0f}, {-0x1.f9a136p+2f, 0x1.bf57ep-23f},
-    {-0x1.f3abb4p+2f, 0x1.57f7a6p-28f}, {-0x1.e8cba6p+2f, -0x1.bb446cp-23f},
-    {-0x1.df113cp+2f, 0x1.44b3e8p-24f}, {-0x1.d6446p+2f, -0x1.a6d376p-26f},
-    {-0x1.ce3baep+2f, 0x1.27bda8p-23f}, {-0x1.c6d7b2p+2f, -0x1.bc222p-23f},
-    {-0x1.cp+2f, 0x0.0p+0f}, {-0x1.b9a136p+2f, 0x1.bf57ep-23f},
-    {-0x1.b3abb4p+2f, 0x1.57f7a6p-28f}, {-0x1.a8cba6p+2f, -0x1.bb446cp-23f},
-    {-0x1.9f113cp+2f, 0x1.44b3e8p-24f}, {-0x1.96446p+2f, -0x1.a6d376p-26f},
-    {-0x1.8e3baep+2f, 0x1.27bda8p-23f}, {-0x1.86d7b2p+2f, -0x1.bc222p-23f},
-    {-0x1.8p+2f, 0x0.0p+0f}, {-0x1.79a136p+2f, 0x1.bf57ep-23f},
-    {-0x1.73abb4p+2f, 0x1.57f7a6p-28f}, {-0x1.68cba6p+2f, -0x1.bb446cp-23f},
-    {-0x1.5f113cp+2f, 0x1.44b3e8p-24f}, {-0x1.56446p+2f, -0x1.a6d376p-26f},
-    {-0x1.4e3baep+2f, 0x1.27bda8p-23f}, {-0x1.46d7b2p+2f, -0x1.bc222p-23f},
-    {-0x1.4p+2f, 0x0.0p+0f}, {-0x1.39a136p+2f, 0x1.bf57ep-23f},
-    {-0x1.33abb4p+2f, 0x1.57f7a6p-28f}, {-0x1.28cba6p+2f, -0x1.bb446cp-23f},
-    {-0x1.1f113cp+2f, 0x1.44b3e8p-24f}, {-0x1.16446p+2f, -0x1.a6d376p-26f},
-    {-0x1.0e3baep+2f, 0x1.27bda8p-23f}, {-0x1.06d7b2p+2f, -0x1.bc222p-23f},
-    {-0x1.0p+2f, 0x0.0p+0f}, {-0x1.f3426ap+1f, -0x1.02a082p-25f},
-    {-0x1.e75768p+1f, 0x1.57f7a6p-28f}, {-0x1.d1974ep+1f, 0x1.12ee4ep-25f},
-    {-0x1.be2278p+1f, 0x1.44b3e8p-24f}, {-0x1.ac88cp+1f, -0x1.a6d376p-26f},
-    {-0x1.9c775ap+1f, -0x1.b084bp-24f}, {-0x1.8daf66p+1f, 0x1.0f7782p-25f},
-    {-0x1.8p+1f, 0x0.0p+0f}, {-0x1.73426ap+1f, -0x1.02a082p-25f},
-    {-0x1.675768p+1f, 0x1.57f7a6p-28f}, {-0x1.51974ep+1f, 0x1.12ee4ep-25f},
-    {-0x1.3e2278p+1f, 0x1.44b3e8p-24f}, {-0x1.2c88cp+1f, -0x1.a6d376p-26f},
-    {-0x1.1c775ap+1f, -0x1.b084bp-24f}, {-0x1.0daf66p+1f, 0x1.0f7782p-25f},
-    {-0x1.0p+1f, 0x0.0p+0f}, {-0x1.e684d4p+0f, -0x1.02a082p-25f},
-    {-0x1.ceaedp+0f, 0x1.57f7a6p-28f}, {-0x1.a32e9cp+0f, 0x1.12ee4ep-25f},
-    {-0x1.7c44eep+0f, -0x1.76982ep-25f}, {-0x1.59118p+0f, -0x1.a6d376p-26f},
-    {-0x1.38eeb6p+0f, 0x1.3ded44p-26f}, {-0x1.1b5eccp+0f, 0x1.0f7782p-25f},
-    {-0x1.0p+0f, 0x0.0p+0f}, {-0x1.cd09aap-1f, 0x1.fabefcp-26f},
-    {-0x1.9d5dap-1f, 0x1.57f7a6p-28f}, {-0x1.465d36p-1f, -0x1.da2362p-26f},
-    {-0x1.f113bap-2f, -0x1.da60bcp-27f}, {-0x1.644602p-2f, 0x1.64b22ap-28f},
-    {-0x1.c775aep-3f, 0x1.ef6a1ep-29f}, {-0x1.b5ecb8p-4f, 0x1.eef03p-30f},
-    {0x0.0p+0f, 0x0.0p+0f}, {__builtin_nanf(""), 0.0f},
+#include "coat_tables.inc"
+
+// ---------------------------------------------------------------------------------------
+// Storage mode of one moment: FP8 format and whether the dynamic range expansion is applied
+// (the rows / columns of Table 1).  StaticMode folds at compile time (the default E4M3 + expansion
+// fast path); RuntimeMode carries the two switches as wavefront-uniform values, so one kernel per
+// group size serves the other fifteen combinations.
+// ---------------------------------------------------------------------------------------
+template <bool E5M2, bool EXPAND>
+struct StaticMode {
+  __device__ __forceinline__ bool e5m2() const { return E5M2; }
+  __device__ __forceinline__ bool expand() const { return EXPAND; }
 };
+struct RuntimeMode {
+  bool e5, ex;
+  __device__ __forceinline__ bool e5m2() const { return e5; }
+  __device__ __forceinline__ bool expand() const { return ex; }
+};
+typedef StaticMode<false, true> DefaultMode;
+
+template <class Mode> __device__ __forceinline__ float fmt_max(const Mode& md) { return md.e5m2() ? 57344.0f : 448.0f; }
+template <class Mode> __device__ __forceinline__ float fmt_inv_max(const Mode& md) {
+  return md.e5m2() ? 1.0f / 57344.0f : 1.0f / 448.0f;
+}
+// log2(fmax) and log2(fmax / smallest subnormal): 448 * 2^9 (Sec. 4.1) and 57344 * 2^16
+template <class Mode> __device__ __forceinline__ float fmt_log2_max(const Mode& md) {
+  return md.e5m2() ? 15.807354922057604f : 8.807354922057604f;
+}
+template <class Mode> __device__ __forceinline__ float fmt_log2_range(const Mode& md) {
+  return md.e5m2() ? 31.807354922057604f : 17.807354922057606f;
+}
 
 struct StepArgs {
   float* w;
@@ -126,19 +85,20 @@ struct StepArgs {
   float denom_scale;     // sqrt((1 - beta2) / (1 - beta2^t))
   float eps;
   float k_min, k_max;
-  uint32_t expand;
+  RuntimeMode mode_m, mode_v;
 };
 
 struct QuantArgs {
   const float* x; uint8_t* q; float* scale; float* k;
   uint64_t n, n_full, n_groups;
   float k_min, k_max;
-  uint32_t expand;
+  RuntimeMode mode;
 };
 
 struct DequantArgs {
   const uint8_t* q; const float* scale; const float* k; float* x;
   uint64_t n, n_full, n_groups;
+  RuntimeMode mode;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -176,7 +136,7 @@ __device__ __forceinline__ float group_allreduce(float x) {
 }
 
 // Compile-time streaming hints (bit mask): 1 load codes, 2 store codes, 4 load gradients,
-// 8 load weights, 16 store weights.  A set bit issues the access as non-temporal.
+// 8 load fp32, 16 store fp32.  A set bit issues the access as non-temporal.
 #ifndef COAT_NT
 #define COAT_NT 31
 #endif
@@ -191,92 +151,45 @@ __device__ __forceinline__ void stg(T* p, T v) {
   else *p = v;
 }
 
-template <bool GUARD>
-__device__ __forceinline__ void load_f32x16(const float* p, uint64_t base, uint64_t n, float (&x)[kEPL]) {
-  if constexpr (!GUARD) {
-    const f32x4* q = reinterpret_cast<const f32x4*>(p + base);
+// Element-wise guarded accesses straight into the lane layout: only the ragged last chunk
+// (n mod 1024 elements, one wavefront) uses them.
+__device__ __forceinline__ void load_f32x16_guarded(const float* p, uint64_t base, uint64_t n, float (&x)[kEPL]) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      f32x4 t = ldg<8>(q + j);
-      x[4 * j + 0] = t.x; x[4 * j + 1] = t.y; x[4 * j + 2] = t.z; x[4 * j + 3] = t.w;
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < kEPL; ++e) x[e] = (base + e < n) ? p[base + e] : 0.0f;
-  }
+  for (int e = 0; e < kEPL; ++e) x[e] = (base + e < n) ? p[base + e] : 0.0f;
 }
-
-template <bool GUARD>
-__device__ __forceinline__ void store_f32x16(float* p, uint64_t base, uint64_t n, const float (&x)[kEPL]) {
-  if constexpr (!GUARD) {
-    f32x4* q = reinterpret_cast<f32x4*>(p + base);
+__device__ __forceinline__ void store_f32x16_guarded(float* p, uint64_t base, uint64_t n, const float (&x)[kEPL]) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      f32x4 t = {x[4 * j + 0], x[4 * j + 1], x[4 * j + 2], x[4 * j + 3]};
-      stg<16>(q + j, t);
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < kEPL; ++e)
-      if (base + e < n) p[base + e] = x[e];
-  }
+  for (int e = 0; e < kEPL; ++e)
+    if (base + e < n) p[base + e] = x[e];
 }
-
-// 16 bf16 gradients -> fp32 (a bf16 is the upper half of an fp32)
-template <bool GUARD>
-__device__ __forceinline__ void load_bf16x16(const uint16_t* p, uint64_t base, uint64_t n, float (&x)[kEPL]) {
-  if constexpr (!GUARD) {
-    const u32x4* q = reinterpret_cast<const u32x4*>(p + base);
+// a bf16 is the upper half of an fp32
+__device__ __forceinline__ void load_bf16x16_guarded(const uint16_t* p, uint64_t base, uint64_t n, float (&x)[kEPL]) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      u32x4 t = ldg<4>(q + j);
-      x[8 * j + 0] = as_f32(t.x << 16); x[8 * j + 1] = as_f32(t.x & 0xffff0000u);
-      x[8 * j + 2] = as_f32(t.y << 16); x[8 * j + 3] = as_f32(t.y & 0xffff0000u);
-      x[8 * j + 4] = as_f32(t.z << 16); x[8 * j + 5] = as_f32(t.z & 0xffff0000u);
-      x[8 * j + 6] = as_f32(t.w << 16); x[8 * j + 7] = as_f32(t.w & 0xffff0000u);
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < kEPL; ++e)
-      x[e] = (base + e < n) ? as_f32(static_cast<uint32_t>(p[base + e]) << 16) : 0.0f;
-  }
+  for (int e = 0; e < kEPL; ++e)
+    x[e] = (base + e < n) ? as_f32(static_cast<uint32_t>(p[base + e]) << 16) : 0.0f;
 }
-
 // 16 code bytes as four dwords, element e in byte (e & 3) of dword (e >> 2)
-template <bool GUARD>
-__device__ __forceinline__ void load_codes16(const uint8_t* p, uint64_t base, uint64_t n, uint32_t (&c)[4]) {
-  if constexpr (!GUARD) {
-    u32x4 t = ldg<1>(reinterpret_cast<const u32x4*>(p + base));
-    c[0] = t.x; c[1] = t.y; c[2] = t.z; c[3] = t.w;
-  } else {
+__device__ __forceinline__ void load_codes16_guarded(const uint8_t* p, uint64_t base, uint64_t n, uint32_t (&c)[4]) {
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      uint32_t v = 0;
+  for (int d = 0; d < 4; ++d) {
+    uint32_t v = 0;
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
-        if (base + 4 * d + b < n) v |= static_cast<uint32_t>(p[base + 4 * d + b]) << (8 * b);
-      c[d] = v;
-    }
+    for (int b = 0; b < 4; ++b)
+      if (base + 4 * d + b < n) v |= static_cast<uint32_t>(p[base + 4 * d + b]) << (8 * b);
+    c[d] = v;
   }
 }
-
-template <bool GUARD>
-__device__ __forceinline__ void store_codes16(uint8_t* p, uint64_t base, uint64_t n, const uint32_t (&c)[4]) {
-  if constexpr (!GUARD) {
-    u32x4 t = {c[0], c[1], c[2], c[3]};
-    stg<2>(reinterpret_cast<u32x4*>(p + base), t);
-  } else {
+__device__ __forceinline__ void store_codes16_guarded(uint8_t* p, uint64_t base, uint64_t n, const uint32_t (&c)[4]) {
 #pragma unroll
-    for (int e = 0; e < kEPL; ++e)
-      if (base + e < n) p[base + e] = static_cast<uint8_t>(c[e >> 2] >> (8 * (e & 3)));
-  }
+  for (int e = 0; e < kEPL; ++e)
+    if (base + e < n) p[base + e] = static_cast<uint8_t>(c[e >> 2] >> (8 * (e & 3)));
 }
 
 // ---------------------------------------------------------------------------------------
 // LDS staging: HBM likes every load/store instruction of a wavefront to cover one contiguous
 // span (and to be issued as a streaming access), the arithmetic wants every lane to own 16
-// consecutive elements.  A 4 KiB (fp32) / 2 KiB (bf16) per-wavefront LDS tile converts between
-// the two: rows of 64 x 16 B on the memory side, 64 B (32 B) per lane on the register side.
+// consecutive elements.  A per-wavefront LDS tile converts between the two: rows of 64 x 16 B on
+// the memory side, 64 B (fp32) or 32 B (bf16) per lane on the register side.
 // 16-byte slot s lives at s + (s >> 3) (one pad slot after every eight), which makes both access
 // patterns conflict free and keeps every address of a lane a constant offset from one of two
 // per-lane bases: row side 72 j + lane + (lane >> 3), lane side 4 lane + (lane >> 1) + i (fp32)
@@ -290,7 +203,7 @@ struct StageTiles { f32x4* w; u32x4* g; };
 
 // rows (memory side) -> 16 consecutive fp32 per lane, through the wavefront's fp32 tile
 __device__ __forceinline__ void tile_rows_to_lanes(f32x4* tile, int lane, const f32x4 (&rows)[4], float (&x)[kEPL]) {
-  f32x4* const row = tile + lane + (lane >> 3);          // + 72 j
+  f32x4* const row = tile + lane + (lane >> 3);            // + 72 j
   const f32x4* const own = tile + 4 * lane + (lane >> 1);  // + i
 #pragma unroll
   for (int j = 0; j < 4; ++j) row[72 * j] = rows[j];
@@ -302,7 +215,6 @@ __device__ __forceinline__ void tile_rows_to_lanes(f32x4* tile, int lane, const 
 }
 
 // 16 consecutive fp32 per lane -> rows, written straight to memory (p: start of the chunk)
-template <int NT_BIT>
 __device__ __forceinline__ void tile_lanes_to_rows_store(f32x4* tile, int lane, const float (&x)[kEPL], float* p) {
   const f32x4* const row = tile + lane + (lane >> 3);
   f32x4* const own = tile + 4 * lane + (lane >> 1);
@@ -313,18 +225,36 @@ __device__ __forceinline__ void tile_lanes_to_rows_store(f32x4* tile, int lane, 
   }
   f32x4* q = reinterpret_cast<f32x4*>(p);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) stg<NT_BIT>(q + 64 * j + lane, row[72 * j]);
+  for (int j = 0; j < 4; ++j) stg<16>(q + 64 * j + lane, row[72 * j]);
 }
 
+// rows of bf16 -> 16 consecutive gradients per lane as fp32
+__device__ __forceinline__ void tile_rows_to_lanes_bf16(u32x4* tile, int lane, const u32x4 (&rows)[2], float (&g)[kEPL]) {
+  u32x4* const row = tile + lane + (lane >> 3);            // + 72 j
+  const u32x4* const own = tile + 2 * lane + (lane >> 2);  // + j
+#pragma unroll
+  for (int j = 0; j < 2; ++j) row[72 * j] = rows[j];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const u32x4 t = own[j];
+    g[8 * j + 0] = as_f32(t.x << 16); g[8 * j + 1] = as_f32(t.x & 0xffff0000u);
+    g[8 * j + 2] = as_f32(t.y << 16); g[8 * j + 3] = as_f32(t.y & 0xffff0000u);
+    g[8 * j + 4] = as_f32(t.z << 16); g[8 * j + 5] = as_f32(t.z & 0xffff0000u);
+    g[8 * j + 6] = as_f32(t.w << 16); g[8 * j + 7] = as_f32(t.w & 0xffff0000u);
+  }
+}
+
+// The lookup table in LDS: per format 256 entries so that the whole code byte indexes it (the sign
+// bit is ignored).  TABLES = 1 loads E4M3 only, 2 loads E4M3 then E5M2.
+template <int TABLES>
 __device__ __forceinline__ void fill_lut(Log2Entry* lut) {
-  // 256 entries so that the whole code byte indexes it (the sign bit is ignored)
-  for (int i = threadIdx.x; i < 256; i += blockDim.x) lut[i] = kLog2CodeOverMax[i & 127];
+  for (int i = threadIdx.x; i < 256 * TABLES; i += blockDim.x) lut[i] = kLog2Code[i >> 8][i & 127];
   __syncthreads();
 }
 
 constexpr float kLn2 = 0.6931471805599453f;
 
-// |c/448|^(1/k) for 16 codes.
+// |c/fmax|^(1/k) for 16 codes.
 //   ACCURATE = false: exp2(L * (1/k)), good to about |L/k| * 2^-22 relative;
 //   ACCURATE = true : the rounding of the product and of 1/k is recovered with one fma
 //     (r = L - t*k is the exact residual of t = fl(L * fl(1/k)) against L/k, times k), the
@@ -357,44 +287,65 @@ __device__ __forceinline__ void inverse_expand16(const Log2Entry* lut, const uin
 }
 
 // plain dequantizer without expansion: the decoded code itself (to be multiplied by the scale)
-template <bool SIGNED>
+template <bool E5M2>
 __device__ __forceinline__ void decode16(const uint32_t (&c)[4], float (&y)[kEPL]) {
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
-    y[4 * d + 0] = __builtin_amdgcn_cvt_f32_fp8(c[d], 0);
-    y[4 * d + 1] = __builtin_amdgcn_cvt_f32_fp8(c[d], 1);
-    y[4 * d + 2] = __builtin_amdgcn_cvt_f32_fp8(c[d], 2);
-    y[4 * d + 3] = __builtin_amdgcn_cvt_f32_fp8(c[d], 3);
+    if constexpr (E5M2) {
+      y[4 * d + 0] = __builtin_amdgcn_cvt_f32_bf8(c[d], 0);
+      y[4 * d + 1] = __builtin_amdgcn_cvt_f32_bf8(c[d], 1);
+      y[4 * d + 2] = __builtin_amdgcn_cvt_f32_bf8(c[d], 2);
+      y[4 * d + 3] = __builtin_amdgcn_cvt_f32_bf8(c[d], 3);
+    } else {
+      y[4 * d + 0] = __builtin_amdgcn_cvt_f32_fp8(c[d], 0);
+      y[4 * d + 1] = __builtin_amdgcn_cvt_f32_fp8(c[d], 1);
+      y[4 * d + 2] = __builtin_amdgcn_cvt_f32_fp8(c[d], 2);
+      y[4 * d + 3] = __builtin_amdgcn_cvt_f32_fp8(c[d], 3);
+    }
   }
+}
+
+// Dequantize 16 codes of one moment up to a per-group factor: the stored value is y * factor with
+//   expansion on : y = +-|c/fmax|^(1/k), factor = fmax * scale      (Sec. 4.2, after the DQ of Sec. 3)
+//   expansion off: y = c,               factor = scale              (k is 1 in this mode, not read)
+template <bool SIGNED, bool ACCURATE, class Mode>
+__device__ __forceinline__ float dequant16(const Mode& md, const Log2Entry* lut, const uint32_t (&c)[4],
+                                           float scale, float k, float (&y)[kEPL]) {
+  if (md.expand()) {
+    inverse_expand16<SIGNED, ACCURATE>(lut + (md.e5m2() ? 256 : 0), c, k, hw_rcp(k), y);
+    return fmt_max(md) * scale;
+  }
+  if (md.e5m2()) decode16<true>(c, y);
+  else decode16<false>(c, y);
+  return scale;
 }
 
 struct GroupQuant { float scale, k, inv_a; };
 
 // Per-group scale and exponent from the group's extreme magnitudes (Definition 1, Sec. 4.2).
-// amin is the minimum over NON-ZERO magnitudes (+inf when there is none).
-// EXPAND: inv_a = 1/(448 scale), the reciprocal of the magnitude the top code stands for.
-// !EXPAND: k = 1 and inv_a = 1/scale, so that the value to round is simply x / scale (Sec. 3).
-template <bool EXPAND>
-__device__ __forceinline__ GroupQuant group_quant_params(float amax, float amin, float k_min, float k_max,
-                                                         float unit = 1.0f) {
-  // The values reduced over are x / unit (unit = 1 - beta inside the step, 1 otherwise): the
-  // stored scale refers to x, the reciprocal returned refers to the values as they are held.
+// amin is the minimum over NON-ZERO magnitudes (+inf when there is none).  The values reduced
+// over are x / unit (unit = 1 - beta inside the step, 1 otherwise): the stored scale refers to x.
+//   expansion on : inv_a = unit / (fmax * scale), so that (held value) * inv_a = |x| / (fmax*scale)
+//   expansion off: k = 1; inv_a only flags an empty group (the quotient is formed exactly)
+template <class Mode>
+__device__ __forceinline__ GroupQuant group_quant_params(const Mode& md, float amax, float amin, float k_min,
+                                                         float k_max, float unit) {
   GroupQuant r;
-  // amax / 448, correctly rounded: multiply by the rounded reciprocal, then one residual step
-  constexpr float inv448 = 1.0f / 448.0f;
+  // amax / fmax, correctly rounded: multiply by the rounded reciprocal, then one residual step
+  const float inv_fmax = fmt_inv_max(md), fmax = fmt_max(md);
   const float ax = amax * unit;
-  float s = ax * inv448;
-  s = __builtin_fmaf(__builtin_fmaf(-kE4M3Max, s, ax), inv448, s);
+  float s = ax * inv_fmax;
+  s = __builtin_fmaf(__builtin_fmaf(-fmax, s, ax), inv_fmax, s);
   float k = 1.0f;
-  if constexpr (EXPAND) {
+  if (md.expand()) {
     // two hardware reciprocals (1 ulp each) are enough here: k moves by ~2 ulp
     // (the max keeps a ratio that rounds below 1 from turning the huge k negative)
     const float ratio = __builtin_fmaxf(amax * hw_rcp(amin), 1.0f);   // R_X
-    float kk = kLog2Range * hw_rcp(hw_log2(ratio));
+    float kk = fmt_log2_range(md) * hw_rcp(hw_log2(ratio));
     kk = __builtin_amdgcn_fmed3f(kk, k_min, k_max);
     k = (amax != amin) ? kk : 1.0f;
   }
-  const float inv_a = unit * hw_rcp(EXPAND ? kE4M3Max * s : s);
+  const float inv_a = unit * hw_rcp(md.expand() ? fmax * s : s);
   const bool empty = !(amax > 0.0f);                 // all zero: scale 0, k 1, every code 0
   r.scale = empty ? 0.0f : s;
   r.k = empty ? 1.0f : k;
@@ -421,37 +372,49 @@ __device__ __forceinline__ void lane_extremes(const float (&x)[kEPL], float& ama
   amax = hi; amin = lo;
 }
 
-// Quantize 16 values to E4M3 codes (native convert: round to nearest even; magnitudes up to 464
-// round to 448, and the value to convert never exceeds 448 * (1 + 2^-22)^k_max).
-//   EXPAND : code = E4M3( sign(x) * 448 * (|x| * inv_a)^k ),  inv_a = 1/(448 scale)
-//   !EXPAND: code = E4M3( x / scale ) with the correctly rounded fp32 quotient (this mode is the
-//            plain quantizer of Sec. 3 kept as a baseline; it is not tuned)
+template <bool E5M2>
+__device__ __forceinline__ uint32_t pack4(const float (&q)[4]) {
+  if constexpr (E5M2) {
+    const uint32_t p = __builtin_amdgcn_cvt_pk_bf8_f32(q[0], q[1], 0u, false);
+    return __builtin_amdgcn_cvt_pk_bf8_f32(q[2], q[3], p, true);
+  } else {
+    const uint32_t p = __builtin_amdgcn_cvt_pk_fp8_f32(q[0], q[1], 0u, false);
+    return __builtin_amdgcn_cvt_pk_fp8_f32(q[2], q[3], p, true);
+  }
+}
+
+// Quantize 16 held values (x / unit) to FP8 codes.  The native converts round to nearest even and
+// round magnitudes up to fmax * (1 + 2^-5) (E4M3: 464) back to fmax; the value converted never
+// exceeds fmax * (1 + 2^-22)^k_max, so no clamp is needed.
+//   expansion on : code = FP8( sign(x) * fmax * (|x| / (fmax*scale))^k ) as one fma in the exponent:
+//                  exp2(k log2 r + log2 fmax), rounded once at magnitude <= log2(range)/2
+//                  (log2 0 = -inf, so a zero stays zero)
+//   expansion off: code = FP8( x / scale ) with the correctly rounded fp32 quotient (the plain
+//                  quantizer of Sec. 3, kept as a baseline; it is not tuned)
 // SIGNED = false (second moment, never negative) skips the sign transfer.
-template <bool EXPAND, bool SIGNED>
-__device__ __forceinline__ void quantize16(const float (&x)[kEPL], const GroupQuant& gq, uint32_t (&c)[4],
-                                           float unit = 1.0f) {
+template <bool SIGNED, class Mode>
+__device__ __forceinline__ void quantize16(const Mode& md, const float (&x)[kEPL], const GroupQuant& gq,
+                                           uint32_t (&c)[4], float unit) {
+  const float log2_fmax = fmt_log2_max(md);
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
     float q[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       const float xv = x[4 * d + b];
-      if constexpr (EXPAND) {
-        // 448 r^k = exp2(k log2 r + log2 448): one fma, rounded once at magnitude <= 9
-        // (log2 0 = -inf, so a zero stays zero)
-        const float m = hw_exp2(__builtin_fmaf(hw_log2(__builtin_fabsf(xv) * gq.inv_a), gq.k, kLog2E4M3Max));
+      if (md.expand()) {
+        const float m = hw_exp2(__builtin_fmaf(hw_log2(__builtin_fabsf(xv) * gq.inv_a), gq.k, log2_fmax));
         q[b] = SIGNED ? as_f32(as_u32(m) | (as_u32(xv) & 0x80000000u)) : m;
       } else {
         q[b] = gq.inv_a != 0.0f ? (xv * unit) / gq.scale : 0.0f;   // IEEE division: correctly rounded
       }
     }
-    uint32_t p = __builtin_amdgcn_cvt_pk_fp8_f32(q[0], q[1], 0u, false);
-    c[d] = __builtin_amdgcn_cvt_pk_fp8_f32(q[2], q[3], p, true);
+    c[d] = md.e5m2() ? pack4<true>(q) : pack4<false>(q);
   }
 }
 
 // ---------------------------------------------------------------------------------------
-// the fused step: one chunk of 1024 elements per wavefront iteration
+// the fused step
 // ---------------------------------------------------------------------------------------
 
 // Per-group metadata of one chunk as one lane sees it (its own group's words).
@@ -459,27 +422,15 @@ struct GroupMeta { float m_scale, m_k, v_scale, v_k; };
 
 // The arithmetic of the step on one lane's 16 elements, registers in, registers out:
 // w (in/out), g, codes (in/out), metadata (in/out).  Cross-lane traffic: the group reductions.
-template <int G, bool EXPAND>
-__device__ __forceinline__ void step_core(const StepArgs& a, const Log2Entry* lut, float (&w)[kEPL],
-                                          const float (&g)[kEPL], uint32_t (&mc)[4], uint32_t (&vc)[4],
-                                          GroupMeta& meta) {
+template <int G, class ModeM, class ModeV>
+__device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, const ModeV& mv,
+                                          const Log2Entry* lut, float (&w)[kEPL], const float (&g)[kEPL],
+                                          uint32_t (&mc)[4], uint32_t (&vc)[4], GroupMeta& meta) {
   constexpr int LPG = G / kEPL;                      // lanes per group
   float m[kEPL], v[kEPL];
-  float m_fac, v_fac;                                // beta/(1-beta) * (magnitude of the decoded unit)
-  if constexpr (EXPAND) {
-    // m = (448 scale) * |c/448|^(1/k).  A plain hardware reciprocal of k is enough: the
-    // compensated path recovers its error, the other one is modelled with it.
-    inverse_expand16<true, true>(lut, mc, meta.m_k, hw_rcp(meta.m_k), m);
-    inverse_expand16<false, false>(lut, vc, meta.v_k, hw_rcp(meta.v_k), v);
-    m_fac = a.beta1_ratio * (kE4M3Max * meta.m_scale);
-    v_fac = a.beta2_ratio * (kE4M3Max * meta.v_scale);
-  } else {
-    // plain dequantizer: m = scale * c (k is 1 in this mode and is not read)
-    decode16<true>(mc, m);
-    decode16<false>(vc, v);
-    m_fac = a.beta1_ratio * meta.m_scale;
-    v_fac = a.beta2_ratio * meta.v_scale;
-  }
+  // beta/(1-beta) * (magnitude of the decoded unit)
+  const float m_fac = a.beta1_ratio * dequant16<true, true>(mm, lut, mc, meta.m_scale, meta.m_k, m);
+  const float v_fac = a.beta2_ratio * dequant16<false, false>(mv, lut, vc, meta.v_scale, meta.v_k, v);
 
 #pragma unroll
   for (int e = 0; e < kEPL; ++e) {
@@ -502,10 +453,10 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const Log2Entry* lu
   m_min = group_allreduce<LPG, false>(m_min);
   v_max = group_allreduce<LPG, true>(v_max);
   v_min = group_allreduce<LPG, false>(v_min);
-  const GroupQuant qm = group_quant_params<EXPAND>(m_max, m_min, a.k_min, a.k_max, a.one_minus_beta1);
-  const GroupQuant qv = group_quant_params<EXPAND>(v_max, v_min, a.k_min, a.k_max, a.one_minus_beta2);
-  quantize16<EXPAND, true>(m, qm, mc, a.one_minus_beta1);
-  quantize16<EXPAND, false>(v, qv, vc, a.one_minus_beta2);
+  const GroupQuant qm = group_quant_params(mm, m_max, m_min, a.k_min, a.k_max, a.one_minus_beta1);
+  const GroupQuant qv = group_quant_params(mv, v_max, v_min, a.k_min, a.k_max, a.one_minus_beta2);
+  quantize16<true>(mm, m, qm, mc, a.one_minus_beta1);
+  quantize16<false>(mv, v, qv, vc, a.one_minus_beta2);
   meta.m_scale = qm.scale; meta.m_k = qm.k;
   meta.v_scale = qv.scale; meta.v_k = qv.k;
 }
@@ -519,7 +470,7 @@ struct RawChunk {
   GroupMeta meta;
 };
 
-template <int G, bool EXPAND>
+template <int G>
 __device__ __forceinline__ void issue_loads(const StepArgs& a, uint64_t chunk, int lane, RawChunk& r) {
   constexpr int LPG = G / kEPL;
   // chunk is uniform over the wavefront: the array bases below are scalar, lanes add 32-bit offsets
@@ -538,39 +489,29 @@ __device__ __forceinline__ void issue_loads(const StepArgs& a, uint64_t chunk, i
   r.vc = ldg<1>(vq + lane);
   r.meta.m_scale = a.ms[gb + gl];
   r.meta.v_scale = a.vs[gb + gl];
-  if constexpr (EXPAND) { r.meta.m_k = a.mk[gb + gl]; r.meta.v_k = a.vk[gb + gl]; }
-  else { r.meta.m_k = 1.0f; r.meta.v_k = 1.0f; }
+  r.meta.m_k = a.mk[gb + gl];          // written as 1 (and ignored) by a moment stored without expansion
+  r.meta.v_k = a.vk[gb + gl];
 }
 
 // One full chunk: rows -> lane layout through the LDS tiles, the arithmetic, and back out.
-template <int G, bool EXPAND>
-__device__ __forceinline__ void process_chunk(const StepArgs& a, const Log2Entry* lut, const StageTiles& tiles,
-                                              uint64_t chunk, int lane, RawChunk& r) {
+template <int G, class ModeM, class ModeV>
+__device__ __forceinline__ void process_chunk(const StepArgs& a, const ModeM& mm, const ModeV& mv,
+                                              const Log2Entry* lut, const StageTiles& tiles, uint64_t chunk,
+                                              int lane, RawChunk& r) {
   constexpr int LPG = G / kEPL;
   const uint64_t cb = chunk * kChunk;
   const uint64_t gb = chunk * (kChunk / G);
-  u32x4* const g_row = tiles.g + lane + (lane >> 3);          // + 72 j
-  u32x4* const g_own = tiles.g + 2 * lane + (lane >> 2);      // + j
 
   float w[kEPL], g[kEPL];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) g_row[72 * j] = r.g[j];
+  tile_rows_to_lanes_bf16(tiles.g, lane, r.g, g);
   tile_rows_to_lanes(tiles.w, lane, r.w, w);
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const u32x4 t = g_own[j];
-    g[8 * j + 0] = as_f32(t.x << 16); g[8 * j + 1] = as_f32(t.x & 0xffff0000u);
-    g[8 * j + 2] = as_f32(t.y << 16); g[8 * j + 3] = as_f32(t.y & 0xffff0000u);
-    g[8 * j + 4] = as_f32(t.z << 16); g[8 * j + 5] = as_f32(t.z & 0xffff0000u);
-    g[8 * j + 6] = as_f32(t.w << 16); g[8 * j + 7] = as_f32(t.w & 0xffff0000u);
-  }
   uint32_t mc[4] = {r.mc.x, r.mc.y, r.mc.z, r.mc.w};
   uint32_t vc[4] = {r.vc.x, r.vc.y, r.vc.z, r.vc.w};
   GroupMeta meta = r.meta;
 
-  step_core<G, EXPAND>(a, lut, w, g, mc, vc, meta);
+  step_core<G>(a, mm, mv, lut, w, g, mc, vc, meta);
 
-  tile_lanes_to_rows_store<16>(tiles.w, lane, w, a.w + cb);
+  tile_lanes_to_rows_store(tiles.w, lane, w, a.w + cb);
   const u32x4 mo = {mc[0], mc[1], mc[2], mc[3]}, vo = {vc[0], vc[1], vc[2], vc[3]};
   stg<2>(reinterpret_cast<u32x4*>(a.mq + cb) + lane, mo);
   stg<2>(reinterpret_cast<u32x4*>(a.vq + cb) + lane, vo);
@@ -581,14 +522,30 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const Log2Entry
   }
 }
 
+template <bool GENERIC> struct ModesOf;
+template <> struct ModesOf<false> {
+  typedef DefaultMode M;
+  __device__ static DefaultMode m(const StepArgs&) { return DefaultMode(); }
+  __device__ static DefaultMode v(const StepArgs&) { return DefaultMode(); }
+};
+template <> struct ModesOf<true> {
+  typedef RuntimeMode M;
+  __device__ static RuntimeMode m(const StepArgs& a) { return a.mode_m; }
+  __device__ static RuntimeMode v(const StepArgs& a) { return a.mode_v; }
+};
+
 // Main kernel: one chunk per wavefront (the loop only runs again for buffers with more chunks
 // than the grid has wavefronts).  The first chunk's loads are issued before the block fills its
 // lookup table, so the table's latency hides behind them.
-template <int G, bool EXPAND>
+// GENERIC = false: both moments E4M3 with expansion (the method as the paper runs it);
+// GENERIC = true : per-moment format and expansion read from the arguments (Table 1's grid).
+template <int G, bool GENERIC>
 __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
-  __shared__ Log2Entry lut[256];
+  constexpr int kTables = GENERIC ? 2 : 1;
+  __shared__ Log2Entry lut[256 * kTables];
   __shared__ f32x4 tile_w[kWavesPerBlock * kTileSlotsW];
   __shared__ u32x4 tile_g[kWavesPerBlock * kTileSlotsG];
+  const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(a), mv = ModesOf<GENERIC>::v(a);
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wavefront-uniform
   const StageTiles tiles = {tile_w + wv * kTileSlotsW, tile_g + wv * kTileSlotsG};
@@ -597,21 +554,23 @@ __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
 
   RawChunk r;
   const bool have = chunk < a.n_full;
-  if (have) issue_loads<G, EXPAND>(a, chunk, lane, r);
-  fill_lut(lut);                                     // every wavefront of the block reaches this
-  if (have) process_chunk<G, EXPAND>(a, lut, tiles, chunk, lane, r);
+  if (have) issue_loads<G>(a, chunk, lane, r);
+  fill_lut<kTables>(lut);                            // every wavefront of the block reaches this
+  if (have) process_chunk<G>(a, mm, mv, lut, tiles, chunk, lane, r);
   for (chunk += stride; chunk < a.n_full; chunk += stride) {
-    issue_loads<G, EXPAND>(a, chunk, lane, r);
-    process_chunk<G, EXPAND>(a, lut, tiles, chunk, lane, r);
+    issue_loads<G>(a, chunk, lane, r);
+    process_chunk<G>(a, mm, mv, lut, tiles, chunk, lane, r);
   }
 }
 
 // The ragged last chunk (n % 1024 elements): one wavefront, element-wise guarded accesses
 // straight into the lane layout.
-template <int G, bool EXPAND>
+template <int G, bool GENERIC>
 __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
-  __shared__ Log2Entry lut[256];
-  fill_lut(lut);
+  constexpr int kTables = GENERIC ? 2 : 1;
+  __shared__ Log2Entry lut[256 * kTables];
+  fill_lut<kTables>(lut);
+  const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(a), mv = ModesOf<GENERIC>::v(a);
   constexpr int LPG = G / kEPL;
   const int lane = threadIdx.x;
   const uint64_t chunk = a.n_full;
@@ -620,19 +579,19 @@ __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
   const bool gvalid = gidx < a.n_groups;
   float w[kEPL], g[kEPL];
   uint32_t mc[4], vc[4];
-  load_f32x16<true>(a.w, base, a.n, w);
-  load_bf16x16<true>(a.g, base, a.n, g);
-  load_codes16<true>(a.mq, base, a.n, mc);
-  load_codes16<true>(a.vq, base, a.n, vc);
+  load_f32x16_guarded(a.w, base, a.n, w);
+  load_bf16x16_guarded(a.g, base, a.n, g);
+  load_codes16_guarded(a.mq, base, a.n, mc);
+  load_codes16_guarded(a.vq, base, a.n, vc);
   GroupMeta meta;
   meta.m_scale = gvalid ? a.ms[gidx] : 0.0f;
   meta.v_scale = gvalid ? a.vs[gidx] : 0.0f;
-  meta.m_k = (EXPAND && gvalid) ? a.mk[gidx] : 1.0f;
-  meta.v_k = (EXPAND && gvalid) ? a.vk[gidx] : 1.0f;
-  step_core<G, EXPAND>(a, lut, w, g, mc, vc, meta);
-  store_f32x16<true>(a.w, base, a.n, w);
-  store_codes16<true>(a.mq, base, a.n, mc);
-  store_codes16<true>(a.vq, base, a.n, vc);
+  meta.m_k = gvalid ? a.mk[gidx] : 1.0f;
+  meta.v_k = gvalid ? a.vk[gidx] : 1.0f;
+  step_core<G>(a, mm, mv, lut, w, g, mc, vc, meta);
+  store_f32x16_guarded(a.w, base, a.n, w);
+  store_codes16_guarded(a.mq, base, a.n, mc);
+  store_codes16_guarded(a.vq, base, a.n, vc);
   if (gvalid && (lane % LPG) == 0) {
     a.ms[gidx] = meta.m_scale; a.mk[gidx] = meta.m_k;
     a.vs[gidx] = meta.v_scale; a.vk[gidx] = meta.v_k;
@@ -640,24 +599,24 @@ __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// standalone quantizer / dequantizer (the two halves of the step)
+// standalone quantizer / dequantizer (the two halves of the step), format and expansion at run time
 // ---------------------------------------------------------------------------------------
 
 // quantize one lane's 16 values (cross-lane: the group reductions) and hand back codes + metadata
-template <int G, bool EXPAND>
+template <int G>
 __device__ __forceinline__ GroupQuant quant_core(const QuantArgs& a, const float (&x)[kEPL], uint32_t (&c)[4]) {
   constexpr int LPG = G / kEPL;
   float hi, lo;
   lane_extremes(x, hi, lo);
   hi = group_allreduce<LPG, true>(hi);
   lo = group_allreduce<LPG, false>(lo);
-  const GroupQuant q = group_quant_params<EXPAND>(hi, lo, a.k_min, a.k_max);
-  quantize16<EXPAND, true>(x, q, c);
+  const GroupQuant q = group_quant_params(a.mode, hi, lo, a.k_min, a.k_max, 1.0f);
+  quantize16<true>(a.mode, x, q, c, 1.0f);
   return q;
 }
 
 // full chunks: coalesced streaming row loads of x staged through the LDS tile, one chunk per wavefront
-template <int G, bool EXPAND>
+template <int G>
 __global__ __launch_bounds__(kBlock) void quant_kernel(QuantArgs a) {
   __shared__ f32x4 tile_x[kWavesPerBlock * kTileSlotsW];
   constexpr int LPG = G / kEPL;
@@ -673,7 +632,7 @@ __global__ __launch_bounds__(kBlock) void quant_kernel(QuantArgs a) {
     float x[kEPL];
     uint32_t c[4];
     tile_rows_to_lanes(tile_x + wv * kTileSlotsW, lane, rows, x);
-    const GroupQuant q = quant_core<G, EXPAND>(a, x, c);
+    const GroupQuant q = quant_core<G>(a, x, c);
     const u32x4 co = {c[0], c[1], c[2], c[3]};
     stg<2>(reinterpret_cast<u32x4*>(a.q + cb) + lane, co);
     if ((lane % LPG) == 0) { a.scale[gb + lane / LPG] = q.scale; a.k[gb + lane / LPG] = q.k; }
@@ -681,7 +640,7 @@ __global__ __launch_bounds__(kBlock) void quant_kernel(QuantArgs a) {
 }
 
 // the ragged last chunk: one wavefront, element-wise guarded accesses
-template <int G, bool EXPAND>
+template <int G>
 __global__ __launch_bounds__(kWave) void quant_tail_kernel(QuantArgs a) {
   constexpr int LPG = G / kEPL;
   const int lane = threadIdx.x;
@@ -689,17 +648,27 @@ __global__ __launch_bounds__(kWave) void quant_tail_kernel(QuantArgs a) {
   const uint64_t gidx = a.n_full * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
   float x[kEPL];
   uint32_t c[4];
-  load_f32x16<true>(a.x, base, a.n, x);
-  const GroupQuant q = quant_core<G, EXPAND>(a, x, c);
-  store_codes16<true>(a.q, base, a.n, c);
+  load_f32x16_guarded(a.x, base, a.n, x);
+  const GroupQuant q = quant_core<G>(a, x, c);
+  store_codes16_guarded(a.q, base, a.n, c);
   if (gidx < a.n_groups && (lane % LPG) == 0) { a.scale[gidx] = q.scale; a.k[gidx] = q.k; }
+}
+
+// The standalone dequantizer always honours the stored k (it is 1 for codes written without
+// expansion), with the compensated exponent.
+__device__ __forceinline__ void dequant_core(const DequantArgs& a, const Log2Entry* lut, const uint32_t (&c)[4],
+                                             float scale, float k, float (&x)[kEPL]) {
+  inverse_expand16<true, true>(lut + (a.mode.e5m2() ? 256 : 0), c, k, hw_rcp(k), x);
+  const float amag = fmt_max(a.mode) * scale;
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) x[e] *= amag;
 }
 
 template <int G>
 __global__ __launch_bounds__(kBlock) void dequant_kernel(DequantArgs a) {
-  __shared__ Log2Entry lut[256];
+  __shared__ Log2Entry lut[512];
   __shared__ f32x4 tile_x[kWavesPerBlock * kTileSlotsW];
-  fill_lut(lut);
+  fill_lut<2>(lut);
   constexpr int LPG = G / kEPL;
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -707,21 +676,17 @@ __global__ __launch_bounds__(kBlock) void dequant_kernel(DequantArgs a) {
   for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
     const uint64_t cb = chunk * kChunk, gb = chunk * (kChunk / G);
     const u32x4 ci = ldg<1>(reinterpret_cast<const u32x4*>(a.q + cb) + lane);
-    const float amag = kE4M3Max * a.scale[gb + lane / LPG];
-    const float k = a.k[gb + lane / LPG];
     const uint32_t c[4] = {ci.x, ci.y, ci.z, ci.w};
     float x[kEPL];
-    inverse_expand16<true, true>(lut, c, k, hw_rcp(k), x);
-#pragma unroll
-    for (int e = 0; e < kEPL; ++e) x[e] *= amag;
-    tile_lanes_to_rows_store<16>(tile_x + wv * kTileSlotsW, lane, x, a.x + cb);
+    dequant_core(a, lut, c, a.scale[gb + lane / LPG], a.k[gb + lane / LPG], x);
+    tile_lanes_to_rows_store(tile_x + wv * kTileSlotsW, lane, x, a.x + cb);
   }
 }
 
 template <int G>
 __global__ __launch_bounds__(kWave) void dequant_tail_kernel(DequantArgs a) {
-  __shared__ Log2Entry lut[256];
-  fill_lut(lut);
+  __shared__ Log2Entry lut[512];
+  fill_lut<2>(lut);
   constexpr int LPG = G / kEPL;
   const int lane = threadIdx.x;
   const uint64_t base = a.n_full * kChunk + static_cast<uint64_t>(lane) * kEPL;
@@ -729,13 +694,9 @@ __global__ __launch_bounds__(kWave) void dequant_tail_kernel(DequantArgs a) {
   const bool gvalid = gidx < a.n_groups;
   uint32_t c[4];
   float x[kEPL];
-  load_codes16<true>(a.q, base, a.n, c);
-  const float amag = kE4M3Max * (gvalid ? a.scale[gidx] : 0.0f);
-  const float k = gvalid ? a.k[gidx] : 1.0f;
-  inverse_expand16<true, true>(lut, c, k, hw_rcp(k), x);
-#pragma unroll
-  for (int e = 0; e < kEPL; ++e) x[e] *= amag;
-  store_f32x16<true>(a.x, base, a.n, x);
+  load_codes16_guarded(a.q, base, a.n, c);
+  dequant_core(a, lut, c, gvalid ? a.scale[gidx] : 0.0f, gvalid ? a.k[gidx] : 1.0f, x);
+  store_f32x16_guarded(a.x, base, a.n, x);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -764,7 +725,7 @@ unsigned grid_for(uint64_t n_full) {
 }
 
 // k bounds: 0,0 selects the defaults; the kernels assume 2^-6 <= k <= 2^16 (finite table
-// sentinel for zero codes, no overflow of the value handed to the E4M3 convert)
+// sentinel for zero codes, no overflow of the value handed to the FP8 convert)
 constexpr float kKLowest = 0.015625f, kKHighest = 65536.0f;
 bool resolve_k_bounds(float& k_min, float& k_max) {
   if (!finite_f(k_min) || !finite_f(k_max)) return false;
@@ -774,14 +735,14 @@ bool resolve_k_bounds(float& k_min, float& k_max) {
 
 int launch_status() { return hipGetLastError() == hipSuccess ? COAT_OK : COAT_ERR_LAUNCH; }
 
-// The step kernel asks for this much dynamic LDS on top of its ~29 KiB of tiles and table, for no
+// The step kernel asks for this much dynamic LDS on top of its ~30 KiB of tiles and table, for no
 // other purpose than to hold a CU to two resident blocks (8 wavefronts): with fewer bytes in
 // flight per CU the HBM controllers see longer same-page runs, and two wavefronts per SIMD are
 // enough to overlap one's arithmetic with the other's loads (measured on the 7B set: 2 blocks
 // 6.04 TB/s, 3 blocks 5.91, 4 blocks 5.81, 1 block 3.66).
 constexpr size_t kStepLdsPad = 24 * 1024;
 
-template <int G, bool EXPAND>
+template <int G, bool GENERIC>
 int launch_step(const StepArgs& a, hipStream_t s) {
   if (a.n_full) {
     const unsigned grid = grid_for(a.n_full);
@@ -789,27 +750,27 @@ int launch_step(const StepArgs& a, hipStream_t s) {
 #ifdef COAT_TUNING
     if (g_tune_lds_pad >= 0) lds = static_cast<size_t>(g_tune_lds_pad);
     if (lds > 32 * 1024)
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&adamw_step_kernel<G, EXPAND>),
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&adamw_step_kernel<G, GENERIC>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
 #endif
-    hipLaunchKernelGGL((adamw_step_kernel<G, EXPAND>), dim3(grid), dim3(kBlock), lds, s, a);
+    hipLaunchKernelGGL((adamw_step_kernel<G, GENERIC>), dim3(grid), dim3(kBlock), lds, s, a);
     if (int rc = launch_status()) return rc;
   }
   if (a.n > a.n_full * kChunk) {
-    hipLaunchKernelGGL((adamw_step_tail_kernel<G, EXPAND>), dim3(1), dim3(kWave), 0, s, a);
+    hipLaunchKernelGGL((adamw_step_tail_kernel<G, GENERIC>), dim3(1), dim3(kWave), 0, s, a);
     if (int rc = launch_status()) return rc;
   }
   return COAT_OK;
 }
 
-template <int G, bool EXPAND>
+template <int G>
 int launch_quant(const QuantArgs& a, hipStream_t s) {
   if (a.n_full) {
-    hipLaunchKernelGGL((quant_kernel<G, EXPAND>), dim3(grid_for(a.n_full)), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((quant_kernel<G>), dim3(grid_for(a.n_full)), dim3(kBlock), 0, s, a);
     if (int rc = launch_status()) return rc;
   }
   if (a.n > a.n_full * kChunk) {
-    hipLaunchKernelGGL((quant_tail_kernel<G, EXPAND>), dim3(1), dim3(kWave), 0, s, a);
+    hipLaunchKernelGGL((quant_tail_kernel<G>), dim3(1), dim3(kWave), 0, s, a);
     if (int rc = launch_status()) return rc;
   }
   return COAT_OK;
@@ -838,19 +799,19 @@ int launch_dequant(const DequantArgs& a, hipStream_t s) {
   }                                         \
   return COAT_ERR_GROUP
 
-int dispatch_step(const StepArgs& a, int32_t G, hipStream_t s) {
-  if (a.expand) { COAT_DISPATCH_G(G, (launch_step<kG, true>(a, s))); }
-  COAT_DISPATCH_G(G, (launch_step<kG, false>(a, s)));
+int dispatch_step(const StepArgs& a, int32_t G, bool generic, hipStream_t s) {
+  if (!generic) { COAT_DISPATCH_G(G, (launch_step<kG, false>(a, s))); }
+  COAT_DISPATCH_G(G, (launch_step<kG, true>(a, s)));
 }
 
-int dispatch_quant(const QuantArgs& a, int32_t G, hipStream_t s) {
-  if (a.expand) { COAT_DISPATCH_G(G, (launch_quant<kG, true>(a, s))); }
-  COAT_DISPATCH_G(G, (launch_quant<kG, false>(a, s)));
-}
+int dispatch_quant(const QuantArgs& a, int32_t G, hipStream_t s) { COAT_DISPATCH_G(G, (launch_quant<kG>(a, s))); }
 
 int dispatch_dequant(const DequantArgs& a, int32_t G, hipStream_t s) {
   COAT_DISPATCH_G(G, (launch_dequant<kG>(a, s)));
 }
+
+constexpr uint32_t kStepFlags = COAT_FLAG_EXPAND | COAT_FLAG_M_E5M2 | COAT_FLAG_V_E5M2 | COAT_FLAG_M_PLAIN |
+                                COAT_FLAG_V_PLAIN;
 
 }  // namespace
 
@@ -868,6 +829,7 @@ int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float
   if (hp->lr < 0.0f || hp->beta1 < 0.0f || hp->beta1 >= 1.0f || hp->beta2 < 0.0f || hp->beta2 >= 1.0f ||
       hp->eps < 0.0f)
     return COAT_ERR_HPARAM;
+  if (hp->flags & ~kStepFlags) return COAT_ERR_HPARAM;
   float k_min = hp->k_min, k_max = hp->k_max;
   if (!resolve_k_bounds(k_min, k_max)) return COAT_ERR_HPARAM;
   if (n == 0) return COAT_OK;
@@ -904,13 +866,19 @@ int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float
   a.denom_scale = static_cast<float>(__builtin_sqrt(omb2 / bc2));
   a.eps = hp->eps;
   a.k_min = k_min; a.k_max = k_max;
-  a.expand = (hp->flags & COAT_FLAG_EXPAND) ? 1u : 0u;
-  return dispatch_step(a, hp->group_size, static_cast<hipStream_t>(hip_stream));
+  const bool expand = (hp->flags & COAT_FLAG_EXPAND) != 0;
+  a.mode_m.e5 = (hp->flags & COAT_FLAG_M_E5M2) != 0;
+  a.mode_v.e5 = (hp->flags & COAT_FLAG_V_E5M2) != 0;
+  a.mode_m.ex = expand && !(hp->flags & COAT_FLAG_M_PLAIN);
+  a.mode_v.ex = expand && !(hp->flags & COAT_FLAG_V_PLAIN);
+  const bool generic = a.mode_m.e5 || a.mode_v.e5 || !a.mode_m.ex || !a.mode_v.ex;
+  return dispatch_step(a, hp->group_size, generic, static_cast<hipStream_t>(hip_stream));
 }
 
 int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags, float k_min, float k_max,
                      uint8_t* q, float* scale, float* k, void* hip_stream) {
   if (!group_ok(G)) return COAT_ERR_GROUP;
+  if (flags & ~(COAT_FLAG_EXPAND | COAT_FLAG_E5M2)) return COAT_ERR_HPARAM;
   if (!resolve_k_bounds(k_min, k_max)) return COAT_ERR_HPARAM;
   if (n == 0) return COAT_OK;
   if (!x || !q || !scale || !k) return COAT_ERR_NULL;
@@ -921,13 +889,15 @@ int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags, floa
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
   a.k_min = k_min; a.k_max = k_max;
-  a.expand = (flags & COAT_FLAG_EXPAND) ? 1u : 0u;
+  a.mode.ex = (flags & COAT_FLAG_EXPAND) != 0;
+  a.mode.e5 = (flags & COAT_FLAG_E5M2) != 0;
   return dispatch_quant(a, G, static_cast<hipStream_t>(hip_stream));
 }
 
 int coat_dequant_group(const uint8_t* q, const float* scale, const float* k, uint64_t n, int32_t G,
-                       float* x, void* hip_stream) {
+                       uint32_t flags, float* x, void* hip_stream) {
   if (!group_ok(G)) return COAT_ERR_GROUP;
+  if (flags & ~(COAT_FLAG_EXPAND | COAT_FLAG_E5M2)) return COAT_ERR_HPARAM;
   if (n == 0) return COAT_OK;
   if (!x || !q || !scale || !k) return COAT_ERR_NULL;
   if (!aligned16(x) || !aligned16(q) || !aligned16(scale) || !aligned16(k)) return COAT_ERR_ALIGN;
@@ -936,6 +906,8 @@ int coat_dequant_group(const uint8_t* q, const float* scale, const float* k, uin
   a.q = q; a.scale = scale; a.k = k; a.x = x;
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
+  a.mode.ex = true;
+  a.mode.e5 = (flags & COAT_FLAG_E5M2) != 0;
   return dispatch_dequant(a, G, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -946,14 +918,14 @@ const char* coat_strerror(int code) {
     case COAT_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
     case COAT_ERR_GROUP: return "group size must be one of 32, 64, 128, 256, 512";
     case COAT_ERR_STEP: return "step must be >= 1";
-    case COAT_ERR_HPARAM: return "hyper-parameter is non-finite or out of its domain";
+    case COAT_ERR_HPARAM: return "hyper-parameter or flag is non-finite, unsupported or out of its domain";
     case COAT_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
     case COAT_ERR_SIZE: return "n is too large";
   }
   return "unknown error code";
 }
 
-int coat_version(void) { return 100; }
+int coat_version(void) { return 200; }
 
 #ifdef COAT_TUNING
 // development builds only: launch-shape knobs for sweeps

@@ -30,8 +30,11 @@ groups they reduce to the stated bar.
           (b) EVERY mismatch, anywhere, must lie inside the band of codes that x_ref +- dx, the
               k bound and the forward error (log2/exp2 of the hardware, a few ulp) allow.  For a
               well conditioned element that band is the neighbouring code: "at most one step".
-  w       |w_gpu - w_ref| <= 1e-6 * |w_ref| + 1e-9 (+ an explicit extra term only in the stress
-          test on states that come from no optimizer trajectory).
+  w       |w_gpu - w_ref| <= 1e-6 * |w_ref| + 1e-9 + 8 ulp of the update |w_ref - w_old| (the update
+          term passes through sqrt, fma, rcp, mul and fma in fp32; for the paper's workloads this
+          term is ~1e-10 and only matters where the update is as large as the weight), plus an
+          explicit model of the update's error only in the stress tests on states that come from
+          no optimizer trajectory.
 """
 import numpy as np
 
@@ -50,8 +53,9 @@ EPS_DQ_M = 6.0 * 2.0 ** -24
 
 #   second moment (plain product exponent): |log2(c/448) / k| <= 17.81 / min(k, 1) is rounded three
 #   times (table, 1/k, product) and enters as ln2 * error, plus exp2 and two roundings
-def eps_dq_v(k_old):
-    return (17.81 / np.minimum(k_old, 1.0)) * 3 * 2.0 ** -24 * np.log(2.0) + 4 * 2.0 ** -24
+def eps_dq_v(k_old, log2_range=17.81):
+    """log2_range: 17.81 for E4M3, 31.81 for E5M2 (the largest |log2(c/fmax)|)."""
+    return (log2_range / np.minimum(k_old, 1.0)) * 3 * 2.0 ** -24 * np.log(2.0) + 4 * 2.0 ** -24
 
 
 def _canon(codes):
@@ -134,7 +138,7 @@ def assert_w(gpu, ref, what="", extra_tol=None):
         what, int(bad.sum()), float((err / tol).max()))
 
 
-def assert_codes(ref_mod, gpu, ref, x_ref, dx, scale_ref, k_ref, tol_k, G, what=""):
+def assert_codes(ref_mod, gpu, ref, x_ref, dx, scale_ref, k_ref, tol_k, G, what="", e5m2=False):
     """Rules (a) and (b) of the module docstring.  x_ref: the fp64 values that were quantized;
     dx: bound on the other side's deviation from them (zeros for exact inputs)."""
     g, r = _canon(gpu), _canon(ref)
@@ -142,6 +146,8 @@ def assert_codes(ref_mod, gpu, ref, x_ref, dx, scale_ref, k_ref, tol_k, G, what=
     ng = (n + G - 1) // G
     neq = np.nonzero(g != r)[0]
     grp = neq // G
+    fmax = 57344.0 if e5m2 else 448.0
+    encode = ref_mod.e5m2_encode if e5m2 else ref_mod.e4m3_encode
 
     # (a) match rate over the regular groups
     regular = tol_k <= K_TOL_REGULAR
@@ -160,7 +166,7 @@ def assert_codes(ref_mod, gpu, ref, x_ref, dx, scale_ref, k_ref, tol_k, G, what=
     if neq.size:
         xi = np.abs(np.asarray(x_ref, dtype=np.float64)[neq])
         dxi = np.asarray(dx, dtype=np.float64)[neq]
-        a = 448.0 * np.asarray(scale_ref, dtype=np.float64)[grp]
+        a = fmax * np.asarray(scale_ref, dtype=np.float64)[grp]
         k = np.asarray(k_ref, dtype=np.float64)[grp]
         tk = np.minimum(tol_k[grp], 0.5)
         free = ~np.isfinite(tol_k[grp])                   # total-cancellation group: anything goes
@@ -170,12 +176,12 @@ def assert_codes(ref_mod, gpu, ref, x_ref, dx, scale_ref, k_ref, tol_k, G, what=
             # forward path: log2 (2 ulp of the result), its product with k, exp2, the scaling
             fwd_hi = np.abs(k * np.log2(np.maximum(r_hi, 1e-300))) * 6 * 2.0 ** -24 * np.log(2.0) + 8 * 2.0 ** -24
             fwd_lo = np.abs(k * np.log2(np.maximum(r_lo, 1e-300))) * 6 * 2.0 ** -24 * np.log(2.0) + 8 * 2.0 ** -24
-            q_hi = np.minimum(448.0 * r_hi ** (k * (1.0 - tk)) * (1.0 + fwd_hi + k * 4e-7), 448.0)
-            q_lo = 448.0 * r_lo ** (k * (1.0 + tk)) * (1.0 - fwd_lo - k * 4e-7)
+            q_hi = np.minimum(fmax * r_hi ** (k * (1.0 - tk)) * (1.0 + fwd_hi + k * 4e-7), fmax)
+            q_lo = fmax * r_lo ** (k * (1.0 + tk)) * (1.0 - fwd_lo - k * 4e-7)
         q_lo = np.where(np.isfinite(q_lo) & (q_lo > 0), q_lo, 0.0)
-        q_hi = np.where(np.isfinite(q_hi), q_hi, 448.0)
-        lo_code = np.array([ref_mod.e4m3_encode(float(v)) & 0x7F for v in q_lo])
-        hi_code = np.array([ref_mod.e4m3_encode(float(v)) & 0x7F for v in q_hi])
+        q_hi = np.where(np.isfinite(q_hi), q_hi, fmax)
+        lo_code = np.array([encode(float(v)) & 0x7F for v in q_lo])
+        hi_code = np.array([encode(float(v)) & 0x7F for v in q_hi])
         gm = g[neq] & 0x7F
         inside = free | ((gm >= lo_code) & (gm <= hi_code))
         sign_ok = free | (((g[neq] ^ r[neq]) & 0x80) == 0) | (gm == 0) | ((r[neq] & 0x7F) == 0) | (dxi >= xi)

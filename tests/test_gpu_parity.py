@@ -58,23 +58,31 @@ def new_moments(ref, st_old, g_bits, G, hp_over):
     """The fp64 new moments of the reference side and the bound dx on how far the fp32 side's
     moments may be from them (see parity.py).  Used for tolerances only, never as expected values."""
     kw = dict(HP)
-    kw.update(hp_over)
+    kw.update({k: v for k, v in hp_over.items() if k in HP})
     b1, b2 = float(np.float32(kw["beta1"])), float(np.float32(kw["beta2"]))
     n = st_old["m_q"].size
-    m_old = ref.dequant_group(st_old["m_q"], st_old["m_scale"], st_old["m_k"], G, f64=True)
-    v_old = ref.dequant_group(st_old["v_q"], st_old["v_scale"], st_old["v_k"], G, f64=True)
+    m_e5, v_e5 = bool(hp_over.get("m_e5m2")), bool(hp_over.get("v_e5m2"))
+    m_old = ref.dequant_group(st_old["m_q"], st_old["m_scale"], st_old["m_k"], G, f64=True, e5m2=m_e5)
+    v_old = ref.dequant_group(st_old["v_q"], st_old["v_scale"], st_old["v_k"], G, f64=True, e5m2=v_e5)
     g = S.bf16_bits_to_f32(g_bits).astype(np.float64)
     m_t = b1 * m_old + (1 - b1) * g
     v_t = b2 * v_old + (1 - b2) * g * g
     dm = EPS_DQ_M * b1 * np.abs(m_old) + 2.0 ** -22 * np.abs(m_t)
-    dv = np.repeat(eps_dq_v(st_old["v_k"].astype(np.float64)), G)[:n] * b2 * v_old + 2.0 ** -22 * v_t
+    ev = eps_dq_v(st_old["v_k"].astype(np.float64), 31.81 if v_e5 else 17.81)
+    dv = np.repeat(ev, G)[:n] * b2 * v_old + 2.0 ** -22 * v_t
     return m_t, dm, v_t, dv
 
 
-def check_step(ref, tag, w_g, st_g, w_r, st_r, st_old, g_bits, G, expand=True, extra_w_tol=None, **over):
-    """st_old: the state both sides started from (it conditions the tolerances)."""
+def check_step(ref, tag, w_g, st_g, w_r, st_r, st_old, g_bits, G, expand=True, extra_w_tol=None, w_old=None,
+               **over):
+    """st_old, w_old: the state both sides started from (it conditions the tolerances)."""
+    if w_old is not None:
+        # the update term itself goes through sqrt, fma, rcp, mul, fma in fp32: <= 8 ulp of its size
+        upd = 8 * 2.0 ** -24 * np.abs(w_r.astype(np.float64) - w_old.astype(np.float64))
+        extra_w_tol = upd if extra_w_tol is None else extra_w_tol + upd
     k_min = over.get("k_min", 0.0) or 0.0625
     k_max = over.get("k_max", 0.0) or 1024.0
+    hp_only = {k: v for k, v in over.items() if k in HP}
     assert_w(w_g, w_r, tag + " w", extra_w_tol)
     assert_scale(st_g["m_scale"], st_r["m_scale"], tag + " m scale")
     assert_scale(st_g["v_scale"], st_r["v_scale"], tag + " v scale")
@@ -82,12 +90,13 @@ def check_step(ref, tag, w_g, st_g, w_r, st_r, st_old, g_bits, G, expand=True, e
     stats = {}
     for name, x, dx in (("m", m_t, dm), ("v", v_t, dv)):
         tol, cl = k_tolerance(st_r[name + "_k"], x, dx, G, k_min, k_max)
-        if not expand:
+        if not expand or over.get(name + "_plain"):
             tol = np.full_like(tol, 1e-6)            # k is 1 on both sides
+            assert np.all(st_g[name + "_k"] == 1.0)
         in_bar = assert_k(st_g[name + "_k"], st_r[name + "_k"], tol, cl, tag + " %s k" % name)
         n_bad, bad_regular, n_irregular = assert_codes(
             ref, st_g[name + "_q"], st_r[name + "_q"], x, dx, st_r[name + "_scale"], st_r[name + "_k"], tol, G,
-            tag + " %s codes" % name)
+            tag + " %s codes" % name, e5m2=bool(over.get(name + "_e5m2")))
         stats[name] = dict(bad=n_bad, bad_regular=bad_regular, irregular=n_irregular, k_in_bar=in_bar)
     assert np.all(st_g["v_q"] < 0x80), tag + ": a second-moment code carries a sign"
     return stats
@@ -100,9 +109,10 @@ def lockstep(coat, ref, n, G, grads_fn, steps, seed, expand=True, state=None, **
     for t in range(1, steps + 1):
         g = grads_fn(t)
         w_g, st_g, _ = gpu_step(coat, w, g, st, G, t, expand, **over)
-        st_old = st
+        st_old, w_old = st, w
         w, st = ref_step(ref, w, g, st, G, t, expand, **over)
-        stats = check_step(ref, "n=%d G=%d step %d" % (n, G, t), w_g, st_g, w, st, st_old, g, G, expand, **over)
+        stats = check_step(ref, "n=%d G=%d step %d" % (n, G, t), w_g, st_g, w, st, st_old, g, G, expand,
+                           w_old=w_old, **over)
         total_bad += stats["m"]["bad_regular"] + stats["v"]["bad_regular"]
     # over the whole run the match rate must hold too
     assert total_bad <= max(2, int(1e-4 * 2 * n * steps)), total_bad
@@ -178,7 +188,7 @@ def quant_inputs(kind, n, seed):
     raise ValueError(kind)
 
 
-def check_quant(ref, tag, x, G, gpu, expect, expand):
+def check_quant(ref, tag, x, G, gpu, expect, expand, e5m2=False):
     """Standalone quantizer: both sides see the same fp32 inputs, so dx = 0 and the stated bar
     applies as it stands (k: 1e-6, widened only by 1/ln R for groups narrower than e)."""
     (q_g, s_g, k_g), (q_r, s_r, k_r) = gpu, expect
@@ -188,7 +198,7 @@ def check_quant(ref, tag, x, G, gpu, expect, expand):
         tol = np.full_like(tol, 1e-6)
     assert_scale(s_g, s_r, tag)
     assert_k(k_g, k_r, tol, cl, tag)
-    assert_codes(ref, q_g, q_r, x, zero, s_r, k_r, tol, G, tag)
+    assert_codes(ref, q_g, q_r, x, zero, s_r, k_r, tol, G, tag, e5m2=e5m2)
 
 
 @pytest.mark.parametrize("G", GROUPS)
@@ -396,3 +406,49 @@ def test_quant_nearly_constant_groups(coat, ref):
     n_bad = int(np.sum(q_g != q_r))
     assert np.all(np.abs((q_g & 0x7F).astype(int) - (q_r & 0x7F).astype(int)) <= 1)
     assert n_bad <= n // 100
+
+
+# --- the format / expansion grid of Table 1 ----------------------------------------------------------
+
+import itertools
+
+GRID = [c for c in itertools.product([False, True], repeat=4) if any(c)]   # all but the default cell
+
+
+@pytest.mark.parametrize("G", [32, 128, 512])
+@pytest.mark.parametrize("expand", [True, False])
+def test_quant_dequant_e5m2(coat, ref, G, expand):
+    n = 21 * 1024 + 3 * G + 9
+    x = quant_inputs("normal", n, seed=G)
+    q_g, s_g, k_g = (t.cpu().numpy() for t in coat.coat_quant_group(dev(x), G, expand=expand, e5m2=True))
+    q_r, s_r, k_r = ref.quant_group(x, G, expand=expand, e5m2=True)
+    check_quant(ref, "e5m2 quant G=%d expand=%s" % (G, expand), x, G, (q_g, s_g, k_g), (q_r, s_r, k_r), expand, e5m2=True)
+    assert np.all((q_g & 0x7F) <= 0x7B)                 # never infinity or NaN
+    # dequantizer on every code byte of the format
+    codes = (np.arange(n) % 256).astype(np.uint8)
+    ng = (n + G - 1) // G
+    rng = np.random.default_rng(G)
+    scale = np.exp(rng.uniform(np.log(1e-14), np.log(1e-4), ng)).astype(np.float32)
+    k = np.exp(rng.uniform(np.log(0.5), np.log(40.0), ng)).astype(np.float32)
+    x_g = coat.coat_dequant_group(dev(codes), dev(scale), dev(k), G, e5m2=True).cpu().numpy().astype(np.float64)
+    x_r = ref.dequant_group(codes, scale, k, G, f64=True, e5m2=True)
+    fin = np.isfinite(x_r)
+    # infinity / NaN codes (never written by the quantizer) come back non-finite
+    assert not np.any(np.isfinite(x_g[~fin]))
+    nz = fin & (x_r != 0)
+    assert np.all(np.abs(x_g[nz] / x_r[nz] - 1.0) <= 8 * 2.0 ** -24)
+    assert np.all(x_g[fin & (x_r == 0)] == 0)
+
+
+@pytest.mark.parametrize("m_e5m2,m_plain,v_e5m2,v_plain", GRID)
+def test_step_format_grid(coat, ref, m_e5m2, m_plain, v_e5m2, v_plain):
+    n, G = 96 * 1024 + 2 * 128 + 5, 128
+    lockstep(coat, ref, n, G, lambda t: S.grads_normal(n, 13, t, G=G, outlier_frac=0.01), steps=3, seed=13,
+             m_e5m2=m_e5m2, m_plain=m_plain, v_e5m2=v_e5m2, v_plain=v_plain)
+
+
+@pytest.mark.parametrize("G", [32, 64, 256, 512])
+def test_step_format_grid_other_group_sizes(coat, ref, G):
+    n = 64 * 1024 + G + 1
+    lockstep(coat, ref, n, G, lambda t: S.grads_lognormal(n, 14, t), steps=2, seed=14, m_e5m2=True, v_plain=True)
+    lockstep(coat, ref, n, G, lambda t: S.grads_normal(n, 15, t), steps=2, seed=15, m_plain=True, v_e5m2=True)
