@@ -121,6 +121,7 @@ def main():
     ap.add_argument("--v-e5m2", action="store_true", help="second moment in E5M2")
     ap.add_argument("--m-plain", action="store_true", help="first moment without dynamic range expansion")
     ap.add_argument("--v-plain", action="store_true", help="second moment without dynamic range expansion")
+    ap.add_argument("--emit-bf16", action="store_true", help="also write the bf16 copy of the new weights (+2 B/param)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (scales the rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -164,13 +165,18 @@ def main():
     else:
         grads = [S.torch_grads_lognormal(n, dev, gen) for _ in range(2)]
     del mask
+    w_bf16 = torch.empty(n, dtype=torch.bfloat16, device=dev) if args.emit_bf16 else None
     torch.cuda.synchronize()
 
     def step(t):
         hp = C.make_hparams(step=t, group_size=G, m_e5m2=args.m_e5m2, v_e5m2=args.v_e5m2,
                             m_plain=args.m_plain, v_plain=args.v_plain, **HP)
-        C.coat_fp8_adamw_step(w, grads[t & 1], st["m_q"], st["m_scale"], st["m_k"],
-                              st["v_q"], st["v_scale"], st["v_k"], hp)
+        if args.emit_bf16:
+            C.coat_fp8_adamw_step_bf16w(w, w_bf16, grads[t & 1], st["m_q"], st["m_scale"], st["m_k"],
+                                        st["v_q"], st["v_scale"], st["v_k"], hp)
+        else:
+            C.coat_fp8_adamw_step(w, grads[t & 1], st["m_q"], st["m_scale"], st["m_k"],
+                                  st["v_q"], st["v_scale"], st["v_k"], hp)
 
     t = 0
     for _ in range(args.warmup):
@@ -198,7 +204,7 @@ def main():
     generic = args.m_e5m2 or args.v_e5m2 or args.m_plain or args.v_plain
     ms_per_step = wall / args.steps * 1e3
     value = n * args.steps / wall
-    algo_bytes = bytes_per_param(G) * n
+    algo_bytes = (bytes_per_param(G) + (2.0 if args.emit_bf16 else 0.0)) * n
     achieved = algo_bytes / avg_launch_s / 1e9
     out = {
         "metric": "params updated/sec, FP8-state AdamW (E4M3 m/v, per-group scale + dynamic range expansion)",
@@ -219,7 +225,7 @@ def main():
                 args.workload], n, G, args.grads) + (
                     ", m %s%s, v %s%s" % ("E5M2" if args.m_e5m2 else "E4M3", "" if args.m_plain else "+expand",
                                             "E5M2" if args.v_e5m2 else "E4M3", "" if args.v_plain else "+expand")
-                    if generic else ""),
+                    if generic else "") + (", bf16 weight copy" if args.emit_bf16 else ""),
             "params": n, "group_size": G, "hbm_gbs": achieved, "hbm_frac_of_peak": achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_profile_traffic(args.workload, G),

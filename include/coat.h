@@ -90,6 +90,18 @@ int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
                         uint64_t n, const coat_adamw_hparams* hp, void* hip_stream);
 
 /*
+ * The same step that ALSO writes the new weights rounded to bf16 (nearest even) into
+ * w_bf16 [n]: the copy a mixed-precision trainer hands to its BF16/FP8 model (the paper trains
+ * such models from FP32 master weights: Sec. 2, Appendix A), produced in the same pass instead of
+ * by a separate cast kernel (+2 bytes written per parameter).  w_bf16 must be 16-byte aligned
+ * and must not overlap the other buffers; NULL makes this call identical to coat_fp8_adamw_step.
+ */
+int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_bf16,
+                              uint8_t* m_q, float* m_scale, float* m_k,
+                              uint8_t* v_q, float* v_scale, float* v_k,
+                              uint64_t n, const coat_adamw_hparams* hp, void* hip_stream);
+
+/*
  * Per-group quantizer with dynamic range expansion (Sec. 3 quantizer Q applied to f(X),
  * Sec. 4.2): the second half of the step on its own.
  * x [n] fp32 in;  q [n] codes, scale/k [ceil(n/G)] out.  All-zero group: scale 0, k 1.

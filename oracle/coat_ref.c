@@ -229,10 +229,25 @@ static double bf16_to_double(uint16_t bits) {
   return (double)cvt.f;
 }
 
+/* fp32 -> bf16, round to nearest even (bf16 is the upper half of an fp32) */
+static uint16_t f32_to_bf16(float f) {
+  union { uint32_t u; float f; } cvt;
+  cvt.f = f;
+  if (f != f) return (uint16_t)((cvt.u >> 16) | 0x0040);      /* keep NaN a NaN */
+  return (uint16_t)((cvt.u + 0x7FFFu + ((cvt.u >> 16) & 1u)) >> 16);
+}
+
 int coat_ref_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
                             uint8_t* m_q, float* m_scale, float* m_k,
                             uint8_t* v_q, float* v_scale, float* v_k,
                             uint64_t n, const coat_ref_hparams* hp) {
+  return coat_ref_fp8_adamw_step_bf16w(w, NULL, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, n, hp);
+}
+
+int coat_ref_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_bf16,
+                                  uint8_t* m_q, float* m_scale, float* m_k,
+                                  uint8_t* v_q, float* v_scale, float* v_k,
+                                  uint64_t n, const coat_ref_hparams* hp) {
   double lr, b1, b2, eps, wd, bc1, bc2;
   float k_min, k_max;
   int32_t G;
@@ -287,6 +302,7 @@ int coat_ref_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
       double v_hat = v_t / bc2;
       /* the weight sees the new moments BEFORE they are quantized */
       w[lo + i] = (float)(wi - lr * (m_hat / (sqrt(v_hat) + eps) + wd * wi));
+      if (w_bf16) w_bf16[lo + i] = f32_to_bf16(w[lo + i]);   /* the model's copy of the new weight */
       mt[i] = (float)m_t;                        /* moments live in fp32 before Q */
       vt[i] = (float)v_t;
     }

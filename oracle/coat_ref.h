@@ -81,6 +81,14 @@ int coat_ref_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
                             uint8_t* v_q, float* v_scale, float* v_k,
                             uint64_t n, const coat_ref_hparams* hp);
 
+/* The same step that also writes the new weights rounded to bf16 (nearest even) into w_bf16 [n]:
+ * the copy a mixed-precision trainer hands to its BF16 model (the paper trains BF16/FP8 models
+ * from FP32 master weights, Sec. 2 and Appendix A).  w_bf16 == NULL: no copy. */
+int coat_ref_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_bf16,
+                                  uint8_t* m_q, float* m_scale, float* m_k,
+                                  uint8_t* v_q, float* v_scale, float* v_k,
+                                  uint64_t n, const coat_ref_hparams* hp);
+
 /* Number of threads the step will use (OpenMP max threads; 1 when built without it). */
 int coat_ref_num_threads(void);
 

@@ -82,6 +82,9 @@ def lib():
         L.coat_ref_fp8_adamw_step.restype = ctypes.c_int
         L.coat_ref_fp8_adamw_step.argtypes = [f32p, u16p, u8p, f32p, f32p, u8p, f32p, f32p,
                                               ctypes.c_uint64, ctypes.POINTER(HParams)]
+        L.coat_ref_fp8_adamw_step_bf16w.restype = ctypes.c_int
+        L.coat_ref_fp8_adamw_step_bf16w.argtypes = [f32p, u16p, u16p, u8p, f32p, f32p, u8p, f32p, f32p,
+                                                    ctypes.c_uint64, ctypes.POINTER(HParams)]
         L.coat_ref_num_threads.restype = ctypes.c_int
         L.coat_ref_num_threads.argtypes = []
         _lib = L
@@ -172,9 +175,19 @@ def make_hparams(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, ste
                    step_flags(expand, m_e5m2, v_e5m2, m_plain, v_plain), k_min, k_max)
 
 
-def fp8_adamw_step(w, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, hp: HParams) -> int:
-    """In-place step on numpy arrays.  grad_bf16 holds raw bf16 bit patterns (uint16)."""
+def fp8_adamw_step(w, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, hp: HParams, w_bf16=None) -> int:
+    """In-place step on numpy arrays.  grad_bf16 holds raw bf16 bit patterns (uint16).
+    w_bf16 (uint16 [n], optional): receives the new weights rounded to bf16."""
     n = w.size
+    if w_bf16 is not None:
+        assert w_bf16.size == n
+        return int(lib().coat_ref_fp8_adamw_step_bf16w(
+            _ptr(w, np.float32, ctypes.c_float), _ptr(w_bf16, np.uint16, ctypes.c_uint16),
+            _ptr(grad_bf16, np.uint16, ctypes.c_uint16),
+            _ptr(m_q, np.uint8, ctypes.c_uint8), _ptr(m_scale, np.float32, ctypes.c_float),
+            _ptr(m_k, np.float32, ctypes.c_float),
+            _ptr(v_q, np.uint8, ctypes.c_uint8), _ptr(v_scale, np.float32, ctypes.c_float),
+            _ptr(v_k, np.float32, ctypes.c_float), n, ctypes.byref(hp)))
     ng = n_groups(n, hp.group_size)
     assert grad_bf16.size == n and m_q.size == n and v_q.size == n
     for a in (m_scale, m_k, v_scale, v_k):

@@ -15,7 +15,7 @@ from . import build as _build
 FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN = 1, 2, 2, 4, 8, 16
 SUPPORTED_GROUP_SIZES = (32, 64, 128, 256, 512)
 
-EXPORTS = ("coat_fp8_adamw_step", "coat_quant_group", "coat_dequant_group", "coat_strerror", "coat_version")
+EXPORTS = ("coat_fp8_adamw_step", "coat_fp8_adamw_step_bf16w", "coat_quant_group", "coat_dequant_group", "coat_strerror", "coat_version")
 
 
 class CoatError(RuntimeError):
@@ -67,6 +67,8 @@ def lib():
         vp = ctypes.c_void_p
         L.coat_fp8_adamw_step.restype = ctypes.c_int
         L.coat_fp8_adamw_step.argtypes = [vp] * 8 + [ctypes.c_uint64, ctypes.POINTER(HParams), vp]
+        L.coat_fp8_adamw_step_bf16w.restype = ctypes.c_int
+        L.coat_fp8_adamw_step_bf16w.argtypes = [vp] * 9 + [ctypes.c_uint64, ctypes.POINTER(HParams), vp]
         L.coat_quant_group.restype = ctypes.c_int
         L.coat_quant_group.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32,
                                        ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
@@ -119,6 +121,18 @@ def coat_fp8_adamw_step(w, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, hp: 
     ng = n_groups(n, hp.group_size) if hp.group_size > 0 else 0
     _check(lib().coat_fp8_adamw_step(
         _dev_ptr(w, torch.float32), _dev_ptr(grad_bf16, torch.bfloat16, n),
+        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, torch.float32, ng), _dev_ptr(m_k, torch.float32, ng),
+        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, torch.float32, ng), _dev_ptr(v_k, torch.float32, ng),
+        n, ctypes.byref(hp), _stream()))
+
+
+def coat_fp8_adamw_step_bf16w(w, w_bf16, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, hp: HParams) -> None:
+    """coat_fp8_adamw_step that also writes the new weights as bfloat16 into w_bf16 [n]."""
+    import torch
+    n = w.numel()
+    ng = n_groups(n, hp.group_size) if hp.group_size > 0 else 0
+    _check(lib().coat_fp8_adamw_step_bf16w(
+        _dev_ptr(w, torch.float32), _dev_ptr(w_bf16, torch.bfloat16, n), _dev_ptr(grad_bf16, torch.bfloat16, n),
         _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, torch.float32, ng), _dev_ptr(m_k, torch.float32, ng),
         _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, torch.float32, ng), _dev_ptr(v_k, torch.float32, ng),
         n, ctypes.byref(hp), _stream()))

@@ -33,6 +33,8 @@ constexpr int kChunk = kWave * kEPL;      // elements one wavefront handles per 
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 #include "coat_tables.inc"
 
@@ -68,6 +70,7 @@ template <class Mode> __device__ __forceinline__ float fmt_log2_range(const Mode
 
 struct StepArgs {
   float* w;
+  uint16_t* wb;          // optional bf16 copy of the new weights (nullptr: none)
   const uint16_t* g;
   uint8_t* mq; float* ms; float* mk;
   uint8_t* vq; float* vs; float* vk;
@@ -242,6 +245,28 @@ __device__ __forceinline__ void tile_rows_to_lanes_bf16(u32x4* tile, int lane, c
     g[8 * j + 4] = as_f32(t.z << 16); g[8 * j + 5] = as_f32(t.z & 0xffff0000u);
     g[8 * j + 6] = as_f32(t.w << 16); g[8 * j + 7] = as_f32(t.w & 0xffff0000u);
   }
+}
+
+// two fp32 -> packed bf16 pair (round to nearest even: the native pack convert)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// 16 consecutive fp32 per lane -> bf16 rows written straight to memory (p: start of the chunk)
+__device__ __forceinline__ void tile_lanes_to_rows_store_bf16(u32x4* tile, int lane, const float (&x)[kEPL],
+                                                              uint16_t* p) {
+  const u32x4* const row = tile + lane + (lane >> 3);
+  u32x4* const own = tile + 2 * lane + (lane >> 2);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const u32x4 t = {pack_bf16(x[8 * j + 0], x[8 * j + 1]), pack_bf16(x[8 * j + 2], x[8 * j + 3]),
+                     pack_bf16(x[8 * j + 4], x[8 * j + 5]), pack_bf16(x[8 * j + 6], x[8 * j + 7])};
+    own[j] = t;
+  }
+  u32x4* q = reinterpret_cast<u32x4*>(p);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) stg<16>(q + 64 * j + lane, row[72 * j]);
 }
 
 // The lookup table in LDS: per format 256 entries so that the whole code byte indexes it (the sign
@@ -512,6 +537,7 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const ModeM& mm
   step_core<G>(a, mm, mv, lut, w, g, mc, vc, meta);
 
   tile_lanes_to_rows_store(tiles.w, lane, w, a.w + cb);
+  if (a.wb) tile_lanes_to_rows_store_bf16(tiles.g, lane, w, a.wb + cb);   // the gradient tile is free by now
   const u32x4 mo = {mc[0], mc[1], mc[2], mc[3]}, vo = {vc[0], vc[1], vc[2], vc[3]};
   stg<2>(reinterpret_cast<u32x4*>(a.mq + cb) + lane, mo);
   stg<2>(reinterpret_cast<u32x4*>(a.vq + cb) + lane, vo);
@@ -590,6 +616,14 @@ __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
   meta.v_k = gvalid ? a.vk[gidx] : 1.0f;
   step_core<G>(a, mm, mv, lut, w, g, mc, vc, meta);
   store_f32x16_guarded(a.w, base, a.n, w);
+  if (a.wb) {
+#pragma unroll
+    for (int e = 0; e < kEPL; e += 2) {
+      const uint32_t pr = pack_bf16(w[e], w[e + 1]);
+      if (base + e < a.n) a.wb[base + e] = static_cast<uint16_t>(pr);
+      if (base + e + 1 < a.n) a.wb[base + e + 1] = static_cast<uint16_t>(pr >> 16);
+    }
+  }
   store_codes16_guarded(a.mq, base, a.n, mc);
   store_codes16_guarded(a.vq, base, a.n, vc);
   if (gvalid && (lane % LPG) == 0) {
@@ -820,6 +854,12 @@ extern "C" {
 int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float* m_scale, float* m_k,
                         uint8_t* v_q, float* v_scale, float* v_k, uint64_t n,
                         const coat_adamw_hparams* hp, void* hip_stream) {
+  return coat_fp8_adamw_step_bf16w(w, nullptr, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, n, hp, hip_stream);
+}
+
+int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_bf16, uint8_t* m_q,
+                              float* m_scale, float* m_k, uint8_t* v_q, float* v_scale, float* v_k,
+                              uint64_t n, const coat_adamw_hparams* hp, void* hip_stream) {
   if (!hp) return COAT_ERR_NULL;
   if (!group_ok(hp->group_size)) return COAT_ERR_GROUP;
   if (hp->step < 1) return COAT_ERR_STEP;
@@ -835,7 +875,7 @@ int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float
   if (n == 0) return COAT_OK;
   if (!w || !grad_bf16 || !m_q || !m_scale || !m_k || !v_q || !v_scale || !v_k) return COAT_ERR_NULL;
   if (!aligned16(w) || !aligned16(grad_bf16) || !aligned16(m_q) || !aligned16(v_q) ||
-      !aligned16(m_scale) || !aligned16(m_k) || !aligned16(v_scale) || !aligned16(v_k))
+      !aligned16(m_scale) || !aligned16(m_k) || !aligned16(v_scale) || !aligned16(v_k) || !aligned16(w_bf16))
     return COAT_ERR_ALIGN;
   if (n > (1ull << 46)) return COAT_ERR_SIZE;
 
@@ -853,7 +893,7 @@ int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float
   if (!(bc1 > 0.0) || !(bc2 > 0.0)) return COAT_ERR_HPARAM;   // beta == 0 gives bc == 1, fine
 
   StepArgs a;
-  a.w = w; a.g = grad_bf16; a.mq = m_q; a.ms = m_scale; a.mk = m_k; a.vq = v_q; a.vs = v_scale; a.vk = v_k;
+  a.w = w; a.wb = w_bf16; a.g = grad_bf16; a.mq = m_q; a.ms = m_scale; a.mk = m_k; a.vq = v_q; a.vs = v_scale; a.vk = v_k;
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(hp->group_size) - 1) / static_cast<uint64_t>(hp->group_size);
   a.one_minus_beta1 = 1.0f - hp->beta1;               // exact (Sterbenz) for beta >= 0.5

@@ -452,3 +452,51 @@ def test_step_format_grid_other_group_sizes(coat, ref, G):
     n = 64 * 1024 + G + 1
     lockstep(coat, ref, n, G, lambda t: S.grads_lognormal(n, 14, t), steps=2, seed=14, m_e5m2=True, v_plain=True)
     lockstep(coat, ref, n, G, lambda t: S.grads_normal(n, 15, t), steps=2, seed=15, m_plain=True, v_e5m2=True)
+
+
+# --- the step that also emits the bf16 model weights ------------------------------------------------
+
+@pytest.mark.parametrize("n,G,generic", [(40 * 1024 + 3 * 128 + 7, 128, False), (9 * 1024 + 65, 64, True), (700, 128, False)])
+def test_step_with_bf16_weight_copy(coat, ref, n, G, generic):
+    w = S.weights(n, 16)
+    st = S.random_state(n, G, seed=16) if not generic else S.zero_state(n, G)
+    g = S.grads_normal(n, 16, 1, G=G, outlier_frac=0.02)
+    kw = dict(m_e5m2=True) if generic else {}
+    hp = coat.make_hparams(step=4, group_size=G, **HP, **kw)
+    pad = 64
+    # plain entry
+    tw, tg = dev(w), dev_bf16(g)
+    ts = {k: dev(v) for k, v in st.items()}
+    coat.coat_fp8_adamw_step(tw, tg, ts["m_q"], ts["m_scale"], ts["m_k"], ts["v_q"], ts["v_scale"], ts["v_k"], hp)
+    # emitting entry, canaries around the bf16 buffer
+    tw2 = dev(w)
+    ts2 = {k: dev(v) for k, v in st.items()}
+    wb = torch.full((n + 2 * pad,), 7.0, dtype=torch.bfloat16, device="cuda")
+    coat.coat_fp8_adamw_step_bf16w(tw2, wb[pad:pad + n], tg, ts2["m_q"], ts2["m_scale"], ts2["m_k"],
+                                   ts2["v_q"], ts2["v_scale"], ts2["v_k"], hp)
+    torch.cuda.synchronize()
+    assert torch.equal(tw, tw2)                                        # nothing else changes
+    for k in ts:
+        assert torch.equal(ts[k], ts2[k]), k
+    assert torch.all(wb[:pad] == 7.0) and torch.all(wb[pad + n:] == 7.0)
+    got = wb[pad:pad + n]
+    assert torch.equal(got.view(torch.int16), tw2.to(torch.bfloat16).view(torch.int16))   # RNE of its own fp32 weights
+    # against the oracle's copy: equal except where the two fp32 weights straddle a bf16 rounding tie
+    w_r = w.copy()
+    st_r = {k: v.copy() for k, v in st.items()}
+    wb_r = np.zeros(n, np.uint16)
+    rh = ref.make_hparams(step=4, group_size=G, **HP, **kw)
+    assert ref.fp8_adamw_step(w_r, g, st_r["m_q"], st_r["m_scale"], st_r["m_k"], st_r["v_q"], st_r["v_scale"],
+                              st_r["v_k"], rh, w_bf16=wb_r) == 0
+    got_bits = got.view(torch.int16).cpu().numpy().view(np.uint16).astype(np.int32)
+    diff = np.abs(got_bits - wb_r.astype(np.int32))
+    assert diff.max() <= 1 and np.mean(diff != 0) <= 2e-3
+
+
+def test_bf16_entry_rejects_misaligned_copy(coat):
+    import ctypes
+    L = coat.lib()
+    ok = ctypes.c_void_p(0x1000)
+    hp = coat.make_hparams()
+    args = [ok, ctypes.c_void_p(0x1002)] + [ok] * 7
+    assert L.coat_fp8_adamw_step_bf16w(*args, 4096, ctypes.byref(hp), None) == -2

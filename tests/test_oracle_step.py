@@ -209,3 +209,23 @@ def test_argument_errors_and_empty_input(ref):
     assert ref.fp8_adamw_step(w, g, st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"], hp) == -1
     hp = ref.make_hparams(step=1, group_size=0, **HP)
     assert ref.lib().coat_ref_fp8_adamw_step(None, None, None, None, None, None, None, None, 0, hp) == 0
+
+
+def test_bf16_weight_copy_is_library_rounding(ref):
+    # the optional bf16 copy is the new fp32 weight rounded to nearest even: torch's cast is the pin
+    n, G = 4096 + 33, 128
+    w = S.weights(n, seed=8)
+    w[:4] = [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), 0.0]      # exact bf16 ties and a zero
+    st = S.zero_state(n, G)
+    g = S.grads_normal(n, seed=8, step=1)
+    g[:4] = 0
+    wb = np.zeros(n, np.uint16)
+    hp = ref.make_hparams(step=1, group_size=G, lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0)
+    w_plain = w.copy()
+    st2 = S.zero_state(n, G)
+    assert ref.fp8_adamw_step(w, g, st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"], hp, w_bf16=wb) == 0
+    assert ref.fp8_adamw_step(w_plain, g, st2["m_q"], st2["m_scale"], st2["m_k"], st2["v_q"], st2["v_scale"], st2["v_k"], hp) == 0
+    assert np.array_equal(w, w_plain) and np.array_equal(st["m_q"], st2["m_q"])   # the copy changes nothing else
+    lib = torch.from_numpy(w).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(wb, lib)
+    assert list(wb[:4]) == [0x3F80, 0x3F82, 0xBF80, 0x0000]                        # ties go to the even mantissa
