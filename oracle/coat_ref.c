@@ -221,6 +221,71 @@ void coat_ref_dequant_group(const uint8_t* q, const float* scale, const float* k
   }
 }
 
+/* ---- activation quantizers (Sec. 5.2): bf16 in, E4M3 out, no expansion ---------------- */
+
+static float bf16_to_float(uint16_t bits) {
+  union { uint32_t u; float f; } cvt;
+  cvt.u = (uint32_t)bits << 16;
+  return cvt.f;
+}
+
+/* 1xG per-group quantization of activations (the fine-grained flow of the non-linear layers;
+ * G = 16 in the paper's experiments): per group S = max|X| / 448, X_fp8 = round(X / S), the
+ * quotient formed in fp32 (the activation arithmetic is not wider than that). */
+void coat_ref_act_quant_group(const uint16_t* x_bf16, uint64_t n, int32_t G,
+                              uint8_t* q, float* scale) {
+  int64_t ng, gi;
+  if (!x_bf16 || !q || !scale || G < 1 || n == 0) return;
+  ng = (int64_t)((n + (uint64_t)G - 1) / (uint64_t)G);
+#pragma omp parallel for schedule(static)
+  for (gi = 0; gi < ng; ++gi) {
+    uint64_t lo = (uint64_t)gi * (uint64_t)G, i;
+    uint64_t len = (n - lo < (uint64_t)G) ? n - lo : (uint64_t)G;
+    float amax = 0.0f, s;
+    for (i = 0; i < len; ++i) {
+      float ax = fabsf(bf16_to_float(x_bf16[lo + i]));
+      if (ax > amax) amax = ax;
+    }
+    s = amax / 448.0f;
+    scale[gi] = s;
+    for (i = 0; i < len; ++i) {
+      float x = bf16_to_float(x_bf16[lo + i]);
+      q[lo + i] = (s > 0.0f) ? coat_ref_e4m3_encode((double)(x / s)) : (uint8_t)(signbit(x) ? 0x80 : 0x00);
+    }
+  }
+}
+
+/* Group Scaling (Sec. 5.2): per-tensor quantization whose max reduction is split in two stages,
+ * (1) the maximum of every 1xG group, kept as an intermediate tensor, (2) the maximum of that
+ * G-times smaller tensor.  Then S = max|X| / 448 for the whole tensor and X_fp8 = round(X / S).
+ * group_amax [ceil(n/G)] and tensor_scale [1] are outputs. */
+void coat_ref_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G,
+                               float* group_amax, float* tensor_scale, uint8_t* q) {
+  int64_t ng, gi, i;
+  float tmax = 0.0f, s;
+  if (!x_bf16 || !q || !group_amax || !tensor_scale || G < 1 || n == 0) return;
+  ng = (int64_t)((n + (uint64_t)G - 1) / (uint64_t)G);
+  for (gi = 0; gi < ng; ++gi) {                  /* stage 1 */
+    uint64_t lo = (uint64_t)gi * (uint64_t)G, j;
+    uint64_t len = (n - lo < (uint64_t)G) ? n - lo : (uint64_t)G;
+    float amax = 0.0f;
+    for (j = 0; j < len; ++j) {
+      float ax = fabsf(bf16_to_float(x_bf16[lo + j]));
+      if (ax > amax) amax = ax;
+    }
+    group_amax[gi] = amax;
+  }
+  for (gi = 0; gi < ng; ++gi)                    /* stage 2 */
+    if (group_amax[gi] > tmax) tmax = group_amax[gi];
+  s = tmax / 448.0f;
+  *tensor_scale = s;
+#pragma omp parallel for schedule(static)
+  for (i = 0; i < (int64_t)n; ++i) {
+    float x = bf16_to_float(x_bf16[i]);
+    q[i] = (s > 0.0f) ? coat_ref_e4m3_encode((double)(x / s)) : (uint8_t)(signbit(x) ? 0x80 : 0x00);
+  }
+}
+
 /* ---- the fused step (Appendix A; update rule of Sec. 3, Eq. 1) ---------------------- */
 
 static double bf16_to_double(uint16_t bits) {

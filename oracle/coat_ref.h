@@ -72,6 +72,19 @@ void coat_ref_dequant_group(const uint8_t* q, const float* scale, const float* k
 void coat_ref_dequant_group_f64(const uint8_t* q, const float* scale, const float* k,
                                 uint64_t n, int32_t G, uint32_t flags, double* x);
 
+/* 1xG per-group activation quantizer (Sec. 5.2: the fine-grained side of the mixed-granularity
+ * flow; G = 16 in the paper's experiments).  x_bf16: raw bf16 patterns.  Per group
+ * scale = fl32(max|x| / 448), code = E4M3(fl32(x / scale)); all-zero group: scale 0, codes 0.
+ * No expansion: that is an optimizer-state technique. */
+void coat_ref_act_quant_group(const uint16_t* x_bf16, uint64_t n, int32_t G,
+                              uint8_t* q, float* scale);
+
+/* Group Scaling (Sec. 5.2): per-tensor quantization with the two-stage max reduction.
+ * Outputs: group_amax [ceil(n/G)] (stage 1), tensor_scale [1] = max(group_amax) / 448 (stage 2),
+ * q [n] = E4M3(fl32(x / tensor_scale)). */
+void coat_ref_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G,
+                               float* group_amax, float* tensor_scale, uint8_t* q);
+
 /* One fused optimizer step (Appendix A): dequantize m, v; update m, v, w; requantize.
  * w: fp32 master weights (in place).  grad_bf16: raw bf16 bit patterns.
  * m_q/v_q: E4M3 codes (in place).  *_scale, *_k: per-group metadata (in place).

@@ -85,6 +85,10 @@ def lib():
         L.coat_ref_fp8_adamw_step_bf16w.restype = ctypes.c_int
         L.coat_ref_fp8_adamw_step_bf16w.argtypes = [f32p, u16p, u16p, u8p, f32p, f32p, u8p, f32p, f32p,
                                                     ctypes.c_uint64, ctypes.POINTER(HParams)]
+        L.coat_ref_act_quant_group.restype = None
+        L.coat_ref_act_quant_group.argtypes = [u16p, ctypes.c_uint64, ctypes.c_int32, u8p, f32p]
+        L.coat_ref_act_quant_tensor.restype = None
+        L.coat_ref_act_quant_tensor.argtypes = [u16p, ctypes.c_uint64, ctypes.c_int32, f32p, f32p, u8p]
         L.coat_ref_num_threads.restype = ctypes.c_int
         L.coat_ref_num_threads.argtypes = []
         _lib = L
@@ -161,6 +165,32 @@ def dequant_group(q: np.ndarray, scale: np.ndarray, k: np.ndarray, G: int, f64: 
                                      _ptr(k, np.float32, ctypes.c_float), n, G, flags,
                                      _ptr(x, np.float32, ctypes.c_float))
     return x
+
+
+def act_quant_group(x_bf16: np.ndarray, G: int):
+    """bf16 bit patterns [n] -> (codes u8 [n], scale f32 [ng])."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16).reshape(-1)
+    n = x.size
+    q = np.zeros(n, np.uint8)
+    scale = np.zeros(n_groups(n, G), np.float32)
+    if n:
+        lib().coat_ref_act_quant_group(_ptr(x, np.uint16, ctypes.c_uint16), n, G,
+                                       _ptr(q, np.uint8, ctypes.c_uint8), _ptr(scale, np.float32, ctypes.c_float))
+    return q, scale
+
+
+def act_quant_tensor(x_bf16: np.ndarray, G: int):
+    """Group Scaling: bf16 bit patterns [n] -> (codes u8 [n], tensor scale f32, group_amax f32 [ng])."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16).reshape(-1)
+    n = x.size
+    q = np.zeros(n, np.uint8)
+    amax = np.zeros(n_groups(n, G), np.float32)
+    ts = np.zeros(1, np.float32)
+    if n:
+        lib().coat_ref_act_quant_tensor(_ptr(x, np.uint16, ctypes.c_uint16), n, G,
+                                        _ptr(amax, np.float32, ctypes.c_float), _ptr(ts, np.float32, ctypes.c_float),
+                                        _ptr(q, np.uint8, ctypes.c_uint8))
+    return q, float(ts[0]), amax
 
 
 def step_flags(expand=True, m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False) -> int:
