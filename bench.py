@@ -104,6 +104,61 @@ def bench_half(args, C, S, torch, dev, gen, n, G):
                      "kernel": "%s_kernel<%d>" % (args.op, G)}}))
 
 
+def bench_act(args, C, S, torch, dev, gen):
+    """The activation quantizers of Sec. 5.2 on a [tokens, hidden] bf16 tensor.  Several distinct
+    input / output buffer sets are cycled so that the working set (far) exceeds the 256 MB of
+    last-level cache and the figure is an HBM figure.  Algorithmic bytes per element:
+      act_group        2 in + 1 out + 4/G scales                              = 3 + 4/G
+      act_tensor       stage 1: 2 in + 4/G out; stage 2: 4/G in; then 2 in + 1 out = 5 + 8/G
+      act_tensor_pre   (group maxima supplied) 4/G in + 2 in + 1 out           = 3 + 4/G"""
+    G = args.act_group_size
+    hidden = 4096
+    n = args.act_tokens * hidden
+    ng = n // G
+    sets = []
+    for _ in range(args.act_buffers):
+        x = S.torch_activations(n, dev, gen, hidden=hidden)
+        sets.append(dict(x=x, q=torch.empty(n, dtype=torch.uint8, device=dev),
+                         pg=torch.empty(ng, dtype=torch.float32, device=dev),
+                         ts=torch.empty(1, dtype=torch.float32, device=dev),
+                         ta=torch.empty(1, dtype=torch.float32, device=dev)))
+    for b in sets:
+        C.coat_act_quant_tensor(b["x"], G, out=(b["q"], b["ts"], b["pg"], b["ta"]))   # valid group maxima for _pre
+
+    def run(i):
+        b = sets[i % len(sets)]
+        if args.op == "act_group":
+            C.coat_act_quant_group(b["x"], G, out=(b["q"], b["pg"]))
+        elif args.op == "act_tensor":
+            C.coat_act_quant_tensor(b["x"], G, out=(b["q"], b["ts"], b["pg"], b["ta"]))
+        else:
+            C.coat_act_quant_tensor_from_group_amax(b["x"], b["pg"], G, out=(b["q"], b["ts"], b["ta"]))
+
+    for i in range(args.warmup):
+        run(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        run(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    avg_s = e0.elapsed_time(e1) / args.steps / 1e3
+    per = {"act_group": 3.0 + 4.0 / G, "act_tensor": 5.0 + 8.0 / G, "act_tensor_pre": 3.0 + 4.0 / G}[args.op]
+    algo = per * n
+    print(json.dumps({
+        "metric": "elements/sec, %s (bf16 -> E4M3, Sec. 5.2)" % args.op,
+        "value": n * args.steps / wall, "unit": "elements/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "activations %d x %d, G=%d, %d buffer sets cycled" % (args.act_tokens, hidden, G, len(sets))},
+        "roofline": {"bound": "hbm", "achieved": algo / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": algo / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "avg_call_us": avg_s * 1e6, "algorithmic_bytes_per_call": algo}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,8 +170,14 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27)
     ap.add_argument("--cpu-steps", type=int, default=12)
-    ap.add_argument("--op", default="step", choices=["step", "quant", "dequant"],
-                    help="step: the fused optimizer step (the metric); quant / dequant: its two halves alone")
+    ap.add_argument("--op", default="step",
+                    choices=["step", "quant", "dequant", "act_group", "act_tensor", "act_tensor_pre"],
+                    help="step: the fused optimizer step (the metric); quant / dequant: its two halves alone; "
+                         "act_*: the activation quantizers (per group, per tensor with Group Scaling, the same "
+                         "with the group maxima supplied)")
+    ap.add_argument("--act-tokens", type=int, default=8192, help="rows of the activation tensor (hidden = 4096)")
+    ap.add_argument("--act-group-size", type=int, default=16)
+    ap.add_argument("--act-buffers", type=int, default=8)
     ap.add_argument("--m-e5m2", action="store_true", help="first moment in E5M2 (a cell of the paper's Table 1)")
     ap.add_argument("--v-e5m2", action="store_true", help="second moment in E5M2")
     ap.add_argument("--m-plain", action="store_true", help="first moment without dynamic range expansion")
@@ -153,6 +214,9 @@ def main():
     assert n % G == 0
 
     gen = S.torch_generator(dev, 0)
+    if args.op.startswith("act_"):
+        bench_act(args, C, S, torch, dev, gen)
+        return
     if args.op != "step":
         bench_half(args, C, S, torch, dev, gen, n, G)
         return

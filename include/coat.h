@@ -1,7 +1,8 @@
 /*
  * coat.h -- C ABI of the MI355X (gfx950) implementation of COAT's FP8-state AdamW step
  * (arxiv 2410.19313: Sec. 3 "Preliminaries", Sec. 4 "Dynamic range expansion",
- * Appendix A "Details about optimizer states quantization").
+ * Appendix A "Details about optimizer states quantization") and of the activation quantizers of
+ * Sec. 5.2 (1xG per-group, and per-tensor with Group Scaling).
  *
  * Conventions shared by every entry point
  *   - Every data pointer is caller-owned DEVICE memory on the current HIP device.  The
@@ -33,7 +34,7 @@ extern "C" {
 #define COAT_OK            0
 #define COAT_ERR_NULL     -1  /* a required pointer is NULL */
 #define COAT_ERR_ALIGN    -2  /* a base pointer is not 16-byte aligned */
-#define COAT_ERR_GROUP    -3  /* group size not one of 32, 64, 128, 256, 512 */
+#define COAT_ERR_GROUP    -3  /* group size not one of 32, 64, 128, 256, 512 (activation quantizers: or 16) */
 #define COAT_ERR_STEP     -4  /* step < 1 */
 #define COAT_ERR_HPARAM   -5  /* non-finite or out-of-domain hyper-parameter, unknown flag bit */
 #define COAT_ERR_LAUNCH   -6  /* the HIP runtime refused the launch */
@@ -120,6 +121,40 @@ int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags,
  */
 int coat_dequant_group(const uint8_t* q, const float* scale, const float* k,
                        uint64_t n, int32_t G, uint32_t flags, float* x, void* hip_stream);
+
+/*
+ * 1xG per-group activation quantizer (Sec. 5.2, the fine-grained side of the mixed-granularity FP8
+ * flow; the paper runs G = 16).  x_bf16 [n] raw bf16 patterns in;  q [n] E4M3 codes and
+ * scale [ceil(n/G)] out:  scale = fl32(max|x| / 448),  code = E4M3(fl32(x / scale)), round to
+ * nearest even, the fp32 quotient correctly rounded.  All-zero group: scale 0, codes signed zeros.
+ * No expansion (that is an optimizer-state technique).  G in {16, 32, 64, 128, 256, 512}.
+ * Inputs must be finite.
+ */
+int coat_act_quant_group(const uint16_t* x_bf16, uint64_t n, int32_t G,
+                         uint8_t* q, float* scale, void* hip_stream);
+
+/*
+ * Group Scaling (Sec. 5.2): per-tensor quantization whose max reduction is split in two stages.
+ *   stage 1  group_amax [ceil(n/G)] (out) = max|x| of every 1xG group,
+ *   stage 2  tensor_amax [1] (out) = max over group_amax,
+ *   then     tensor_scale [1] (out) = fl32(tensor_amax / 448),  q [n] = E4M3(fl32(x / tensor_scale)).
+ * Three launches in stream order on hip_stream; stage 2 accumulates with one device-scope atomic
+ * max per workgroup into tensor_amax, which stage 1 clears from inside its kernel (no memset, so
+ * the sequence may be captured into a graph).  tensor_amax and tensor_scale need 4-byte alignment
+ * only.  G in {16, 32, 64, 128, 256, 512}; n == 0 touches nothing.  Inputs must be finite.
+ */
+int coat_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G,
+                          float* group_amax, float* tensor_amax, float* tensor_scale,
+                          uint8_t* q, void* hip_stream);
+
+/*
+ * The same with stage 1 already done: group_amax [ceil(n/G)] is an INPUT (non-negative group
+ * maxima), as when the operator that produced x emitted them in its epilogue, which is how the
+ * paper removes the cost of the first stage (Sec. 5.2).  Runs stage 2 and the quantization.
+ */
+int coat_act_quant_tensor_from_group_amax(const uint16_t* x_bf16, uint64_t n, int32_t G,
+                                          const float* group_amax, float* tensor_amax,
+                                          float* tensor_scale, uint8_t* q, void* hip_stream);
 
 /* Human-readable text for a return code (static storage, never NULL). */
 const char* coat_strerror(int code);

@@ -15,7 +15,11 @@ from . import build as _build
 FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN = 1, 2, 2, 4, 8, 16
 SUPPORTED_GROUP_SIZES = (32, 64, 128, 256, 512)
 
-EXPORTS = ("coat_fp8_adamw_step", "coat_fp8_adamw_step_bf16w", "coat_quant_group", "coat_dequant_group", "coat_strerror", "coat_version")
+ACT_GROUP_SIZES = (16,) + SUPPORTED_GROUP_SIZES
+
+EXPORTS = ("coat_fp8_adamw_step", "coat_fp8_adamw_step_bf16w", "coat_quant_group", "coat_dequant_group",
+           "coat_act_quant_group", "coat_act_quant_tensor", "coat_act_quant_tensor_from_group_amax",
+           "coat_strerror", "coat_version")
 
 
 class CoatError(RuntimeError):
@@ -74,6 +78,11 @@ def lib():
                                        ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
         L.coat_dequant_group.restype = ctypes.c_int
         L.coat_dequant_group.argtypes = [vp, vp, vp, ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32, vp, vp]
+        L.coat_act_quant_group.restype = ctypes.c_int
+        L.coat_act_quant_group.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, vp, vp, vp]
+        for f in (L.coat_act_quant_tensor, L.coat_act_quant_tensor_from_group_amax):
+            f.restype = ctypes.c_int
+            f.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, vp, vp, vp, vp, vp]
         L.coat_strerror.restype = ctypes.c_char_p
         L.coat_strerror.argtypes = [ctypes.c_int]
         L.coat_version.restype = ctypes.c_int
@@ -168,3 +177,50 @@ def coat_dequant_group(q, scale, k, G: int, out=None, e5m2: bool = False):
                                     _dev_ptr(k, torch.float32, ng), n, G, FLAG_E5M2 if e5m2 else 0,
                                     _dev_ptr(out, torch.float32, n), _stream()))
     return out
+
+
+def coat_act_quant_group(x_bf16, G: int = 16, out=None):
+    """x bfloat16 [n] -> (codes uint8 [n], scale fp32 [ng]): the 1xG activation quantizer."""
+    import torch
+    n = x_bf16.numel()
+    ng = n_groups(n, G) if G > 0 else 0
+    if out is None:
+        out = (torch.empty(n, dtype=torch.uint8, device=x_bf16.device),
+               torch.empty(ng, dtype=torch.float32, device=x_bf16.device))
+    q, scale = out
+    _check(lib().coat_act_quant_group(_dev_ptr(x_bf16, torch.bfloat16), n, G, _dev_ptr(q, torch.uint8, n),
+                                      _dev_ptr(scale, torch.float32, ng), _stream()))
+    return q, scale
+
+
+def coat_act_quant_tensor(x_bf16, G: int = 16, out=None):
+    """x bfloat16 [n] -> (codes uint8 [n], tensor_scale fp32 [1], group_amax fp32 [ng], tensor_amax fp32 [1]):
+    per-tensor quantization with Group Scaling's two-stage max."""
+    import torch
+    n = x_bf16.numel()
+    ng = n_groups(n, G) if G > 0 else 0
+    if out is None:
+        dev = x_bf16.device
+        out = (torch.empty(n, dtype=torch.uint8, device=dev), torch.empty(1, dtype=torch.float32, device=dev),
+               torch.empty(ng, dtype=torch.float32, device=dev), torch.empty(1, dtype=torch.float32, device=dev))
+    q, tscale, gamax, tamax = out
+    _check(lib().coat_act_quant_tensor(_dev_ptr(x_bf16, torch.bfloat16), n, G, _dev_ptr(gamax, torch.float32, ng),
+                                       _dev_ptr(tamax, torch.float32, 1), _dev_ptr(tscale, torch.float32, 1),
+                                       _dev_ptr(q, torch.uint8, n), _stream()))
+    return q, tscale, gamax, tamax
+
+
+def coat_act_quant_tensor_from_group_amax(x_bf16, group_amax, G: int = 16, out=None):
+    """The same with the group maxima supplied by the caller -> (codes, tensor_scale, tensor_amax)."""
+    import torch
+    n = x_bf16.numel()
+    ng = n_groups(n, G) if G > 0 else 0
+    if out is None:
+        dev = x_bf16.device
+        out = (torch.empty(n, dtype=torch.uint8, device=dev), torch.empty(1, dtype=torch.float32, device=dev),
+               torch.empty(1, dtype=torch.float32, device=dev))
+    q, tscale, tamax = out
+    _check(lib().coat_act_quant_tensor_from_group_amax(
+        _dev_ptr(x_bf16, torch.bfloat16), n, G, _dev_ptr(group_amax, torch.float32, ng),
+        _dev_ptr(tamax, torch.float32, 1), _dev_ptr(tscale, torch.float32, 1), _dev_ptr(q, torch.uint8, n), _stream()))
+    return q, tscale, tamax

@@ -734,6 +734,185 @@ __global__ __launch_bounds__(kWave) void dequant_tail_kernel(DequantArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
+// activation quantizers (Sec. 5.2): bf16 in, E4M3 codes out, no expansion.  Same lane layout as the
+// optimizer kernels (16 consecutive elements per lane, rows staged through the bf16 tile), so a
+// 1 x 16 group is exactly one lane and larger groups are the same DPP butterflies.
+// ---------------------------------------------------------------------------------------
+
+struct ActArgs {
+  const uint16_t* x;
+  uint8_t* q;
+  float* per_group;        // per-group scales (1xG quantizer) or per-group maxima (Group Scaling stage 1)
+  uint32_t* tensor_amax;   // max |x| of the tensor as its bit pattern (non-negative floats order like uints)
+  float* tensor_scale;
+  uint64_t n, n_full, n_groups;
+};
+
+template <int G>
+__device__ __forceinline__ float act_group_amax(const float (&x)[kEPL]) {
+  float hi = 0.0f;
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) hi = __builtin_fmaxf(hi, __builtin_fabsf(x[e]));
+  return group_allreduce<G / kEPL, true>(hi);
+}
+
+// codes = E4M3( fl32(x / s) ), s = fl32(amax / 448), every quotient correctly rounded.
+// The sixteen quotients share the divisor, so one IEEE reciprocal r = fl(1/s) serves them all:
+//   q0 = x r, e = x - s q0 (exact in an fma), q = q0 + e r
+// is the correctly rounded x / s for every bf16 x and every s that comes from a bf16 maximum
+// (all 2^14 significand pairs checked exhaustively on the host; the residual stays representable
+// for amax >= 2^-80).  Smaller maxima take the plain division; an all-zero group keeps signed zeros.
+__device__ __forceinline__ float act_quantize16(const float (&x)[kEPL], float amax, uint32_t (&c)[4]) {
+  const float s = amax / 448.0f;
+  if (__builtin_expect(amax >= 0x1p-80f, 1)) {
+    const float r = 1.0f / s;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      float q[4];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const float xv = x[4 * d + b];
+        const float q0 = xv * r;
+        const float qc = __builtin_fmaf(__builtin_fmaf(-s, q0, xv), r, q0);
+        q[b] = as_f32((as_u32(qc) & 0x7fffffffu) | (as_u32(xv) & 0x80000000u));   // -0 / s is -0 (the sum above loses it)
+      }
+      c[d] = pack4<false>(q);
+    }
+  } else {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      float q[4];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const float xv = x[4 * d + b];
+        q[b] = s > 0.0f ? xv / s : __builtin_copysignf(0.0f, xv);
+      }
+      c[d] = pack4<false>(q);
+    }
+  }
+  return s;
+}
+
+// one full chunk of bf16 rows -> the lane layout
+__device__ __forceinline__ void act_load_chunk(const uint16_t* x, uint64_t cb, u32x4* tile, int lane, float (&v)[kEPL]) {
+  const u32x4* xq = reinterpret_cast<const u32x4*>(x + cb);
+  u32x4 rows[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) rows[j] = ldg<4>(xq + 64 * j + lane);
+  tile_rows_to_lanes_bf16(tile, lane, rows, v);
+}
+
+// PER_TENSOR = false: the 1xG quantizer (per-group scale).  PER_TENSOR = true: the last step of
+// Group Scaling, every element divided by the one scale derived from the reduced maximum.
+template <int G, bool PER_TENSOR>
+__global__ __launch_bounds__(kBlock) void act_quant_kernel(ActArgs a) {
+  __shared__ u32x4 tile_x[kWavesPerBlock * kTileSlotsG];
+  constexpr int LPG = G / kEPL;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
+  float tmax = 0.0f;
+  if constexpr (PER_TENSOR) {
+    tmax = as_f32(*a.tensor_amax);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_scale = tmax / 448.0f;
+  }
+  for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
+    const uint64_t cb = chunk * kChunk;
+    float x[kEPL];
+    uint32_t c[4];
+    act_load_chunk(a.x, cb, tile_x + wv * kTileSlotsG, lane, x);
+    const float amax = PER_TENSOR ? tmax : act_group_amax<G>(x);
+    const float s = act_quantize16(x, amax, c);
+    const u32x4 co = {c[0], c[1], c[2], c[3]};
+    stg<2>(reinterpret_cast<u32x4*>(a.q + cb) + lane, co);
+    if constexpr (!PER_TENSOR)
+      if ((lane % LPG) == 0) a.per_group[chunk * (kChunk / G) + lane / LPG] = s;
+  }
+}
+
+template <int G, bool PER_TENSOR>
+__global__ __launch_bounds__(kWave) void act_quant_tail_kernel(ActArgs a) {
+  constexpr int LPG = G / kEPL;
+  const int lane = threadIdx.x;
+  const uint64_t base = a.n_full * kChunk + static_cast<uint64_t>(lane) * kEPL;
+  const uint64_t gidx = a.n_full * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
+  float x[kEPL];
+  uint32_t c[4];
+  load_bf16x16_guarded(a.x, base, a.n, x);
+  float amax;
+  if constexpr (PER_TENSOR) {
+    amax = as_f32(*a.tensor_amax);
+    if (lane == 0) *a.tensor_scale = amax / 448.0f;
+  } else {
+    amax = act_group_amax<G>(x);
+  }
+  const float s = act_quantize16(x, amax, c);
+  store_codes16_guarded(a.q, base, a.n, c);
+  if constexpr (!PER_TENSOR)
+    if (gidx < a.n_groups && (lane % LPG) == 0) a.per_group[gidx] = s;
+}
+
+// Group Scaling stage 1: the maximum of every 1xG group, kept as an intermediate tensor.  The
+// first thread also clears the tensor maximum that stage 2 accumulates into (a store from a
+// kernel, so the sequence can be captured into a graph).
+template <int G>
+__global__ __launch_bounds__(kBlock) void act_group_amax_kernel(ActArgs a) {
+  __shared__ u32x4 tile_x[kWavesPerBlock * kTileSlotsG];
+  constexpr int LPG = G / kEPL;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
+  if (blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_amax = 0u;
+  for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
+    float x[kEPL];
+    act_load_chunk(a.x, chunk * kChunk, tile_x + wv * kTileSlotsG, lane, x);
+    const float amax = act_group_amax<G>(x);
+    if ((lane % LPG) == 0) a.per_group[chunk * (kChunk / G) + lane / LPG] = amax;
+  }
+}
+
+template <int G>
+__global__ __launch_bounds__(kWave) void act_group_amax_tail_kernel(ActArgs a) {
+  constexpr int LPG = G / kEPL;
+  const int lane = threadIdx.x;
+  const uint64_t base = a.n_full * kChunk + static_cast<uint64_t>(lane) * kEPL;
+  const uint64_t gidx = a.n_full * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
+  float x[kEPL];
+  if (lane == 0) *a.tensor_amax = 0u;
+  load_bf16x16_guarded(a.x, base, a.n, x);
+  const float amax = act_group_amax<G>(x);
+  if (gidx < a.n_groups && (lane % LPG) == 0) a.per_group[gidx] = amax;
+}
+
+// Group Scaling stage 2: the maximum of the G-times smaller tensor of group maxima.  Every block
+// folds a strided share, then one atomic max per block on the bit pattern (values are >= 0).
+__global__ __launch_bounds__(kBlock) void act_tensor_amax_kernel(ActArgs a) {
+  __shared__ float part[kWavesPerBlock];
+  const uint64_t n4 = a.n_groups / 4;
+  const f32x4* p4 = reinterpret_cast<const f32x4*>(a.per_group);
+  float hi = 0.0f;
+  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x; i < n4;
+       i += static_cast<uint64_t>(gridDim.x) * kBlock) {
+    const f32x4 v = p4[i];
+    hi = __builtin_fmaxf(__builtin_fmaxf(hi, __builtin_fmaxf(v.x, v.y)), __builtin_fmaxf(v.z, v.w));
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (a.n_groups & 3)) hi = __builtin_fmaxf(hi, a.per_group[4 * n4 + threadIdx.x]);
+  hi = group_allreduce<32, true>(hi);
+  const int lane = threadIdx.x & (kWave - 1);
+  hi = __builtin_fmaxf(hi, __shfl_xor(hi, 32));
+  if (lane == 0) part[threadIdx.x >> 6] = hi;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 1; i < kWavesPerBlock; ++i) hi = __builtin_fmaxf(hi, part[i]);
+    atomicMax(a.tensor_amax, as_u32(__builtin_fabsf(hi)));   // fabs: a -0 must not order above everything
+  }
+}
+
+// clears the accumulator when stage 1 did not run (the caller supplied the group maxima)
+__global__ void act_clear_kernel(uint32_t* p) { *p = 0u; }
+
+// ---------------------------------------------------------------------------------------
 // host side: validation and launch
 // ---------------------------------------------------------------------------------------
 
@@ -844,6 +1023,79 @@ int dispatch_dequant(const DequantArgs& a, int32_t G, hipStream_t s) {
   COAT_DISPATCH_G(G, (launch_dequant<kG>(a, s)));
 }
 
+bool act_group_ok(int32_t G) { return G == 16 || group_ok(G); }
+
+#define COAT_DISPATCH_ACT_G(G, CALL)                  \
+  switch (G) {                                        \
+    case 16: { constexpr int kG = 16; return CALL; }  \
+  }                                                   \
+  COAT_DISPATCH_G(G, CALL)
+
+template <int G, bool PER_TENSOR>
+int launch_act_quant(const ActArgs& a, hipStream_t s) {
+  if (a.n_full) {
+    hipLaunchKernelGGL((act_quant_kernel<G, PER_TENSOR>), dim3(grid_for(a.n_full)), dim3(kBlock), 0, s, a);
+    if (int rc = launch_status()) return rc;
+  }
+  if (a.n > a.n_full * kChunk) {
+    hipLaunchKernelGGL((act_quant_tail_kernel<G, PER_TENSOR>), dim3(1), dim3(kWave), 0, s, a);
+    if (int rc = launch_status()) return rc;
+  }
+  return COAT_OK;
+}
+
+template <int G>
+int launch_act_group_amax(const ActArgs& a, hipStream_t s) {
+  if (a.n_full) {
+    hipLaunchKernelGGL((act_group_amax_kernel<G>), dim3(grid_for(a.n_full)), dim3(kBlock), 0, s, a);
+    if (int rc = launch_status()) return rc;
+  }
+  if (a.n > a.n_full * kChunk) {
+    hipLaunchKernelGGL((act_group_amax_tail_kernel<G>), dim3(1), dim3(kWave), 0, s, a);
+    if (int rc = launch_status()) return rc;
+  }
+  return COAT_OK;
+}
+
+int dispatch_act_quant_group(const ActArgs& a, int32_t G, hipStream_t s) {
+  COAT_DISPATCH_ACT_G(G, (launch_act_quant<kG, false>(a, s)));
+}
+int dispatch_act_group_amax(const ActArgs& a, int32_t G, hipStream_t s) {
+  COAT_DISPATCH_ACT_G(G, (launch_act_group_amax<kG>(a, s)));
+}
+
+// stages 2 and 3 of Group Scaling: reduce the group maxima, then quantize with the one scale
+int launch_act_tensor_rest(const ActArgs& a, hipStream_t s) {
+  const uint64_t need = (a.n_groups / 4 + kBlock - 1) / kBlock;
+  const unsigned grid = static_cast<unsigned>(need < 1 ? 1 : (need > 1024 ? 1024 : need));
+  hipLaunchKernelGGL(act_tensor_amax_kernel, dim3(grid), dim3(kBlock), 0, s, a);
+  if (int rc = launch_status()) return rc;
+  return launch_act_quant<16, true>(a, s);   // the group size plays no part once the scale is per tensor
+}
+
+int act_quant_tensor_impl(const uint16_t* x, uint64_t n, int32_t G, float* group_amax, bool have_group_amax,
+                          float* tensor_amax, float* tensor_scale, uint8_t* q, void* hip_stream) {
+  if (!act_group_ok(G)) return COAT_ERR_GROUP;
+  if (n == 0) return COAT_OK;
+  if (!x || !q || !group_amax || !tensor_amax || !tensor_scale) return COAT_ERR_NULL;
+  if (!aligned16(x) || !aligned16(q) || !aligned16(group_amax)) return COAT_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(tensor_amax) | reinterpret_cast<uintptr_t>(tensor_scale)) & 3u) return COAT_ERR_ALIGN;
+  if (n > (1ull << 46)) return COAT_ERR_SIZE;
+  ActArgs a;
+  a.x = x; a.q = q; a.per_group = group_amax;
+  a.tensor_amax = reinterpret_cast<uint32_t*>(tensor_amax); a.tensor_scale = tensor_scale;
+  a.n = n; a.n_full = n / kChunk;
+  a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (have_group_amax) {
+    hipLaunchKernelGGL(act_clear_kernel, dim3(1), dim3(1), 0, s, a.tensor_amax);
+    if (int rc = launch_status()) return rc;
+  } else {
+    if (int rc = dispatch_act_group_amax(a, G, s)) return rc;
+  }
+  return launch_act_tensor_rest(a, s);
+}
+
 constexpr uint32_t kStepFlags = COAT_FLAG_EXPAND | COAT_FLAG_M_E5M2 | COAT_FLAG_V_E5M2 | COAT_FLAG_M_PLAIN |
                                 COAT_FLAG_V_PLAIN;
 
@@ -951,12 +1203,38 @@ int coat_dequant_group(const uint8_t* q, const float* scale, const float* k, uin
   return dispatch_dequant(a, G, static_cast<hipStream_t>(hip_stream));
 }
 
+int coat_act_quant_group(const uint16_t* x_bf16, uint64_t n, int32_t G, uint8_t* q, float* scale,
+                         void* hip_stream) {
+  if (!act_group_ok(G)) return COAT_ERR_GROUP;
+  if (n == 0) return COAT_OK;
+  if (!x_bf16 || !q || !scale) return COAT_ERR_NULL;
+  if (!aligned16(x_bf16) || !aligned16(q) || !aligned16(scale)) return COAT_ERR_ALIGN;
+  if (n > (1ull << 46)) return COAT_ERR_SIZE;
+  ActArgs a;
+  a.x = x_bf16; a.q = q; a.per_group = scale; a.tensor_amax = nullptr; a.tensor_scale = nullptr;
+  a.n = n; a.n_full = n / kChunk;
+  a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
+  return dispatch_act_quant_group(a, G, static_cast<hipStream_t>(hip_stream));
+}
+
+int coat_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G, float* group_amax,
+                          float* tensor_amax, float* tensor_scale, uint8_t* q, void* hip_stream) {
+  return act_quant_tensor_impl(x_bf16, n, G, group_amax, false, tensor_amax, tensor_scale, q, hip_stream);
+}
+
+int coat_act_quant_tensor_from_group_amax(const uint16_t* x_bf16, uint64_t n, int32_t G,
+                                          const float* group_amax, float* tensor_amax,
+                                          float* tensor_scale, uint8_t* q, void* hip_stream) {
+  return act_quant_tensor_impl(x_bf16, n, G, const_cast<float*>(group_amax), true, tensor_amax, tensor_scale, q,
+                               hip_stream);
+}
+
 const char* coat_strerror(int code) {
   switch (code) {
     case COAT_OK: return "ok";
     case COAT_ERR_NULL: return "a required pointer is NULL";
     case COAT_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
-    case COAT_ERR_GROUP: return "group size must be one of 32, 64, 128, 256, 512";
+    case COAT_ERR_GROUP: return "group size must be one of 32, 64, 128, 256, 512 (activation quantizers: also 16)";
     case COAT_ERR_STEP: return "step must be >= 1";
     case COAT_ERR_HPARAM: return "hyper-parameter or flag is non-finite, unsupported or out of its domain";
     case COAT_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
@@ -965,7 +1243,7 @@ const char* coat_strerror(int code) {
   return "unknown error code";
 }
 
-int coat_version(void) { return 200; }
+int coat_version(void) { return 210; }
 
 #ifdef COAT_TUNING
 // development builds only: launch-shape knobs for sweeps

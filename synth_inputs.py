@@ -47,7 +47,7 @@ def workload_numel(name: str) -> int:
 # any tensor of any step can be regenerated alone.
 # ---------------------------------------------------------------------------------------
 
-_STREAM_W, _STREAM_G, _STREAM_OUTLIER, _STREAM_STATE = 1, 2, 3, 4
+_STREAM_W, _STREAM_G, _STREAM_OUTLIER, _STREAM_STATE, _STREAM_ACT = 1, 2, 3, 4, 5
 
 
 def _rng(seed: int, stream: int, step: int = 0) -> np.random.Generator:
@@ -92,6 +92,20 @@ def grads_lognormal(n: int, seed: int, step: int, base: float = 1e-3, sigma: flo
     z = r.standard_normal(n, dtype=np.float32)
     sign = np.where(r.random(n, dtype=np.float32) < 0.5, np.float32(-1), np.float32(1))
     return f32_to_bf16_bits(np.float32(base) * np.exp(np.float32(sigma) * z) * sign)
+
+
+def activations(n: int, seed: int, hidden: int = 4096, sigma: float = 1.0, channel_frac: float = 1.0 / 512,
+                channel_mult: float = 20.0, spike_frac: float = 1.0 / 4096, spike_mult: float = 60.0) -> np.ndarray:
+    """bf16 activations of a [tokens, hidden] tensor, flattened row-major and cut to n elements:
+    N(0, sigma^2) entries, a fixed set of outlier channels (columns) scaled by channel_mult and sparse
+    single-element spikes scaled by spike_mult -- the heavy-tailed shape transformer activations have."""
+    rng = _rng(seed, _STREAM_ACT)
+    x = rng.standard_normal(n, dtype=np.float32) * np.float32(sigma)
+    cols = np.arange(n, dtype=np.int64) % hidden
+    hot = rng.random(hidden) < channel_frac
+    x[hot[cols]] *= np.float32(channel_mult)
+    x[rng.random(n) < spike_frac] *= np.float32(spike_mult)
+    return f32_to_bf16_bits(x)
 
 
 def zero_state(n: int, G: int):
@@ -174,6 +188,25 @@ def torch_grads_lognormal(n: int, device, gen, base: float = 1e-3, sigma: float 
         z.mul_(torch.where(s, -1.0, 1.0).to(torch.float32))
         g[lo:hi].copy_(z)
     return g
+
+
+def torch_activations(n: int, device, gen, hidden: int = 4096, sigma: float = 1.0, channel_frac: float = 1.0 / 512,
+                      channel_mult: float = 20.0, spike_frac: float = 1.0 / 4096, spike_mult: float = 60.0, out=None):
+    """Device twin of activations() (same distribution, torch's own random stream); n % hidden == 0."""
+    import torch
+    assert n % hidden == 0
+    x = out if out is not None else torch.empty(n, dtype=torch.bfloat16, device=device)
+    hot = torch.rand(hidden, device=device, generator=gen) < channel_frac
+    col_mult = torch.where(hot, channel_mult, 1.0).to(torch.float32)
+    rows_per = max(1, _CHUNK // hidden)
+    for lo in range(0, n // hidden, rows_per):
+        hi = min(n // hidden, lo + rows_per)
+        t = torch.empty((hi - lo, hidden), dtype=torch.float32, device=device).normal_(0.0, sigma, generator=gen)
+        t.mul_(col_mult)
+        spike = torch.rand((hi - lo, hidden), device=device, generator=gen) < spike_frac
+        t.mul_(torch.where(spike, spike_mult, 1.0).to(torch.float32))
+        x[lo * hidden: hi * hidden].copy_(t.view(-1))
+    return x
 
 
 def torch_zero_state(n: int, G: int, device):

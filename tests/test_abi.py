@@ -86,6 +86,28 @@ def test_quant_dequant_reject_bad_arguments(coat):
     assert L.coat_dequant_group(None, None, None, 0, 128, 2, None, None) == 0
 
 
+def test_act_quantizers_reject_bad_arguments(coat):
+    L = coat.lib()
+    ok = ctypes.c_void_p(0x1000)
+    bad16 = ctypes.c_void_p(0x1004)
+    bad4 = ctypes.c_void_p(0x1002)
+    assert L.coat_act_quant_group(ok, 1024, 8, ok, ok, None) == -3
+    assert L.coat_act_quant_group(ok, 1024, 48, ok, ok, None) == -3
+    assert L.coat_act_quant_group(ok, 1024, 16, None, ok, None) == -1
+    assert L.coat_act_quant_group(bad16, 1024, 16, ok, ok, None) == -2
+    assert L.coat_act_quant_group(ok, 1 << 50, 16, ok, ok, None) == -7
+    assert L.coat_act_quant_group(None, 0, 16, None, None, None) == 0
+    for f in (L.coat_act_quant_tensor, L.coat_act_quant_tensor_from_group_amax):
+        assert f(ok, 1024, 24, ok, ok, ok, ok, None) == -3
+        assert f(ok, 1024, 16, None, ok, ok, ok, None) == -1
+        assert f(ok, 1024, 16, ok, None, ok, ok, None) == -1
+        assert f(ok, 1024, 16, ok, ok, ok, None, None) == -1
+        assert f(ok, 1024, 16, bad16, ok, ok, ok, None) == -2
+        assert f(ok, 1024, 16, ok, bad4, ok, ok, None) == -2
+        assert f(ok, 1 << 50, 16, ok, ok, ok, ok, None) == -7
+        assert f(None, 0, 16, None, None, None, None, None) == 0
+
+
 def test_binding_refuses_host_tensors(coat):
     import torch
     x = torch.zeros(1024)

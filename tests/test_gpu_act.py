@@ -1,0 +1,157 @@
+"""GPU parity of the activation quantizers (Sec. 5.2) against the CPU oracle.  Everything here is
+decided bit for bit: the maxima are exact, the scale is one correctly rounded fp32 division, the
+quotient handed to the E4M3 rounding is the correctly rounded fp32 quotient on both sides, and the
+rounding itself is round-to-nearest-even on both sides.  So codes, scales and maxima must be EQUAL."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+ACT_GROUPS = [16, 32, 64, 128, 256, 512]
+SIZES = [1, 15, 16, 17, 1023, 1024, 1025, 5 * 1024 + 77, 200 * 1024 + 331]
+
+
+@pytest.fixture(scope="module")
+def coat():
+    import paper_2410_19313_amd as C
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    C.lib()
+    return C
+
+
+def dev_bf16(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def bf16(x):
+    return S.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def check_group(coat, ref, bits, G, tag):
+    q_r, s_r = ref.act_quant_group(bits, G)
+    q_g, s_g = coat.coat_act_quant_group(dev_bf16(bits), G)
+    torch.cuda.synchronize()
+    q_g, s_g = q_g.cpu().numpy(), s_g.cpu().numpy()
+    assert np.array_equal(s_g.view(np.uint32), s_r.view(np.uint32)), "%s: scales differ" % tag
+    bad = np.flatnonzero(q_g != q_r)
+    assert bad.size == 0, "%s: %d codes differ, first at %d: gpu %#x ref %#x" % (
+        tag, bad.size, bad[0], q_g[bad[0]], q_r[bad[0]])
+
+
+def check_tensor(coat, ref, bits, G, tag):
+    q_r, ts_r, ga_r = ref.act_quant_tensor(bits, G)
+    x = dev_bf16(bits)
+    q_g, ts_g, ga_g, ta_g = coat.coat_act_quant_tensor(x, G)
+    torch.cuda.synchronize()
+    assert np.array_equal(ga_g.cpu().numpy().view(np.uint32), ga_r.view(np.uint32)), "%s: stage-1 maxima differ" % tag
+    assert float(ta_g.item()) == float(ga_r.max()), "%s: stage-2 maximum differs" % tag
+    assert np.float32(ts_g.item()).view(np.uint32) == np.float32(ts_r).view(np.uint32), "%s: tensor scale differs" % tag
+    bad = np.flatnonzero(q_g.cpu().numpy() != q_r)
+    assert bad.size == 0, "%s: %d codes differ, first at %d" % (tag, bad.size, bad[0])
+    # the entry point that takes the group maxima as an input must give the same answer; fill its
+    # outputs with junk first so that stale values cannot pass
+    out = (torch.full_like(q_g, 0x55), torch.full_like(ts_g, -1.0), torch.full_like(ta_g, 7e30))
+    q2, ts2, ta2 = coat.coat_act_quant_tensor_from_group_amax(x, ga_g, G, out=out)
+    torch.cuda.synchronize()
+    assert torch.equal(q2, q_g) and torch.equal(ts2, ts_g) and torch.equal(ta2, ta_g), "%s: from_group_amax differs" % tag
+
+
+@pytest.mark.parametrize("G", ACT_GROUPS)
+def test_per_group_quantizer_matches_oracle(coat, ref, G):
+    for i, n in enumerate(SIZES):
+        check_group(coat, ref, S.activations(n, 100 + i, hidden=256), G, "per-group G=%d n=%d" % (G, n))
+
+
+@pytest.mark.parametrize("G", ACT_GROUPS)
+def test_group_scaling_matches_oracle(coat, ref, G):
+    for i, n in enumerate(SIZES):
+        check_tensor(coat, ref, S.activations(n, 200 + i, hidden=256), G, "per-tensor G=%d n=%d" % (G, n))
+
+
+def test_every_significand_pair(coat, ref):
+    """All 128 x 128 pairs of (significand of the group maximum, significand of an element), each at
+    every exponent distance that still lands in E4M3's range: the division by the scale is the only
+    inexact step, and its rounding depends on the significands alone."""
+    groups = []
+    for am in range(128, 256):
+        top = np.float32(am) * np.float32(2.0 ** -4)                 # [8, 16)
+        xs = [np.float32(xm) * np.float32(2.0 ** (-7 - e)) for e in range(1, 16) for xm in range(128, 256)]
+        xs = np.asarray(xs, dtype=np.float32)                        # 15 * 128 values below the maximum
+        xs[1::2] *= -1.0
+        g = np.empty((xs.size // 15, 16), dtype=np.float32)
+        g[:, 0] = top
+        g[:, 1:] = xs.reshape(-1, 15)
+        groups.append(g)
+    x = np.concatenate(groups).reshape(-1)
+    bits = bf16(x)
+    assert np.array_equal(S.bf16_bits_to_f32(bits), x)               # every value is a bf16
+    check_group(coat, ref, bits, 16, "significand pairs")
+    for am in (128, 171, 200, 255):                                  # per tensor: one maximum per call
+        sel = np.concatenate(groups[am - 128: am - 127]).reshape(-1)
+        check_tensor(coat, ref, bf16(sel), 16, "significand pairs, tensor max %d" % am)
+
+
+def test_degenerate_groups(coat, ref):
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal(4096 + 48).astype(np.float32)
+    x[0:16] = 0.0                                   # all-zero group
+    x[16:32] = -0.0                                 # signed zeros keep their sign bit
+    x[32:48] = 0.0
+    x[40] = -3.0                                    # one non-zero element
+    x[1024:1040] = np.float32(2.0 ** -100) * rng.standard_normal(16).astype(np.float32)   # tiny maximum
+    x[1040:1056] = np.float32(2.0 ** -130)          # fp32-subnormal inputs (scale underflows)
+    x[2048:2064] = np.float32(3.0e38)               # close to the largest bf16
+    x[2064:2080] = 448.0
+    x[2080:2096] = np.float32(2.0 ** -9) * np.arange(16, dtype=np.float32)
+    bits = bf16(x)
+    for G in (16, 32, 128):
+        check_group(coat, ref, bits, G, "degenerate G=%d" % G)
+    tiny = bits.copy()[:4096]
+    tiny_vals = (S.bf16_bits_to_f32(tiny) * np.float32(2.0 ** -110)).astype(np.float32)
+    check_tensor(coat, ref, bf16(tiny_vals), 16, "tiny tensor")
+    check_tensor(coat, ref, bf16(np.zeros(3000, np.float32)), 16, "zero tensor")
+    check_tensor(coat, ref, bits, 64, "degenerate tensor")
+    # empty input: nothing is touched
+    e = torch.empty(0, dtype=torch.bfloat16, device="cuda")
+    q, s = coat.coat_act_quant_group(e, 16)
+    assert q.numel() == 0 and s.numel() == 0
+    q, ts, ga, ta = coat.coat_act_quant_tensor(e, 16, out=(q, torch.full((1,), 5.0, device="cuda"), s,
+                                                           torch.full((1,), 6.0, device="cuda")))
+    assert ts.item() == 5.0 and ta.item() == 6.0
+
+
+def test_repeated_calls_reuse_the_accumulator(coat, ref):
+    """The tensor maximum is accumulated with atomics into caller memory that the library clears
+    itself: a second call on a smaller-valued tensor must not see the first call's maximum."""
+    big = S.activations(64 * 1024, 7, hidden=256)
+    small = bf16(S.bf16_bits_to_f32(S.activations(64 * 1024, 8, hidden=256)) * np.float32(1e-3))
+    xb, xs = dev_bf16(big), dev_bf16(small)
+    out = coat.coat_act_quant_tensor(xb, 16)
+    for x, bits in ((xs, small), (xb, big), (xs, small)):
+        q, ts, ga, ta = coat.coat_act_quant_tensor(x, 16, out=out)
+        torch.cuda.synchronize()
+        q_r, ts_r, ga_r = ref.act_quant_tensor(bits, 16)
+        assert np.float32(ts.item()) == np.float32(ts_r)
+        assert np.array_equal(q.cpu().numpy(), q_r)
+
+
+def test_full_size_activation_tensor(coat, ref):
+    """The bench's activation workload (8192 tokens x 4096 channels, the shape of one Llama-2-7B
+    micro-batch of 4 x 2048 tokens), generated on the device, checked whole against the oracle."""
+    n, hidden = 8192 * 4096, 4096
+    gen = S.torch_generator("cuda", 31)
+    x = S.torch_activations(n, "cuda", gen, hidden=hidden)
+    bits = x.view(torch.int16).cpu().numpy().view(np.uint16)
+    q_g, s_g = coat.coat_act_quant_group(x, 16)
+    qt_g, ts_g, ga_g, ta_g = coat.coat_act_quant_tensor(x, 16)
+    torch.cuda.synchronize()
+    q_r, s_r = ref.act_quant_group(bits, 16)
+    assert np.array_equal(s_g.cpu().numpy().view(np.uint32), s_r.view(np.uint32))
+    assert np.array_equal(q_g.cpu().numpy(), q_r)
+    qt_r, ts_r, ga_r = ref.act_quant_tensor(bits, 16)
+    assert np.array_equal(ga_g.cpu().numpy(), ga_r)
+    assert np.float32(ts_g.item()) == np.float32(ts_r)
+    assert np.array_equal(qt_g.cpu().numpy(), qt_r)
