@@ -122,17 +122,18 @@ def bench_act(args, C, S, torch, dev, gen):
                          pg=torch.empty(ng, dtype=torch.float32, device=dev),
                          ts=torch.empty(1, dtype=torch.float32, device=dev),
                          ta=torch.empty(1, dtype=torch.float32, device=dev)))
+    ws = C.act_workspace(dev)
     for b in sets:
-        C.coat_act_quant_tensor(b["x"], G, out=(b["q"], b["ts"], b["pg"], b["ta"]))   # valid group maxima for _pre
+        C.coat_act_quant_tensor(b["x"], G, out=(b["q"], b["ts"], b["pg"], b["ta"]), workspace=ws)   # group maxima for _pre
 
     def run(i):
         b = sets[i % len(sets)]
         if args.op == "act_group":
             C.coat_act_quant_group(b["x"], G, out=(b["q"], b["pg"]))
         elif args.op == "act_tensor":
-            C.coat_act_quant_tensor(b["x"], G, out=(b["q"], b["ts"], b["pg"], b["ta"]))
+            C.coat_act_quant_tensor(b["x"], G, out=(b["q"], b["ts"], b["pg"], b["ta"]), workspace=ws)
         else:
-            C.coat_act_quant_tensor_from_group_amax(b["x"], b["pg"], G, out=(b["q"], b["ts"], b["ta"]))
+            C.coat_act_quant_tensor_from_group_amax(b["x"], b["pg"], G, out=(b["q"], b["ts"], b["ta"]), workspace=ws)
 
     for i in range(args.warmup):
         run(i)

@@ -138,14 +138,18 @@ int coat_act_quant_group(const uint16_t* x_bf16, uint64_t n, int32_t G,
  *   stage 1  group_amax [ceil(n/G)] (out) = max|x| of every 1xG group,
  *   stage 2  tensor_amax [1] (out) = max over group_amax,
  *   then     tensor_scale [1] (out) = fl32(tensor_amax / 448),  q [n] = E4M3(fl32(x / tensor_scale)).
- * Three launches in stream order on hip_stream; stage 2 accumulates with one device-scope atomic
- * max per workgroup into tensor_amax, which stage 1 clears from inside its kernel (no memset, so
- * the sequence may be captured into a graph).  tensor_amax and tensor_scale need 4-byte alignment
- * only.  G in {16, 32, 64, 128, 256, 512}; n == 0 touches nothing.  Inputs must be finite.
+ * Three launches in stream order on hip_stream.  Stage 2 leaves one partial maximum per workgroup
+ * in `workspace` (COAT_ACT_WORKSPACE_FLOATS floats of caller-owned device scratch, 16-byte
+ * aligned, contents undefined before and after the call) and the quantizing kernel folds them: no
+ * atomics, no memset, so the result is deterministic and the sequence may be captured into a
+ * graph.  Calls that share a workspace must not overlap.  tensor_amax and tensor_scale need
+ * 4-byte alignment only.  G in {16, 32, 64, 128, 256, 512}; n == 0 touches nothing.  Inputs must
+ * be finite.
  */
+#define COAT_ACT_WORKSPACE_FLOATS 64
 int coat_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G,
-                          float* group_amax, float* tensor_amax, float* tensor_scale,
-                          uint8_t* q, void* hip_stream);
+                          float* group_amax, float* workspace, float* tensor_amax,
+                          float* tensor_scale, uint8_t* q, void* hip_stream);
 
 /*
  * The same with stage 1 already done: group_amax [ceil(n/G)] is an INPUT (non-negative group
@@ -153,8 +157,9 @@ int coat_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G,
  * paper removes the cost of the first stage (Sec. 5.2).  Runs stage 2 and the quantization.
  */
 int coat_act_quant_tensor_from_group_amax(const uint16_t* x_bf16, uint64_t n, int32_t G,
-                                          const float* group_amax, float* tensor_amax,
-                                          float* tensor_scale, uint8_t* q, void* hip_stream);
+                                          const float* group_amax, float* workspace,
+                                          float* tensor_amax, float* tensor_scale, uint8_t* q,
+                                          void* hip_stream);
 
 /* Human-readable text for a return code (static storage, never NULL). */
 const char* coat_strerror(int code);

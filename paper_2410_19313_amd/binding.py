@@ -16,6 +16,7 @@ FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN = 1
 SUPPORTED_GROUP_SIZES = (32, 64, 128, 256, 512)
 
 ACT_GROUP_SIZES = (16,) + SUPPORTED_GROUP_SIZES
+ACT_WORKSPACE_FLOATS = 64
 
 EXPORTS = ("coat_fp8_adamw_step", "coat_fp8_adamw_step_bf16w", "coat_quant_group", "coat_dequant_group",
            "coat_act_quant_group", "coat_act_quant_tensor", "coat_act_quant_tensor_from_group_amax",
@@ -82,7 +83,7 @@ def lib():
         L.coat_act_quant_group.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, vp, vp, vp]
         for f in (L.coat_act_quant_tensor, L.coat_act_quant_tensor_from_group_amax):
             f.restype = ctypes.c_int
-            f.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, vp, vp, vp, vp, vp]
+            f.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
         L.coat_strerror.restype = ctypes.c_char_p
         L.coat_strerror.argtypes = [ctypes.c_int]
         L.coat_version.restype = ctypes.c_int
@@ -193,34 +194,46 @@ def coat_act_quant_group(x_bf16, G: int = 16, out=None):
     return q, scale
 
 
-def coat_act_quant_tensor(x_bf16, G: int = 16, out=None):
+def act_workspace(device):
+    """Scratch for the per-tensor quantizer's stage 2 (contents undefined; one per concurrent call)."""
+    import torch
+    return torch.empty(ACT_WORKSPACE_FLOATS, dtype=torch.float32, device=device)
+
+
+def coat_act_quant_tensor(x_bf16, G: int = 16, out=None, workspace=None):
     """x bfloat16 [n] -> (codes uint8 [n], tensor_scale fp32 [1], group_amax fp32 [ng], tensor_amax fp32 [1]):
     per-tensor quantization with Group Scaling's two-stage max."""
     import torch
     n = x_bf16.numel()
     ng = n_groups(n, G) if G > 0 else 0
+    dev = x_bf16.device
     if out is None:
-        dev = x_bf16.device
         out = (torch.empty(n, dtype=torch.uint8, device=dev), torch.empty(1, dtype=torch.float32, device=dev),
                torch.empty(ng, dtype=torch.float32, device=dev), torch.empty(1, dtype=torch.float32, device=dev))
+    if workspace is None:
+        workspace = act_workspace(dev)
     q, tscale, gamax, tamax = out
     _check(lib().coat_act_quant_tensor(_dev_ptr(x_bf16, torch.bfloat16), n, G, _dev_ptr(gamax, torch.float32, ng),
+                                       _dev_ptr(workspace, torch.float32, ACT_WORKSPACE_FLOATS),
                                        _dev_ptr(tamax, torch.float32, 1), _dev_ptr(tscale, torch.float32, 1),
                                        _dev_ptr(q, torch.uint8, n), _stream()))
     return q, tscale, gamax, tamax
 
 
-def coat_act_quant_tensor_from_group_amax(x_bf16, group_amax, G: int = 16, out=None):
+def coat_act_quant_tensor_from_group_amax(x_bf16, group_amax, G: int = 16, out=None, workspace=None):
     """The same with the group maxima supplied by the caller -> (codes, tensor_scale, tensor_amax)."""
     import torch
     n = x_bf16.numel()
     ng = n_groups(n, G) if G > 0 else 0
+    dev = x_bf16.device
     if out is None:
-        dev = x_bf16.device
         out = (torch.empty(n, dtype=torch.uint8, device=dev), torch.empty(1, dtype=torch.float32, device=dev),
                torch.empty(1, dtype=torch.float32, device=dev))
+    if workspace is None:
+        workspace = act_workspace(dev)
     q, tscale, tamax = out
     _check(lib().coat_act_quant_tensor_from_group_amax(
         _dev_ptr(x_bf16, torch.bfloat16), n, G, _dev_ptr(group_amax, torch.float32, ng),
+        _dev_ptr(workspace, torch.float32, ACT_WORKSPACE_FLOATS),
         _dev_ptr(tamax, torch.float32, 1), _dev_ptr(tscale, torch.float32, 1), _dev_ptr(q, torch.uint8, n), _stream()))
     return q, tscale, tamax

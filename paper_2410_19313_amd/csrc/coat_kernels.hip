@@ -743,7 +743,9 @@ struct ActArgs {
   const uint16_t* x;
   uint8_t* q;
   float* per_group;        // per-group scales (1xG quantizer) or per-group maxima (Group Scaling stage 1)
-  uint32_t* tensor_amax;   // max |x| of the tensor as its bit pattern (non-negative floats order like uints)
+  float* partial;          // Group Scaling stage 2: one partial maximum per workgroup (caller's workspace)
+  int n_partial;           // how many of them the stage-2 launch writes (<= kActPartials)
+  float* tensor_amax;      // max |x| of the tensor
   float* tensor_scale;
   uint64_t n, n_full, n_groups;
 };
@@ -802,6 +804,14 @@ __device__ __forceinline__ void act_load_chunk(const uint16_t* x, uint64_t cb, u
   tile_rows_to_lanes_bf16(tile, lane, rows, v);
 }
 
+// The end of Group Scaling's stage 2: every wavefront folds the (at most 64) per-workgroup partial
+// maxima itself, one per lane; all lanes return the tensor maximum.
+__device__ __forceinline__ float act_fold_partials(const ActArgs& a, int lane) {
+  float hi = lane < a.n_partial ? a.partial[lane] : 0.0f;
+  hi = group_allreduce<32, true>(hi);
+  return __builtin_fmaxf(hi, __shfl_xor(hi, 32));
+}
+
 // PER_TENSOR = false: the 1xG quantizer (per-group scale).  PER_TENSOR = true: the last step of
 // Group Scaling, every element divided by the one scale derived from the reduced maximum.
 template <int G, bool PER_TENSOR>
@@ -813,8 +823,8 @@ __global__ __launch_bounds__(kBlock) void act_quant_kernel(ActArgs a) {
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
   float tmax = 0.0f;
   if constexpr (PER_TENSOR) {
-    tmax = as_f32(*a.tensor_amax);
-    if (blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_scale = tmax / 448.0f;
+    tmax = act_fold_partials(a, lane);
+    if (blockIdx.x == 0 && threadIdx.x == 0) { *a.tensor_amax = tmax; *a.tensor_scale = tmax / 448.0f; }
   }
   for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
     const uint64_t cb = chunk * kChunk;
@@ -841,8 +851,8 @@ __global__ __launch_bounds__(kWave) void act_quant_tail_kernel(ActArgs a) {
   load_bf16x16_guarded(a.x, base, a.n, x);
   float amax;
   if constexpr (PER_TENSOR) {
-    amax = as_f32(*a.tensor_amax);
-    if (lane == 0) *a.tensor_scale = amax / 448.0f;
+    amax = act_fold_partials(a, lane);
+    if (lane == 0) { *a.tensor_amax = amax; *a.tensor_scale = amax / 448.0f; }
   } else {
     amax = act_group_amax<G>(x);
   }
@@ -852,9 +862,7 @@ __global__ __launch_bounds__(kWave) void act_quant_tail_kernel(ActArgs a) {
     if (gidx < a.n_groups && (lane % LPG) == 0) a.per_group[gidx] = s;
 }
 
-// Group Scaling stage 1: the maximum of every 1xG group, kept as an intermediate tensor.  The
-// first thread also clears the tensor maximum that stage 2 accumulates into (a store from a
-// kernel, so the sequence can be captured into a graph).
+// Group Scaling stage 1: the maximum of every 1xG group, kept as an intermediate tensor.
 template <int G>
 __global__ __launch_bounds__(kBlock) void act_group_amax_kernel(ActArgs a) {
   __shared__ u32x4 tile_x[kWavesPerBlock * kTileSlotsG];
@@ -862,7 +870,6 @@ __global__ __launch_bounds__(kBlock) void act_group_amax_kernel(ActArgs a) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
-  if (blockIdx.x == 0 && threadIdx.x == 0) *a.tensor_amax = 0u;
   for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
     float x[kEPL];
     act_load_chunk(a.x, chunk * kChunk, tile_x + wv * kTileSlotsG, lane, x);
@@ -878,39 +885,48 @@ __global__ __launch_bounds__(kWave) void act_group_amax_tail_kernel(ActArgs a) {
   const uint64_t base = a.n_full * kChunk + static_cast<uint64_t>(lane) * kEPL;
   const uint64_t gidx = a.n_full * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
   float x[kEPL];
-  if (lane == 0) *a.tensor_amax = 0u;
   load_bf16x16_guarded(a.x, base, a.n, x);
   const float amax = act_group_amax<G>(x);
   if (gidx < a.n_groups && (lane % LPG) == 0) a.per_group[gidx] = amax;
 }
 
-// Group Scaling stage 2: the maximum of the G-times smaller tensor of group maxima.  Every block
-// folds a strided share, then one atomic max per block on the bit pattern (values are >= 0).
-__global__ __launch_bounds__(kBlock) void act_tensor_amax_kernel(ActArgs a) {
-  __shared__ float part[kWavesPerBlock];
+// Group Scaling stage 2: the maximum of the G-times smaller tensor of group maxima.  At most 64
+// large workgroups each fold a strided share and store one partial maximum; the quantizing kernel
+// that follows folds those in every wavefront.  No atomics (same-address atomic maxima serialize
+// at about 11 ns each here, which cost more than the whole reduction), nothing to clear, and the
+// result does not depend on the order in which workgroups finish.
+template <int BLOCK, int UNROLL>
+__global__ __launch_bounds__(BLOCK) void act_tensor_amax_kernel(ActArgs a) {
+  __shared__ float part[BLOCK / kWave];
   const uint64_t n4 = a.n_groups / 4;
   const f32x4* p4 = reinterpret_cast<const f32x4*>(a.per_group);
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * BLOCK;
   float hi = 0.0f;
-  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x; i < n4;
-       i += static_cast<uint64_t>(gridDim.x) * kBlock) {
+  uint64_t i = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x;
+  for (; i + (UNROLL - 1) * stride < n4; i += UNROLL * stride) {     // UNROLL independent loads in flight
+    f32x4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) v[u] = p4[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+      hi = __builtin_fmaxf(__builtin_fmaxf(hi, __builtin_fmaxf(v[u].x, v[u].y)), __builtin_fmaxf(v[u].z, v[u].w));
+  }
+  for (; i < n4; i += stride) {
     const f32x4 v = p4[i];
     hi = __builtin_fmaxf(__builtin_fmaxf(hi, __builtin_fmaxf(v.x, v.y)), __builtin_fmaxf(v.z, v.w));
   }
   if (blockIdx.x == 0 && threadIdx.x < (a.n_groups & 3)) hi = __builtin_fmaxf(hi, a.per_group[4 * n4 + threadIdx.x]);
   hi = group_allreduce<32, true>(hi);
-  const int lane = threadIdx.x & (kWave - 1);
   hi = __builtin_fmaxf(hi, __shfl_xor(hi, 32));
-  if (lane == 0) part[threadIdx.x >> 6] = hi;
+  if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x >> 6] = hi;
   __syncthreads();
   if (threadIdx.x == 0) {
 #pragma unroll
-    for (int i = 1; i < kWavesPerBlock; ++i) hi = __builtin_fmaxf(hi, part[i]);
-    atomicMax(a.tensor_amax, as_u32(__builtin_fabsf(hi)));   // fabs: a -0 must not order above everything
+    for (int w = 1; w < BLOCK / kWave; ++w) hi = __builtin_fmaxf(hi, part[w]);
+    a.partial[blockIdx.x] = hi;
   }
 }
 
-// clears the accumulator when stage 1 did not run (the caller supplied the group maxima)
-__global__ void act_clear_kernel(uint32_t* p) { *p = 0u; }
 
 // ---------------------------------------------------------------------------------------
 // host side: validation and launch
@@ -1065,34 +1081,33 @@ int dispatch_act_group_amax(const ActArgs& a, int32_t G, hipStream_t s) {
 }
 
 // stages 2 and 3 of Group Scaling: reduce the group maxima, then quantize with the one scale
-int launch_act_tensor_rest(const ActArgs& a, hipStream_t s) {
-  const uint64_t need = (a.n_groups / 4 + kBlock - 1) / kBlock;
-  const unsigned grid = static_cast<unsigned>(need < 1 ? 1 : (need > 1024 ? 1024 : need));
-  hipLaunchKernelGGL(act_tensor_amax_kernel, dim3(grid), dim3(kBlock), 0, s, a);
+constexpr int kStage2Block = 1024, kStage2Unroll = 4, kStage2MaxGrid = COAT_ACT_WORKSPACE_FLOATS;
+static_assert(kStage2MaxGrid <= kWave, "one partial maximum per lane");
+int launch_act_tensor_rest(ActArgs a, hipStream_t s) {
+  const uint64_t need = (a.n_groups / 4 + kStage2Block * kStage2Unroll - 1) / (kStage2Block * kStage2Unroll);
+  const unsigned grid = static_cast<unsigned>(need < 1 ? 1 : (need > kStage2MaxGrid ? kStage2MaxGrid : need));
+  a.n_partial = static_cast<int>(grid);
+  hipLaunchKernelGGL((act_tensor_amax_kernel<kStage2Block, kStage2Unroll>), dim3(grid), dim3(kStage2Block), 0, s, a);
   if (int rc = launch_status()) return rc;
   return launch_act_quant<16, true>(a, s);   // the group size plays no part once the scale is per tensor
 }
 
 int act_quant_tensor_impl(const uint16_t* x, uint64_t n, int32_t G, float* group_amax, bool have_group_amax,
-                          float* tensor_amax, float* tensor_scale, uint8_t* q, void* hip_stream) {
+                          float* workspace, float* tensor_amax, float* tensor_scale, uint8_t* q, void* hip_stream) {
   if (!act_group_ok(G)) return COAT_ERR_GROUP;
   if (n == 0) return COAT_OK;
-  if (!x || !q || !group_amax || !tensor_amax || !tensor_scale) return COAT_ERR_NULL;
-  if (!aligned16(x) || !aligned16(q) || !aligned16(group_amax)) return COAT_ERR_ALIGN;
+  if (!x || !q || !group_amax || !workspace || !tensor_amax || !tensor_scale) return COAT_ERR_NULL;
+  if (!aligned16(x) || !aligned16(q) || !aligned16(group_amax) || !aligned16(workspace)) return COAT_ERR_ALIGN;
   if ((reinterpret_cast<uintptr_t>(tensor_amax) | reinterpret_cast<uintptr_t>(tensor_scale)) & 3u) return COAT_ERR_ALIGN;
   if (n > (1ull << 46)) return COAT_ERR_SIZE;
   ActArgs a;
   a.x = x; a.q = q; a.per_group = group_amax;
-  a.tensor_amax = reinterpret_cast<uint32_t*>(tensor_amax); a.tensor_scale = tensor_scale;
+  a.partial = workspace; a.n_partial = 0; a.tensor_amax = tensor_amax; a.tensor_scale = tensor_scale;
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (have_group_amax) {
-    hipLaunchKernelGGL(act_clear_kernel, dim3(1), dim3(1), 0, s, a.tensor_amax);
-    if (int rc = launch_status()) return rc;
-  } else {
+  if (!have_group_amax)
     if (int rc = dispatch_act_group_amax(a, G, s)) return rc;
-  }
   return launch_act_tensor_rest(a, s);
 }
 
@@ -1211,22 +1226,22 @@ int coat_act_quant_group(const uint16_t* x_bf16, uint64_t n, int32_t G, uint8_t*
   if (!aligned16(x_bf16) || !aligned16(q) || !aligned16(scale)) return COAT_ERR_ALIGN;
   if (n > (1ull << 46)) return COAT_ERR_SIZE;
   ActArgs a;
-  a.x = x_bf16; a.q = q; a.per_group = scale; a.tensor_amax = nullptr; a.tensor_scale = nullptr;
+  a.x = x_bf16; a.q = q; a.per_group = scale; a.partial = nullptr; a.n_partial = 0; a.tensor_amax = nullptr; a.tensor_scale = nullptr;
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
   return dispatch_act_quant_group(a, G, static_cast<hipStream_t>(hip_stream));
 }
 
-int coat_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G, float* group_amax,
+int coat_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G, float* group_amax, float* workspace,
                           float* tensor_amax, float* tensor_scale, uint8_t* q, void* hip_stream) {
-  return act_quant_tensor_impl(x_bf16, n, G, group_amax, false, tensor_amax, tensor_scale, q, hip_stream);
+  return act_quant_tensor_impl(x_bf16, n, G, group_amax, false, workspace, tensor_amax, tensor_scale, q, hip_stream);
 }
 
 int coat_act_quant_tensor_from_group_amax(const uint16_t* x_bf16, uint64_t n, int32_t G,
-                                          const float* group_amax, float* tensor_amax,
+                                          const float* group_amax, float* workspace, float* tensor_amax,
                                           float* tensor_scale, uint8_t* q, void* hip_stream) {
-  return act_quant_tensor_impl(x_bf16, n, G, const_cast<float*>(group_amax), true, tensor_amax, tensor_scale, q,
-                               hip_stream);
+  return act_quant_tensor_impl(x_bf16, n, G, const_cast<float*>(group_amax), true, workspace, tensor_amax,
+                               tensor_scale, q, hip_stream);
 }
 
 const char* coat_strerror(int code) {

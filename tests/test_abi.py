@@ -98,14 +98,17 @@ def test_act_quantizers_reject_bad_arguments(coat):
     assert L.coat_act_quant_group(ok, 1 << 50, 16, ok, ok, None) == -7
     assert L.coat_act_quant_group(None, 0, 16, None, None, None) == 0
     for f in (L.coat_act_quant_tensor, L.coat_act_quant_tensor_from_group_amax):
-        assert f(ok, 1024, 24, ok, ok, ok, ok, None) == -3
-        assert f(ok, 1024, 16, None, ok, ok, ok, None) == -1
-        assert f(ok, 1024, 16, ok, None, ok, ok, None) == -1
-        assert f(ok, 1024, 16, ok, ok, ok, None, None) == -1
-        assert f(ok, 1024, 16, bad16, ok, ok, ok, None) == -2
-        assert f(ok, 1024, 16, ok, bad4, ok, ok, None) == -2
-        assert f(ok, 1 << 50, 16, ok, ok, ok, ok, None) == -7
-        assert f(None, 0, 16, None, None, None, None, None) == 0
+        #  x, n, G, group_amax, workspace, tensor_amax, tensor_scale, q, stream
+        assert f(ok, 1024, 24, ok, ok, ok, ok, ok, None) == -3
+        assert f(ok, 1024, 16, None, ok, ok, ok, ok, None) == -1
+        assert f(ok, 1024, 16, ok, None, ok, ok, ok, None) == -1
+        assert f(ok, 1024, 16, ok, ok, None, ok, ok, None) == -1
+        assert f(ok, 1024, 16, ok, ok, ok, ok, None, None) == -1
+        assert f(ok, 1024, 16, bad16, ok, ok, ok, ok, None) == -2
+        assert f(ok, 1024, 16, ok, bad16, ok, ok, ok, None) == -2
+        assert f(ok, 1024, 16, ok, ok, bad4, ok, ok, None) == -2
+        assert f(ok, 1 << 50, 16, ok, ok, ok, ok, ok, None) == -7
+        assert f(None, 0, 16, None, None, None, None, None, None) == 0
 
 
 def test_binding_refuses_host_tensors(coat):

@@ -120,22 +120,29 @@ def test_degenerate_groups(coat, ref):
     assert q.numel() == 0 and s.numel() == 0
     q, ts, ga, ta = coat.coat_act_quant_tensor(e, 16, out=(q, torch.full((1,), 5.0, device="cuda"), s,
                                                            torch.full((1,), 6.0, device="cuda")))
+    torch.cuda.synchronize()
     assert ts.item() == 5.0 and ta.item() == 6.0
 
 
-def test_repeated_calls_reuse_the_accumulator(coat, ref):
-    """The tensor maximum is accumulated with atomics into caller memory that the library clears
-    itself: a second call on a smaller-valued tensor must not see the first call's maximum."""
+def test_repeated_calls_share_outputs_and_workspace(coat, ref):
+    """Calls in a row into the same outputs and the same workspace, alternating a large-valued and
+    a small-valued tensor and a short one: no call may see an earlier call's maxima or partials."""
     big = S.activations(64 * 1024, 7, hidden=256)
     small = bf16(S.bf16_bits_to_f32(S.activations(64 * 1024, 8, hidden=256)) * np.float32(1e-3))
     xb, xs = dev_bf16(big), dev_bf16(small)
-    out = coat.coat_act_quant_tensor(xb, 16)
+    ws = torch.full((coat.ACT_WORKSPACE_FLOATS,), 3e38, device="cuda")     # junk that would win every max
+    out = coat.coat_act_quant_tensor(xb, 16, workspace=ws)
     for x, bits in ((xs, small), (xb, big), (xs, small)):
-        q, ts, ga, ta = coat.coat_act_quant_tensor(x, 16, out=out)
+        q, ts, ga, ta = coat.coat_act_quant_tensor(x, 16, out=out, workspace=ws)
         torch.cuda.synchronize()
         q_r, ts_r, ga_r = ref.act_quant_tensor(bits, 16)
         assert np.float32(ts.item()) == np.float32(ts_r)
         assert np.array_equal(q.cpu().numpy(), q_r)
+    short = small[:5000]
+    q, ts, ga, ta = coat.coat_act_quant_tensor(dev_bf16(short), 16, workspace=ws)
+    torch.cuda.synchronize()
+    q_r, ts_r, ga_r = ref.act_quant_tensor(short, 16)
+    assert np.float32(ts.item()) == np.float32(ts_r) and np.array_equal(q.cpu().numpy(), q_r)
 
 
 def test_full_size_activation_tensor(coat, ref):
@@ -146,8 +153,15 @@ def test_full_size_activation_tensor(coat, ref):
     x = S.torch_activations(n, "cuda", gen, hidden=hidden)
     bits = x.view(torch.int16).cpu().numpy().view(np.uint16)
     q_g, s_g = coat.coat_act_quant_group(x, 16)
-    qt_g, ts_g, ga_g, ta_g = coat.coat_act_quant_tensor(x, 16)
+    ws = coat.act_workspace("cuda")
+    qt_g, ts_g, ga_g, ta_g = coat.coat_act_quant_tensor(x, 16, workspace=ws)
+    # all 64 stage-2 partial maxima are in use now; a short, small-valued tensor through the same
+    # workspace right after (one partial) must not see the other 63
+    short = S.f32_to_bf16_bits(S.bf16_bits_to_f32(bits[:70000]) * np.float32(2.0 ** -7))
+    qs_g, tss_g, _, _ = coat.coat_act_quant_tensor(dev_bf16(short), 16, workspace=ws)
     torch.cuda.synchronize()
+    qs_r, tss_r, _ = ref.act_quant_tensor(short, 16)
+    assert np.float32(tss_g.item()) == np.float32(tss_r) and np.array_equal(qs_g.cpu().numpy(), qs_r)
     q_r, s_r = ref.act_quant_group(bits, 16)
     assert np.array_equal(s_g.cpu().numpy().view(np.uint32), s_r.view(np.uint32))
     assert np.array_equal(q_g.cpu().numpy(), q_r)
