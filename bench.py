@@ -184,6 +184,9 @@ def main():
     ap.add_argument("--m-plain", action="store_true", help="first moment without dynamic range expansion")
     ap.add_argument("--v-plain", action="store_true", help="second moment without dynamic range expansion")
     ap.add_argument("--emit-bf16", action="store_true", help="also write the bf16 copy of the new weights (+2 B/param)")
+    ap.add_argument("--multi", action="store_true",
+                    help="step the workload as its separate tensors through ONE multi-tensor launch")
+    ap.add_argument("--multi-small", type=int, default=0, help="with --multi: also split off this many 4096-element tensors")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (scales the rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -233,10 +236,37 @@ def main():
     w_bf16 = torch.empty(n, dtype=torch.bfloat16, device=dev) if args.emit_bf16 else None
     torch.cuda.synchronize()
 
+    plans = None
+    if args.multi:
+        # the same flat buffers seen as the workload's separate tensors (the model's weight matrices, plus
+        # --multi-small extra 4096-element vectors standing in for norm weights), one plan per gradient buffer
+        sizes = [r * c for r, c in S.workload_shapes(args.workload)]
+        for _ in range(args.multi_small):
+            big = max(range(len(sizes)), key=lambda i: sizes[i])
+            sizes[big] -= 4096
+            sizes.append(4096)
+        assert sum(sizes) == n and all(x % G == 0 for x in sizes)
+        plans = []
+        for gbuf in grads:
+            tens, off = [], 0
+            for x in sizes:
+                d = dict(w=w[off:off + x], grad=gbuf[off:off + x], weight_decay=HP["weight_decay"])
+                for k in ("m_q", "v_q"):
+                    d[k] = st[k][off:off + x]
+                for k in ("m_scale", "m_k", "v_scale", "v_k"):
+                    d[k] = st[k][off // G:(off + x) // G]
+                if args.emit_bf16:
+                    d["w_bf16"] = w_bf16[off:off + x]
+                tens.append(d)
+                off += x
+            plans.append(C.MultiPlan(tens, G))
+
     def step(t):
         hp = C.make_hparams(step=t, group_size=G, m_e5m2=args.m_e5m2, v_e5m2=args.v_e5m2,
                             m_plain=args.m_plain, v_plain=args.v_plain, **HP)
-        if args.emit_bf16:
+        if plans is not None:
+            C.coat_fp8_adamw_step_multi(plans[t & 1], hp)
+        elif args.emit_bf16:
             C.coat_fp8_adamw_step_bf16w(w, w_bf16, grads[t & 1], st["m_q"], st["m_scale"], st["m_k"],
                                         st["v_q"], st["v_scale"], st["v_k"], hp)
         else:
@@ -290,15 +320,16 @@ def main():
                 args.workload], n, G, args.grads) + (
                     ", m %s%s, v %s%s" % ("E5M2" if args.m_e5m2 else "E4M3", "" if args.m_plain else "+expand",
                                             "E5M2" if args.v_e5m2 else "E4M3", "" if args.v_plain else "+expand")
-                    if generic else "") + (", bf16 weight copy" if args.emit_bf16 else ""),
+                    if generic else "") + (", bf16 weight copy" if args.emit_bf16 else "") + (
+                        ", %d tensors in one multi-tensor launch" % len(plans[0].tensors) if plans else ""),
             "params": n, "group_size": G, "hbm_gbs": achieved, "hbm_frac_of_peak": achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_profile_traffic(args.workload, G),
                      "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_ms": avg_launch_s * 1e3,
-                     "kernel": "adamw_step_kernel<%d, %s>" % (G, "generic" if generic else "default")},
+                     "kernel": "adamw_step%s_kernel<%d, %s>" % ("_multi" if plans else "", G, "generic" if generic else "default")},
     }
     # free the device buffers before the host-side baseline allocates its own arrays
-    del w, st, grads
+    del w, st, grads, plans
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(G, min(args.cpu_sample, n), args.cpu_steps)

@@ -25,6 +25,7 @@
 #ifndef COAT_H
 #define COAT_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -38,7 +39,8 @@ extern "C" {
 #define COAT_ERR_STEP     -4  /* step < 1 */
 #define COAT_ERR_HPARAM   -5  /* non-finite or out-of-domain hyper-parameter, unknown flag bit */
 #define COAT_ERR_LAUNCH   -6  /* the HIP runtime refused the launch */
-#define COAT_ERR_SIZE     -7  /* n exceeds what the launch geometry supports */
+#define COAT_ERR_SIZE     -7  /* n exceeds what the launch geometry supports, or a buffer is too small */
+#define COAT_ERR_PLAN     -8  /* not a plan blob written by coat_multi_plan_build */
 
 /* Flags.  The per-moment bits select a cell of the paper's Table 1 (each moment stored as E4M3 or
  * E5M2, with or without the expansion); the default (COAT_FLAG_EXPAND alone) is the method as
@@ -101,6 +103,55 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
                               uint8_t* m_q, float* m_scale, float* m_k,
                               uint8_t* v_q, float* v_scale, float* v_k,
                               uint64_t n, const coat_adamw_hparams* hp, void* hip_stream);
+
+/*
+ * Many tensors in one launch.  A model's parameters are hundreds of separate tensors, many of
+ * them small (norm weights, biases); stepping them one call each costs a launch per tensor.  The
+ * paper's optimizer treats every tensor alike (Sec. 3: groups of G consecutive elements, each
+ * tensor on its own), so the multi-tensor step is the single-tensor step applied to each entry:
+ * groups never span two tensors, a tensor's last group is short when n % G != 0, and results are
+ * bit-identical to one coat_fp8_adamw_step_bf16w call per tensor with that tensor's weight decay.
+ *
+ * coat_tensor_desc: the arguments of coat_fp8_adamw_step_bf16w for one tensor (device pointers,
+ * same alignment rules; w_bf16 may be NULL) plus its own weight decay (decay / no-decay parameter
+ * groups); hp->weight_decay is ignored by the multi-tensor step.  n == 0 entries are skipped.
+ *
+ * Usage: 1. size a HOST buffer with coat_multi_plan_bytes and fill it with coat_multi_plan_build
+ * (pure host code: pointers are validated, never dereferenced; the blob holds the descriptors
+ * and, per 1024-element chunk, the index of its tensor: 96 bytes per tensor + 4 bytes per chunk);
+ * 2. copy the blob to 16-byte-aligned device memory; 3. call coat_fp8_adamw_step_multi every step
+ * with both copies (the host copy's 64-byte header gives the launch size, the kernels read the
+ * device copy).  The plan stays valid while the tensors' addresses and sizes do; it does not
+ * depend on the hyper-parameters or on G.  To step only a shard of a tensor, describe the shard
+ * (see coat_shard_range).
+ * coat_multi_plan_bytes returns 0 on an invalid argument (NULL with count > 0, an n above 2^46, or
+ * more than 2^32 chunks in total).
+ */
+typedef struct {
+  float*          w;
+  uint16_t*       w_bf16;        /* optional bf16 copy of the new weights, or NULL */
+  const uint16_t* grad_bf16;
+  uint8_t*        m_q;  float* m_scale;  float* m_k;
+  uint8_t*        v_q;  float* v_scale;  float* v_k;
+  uint64_t        n;
+  float           weight_decay;  /* lambda of this tensor */
+  uint32_t        reserved;      /* set to 0 */
+} coat_tensor_desc;
+
+size_t coat_multi_plan_bytes(const coat_tensor_desc* descs, uint32_t count);
+int coat_multi_plan_build(const coat_tensor_desc* descs, uint32_t count, void* plan_host, size_t plan_bytes);
+int coat_fp8_adamw_step_multi(const void* plan_host, const void* plan_device,
+                              const coat_adamw_hparams* hp, void* hip_stream);
+
+/*
+ * The part of a flat tensor of n elements that rank `rank` of `world` owns when optimizer states
+ * are sharded (ZeRO / FSDP style; Sec. 3: every rank quantizes its own shard with its own
+ * statistics): shards are contiguous, cut at multiples of G so that no group spans two ranks, and
+ * differ by at most one group.  Pure host code.  Writes [*begin, *end); an empty shard has
+ * *begin == *end.  Offsetting the element pointers by *begin and the per-group pointers by
+ * *begin / G describes the shard to any entry point here.
+ */
+int coat_shard_range(uint64_t n, int32_t G, uint32_t rank, uint32_t world, uint64_t* begin, uint64_t* end);
 
 /*
  * Per-group quantizer with dynamic range expansion (Sec. 3 quantizer Q applied to f(X),

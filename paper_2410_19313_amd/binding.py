@@ -20,6 +20,7 @@ ACT_WORKSPACE_FLOATS = 64
 
 EXPORTS = ("coat_fp8_adamw_step", "coat_fp8_adamw_step_bf16w", "coat_quant_group", "coat_dequant_group",
            "coat_act_quant_group", "coat_act_quant_tensor", "coat_act_quant_tensor_from_group_amax",
+           "coat_multi_plan_bytes", "coat_multi_plan_build", "coat_fp8_adamw_step_multi", "coat_shard_range",
            "coat_strerror", "coat_version")
 
 
@@ -43,6 +44,17 @@ class HParams(ctypes.Structure):
         ("flags", ctypes.c_uint32),
         ("k_min", ctypes.c_float),
         ("k_max", ctypes.c_float),
+    ]
+
+
+class TensorDesc(ctypes.Structure):
+    """Mirror of coat_tensor_desc."""
+
+    _fields_ = [
+        ("w", ctypes.c_void_p), ("w_bf16", ctypes.c_void_p), ("grad_bf16", ctypes.c_void_p),
+        ("m_q", ctypes.c_void_p), ("m_scale", ctypes.c_void_p), ("m_k", ctypes.c_void_p),
+        ("v_q", ctypes.c_void_p), ("v_scale", ctypes.c_void_p), ("v_k", ctypes.c_void_p),
+        ("n", ctypes.c_uint64), ("weight_decay", ctypes.c_float), ("reserved", ctypes.c_uint32),
     ]
 
 
@@ -84,6 +96,15 @@ def lib():
         for f in (L.coat_act_quant_tensor, L.coat_act_quant_tensor_from_group_amax):
             f.restype = ctypes.c_int
             f.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
+        L.coat_multi_plan_bytes.restype = ctypes.c_size_t
+        L.coat_multi_plan_bytes.argtypes = [ctypes.POINTER(TensorDesc), ctypes.c_uint32]
+        L.coat_multi_plan_build.restype = ctypes.c_int
+        L.coat_multi_plan_build.argtypes = [ctypes.POINTER(TensorDesc), ctypes.c_uint32, vp, ctypes.c_size_t]
+        L.coat_fp8_adamw_step_multi.restype = ctypes.c_int
+        L.coat_fp8_adamw_step_multi.argtypes = [vp, vp, ctypes.POINTER(HParams), vp]
+        L.coat_shard_range.restype = ctypes.c_int
+        L.coat_shard_range.argtypes = [ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_uint32,
+                                       ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
         L.coat_strerror.restype = ctypes.c_char_p
         L.coat_strerror.argtypes = [ctypes.c_int]
         L.coat_version.restype = ctypes.c_int
@@ -237,3 +258,60 @@ def coat_act_quant_tensor_from_group_amax(x_bf16, group_amax, G: int = 16, out=N
         _dev_ptr(workspace, torch.float32, ACT_WORKSPACE_FLOATS),
         _dev_ptr(tamax, torch.float32, 1), _dev_ptr(tscale, torch.float32, 1), _dev_ptr(q, torch.uint8, n), _stream()))
     return q, tscale, tamax
+
+
+def coat_shard_range(n: int, G: int, rank: int, world: int):
+    """[begin, end) of the elements rank `rank` of `world` owns: contiguous, cut at multiples of G."""
+    b, e = ctypes.c_uint64(), ctypes.c_uint64()
+    _check(lib().coat_shard_range(n, G, rank, world, ctypes.byref(b), ctypes.byref(e)))
+    return b.value, e.value
+
+
+def coat_multi_plan_build(descs) -> bytes:
+    """Host side of the multi-tensor step: a list of TensorDesc -> the plan blob (bytes)."""
+    arr = (TensorDesc * max(1, len(descs)))(*descs)
+    size = lib().coat_multi_plan_bytes(arr, len(descs))
+    if size == 0:
+        raise CoatError(-7, strerror(-7))
+    buf = ctypes.create_string_buffer(size)
+    _check(lib().coat_multi_plan_build(arr, len(descs), buf, size))
+    return buf.raw
+
+
+class MultiPlan:
+    """The plan of a multi-tensor step: built from per-tensor device tensors, kept in host memory
+    (header) and device memory (what the kernels read).  Holds references to the tensors it describes."""
+
+    def __init__(self, tensors, G: int):
+        """tensors: a list of dicts with keys w, grad, m_q, m_scale, m_k, v_q, v_scale, v_k and optionally
+        w_bf16 and weight_decay (default 0.0).  G is only used to check the metadata sizes here."""
+        import torch
+        descs = []
+        for t in tensors:
+            n = t["w"].numel()
+            ng = n_groups(n, G)
+            wb = t.get("w_bf16")
+            descs.append(TensorDesc(
+                _dev_ptr(t["w"], torch.float32).value or 0,
+                (_dev_ptr(wb, torch.bfloat16, n).value or 0) if wb is not None else 0,
+                _dev_ptr(t["grad"], torch.bfloat16, n).value or 0,
+                _dev_ptr(t["m_q"], torch.uint8, n).value or 0, _dev_ptr(t["m_scale"], torch.float32, ng).value or 0,
+                _dev_ptr(t["m_k"], torch.float32, ng).value or 0,
+                _dev_ptr(t["v_q"], torch.uint8, n).value or 0, _dev_ptr(t["v_scale"], torch.float32, ng).value or 0,
+                _dev_ptr(t["v_k"], torch.float32, ng).value or 0,
+                n, float(t.get("weight_decay", 0.0)), 0))
+        self.tensors = list(tensors)
+        self.group_size = G
+        self.host = coat_multi_plan_build(descs)
+        self._host_buf = ctypes.create_string_buffer(self.host, len(self.host))
+        dev = tensors[0]["w"].device if tensors else torch.device("cuda")
+        self.device = torch.frombuffer(bytearray(self.host), dtype=torch.uint8).to(dev)
+
+
+def coat_fp8_adamw_step_multi(plan: MultiPlan, hp: HParams) -> None:
+    """One fused step over every tensor of the plan in a single launch (hp.weight_decay is ignored:
+    each tensor carries its own)."""
+    if hp.group_size != plan.group_size:
+        raise ValueError("the plan's metadata buffers were sized for G=%d" % plan.group_size)
+    _check(lib().coat_fp8_adamw_step_multi(ctypes.cast(plan._host_buf, ctypes.c_void_p),
+                                           ctypes.c_void_p(plan.device.data_ptr()), ctypes.byref(hp), _stream()))

@@ -591,14 +591,10 @@ __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
 
 // The ragged last chunk (n % 1024 elements): one wavefront, element-wise guarded accesses
 // straight into the lane layout.
-template <int G, bool GENERIC>
-__global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
-  constexpr int kTables = GENERIC ? 2 : 1;
-  __shared__ Log2Entry lut[256 * kTables];
-  fill_lut<kTables>(lut);
-  const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(a), mv = ModesOf<GENERIC>::v(a);
+template <int G, class ModeM, class ModeV>
+__device__ __forceinline__ void process_tail_chunk(const StepArgs& a, const ModeM& mm, const ModeV& mv,
+                                                   const Log2Entry* lut, int lane) {
   constexpr int LPG = G / kEPL;
-  const int lane = threadIdx.x;
   const uint64_t chunk = a.n_full;
   const uint64_t base = chunk * kChunk + static_cast<uint64_t>(lane) * kEPL;
   const uint64_t gidx = chunk * (kChunk / G) + static_cast<uint64_t>(lane / LPG);
@@ -629,6 +625,91 @@ __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
   if (gvalid && (lane % LPG) == 0) {
     a.ms[gidx] = meta.m_scale; a.mk[gidx] = meta.m_k;
     a.vs[gidx] = meta.v_scale; a.vk[gidx] = meta.v_k;
+  }
+}
+
+template <int G, bool GENERIC>
+__global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
+  constexpr int kTables = GENERIC ? 2 : 1;
+  __shared__ Log2Entry lut[256 * kTables];
+  fill_lut<kTables>(lut);
+  const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(a), mv = ModesOf<GENERIC>::v(a);
+  process_tail_chunk<G>(a, mm, mv, lut, threadIdx.x);
+}
+
+// ---------------------------------------------------------------------------------------
+// Many tensors in one launch.  The plan (built once on the host, resident in device memory) holds
+// one descriptor per tensor and, per 1024-element chunk of the concatenation, the index of the
+// tensor it belongs to: a wavefront reads its chunk's entry, then that tensor's descriptor, and
+// from there on runs exactly the single-tensor code (full chunk or a tensor's ragged last one).
+// ---------------------------------------------------------------------------------------
+struct TensorDesc {
+  float* w; uint16_t* wb; const uint16_t* g;
+  uint8_t* mq; float* ms; float* mk;
+  uint8_t* vq; float* vs; float* vk;
+  uint64_t n;
+  uint64_t first_chunk;     // index of the tensor's first chunk in the concatenation
+  float weight_decay;
+  uint32_t reserved;
+};
+static_assert(sizeof(TensorDesc) == 96, "plan layout");
+
+struct PlanHeader {
+  uint64_t magic;
+  uint32_t version, count;
+  uint64_t total_chunks;
+  uint64_t desc_offset, map_offset, bytes;
+  uint64_t reserved[2];
+};
+static_assert(sizeof(PlanHeader) == 64, "plan layout");
+constexpr uint64_t kPlanMagic = 0x314e4c5054414f43ull;     // "COATPLN1"
+
+struct MultiArgs {
+  StepArgs base;             // the shared hyper-parameter constants; pointers and sizes are per tensor
+  const TensorDesc* descs;
+  const uint32_t* chunk_tensor;
+  uint64_t total_chunks;
+  double neg_lr;             // -lr: the decay factor -lr * lambda is formed per tensor, in fp64 like the host does
+  int32_t group_size;
+};
+
+template <int G, bool GENERIC>
+__global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) {
+  constexpr int kTables = GENERIC ? 2 : 1;
+  __shared__ Log2Entry lut[256 * kTables];
+  __shared__ f32x4 tile_w[kWavesPerBlock * kTileSlotsW];
+  __shared__ u32x4 tile_g[kWavesPerBlock * kTileSlotsG];
+  const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(ma.base), mv = ModesOf<GENERIC>::v(ma.base);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const StageTiles tiles = {tile_w + wv * kTileSlotsW, tile_g + wv * kTileSlotsG};
+  const uint64_t gc = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv;   // the host sizes the grid to cover every chunk
+
+  StepArgs a = ma.base;
+  uint64_t chunk = 0;
+  // everything here is uniform over the wavefront (gc is), so the descriptor travels in scalar registers
+  auto locate = [&](uint64_t c) {
+    const uint32_t t = __builtin_amdgcn_readfirstlane(ma.chunk_tensor[c]);
+    const TensorDesc& d = ma.descs[t];
+    a.w = d.w; a.wb = d.wb; a.g = d.g; a.mq = d.mq; a.ms = d.ms; a.mk = d.mk; a.vq = d.vq; a.vs = d.vs; a.vk = d.vk;
+    a.n = d.n; a.n_full = d.n / kChunk;
+    a.n_groups = (d.n + G - 1) / G;
+    a.neg_lr_wd = static_cast<float>(ma.neg_lr * static_cast<double>(d.weight_decay));
+    chunk = c - d.first_chunk;
+  };
+
+  RawChunk r;
+  const bool have = gc < ma.total_chunks;
+  bool full = false;
+  if (have) {
+    locate(gc);
+    full = chunk < a.n_full;
+    if (full) issue_loads<G>(a, chunk, lane, r);
+  }
+  fill_lut<kTables>(lut);                            // every wavefront of the block reaches this
+  if (have) {
+    if (full) process_chunk<G>(a, mm, mv, lut, tiles, chunk, lane, r);
+    else process_tail_chunk<G>(a, mm, mv, lut, lane);
   }
 }
 
@@ -934,6 +1015,7 @@ __global__ __launch_bounds__(BLOCK) void act_tensor_amax_kernel(ActArgs a) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool finite_f(float x) { return x == x && x - x == 0.0f; }
+constexpr uint64_t kMaxElements = 1ull << 46;
 bool group_ok(int32_t G) { return G == 32 || G == 64 || G == 128 || G == 256 || G == 512; }
 
 #ifdef COAT_TUNING
@@ -1099,7 +1181,7 @@ int act_quant_tensor_impl(const uint16_t* x, uint64_t n, int32_t G, float* group
   if (!x || !q || !group_amax || !workspace || !tensor_amax || !tensor_scale) return COAT_ERR_NULL;
   if (!aligned16(x) || !aligned16(q) || !aligned16(group_amax) || !aligned16(workspace)) return COAT_ERR_ALIGN;
   if ((reinterpret_cast<uintptr_t>(tensor_amax) | reinterpret_cast<uintptr_t>(tensor_scale)) & 3u) return COAT_ERR_ALIGN;
-  if (n > (1ull << 46)) return COAT_ERR_SIZE;
+  if (n > kMaxElements) return COAT_ERR_SIZE;
   ActArgs a;
   a.x = x; a.q = q; a.per_group = group_amax;
   a.partial = workspace; a.n_partial = 0; a.tensor_amax = tensor_amax; a.tensor_scale = tensor_scale;
@@ -1111,22 +1193,31 @@ int act_quant_tensor_impl(const uint16_t* x, uint64_t n, int32_t G, float* group
   return launch_act_tensor_rest(a, s);
 }
 
+template <int G, bool GENERIC>
+int launch_step_multi(const MultiArgs& ma, hipStream_t s) {
+  const uint64_t blocks = (ma.total_chunks + kWavesPerBlock - 1) / kWavesPerBlock;
+  hipLaunchKernelGGL((adamw_step_multi_kernel<G, GENERIC>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock),
+                     kStepLdsPad, s, ma);
+  return launch_status();
+}
+
+int dispatch_step_multi(const MultiArgs& ma, int32_t G, bool generic, hipStream_t s) {
+  if (!generic) { COAT_DISPATCH_G(G, (launch_step_multi<kG, false>(ma, s))); }
+  COAT_DISPATCH_G(G, (launch_step_multi<kG, true>(ma, s)));
+}
+
 constexpr uint32_t kStepFlags = COAT_FLAG_EXPAND | COAT_FLAG_M_E5M2 | COAT_FLAG_V_E5M2 | COAT_FLAG_M_PLAIN |
                                 COAT_FLAG_V_PLAIN;
 
-}  // namespace
+constexpr uint64_t kMaxPlanChunks = 1ull << 32;     // one launch covers them all (4 per workgroup)
 
-extern "C" {
-
-int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float* m_scale, float* m_k,
-                        uint8_t* v_q, float* v_scale, float* v_k, uint64_t n,
-                        const coat_adamw_hparams* hp, void* hip_stream) {
-  return coat_fp8_adamw_step_bf16w(w, nullptr, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, n, hp, hip_stream);
+size_t plan_map_offset(uint32_t count) {
+  return sizeof(PlanHeader) + ((static_cast<size_t>(count) * sizeof(TensorDesc) + 63) / 64) * 64;
 }
 
-int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_bf16, uint8_t* m_q,
-                              float* m_scale, float* m_k, uint8_t* v_q, float* v_scale, float* v_k,
-                              uint64_t n, const coat_adamw_hparams* hp, void* hip_stream) {
+// Validates the hyper-parameters and fills every field of StepArgs that does not depend on the
+// tensor (the pointers, sizes and the decay factor are set by the caller).
+int step_constants(const coat_adamw_hparams* hp, StepArgs& a, bool& generic) {
   if (!hp) return COAT_ERR_NULL;
   if (!group_ok(hp->group_size)) return COAT_ERR_GROUP;
   if (hp->step < 1) return COAT_ERR_STEP;
@@ -1139,12 +1230,6 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
   if (hp->flags & ~kStepFlags) return COAT_ERR_HPARAM;
   float k_min = hp->k_min, k_max = hp->k_max;
   if (!resolve_k_bounds(k_min, k_max)) return COAT_ERR_HPARAM;
-  if (n == 0) return COAT_OK;
-  if (!w || !grad_bf16 || !m_q || !m_scale || !m_k || !v_q || !v_scale || !v_k) return COAT_ERR_NULL;
-  if (!aligned16(w) || !aligned16(grad_bf16) || !aligned16(m_q) || !aligned16(v_q) ||
-      !aligned16(m_scale) || !aligned16(m_k) || !aligned16(v_scale) || !aligned16(v_k) || !aligned16(w_bf16))
-    return COAT_ERR_ALIGN;
-  if (n > (1ull << 46)) return COAT_ERR_SIZE;
 
   // bias corrections in fp64 on the host (Sec. 3: 1 - beta^t)
   const double b1 = hp->beta1, b2 = hp->beta2;
@@ -1159,17 +1244,12 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
   const double bc1 = 1.0 - p1, bc2 = 1.0 - p2;
   if (!(bc1 > 0.0) || !(bc2 > 0.0)) return COAT_ERR_HPARAM;   // beta == 0 gives bc == 1, fine
 
-  StepArgs a;
-  a.w = w; a.wb = w_bf16; a.g = grad_bf16; a.mq = m_q; a.ms = m_scale; a.mk = m_k; a.vq = v_q; a.vs = v_scale; a.vk = v_k;
-  a.n = n; a.n_full = n / kChunk;
-  a.n_groups = (n + static_cast<uint64_t>(hp->group_size) - 1) / static_cast<uint64_t>(hp->group_size);
   a.one_minus_beta1 = 1.0f - hp->beta1;               // exact (Sterbenz) for beta >= 0.5
   a.one_minus_beta2 = 1.0f - hp->beta2;
   const double omb1 = a.one_minus_beta1, omb2 = a.one_minus_beta2;
   a.beta1_ratio = static_cast<float>(b1 / omb1);
   a.beta2_ratio = static_cast<float>(b2 / omb2);
   a.neg_lr_m = static_cast<float>(-static_cast<double>(hp->lr) * omb1 / bc1);
-  a.neg_lr_wd = static_cast<float>(-static_cast<double>(hp->lr) * static_cast<double>(hp->weight_decay));
   a.denom_scale = static_cast<float>(__builtin_sqrt(omb2 / bc2));
   a.eps = hp->eps;
   a.k_min = k_min; a.k_max = k_max;
@@ -1178,8 +1258,123 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
   a.mode_v.e5 = (hp->flags & COAT_FLAG_V_E5M2) != 0;
   a.mode_m.ex = expand && !(hp->flags & COAT_FLAG_M_PLAIN);
   a.mode_v.ex = expand && !(hp->flags & COAT_FLAG_V_PLAIN);
-  const bool generic = a.mode_m.e5 || a.mode_v.e5 || !a.mode_m.ex || !a.mode_v.ex;
+  generic = a.mode_m.e5 || a.mode_v.e5 || !a.mode_m.ex || !a.mode_v.ex;
+  return COAT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float* m_scale, float* m_k,
+                        uint8_t* v_q, float* v_scale, float* v_k, uint64_t n,
+                        const coat_adamw_hparams* hp, void* hip_stream) {
+  return coat_fp8_adamw_step_bf16w(w, nullptr, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, n, hp, hip_stream);
+}
+
+int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_bf16, uint8_t* m_q,
+                              float* m_scale, float* m_k, uint8_t* v_q, float* v_scale, float* v_k,
+                              uint64_t n, const coat_adamw_hparams* hp, void* hip_stream) {
+  StepArgs a;
+  bool generic = false;
+  if (int rc = step_constants(hp, a, generic)) return rc;
+  if (n == 0) return COAT_OK;
+  if (!w || !grad_bf16 || !m_q || !m_scale || !m_k || !v_q || !v_scale || !v_k) return COAT_ERR_NULL;
+  if (!aligned16(w) || !aligned16(grad_bf16) || !aligned16(m_q) || !aligned16(v_q) ||
+      !aligned16(m_scale) || !aligned16(m_k) || !aligned16(v_scale) || !aligned16(v_k) || !aligned16(w_bf16))
+    return COAT_ERR_ALIGN;
+  if (n > kMaxElements) return COAT_ERR_SIZE;
+  a.w = w; a.wb = w_bf16; a.g = grad_bf16; a.mq = m_q; a.ms = m_scale; a.mk = m_k; a.vq = v_q; a.vs = v_scale; a.vk = v_k;
+  a.n = n; a.n_full = n / kChunk;
+  a.n_groups = (n + static_cast<uint64_t>(hp->group_size) - 1) / static_cast<uint64_t>(hp->group_size);
+  a.neg_lr_wd = static_cast<float>(-static_cast<double>(hp->lr) * static_cast<double>(hp->weight_decay));
   return dispatch_step(a, hp->group_size, generic, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t coat_multi_plan_bytes(const coat_tensor_desc* descs, uint32_t count) {
+  if (count && !descs) return 0;
+  uint64_t chunks = 0;
+  for (uint32_t t = 0; t < count; ++t) {
+    if (descs[t].n > kMaxElements) return 0;
+    chunks += (descs[t].n + kChunk - 1) / kChunk;
+  }
+  if (chunks > kMaxPlanChunks) return 0;
+  return plan_map_offset(count) + static_cast<size_t>(chunks) * sizeof(uint32_t);
+}
+
+int coat_multi_plan_build(const coat_tensor_desc* descs, uint32_t count, void* plan_host, size_t plan_bytes) {
+  if (!plan_host || (count && !descs)) return COAT_ERR_NULL;
+  const size_t need = coat_multi_plan_bytes(descs, count);
+  if (need == 0 || plan_bytes < need) return COAT_ERR_SIZE;
+  for (uint32_t t = 0; t < count; ++t) {
+    const coat_tensor_desc& d = descs[t];
+    if (d.n == 0) continue;
+    if (!d.w || !d.grad_bf16 || !d.m_q || !d.m_scale || !d.m_k || !d.v_q || !d.v_scale || !d.v_k) return COAT_ERR_NULL;
+    if (!aligned16(d.w) || !aligned16(d.grad_bf16) || !aligned16(d.m_q) || !aligned16(d.v_q) || !aligned16(d.m_scale) ||
+        !aligned16(d.m_k) || !aligned16(d.v_scale) || !aligned16(d.v_k) || !aligned16(d.w_bf16))
+      return COAT_ERR_ALIGN;
+    if (!finite_f(d.weight_decay)) return COAT_ERR_HPARAM;
+  }
+  unsigned char* blob = static_cast<unsigned char*>(plan_host);
+  PlanHeader h = {};
+  h.magic = kPlanMagic; h.version = 1; h.count = count;
+  h.desc_offset = sizeof(PlanHeader); h.map_offset = plan_map_offset(count); h.bytes = need;
+  TensorDesc* dd = reinterpret_cast<TensorDesc*>(blob + h.desc_offset);
+  uint32_t* map = reinterpret_cast<uint32_t*>(blob + h.map_offset);
+  uint64_t chunk = 0;
+  for (uint32_t t = 0; t < count; ++t) {
+    const coat_tensor_desc& d = descs[t];
+    TensorDesc o = {};
+    o.w = d.w; o.wb = d.w_bf16; o.g = d.grad_bf16; o.mq = d.m_q; o.ms = d.m_scale; o.mk = d.m_k;
+    o.vq = d.v_q; o.vs = d.v_scale; o.vk = d.v_k; o.n = d.n; o.first_chunk = chunk; o.weight_decay = d.weight_decay;
+    __builtin_memcpy(dd + t, &o, sizeof o);
+    const uint64_t c = (d.n + kChunk - 1) / kChunk;
+    for (uint64_t i = 0; i < c; ++i) map[chunk + i] = t;
+    chunk += c;
+  }
+  h.total_chunks = chunk;
+  __builtin_memcpy(blob, &h, sizeof h);
+  return COAT_OK;
+}
+
+int coat_fp8_adamw_step_multi(const void* plan_host, const void* plan_device, const coat_adamw_hparams* hp,
+                              void* hip_stream) {
+  MultiArgs ma;
+  bool generic = false;
+  if (int rc = step_constants(hp, ma.base, generic)) return rc;
+  if (!plan_host) return COAT_ERR_NULL;
+  PlanHeader h;
+  __builtin_memcpy(&h, plan_host, sizeof h);
+  if (h.magic != kPlanMagic || h.version != 1 || h.desc_offset != sizeof(PlanHeader) ||
+      h.map_offset != plan_map_offset(h.count) || h.total_chunks > kMaxPlanChunks)
+    return COAT_ERR_PLAN;
+  if (h.total_chunks == 0) return COAT_OK;
+  if (!plan_device) return COAT_ERR_NULL;
+  if (!aligned16(plan_device)) return COAT_ERR_ALIGN;
+  const unsigned char* dev = static_cast<const unsigned char*>(plan_device);
+  ma.base.w = nullptr; ma.base.wb = nullptr; ma.base.g = nullptr; ma.base.mq = nullptr; ma.base.ms = nullptr;
+  ma.base.mk = nullptr; ma.base.vq = nullptr; ma.base.vs = nullptr; ma.base.vk = nullptr;
+  ma.base.n = 0; ma.base.n_full = 0; ma.base.n_groups = 0; ma.base.neg_lr_wd = 0.0f;
+  ma.descs = reinterpret_cast<const TensorDesc*>(dev + h.desc_offset);
+  ma.chunk_tensor = reinterpret_cast<const uint32_t*>(dev + h.map_offset);
+  ma.total_chunks = h.total_chunks;
+  ma.neg_lr = -static_cast<double>(hp->lr);
+  ma.group_size = hp->group_size;
+  return dispatch_step_multi(ma, hp->group_size, generic, static_cast<hipStream_t>(hip_stream));
+}
+
+int coat_shard_range(uint64_t n, int32_t G, uint32_t rank, uint32_t world, uint64_t* begin, uint64_t* end) {
+  if (!begin || !end) return COAT_ERR_NULL;
+  if (G < 1) return COAT_ERR_GROUP;
+  if (world == 0 || rank >= world) return COAT_ERR_HPARAM;
+  const uint64_t g = static_cast<uint64_t>(G);
+  const uint64_t groups = n / g + (n % g != 0);
+  const uint64_t base = groups / world, extra = groups % world;           // the first `extra` ranks own one more
+  const uint64_t g0 = rank * base + (rank < extra ? rank : extra);
+  const uint64_t g1 = g0 + base + (rank < extra ? 1 : 0);
+  *begin = g0 * g < n ? g0 * g : n;
+  *end = g1 * g < n ? g1 * g : n;
+  return COAT_OK;
 }
 
 int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags, float k_min, float k_max,
@@ -1190,7 +1385,7 @@ int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags, floa
   if (n == 0) return COAT_OK;
   if (!x || !q || !scale || !k) return COAT_ERR_NULL;
   if (!aligned16(x) || !aligned16(q) || !aligned16(scale) || !aligned16(k)) return COAT_ERR_ALIGN;
-  if (n > (1ull << 46)) return COAT_ERR_SIZE;
+  if (n > kMaxElements) return COAT_ERR_SIZE;
   QuantArgs a;
   a.x = x; a.q = q; a.scale = scale; a.k = k;
   a.n = n; a.n_full = n / kChunk;
@@ -1208,7 +1403,7 @@ int coat_dequant_group(const uint8_t* q, const float* scale, const float* k, uin
   if (n == 0) return COAT_OK;
   if (!x || !q || !scale || !k) return COAT_ERR_NULL;
   if (!aligned16(x) || !aligned16(q) || !aligned16(scale) || !aligned16(k)) return COAT_ERR_ALIGN;
-  if (n > (1ull << 46)) return COAT_ERR_SIZE;
+  if (n > kMaxElements) return COAT_ERR_SIZE;
   DequantArgs a;
   a.q = q; a.scale = scale; a.k = k; a.x = x;
   a.n = n; a.n_full = n / kChunk;
@@ -1224,7 +1419,7 @@ int coat_act_quant_group(const uint16_t* x_bf16, uint64_t n, int32_t G, uint8_t*
   if (n == 0) return COAT_OK;
   if (!x_bf16 || !q || !scale) return COAT_ERR_NULL;
   if (!aligned16(x_bf16) || !aligned16(q) || !aligned16(scale)) return COAT_ERR_ALIGN;
-  if (n > (1ull << 46)) return COAT_ERR_SIZE;
+  if (n > kMaxElements) return COAT_ERR_SIZE;
   ActArgs a;
   a.x = x_bf16; a.q = q; a.per_group = scale; a.partial = nullptr; a.n_partial = 0; a.tensor_amax = nullptr; a.tensor_scale = nullptr;
   a.n = n; a.n_full = n / kChunk;
@@ -1253,12 +1448,13 @@ const char* coat_strerror(int code) {
     case COAT_ERR_STEP: return "step must be >= 1";
     case COAT_ERR_HPARAM: return "hyper-parameter or flag is non-finite, unsupported or out of its domain";
     case COAT_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
-    case COAT_ERR_SIZE: return "n is too large";
+    case COAT_ERR_SIZE: return "n is too large, or the plan buffer is too small";
+    case COAT_ERR_PLAN: return "the plan blob is not one that coat_multi_plan_build wrote";
   }
   return "unknown error code";
 }
 
-int coat_version(void) { return 210; }
+int coat_version(void) { return 220; }
 
 #ifdef COAT_TUNING
 // development builds only: launch-shape knobs for sweeps

@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(coat):
 
 
 def test_error_codes_have_text(coat):
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         assert coat.strerror(code) and "unknown" not in coat.strerror(code)
     assert "unknown" in coat.strerror(-99)
 
@@ -109,6 +109,97 @@ def test_act_quantizers_reject_bad_arguments(coat):
         assert f(ok, 1024, 16, ok, ok, bad4, ok, ok, None) == -2
         assert f(ok, 1 << 50, 16, ok, ok, ok, ok, ok, None) == -7
         assert f(None, 0, 16, None, None, None, None, None, None) == 0
+
+
+def fake_desc(coat, n, wd=0.0, base=0x10000, **over):
+    kw = dict(w=base, w_bf16=0, grad_bf16=base, m_q=base, m_scale=base, m_k=base, v_q=base, v_scale=base, v_k=base)
+    kw.update(over)
+    return coat.TensorDesc(kw["w"], kw["w_bf16"], kw["grad_bf16"], kw["m_q"], kw["m_scale"], kw["m_k"],
+                           kw["v_q"], kw["v_scale"], kw["v_k"], n, wd, 0)
+
+
+def test_multi_plan_layout_is_what_the_header_documents(coat):
+    """The plan is host-built data: check it against the documented layout with an independent
+    reconstruction (chunk -> tensor map by brute force)."""
+    import numpy as np
+    sizes = [5000, 0, 1024, 7, 1 << 20, 1023, 1025]
+    descs = [fake_desc(coat, n, wd=0.01 * i, base=0x10000 * (i + 1)) for i, n in enumerate(sizes)]
+    blob = coat.coat_multi_plan_build(descs)
+    chunks = [(n + 1023) // 1024 for n in sizes]
+    desc_bytes = (96 * len(sizes) + 63) // 64 * 64
+    assert len(blob) == 64 + desc_bytes + 4 * sum(chunks)
+    magic, = np.frombuffer(blob[:8], np.uint64)
+    assert bytes(blob[:8]) == b"COATPLN1" and magic != 0
+    version, count = np.frombuffer(blob[8:16], np.uint32)
+    total, d_off, m_off, nbytes = np.frombuffer(blob[16:48], np.uint64)
+    assert (version, count, total, d_off, m_off, nbytes) == (1, len(sizes), sum(chunks), 64, 64 + desc_bytes, len(blob))
+    cmap = np.frombuffer(blob[m_off:], np.uint32)
+    expect = np.concatenate([np.full(c, t, np.uint32) for t, c in enumerate(chunks)])
+    assert np.array_equal(cmap, expect)
+    first = np.cumsum([0] + chunks[:-1])
+    for t, n in enumerate(sizes):
+        rec = blob[64 + 96 * t: 64 + 96 * (t + 1)]
+        ptrs = np.frombuffer(rec[:72], np.uint64)
+        assert ptrs[0] == 0x10000 * (t + 1) and ptrs[1] == 0 and np.all(ptrs[2:] == 0x10000 * (t + 1))
+        assert np.frombuffer(rec[72:88], np.uint64).tolist() == [n, first[t]]
+        assert np.frombuffer(rec[88:92], np.float32)[0] == np.float32(0.01 * t)
+
+
+def test_multi_plan_and_step_reject_bad_arguments(coat):
+    L = coat.lib()
+    good = [fake_desc(coat, 4096)]
+    arr = (coat.TensorDesc * 1)(*good)
+    size = L.coat_multi_plan_bytes(arr, 1)
+    assert size == 64 + 128 + 16
+    buf = ctypes.create_string_buffer(size)
+    assert L.coat_multi_plan_bytes(None, 1) == 0
+    assert L.coat_multi_plan_bytes(None, 0) == 64                     # an empty plan is legal
+    assert L.coat_multi_plan_build(arr, 1, None, size) == -1
+    assert L.coat_multi_plan_build(arr, 1, buf, size - 1) == -7
+    for field, bad, code in (("w", 0, -1), ("v_k", 0, -1), ("w", 0x10004, -2), ("m_q", 0x10008, -2), ("w_bf16", 0x10002, -2)):
+        arr2 = (coat.TensorDesc * 1)(fake_desc(coat, 4096, **{field: bad}))
+        assert L.coat_multi_plan_build(arr2, 1, buf, size) == code, field
+    arr3 = (coat.TensorDesc * 1)(fake_desc(coat, 4096, wd=float("nan")))
+    assert L.coat_multi_plan_build(arr3, 1, buf, size) == -5
+    arr4 = (coat.TensorDesc * 1)(fake_desc(coat, 1 << 50))
+    assert L.coat_multi_plan_bytes(arr4, 1) == 0
+    assert L.coat_multi_plan_build(arr, 1, buf, size) == 0
+    dev = ctypes.c_void_p(0x20000)
+    hp = coat.make_hparams()
+    assert L.coat_fp8_adamw_step_multi(None, dev, ctypes.byref(hp), None) == -1
+    assert L.coat_fp8_adamw_step_multi(buf, None, ctypes.byref(hp), None) == -1
+    assert L.coat_fp8_adamw_step_multi(buf, ctypes.c_void_p(0x20004), ctypes.byref(hp), None) == -2
+    assert L.coat_fp8_adamw_step_multi(buf, dev, None, None) == -1
+    assert L.coat_fp8_adamw_step_multi(buf, dev, ctypes.byref(coat.make_hparams(group_size=48)), None) == -3
+    assert L.coat_fp8_adamw_step_multi(buf, dev, ctypes.byref(coat.make_hparams(step=0)), None) == -4
+    junk = ctypes.create_string_buffer(b"\x01" * size, size)
+    assert L.coat_fp8_adamw_step_multi(junk, dev, ctypes.byref(hp), None) == -8
+    empty = ctypes.create_string_buffer(64)
+    assert L.coat_multi_plan_build(None, 0, empty, 64) == 0
+    assert L.coat_fp8_adamw_step_multi(empty, None, ctypes.byref(hp), None) == 0      # nothing to do
+
+
+def test_shard_range_partitions_at_group_boundaries(coat):
+    for n, G, world in ((0, 128, 4), (1, 128, 4), (1000, 128, 3), (4096, 128, 8), (4097, 32, 5), (10 ** 9 + 7, 512, 64),
+                        (300, 128, 8)):
+        prev = 0
+        sizes = []
+        for r in range(world):
+            b, e = coat.coat_shard_range(n, G, r, world)
+            assert b == prev and b <= e <= n
+            assert b % G == 0 or b == n
+            assert e % G == 0 or e == n
+            sizes.append((e - b + G - 1) // G)
+            prev = e
+        assert prev == n                                         # the shards tile [0, n)
+        assert max(sizes) - min(sizes) <= 1                      # in groups: balanced to one group
+        assert sizes == sorted(sizes, reverse=True)              # the larger shards come first
+    L = coat.lib()
+    b, e = ctypes.c_uint64(), ctypes.c_uint64()
+    assert L.coat_shard_range(10, 128, 4, 4, ctypes.byref(b), ctypes.byref(e)) == -5
+    assert L.coat_shard_range(10, 128, 0, 0, ctypes.byref(b), ctypes.byref(e)) == -5
+    assert L.coat_shard_range(10, 0, 0, 1, ctypes.byref(b), ctypes.byref(e)) == -3
+    assert L.coat_shard_range(10, 128, 0, 1, None, ctypes.byref(e)) == -1
 
 
 def test_binding_refuses_host_tensors(coat):
