@@ -557,18 +557,21 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const ModeM& mm
 // the same moment and HBM sees their adjacent rows together, which keeps DRAM pages open
 // (measured on the 7B set with three resident workgroups per CU: 15.85 -> 15.05 ms; spans of
 // 32..128 chunks are equally good, 16 or >= 512 lose most of the gain; a probe that only its own
-// wavefront reads, or one that hits in L2, gains nothing).  The empty asm emits no instruction: it
-// makes the chunk index depend on the probed word so that the compiler keeps the loads behind it.
+// wavefront reads, or one that hits in L2, gains nothing; the lighter kernels, whose wavefronts
+// live too briefly to wait, gain nothing either, except the quantizer).  The empty asm emits no
+// instruction: it makes the chunk index depend on the probed word so that the compiler keeps the
+// loads behind it.
 #ifndef COAT_GATE_SHIFT
 #define COAT_GATE_SHIFT 5
 #endif
 constexpr int kGateSpan = 1 << COAT_GATE_SHIFT;
-__device__ __forceinline__ uint64_t gate_on_neighbourhood(const float* per_group, uint64_t chunk, int groups_per_chunk) {
+// `words`: any array of the operand with a fixed number of 32-bit words per chunk.
+__device__ __forceinline__ uint64_t gate_on_neighbourhood(const void* words, uint64_t chunk, int words_per_chunk) {
 #ifdef COAT_NO_GATE
   return chunk;
 #endif
   const uint64_t first = chunk & ~static_cast<uint64_t>(kGateSpan - 1);
-  const uint32_t probe = __builtin_amdgcn_readfirstlane(as_u32(per_group[first * groups_per_chunk]));
+  const uint32_t probe = __builtin_amdgcn_readfirstlane(static_cast<const uint32_t*>(words)[first * words_per_chunk]);
   uint32_t lo = static_cast<uint32_t>(chunk);
   asm volatile("" : "+s"(lo) : "s"(probe));
   return (chunk & 0xffffffff00000000ull) | lo;
@@ -681,6 +684,21 @@ struct TensorDesc {
 };
 static_assert(sizeof(TensorDesc) == 96, "plan layout");
 
+// The same record as the kernel reads it: pointers loaded from memory are generic to the compiler,
+// which would cost flat_load / flat_store; typed as global memory they get the same global_load
+// (scalar base + lane offset) forms as the single-tensor kernel's arguments.
+#define COAT_GLOBAL_AS __attribute__((address_space(1)))
+struct TensorDescDev {
+  COAT_GLOBAL_AS float* w; COAT_GLOBAL_AS uint16_t* wb; COAT_GLOBAL_AS const uint16_t* g;
+  COAT_GLOBAL_AS uint8_t* mq; COAT_GLOBAL_AS float* ms; COAT_GLOBAL_AS float* mk;
+  COAT_GLOBAL_AS uint8_t* vq; COAT_GLOBAL_AS float* vs; COAT_GLOBAL_AS float* vk;
+  uint64_t n;
+  uint64_t first_chunk;
+  float weight_decay;
+  uint32_t reserved;
+};
+static_assert(sizeof(TensorDescDev) == sizeof(TensorDesc), "plan layout");
+
 struct PlanHeader {
   uint64_t magic;
   uint32_t version, count;
@@ -717,8 +735,10 @@ __global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) 
   // everything here is uniform over the wavefront (gc is), so the descriptor travels in scalar registers
   auto locate = [&](uint64_t c) {
     const uint32_t t = __builtin_amdgcn_readfirstlane(ma.chunk_tensor[c]);
-    const TensorDesc& d = ma.descs[t];
-    a.w = d.w; a.wb = d.wb; a.g = d.g; a.mq = d.mq; a.ms = d.ms; a.mk = d.mk; a.vq = d.vq; a.vs = d.vs; a.vk = d.vk;
+    const TensorDescDev& d = reinterpret_cast<const TensorDescDev*>(ma.descs)[t];
+    a.w = (float*)d.w; a.wb = (uint16_t*)d.wb; a.g = (const uint16_t*)d.g;
+    a.mq = (uint8_t*)d.mq; a.ms = (float*)d.ms; a.mk = (float*)d.mk;
+    a.vq = (uint8_t*)d.vq; a.vs = (float*)d.vs; a.vk = (float*)d.vk;
     a.n = d.n; a.n_full = d.n / kChunk;
     a.n_groups = (d.n + G - 1) / G;
     a.neg_lr_wd = static_cast<float>(ma.neg_lr * static_cast<double>(d.weight_decay));
@@ -769,6 +789,7 @@ __global__ __launch_bounds__(kBlock) void quant_kernel(QuantArgs a) {
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
   for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
+    chunk = gate_on_neighbourhood(a.x, chunk, kChunk);   // measured: 871 -> 845 us on 2^30 elements
     const uint64_t cb = chunk * kChunk, gb = chunk * (kChunk / G);
     const f32x4* xq = reinterpret_cast<const f32x4*>(a.x + cb);
     f32x4 rows[4];
