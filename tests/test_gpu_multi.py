@@ -154,3 +154,43 @@ def test_plan_survives_many_steps_and_only_touches_its_tensors(coat):
         for k, t in raw.items():
             assert torch.all(t[:pad] == fills[k]) and torch.all(t[-pad:] == fills[k]), "guard bytes of %s changed" % k
         assert torch.all(torch.isfinite(d["w"])) and torch.all(d["m_scale"] > 0) and torch.all(d["v_scale"] > 0)
+
+
+@pytest.mark.parametrize("workload", ["cfg2", "cfg3"])
+def test_full_size_multi_equals_flat(coat, workload):
+    """The bench's --multi configuration: the workload's weight matrices as separate tensors carved
+    out of one flat buffer, stepped by one multi-tensor launch, must equal the flat single-tensor
+    step bit for bit (two steps from the zero state)."""
+    dev = torch.device("cuda:0")
+    G = 128
+    sizes = [r * c for r, c in S.workload_shapes(workload)]
+    n = sum(sizes)
+    free, _ = torch.cuda.mem_get_info()
+    if free < n * 18 + (1 << 31):
+        pytest.skip("needs %.0f GB of device memory" % (n * 18 / 1e9))
+    gen = S.torch_generator(dev, 3)
+    w = S.torch_weights(n, dev, gen)
+    g = S.torch_grads_normal(n, dev, gen, G=G, outlier_mask=S.torch_outlier_group_mask(n // G, dev, gen, 0.01))
+    st = S.torch_zero_state(n, G, dev)
+    w2, st2 = w.clone(), {k: v.clone() for k, v in st.items()}
+    tens, off = [], 0
+    for x in sizes:
+        d = dict(w=w2[off:off + x], grad=g[off:off + x], weight_decay=HP["weight_decay"])
+        for k in ("m_q", "v_q"):
+            d[k] = st2[k][off:off + x]
+        for k in ("m_scale", "m_k", "v_scale", "v_k"):
+            d[k] = st2[k][off // G:(off + x) // G]
+        tens.append(d)
+        off += x
+    plan = coat.MultiPlan(tens, G)
+    for t in (1, 2):
+        hp = coat.make_hparams(step=t, group_size=G, **HP)
+        coat.coat_fp8_adamw_step(w, g, st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"], hp)
+        coat.coat_fp8_adamw_step_multi(plan, hp)
+        torch.cuda.synchronize()
+        assert torch.equal(w.view(torch.int32), w2.view(torch.int32)), "%s step %d: w differs" % (workload, t)
+        for k in st:
+            a, b = st[k], st2[k]
+            if a.dtype != torch.uint8:
+                a, b = a.view(torch.int32), b.view(torch.int32)
+            assert torch.equal(a, b), "%s step %d: %s differs" % (workload, t, k)
