@@ -209,6 +209,25 @@ def torch_activations(n: int, device, gen, hidden: int = 4096, sigma: float = 1.
     return x
 
 
+def torch_moments(n: int, device, gen, G: int = 128, base: float = 1e-3, group_sigma: float = 1.0,
+                  gamma_shape: float = 4.0):
+    """fp32 first and second moments with the shape Sec. 4.1 describes: every group of G has its own
+    gradient scale s_g = base * exp(group_sigma * z) (so scales differ widely ACROSS groups), while
+    inside a group the dynamic range is small: m = s_g * N(0, 0.3^2), v = s_g^2 * Gamma(shape) / shape
+    (what an exponential average of squared gradients of that scale looks like).  n % G == 0."""
+    import torch
+    assert n % G == 0
+    z = torch.empty(n // G, dtype=torch.float32, device=device).normal_(0.0, 1.0, generator=gen)
+    s = (z * group_sigma).exp_().mul_(base).unsqueeze(1)
+    m = torch.empty((n // G, G), dtype=torch.float32, device=device).normal_(0.0, 0.3, generator=gen).mul_(s)
+    acc = torch.zeros((n // G, G), dtype=torch.float32, device=device)
+    for _ in range(int(gamma_shape)):                         # Gamma(k) for integer k = sum of k exponentials
+        u = torch.rand((n // G, G), device=device, generator=gen).clamp_(min=1e-12)
+        acc.sub_(u.log_())
+    v = acc.div_(gamma_shape).mul_(s * s)
+    return m.reshape(-1), v.reshape(-1)
+
+
 def torch_zero_state(n: int, G: int, device):
     import torch
     ng = (n + G - 1) // G

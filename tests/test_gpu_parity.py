@@ -500,3 +500,36 @@ def test_bf16_entry_rejects_misaligned_copy(coat):
     hp = coat.make_hparams()
     args = [ok, ctypes.c_void_p(0x1002)] + [ok] * 7
     assert L.coat_fp8_adamw_step_bf16w(*args, 4096, ctypes.byref(hp), None) == -2
+
+
+# --- the experiment of Table 1 on the GPU path --------------------------------------------------
+
+def test_table1_structure_on_the_gpu_path(coat, ref):
+    """The sixteen cells of Table 1 computed through the HIP quantizer / dequantizer on synthetic
+    moments: each cell must agree with the same cell computed by the oracle, and the structure
+    the paper reports must hold (expansion helps either moment in either format; the best cells are
+    those with E4M3+Expand for the first moment and an expanded second moment, whose two formats
+    differ by about a percent in the paper as well).  The paper's absolute values need its real
+    optimizer states: unpinned."""
+    from paper_2410_19313_amd.table1 import CELLS, table1
+    n, G, seed = 1 << 18, 128, 4
+    labels, rows = table1(n, G, seed)
+    gen = S.torch_generator(torch.device("cuda:0"), seed)
+    m, v = (t.cpu().numpy() for t in S.torch_moments(n, torch.device("cuda:0"), gen, G=G))
+    exact = m.astype(np.float64) / (np.sqrt(v.astype(np.float64)) + 1e-8)
+
+    def through(x, e5, ex):
+        return ref.dequant_group(*ref.quant_group(x, G, expand=ex, e5m2=e5), G, f64=True, e5m2=e5)
+
+    mh = [through(m, e5, ex) for _, e5, ex in CELLS]
+    vh = [through(v, e5, ex) for _, e5, ex in CELLS]
+    for i in range(4):
+        for j in range(4):
+            want = float(np.mean((mh[i] / (np.sqrt(vh[j]) + 1e-8) - exact) ** 2))
+            assert abs(rows[i][j] - want) <= 2e-3 * want, (labels[i], labels[j], rows[i][j], want)
+    r = np.asarray(rows)
+    plain = {0: 1, 2: 3}                                  # index of a plain cell -> its +Expand twin
+    for p, e in plain.items():
+        assert np.all(r[e, :] < r[p, :]) and np.all(r[:, e] < r[:, p])
+    assert min(r[1, 1], r[1, 3]) == r.min() and r[1, 1] <= 1.1 * r.min()
+    assert r[0, 0] > 1.3 * r[1, 1]                        # the direction of the paper's 1.63x
