@@ -117,10 +117,19 @@ static void resolve_k_bounds(float* k_min, float* k_max) {
   if (*k_min == 0.0f && *k_max == 0.0f) { *k_min = 0.0625f; *k_max = 1024.0f; }
 }
 
-static void quant_one_group(const float* x, uint64_t len, int expand, fmt_t f,
+/* Smallest bf16 value that is not below s (s > 0 and finite): the scale "stored in BF16" of Sec. 3.
+ * Rounding UP keeps every |x| / (fmax * scale) at or below 1, so no code saturates. */
+static float bf16_ceil(float s) {
+  union { uint32_t u; float f; } cvt;
+  cvt.f = s;
+  cvt.u = (cvt.u + 0xFFFFu) & 0xFFFF0000u;
+  return cvt.f;
+}
+
+static void quant_one_group(const float* x, uint64_t len, int expand, fmt_t f, int scale16,
                             float k_min, float k_max,
                             uint8_t* q, float* scale_out, float* k_out) {
-  double amax = 0.0, amin = INFINITY;
+  double amax = 0.0, amin = INFINITY, top;
   float scale, k = 1.0f;
   double a, kd;
   uint64_t i;
@@ -139,9 +148,17 @@ static void quant_one_group(const float* x, uint64_t len, int expand, fmt_t f,
     return;
   }
   scale = (float)(amax / f.fmax);                /* S_X of Sec. 3, kept in fp32 */
+  top = amax;
+  if (scale16) {
+    /* BF16 scale: the group is normalized by fmax * scale >= amax, so the range that has to fit
+     * the format is (fmax * scale) / amin: k from that ratio keeps the smallest element
+     * representable (with amax / amin the whole group would shrink by (amax / (fmax scale))^k) */
+    scale = bf16_ceil(scale);
+    top = f.fmax * (double)scale;
+  }
   if (expand && amax != amin) {
     /* optimal k of Sec. 4.2: R_X^k = R_format */
-    kd = f.log2_range / log2(amax / amin);
+    kd = f.log2_range / log2(top / amin);
     if (kd < (double)k_min) kd = (double)k_min;
     if (kd > (double)k_max) kd = (double)k_max;
     k = (float)kd;
@@ -187,7 +204,7 @@ void coat_ref_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags,
     uint64_t lo = (uint64_t)gi * (uint64_t)G;
     uint64_t len = (n - lo < (uint64_t)G) ? n - lo : (uint64_t)G;
     quant_one_group(x + lo, len, (flags & COAT_REF_FLAG_EXPAND) != 0, fmt_of((flags & COAT_REF_FLAG_E5M2) != 0),
-                    k_min, k_max, q + lo, scale + gi, k + gi);
+                    (flags & COAT_REF_FLAG_BF16_SCALE) != 0, k_min, k_max, q + lo, scale + gi, k + gi);
   }
 }
 
@@ -317,7 +334,7 @@ int coat_ref_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* gr
   float k_min, k_max;
   int32_t G;
   int64_t ng, gi;
-  int failed = 0, expand_m, expand_v;
+  int failed = 0, expand_m, expand_v, scale16;
   fmt_t fm, fv;
 
   if (!hp) return -1;
@@ -337,6 +354,7 @@ int coat_ref_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* gr
   fv = fmt_of((hp->flags & COAT_REF_FLAG_V_E5M2) != 0);
   expand_m = (hp->flags & COAT_REF_FLAG_EXPAND) && !(hp->flags & COAT_REF_FLAG_M_PLAIN);
   expand_v = (hp->flags & COAT_REF_FLAG_EXPAND) && !(hp->flags & COAT_REF_FLAG_V_PLAIN);
+  scale16 = (hp->flags & COAT_REF_FLAG_BF16_SCALE) != 0;
 
 #pragma omp parallel for schedule(static)
   for (gi = 0; gi < ng; ++gi) {
@@ -373,8 +391,8 @@ int coat_ref_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* gr
     }
 
     /* m^q_t, S = Q(m_t);  v^q_t, S = Q(v_t) */
-    quant_one_group(mt, len, expand_m, fm, k_min, k_max, m_q + lo, m_scale + gi, m_k + gi);
-    quant_one_group(vt, len, expand_v, fv, k_min, k_max, v_q + lo, v_scale + gi, v_k + gi);
+    quant_one_group(mt, len, expand_m, fm, scale16, k_min, k_max, m_q + lo, m_scale + gi, m_k + gi);
+    quant_one_group(vt, len, expand_v, fv, scale16, k_min, k_max, v_q + lo, v_scale + gi, v_k + gi);
     free(m); free(mt);
   }
   return failed ? -1 : 0;

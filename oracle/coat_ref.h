@@ -39,6 +39,9 @@ typedef struct {
 #define COAT_REF_FLAG_V_E5M2  4u   /* second moment stored as E5M2 */
 #define COAT_REF_FLAG_M_PLAIN 8u   /* first moment: plain quantizer even when EXPAND is set */
 #define COAT_REF_FLAG_V_PLAIN 16u  /* second moment: plain quantizer even when EXPAND is set */
+#define COAT_REF_FLAG_BF16_SCALE 32u /* scales are stored in BF16 (Sec. 3): rounded UP to a bf16 value, which
+                                        the quantizer then uses; k from (fmax * scale) / amin.  The arrays
+                                        stay float here; every value in them is a bf16. */
 
 /* OCP FP8 E4M3 ("FN"): 1-4-3 bits, bias 7, no infinity, 0x7F/0xFF are NaN, largest
  * finite 448 and smallest positive 2^-9 (the two constants Sec. 3 prints). */
