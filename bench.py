@@ -183,6 +183,7 @@ def main():
     ap.add_argument("--v-e5m2", action="store_true", help="second moment in E5M2")
     ap.add_argument("--m-plain", action="store_true", help="first moment without dynamic range expansion")
     ap.add_argument("--v-plain", action="store_true", help="second moment without dynamic range expansion")
+    ap.add_argument("--bf16-scale", action="store_true", help="per-group scales stored as bf16 (14 + 24/G B/param)")
     ap.add_argument("--emit-bf16", action="store_true", help="also write the bf16 copy of the new weights (+2 B/param)")
     ap.add_argument("--multi", action="store_true",
                     help="step the workload as its separate tensors through ONE multi-tensor launch")
@@ -226,6 +227,8 @@ def main():
         return
     w = S.torch_weights(n, dev, gen)
     st = S.torch_zero_state(n, G, dev)
+    if args.bf16_scale:
+        st["m_scale"], st["v_scale"] = st["m_scale"].to(torch.bfloat16), st["v_scale"].to(torch.bfloat16)
     mask = S.torch_outlier_group_mask(n // G, dev, gen, 0.01)
     # two gradient buffers, alternated, so that consecutive steps do not see identical input
     if args.grads == "normal":
@@ -263,7 +266,7 @@ def main():
 
     def step(t):
         hp = C.make_hparams(step=t, group_size=G, m_e5m2=args.m_e5m2, v_e5m2=args.v_e5m2,
-                            m_plain=args.m_plain, v_plain=args.v_plain, **HP)
+                            m_plain=args.m_plain, v_plain=args.v_plain, bf16_scale=args.bf16_scale, **HP)
         if plans is not None:
             C.coat_fp8_adamw_step_multi(plans[t & 1], hp)
         elif args.emit_bf16:
@@ -296,10 +299,10 @@ def main():
     if not finite:
         sys.exit("bench.py: non-finite weights after the timed steps")
 
-    generic = args.m_e5m2 or args.v_e5m2 or args.m_plain or args.v_plain
+    generic = args.m_e5m2 or args.v_e5m2 or args.m_plain or args.v_plain or args.bf16_scale
     ms_per_step = wall / args.steps * 1e3
     value = n * args.steps / wall
-    algo_bytes = (bytes_per_param(G) + (2.0 if args.emit_bf16 else 0.0)) * n
+    algo_bytes = (bytes_per_param(G) + (2.0 if args.emit_bf16 else 0.0) - (8.0 / G if args.bf16_scale else 0.0)) * n
     achieved = algo_bytes / avg_launch_s / 1e9
     out = {
         "metric": "params updated/sec, FP8-state AdamW (E4M3 m/v, per-group scale + dynamic range expansion)",
@@ -320,11 +323,12 @@ def main():
                 args.workload], n, G, args.grads) + (
                     ", m %s%s, v %s%s" % ("E5M2" if args.m_e5m2 else "E4M3", "" if args.m_plain else "+expand",
                                             "E5M2" if args.v_e5m2 else "E4M3", "" if args.v_plain else "+expand")
-                    if generic else "") + (", bf16 weight copy" if args.emit_bf16 else "") + (
+                    if generic else "") + (", bf16 weight copy" if args.emit_bf16 else "") + (", bf16 scales" if args.bf16_scale else "") + (
                         ", %d tensors in one multi-tensor launch" % len(plans[0].tensors) if plans else ""),
             "params": n, "group_size": G, "hbm_gbs": achieved, "hbm_frac_of_peak": achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_profile_traffic(args.workload, G),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": (read_profile_traffic(args.workload, G)
+                                 if not (generic or args.emit_bf16 or plans) else None),   # the counters were read for the default kernel
                      "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_ms": avg_launch_s * 1e3,
                      "kernel": "adamw_step%s_kernel<%d, %s>" % ("_multi" if plans else "", G, "generic" if generic else "default")},
     }

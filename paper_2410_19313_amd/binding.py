@@ -12,7 +12,7 @@ import os
 
 from . import build as _build
 
-FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN = 1, 2, 2, 4, 8, 16
+FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN, FLAG_BF16_SCALE = 1, 2, 2, 4, 8, 16, 32
 SUPPORTED_GROUP_SIZES = (32, 64, 128, 256, 512)
 
 ACT_GROUP_SIZES = (16,) + SUPPORTED_GROUP_SIZES
@@ -58,16 +58,22 @@ class TensorDesc(ctypes.Structure):
     ]
 
 
-def step_flags(expand=True, m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False) -> int:
+def step_flags(expand=True, m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False) -> int:
     return ((FLAG_EXPAND if expand else 0) | (FLAG_M_E5M2 if m_e5m2 else 0) | (FLAG_V_E5M2 if v_e5m2 else 0)
-            | (FLAG_M_PLAIN if m_plain else 0) | (FLAG_V_PLAIN if v_plain else 0))
+            | (FLAG_M_PLAIN if m_plain else 0) | (FLAG_V_PLAIN if v_plain else 0)
+            | (FLAG_BF16_SCALE if bf16_scale else 0))
+
+
+def _scale_dtype(flags: int):
+    import torch
+    return torch.bfloat16 if flags & FLAG_BF16_SCALE else torch.float32
 
 
 def make_hparams(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1,
                  group_size=128, expand=True, k_min=0.0, k_max=0.0,
-                 m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False) -> HParams:
+                 m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False) -> HParams:
     return HParams(lr, beta1, beta2, eps, weight_decay, int(step), int(group_size),
-                   step_flags(expand, m_e5m2, v_e5m2, m_plain, v_plain), k_min, k_max)
+                   step_flags(expand, m_e5m2, v_e5m2, m_plain, v_plain, bf16_scale), k_min, k_max)
 
 
 _lib = None
@@ -152,8 +158,8 @@ def coat_fp8_adamw_step(w, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, hp: 
     ng = n_groups(n, hp.group_size) if hp.group_size > 0 else 0
     _check(lib().coat_fp8_adamw_step(
         _dev_ptr(w, torch.float32), _dev_ptr(grad_bf16, torch.bfloat16, n),
-        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, torch.float32, ng), _dev_ptr(m_k, torch.float32, ng),
-        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, torch.float32, ng), _dev_ptr(v_k, torch.float32, ng),
+        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, _scale_dtype(hp.flags), ng), _dev_ptr(m_k, torch.float32, ng),
+        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, _scale_dtype(hp.flags), ng), _dev_ptr(v_k, torch.float32, ng),
         n, ctypes.byref(hp), _stream()))
 
 
@@ -164,39 +170,40 @@ def coat_fp8_adamw_step_bf16w(w, w_bf16, grad_bf16, m_q, m_scale, m_k, v_q, v_sc
     ng = n_groups(n, hp.group_size) if hp.group_size > 0 else 0
     _check(lib().coat_fp8_adamw_step_bf16w(
         _dev_ptr(w, torch.float32), _dev_ptr(w_bf16, torch.bfloat16, n), _dev_ptr(grad_bf16, torch.bfloat16, n),
-        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, torch.float32, ng), _dev_ptr(m_k, torch.float32, ng),
-        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, torch.float32, ng), _dev_ptr(v_k, torch.float32, ng),
+        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, _scale_dtype(hp.flags), ng), _dev_ptr(m_k, torch.float32, ng),
+        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, _scale_dtype(hp.flags), ng), _dev_ptr(v_k, torch.float32, ng),
         n, ctypes.byref(hp), _stream()))
 
 
 def coat_quant_group(x, G: int, expand: bool = True, k_min: float = 0.0, k_max: float = 0.0,
-                     out=None, e5m2: bool = False):
-    """x fp32 [n] -> (codes uint8 [n], scale fp32 [ng], k fp32 [ng]) written on the device."""
+                     out=None, e5m2: bool = False, bf16_scale: bool = False):
+    """x fp32 [n] -> (codes uint8 [n], scale fp32 (bfloat16 with bf16_scale) [ng], k fp32 [ng]) on the device."""
     import torch
     n = x.numel()
     ng = n_groups(n, G) if G > 0 else 0
+    flags = (FLAG_EXPAND if expand else 0) | (FLAG_E5M2 if e5m2 else 0) | (FLAG_BF16_SCALE if bf16_scale else 0)
     if out is None:
         out = (torch.empty(n, dtype=torch.uint8, device=x.device),
-               torch.empty(ng, dtype=torch.float32, device=x.device),
+               torch.empty(ng, dtype=_scale_dtype(flags), device=x.device),
                torch.empty(ng, dtype=torch.float32, device=x.device))
     q, scale, k = out
-    _check(lib().coat_quant_group(_dev_ptr(x, torch.float32), n, G,
-                                  (FLAG_EXPAND if expand else 0) | (FLAG_E5M2 if e5m2 else 0),
+    _check(lib().coat_quant_group(_dev_ptr(x, torch.float32), n, G, flags,
                                   k_min, k_max, _dev_ptr(q, torch.uint8, n),
-                                  _dev_ptr(scale, torch.float32, ng), _dev_ptr(k, torch.float32, ng),
+                                  _dev_ptr(scale, _scale_dtype(flags), ng), _dev_ptr(k, torch.float32, ng),
                                   _stream()))
     return q, scale, k
 
 
 def coat_dequant_group(q, scale, k, G: int, out=None, e5m2: bool = False):
-    """codes uint8 [n] + per-group scale, k -> fp32 [n] on the device."""
+    """codes uint8 [n] + per-group scale (fp32 or bfloat16), k -> fp32 [n] on the device."""
     import torch
     n = q.numel()
     ng = n_groups(n, G) if G > 0 else 0
     if out is None:
         out = torch.empty(n, dtype=torch.float32, device=q.device)
-    _check(lib().coat_dequant_group(_dev_ptr(q, torch.uint8), _dev_ptr(scale, torch.float32, ng),
-                                    _dev_ptr(k, torch.float32, ng), n, G, FLAG_E5M2 if e5m2 else 0,
+    flags = (FLAG_E5M2 if e5m2 else 0) | (FLAG_BF16_SCALE if scale.dtype == torch.bfloat16 else 0)
+    _check(lib().coat_dequant_group(_dev_ptr(q, torch.uint8), _dev_ptr(scale, _scale_dtype(flags), ng),
+                                    _dev_ptr(k, torch.float32, ng), n, G, flags,
                                     _dev_ptr(out, torch.float32, n), _stream()))
     return out
 
@@ -287,6 +294,8 @@ class MultiPlan:
         w_bf16 and weight_decay (default 0.0).  G is only used to check the metadata sizes here."""
         import torch
         descs = []
+        sdt = tensors[0]["m_scale"].dtype if tensors else torch.float32     # fp32, or bfloat16 for COAT_FLAG_BF16_SCALE
+        self.bf16_scale = sdt == torch.bfloat16
         for t in tensors:
             n = t["w"].numel()
             ng = n_groups(n, G)
@@ -295,9 +304,9 @@ class MultiPlan:
                 _dev_ptr(t["w"], torch.float32).value or 0,
                 (_dev_ptr(wb, torch.bfloat16, n).value or 0) if wb is not None else 0,
                 _dev_ptr(t["grad"], torch.bfloat16, n).value or 0,
-                _dev_ptr(t["m_q"], torch.uint8, n).value or 0, _dev_ptr(t["m_scale"], torch.float32, ng).value or 0,
+                _dev_ptr(t["m_q"], torch.uint8, n).value or 0, _dev_ptr(t["m_scale"], sdt, ng).value or 0,
                 _dev_ptr(t["m_k"], torch.float32, ng).value or 0,
-                _dev_ptr(t["v_q"], torch.uint8, n).value or 0, _dev_ptr(t["v_scale"], torch.float32, ng).value or 0,
+                _dev_ptr(t["v_q"], torch.uint8, n).value or 0, _dev_ptr(t["v_scale"], sdt, ng).value or 0,
                 _dev_ptr(t["v_k"], torch.float32, ng).value or 0,
                 n, float(t.get("weight_decay", 0.0)), 0))
         self.tensors = list(tensors)
@@ -313,5 +322,7 @@ def coat_fp8_adamw_step_multi(plan: MultiPlan, hp: HParams) -> None:
     each tensor carries its own)."""
     if hp.group_size != plan.group_size:
         raise ValueError("the plan's metadata buffers were sized for G=%d" % plan.group_size)
+    if bool(hp.flags & FLAG_BF16_SCALE) != plan.bf16_scale:
+        raise ValueError("COAT_FLAG_BF16_SCALE must match the dtype of the plan's scale tensors")
     _check(lib().coat_fp8_adamw_step_multi(ctypes.cast(plan._host_buf, ctypes.c_void_p),
                                            ctypes.c_void_p(plan.device.data_ptr()), ctypes.byref(hp), _stream()))

@@ -48,11 +48,14 @@ template <bool E5M2, bool EXPAND>
 struct StaticMode {
   __device__ __forceinline__ bool e5m2() const { return E5M2; }
   __device__ __forceinline__ bool expand() const { return EXPAND; }
+  __device__ __forceinline__ bool scale16() const { return false; }
 };
 struct RuntimeMode {
   bool e5, ex;
+  bool s16;   // the per-group scales are stored as bf16 (Sec. 3) instead of fp32
   __device__ __forceinline__ bool e5m2() const { return e5; }
   __device__ __forceinline__ bool expand() const { return ex; }
+  __device__ __forceinline__ bool scale16() const { return s16; }
 };
 typedef StaticMode<false, true> DefaultMode;
 
@@ -110,6 +113,19 @@ struct DequantArgs {
 
 __device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// Per-group scale i of an array that holds fp32 or, with scale16, bf16 values (the pointer is typed
+// float* either way).  A stored bf16 scale is exact: the quantizer rounded it before using it.
+template <class Mode>
+__device__ __forceinline__ float load_scale(const Mode& md, const float* p, uint64_t i) {
+  if (md.scale16()) return as_f32(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(p)[i]) << 16);
+  return p[i];
+}
+template <class Mode>
+__device__ __forceinline__ void store_scale(const Mode& md, float* p, uint64_t i, float s) {
+  if (md.scale16()) reinterpret_cast<uint16_t*>(p)[i] = static_cast<uint16_t>(as_u32(s) >> 16);
+  else p[i] = s;
+}
 
 __device__ __forceinline__ float hw_log2(float x) { return __builtin_amdgcn_logf(x); }
 __device__ __forceinline__ float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -361,11 +377,18 @@ __device__ __forceinline__ GroupQuant group_quant_params(const Mode& md, float a
   const float ax = amax * unit;
   float s = ax * inv_fmax;
   s = __builtin_fmaf(__builtin_fmaf(-fmax, s, ax), inv_fmax, s);
+  float top = amax;                                  // what the group is normalized by, in held units
+  if (md.scale16()) {
+    // BF16 scale: round UP to a bf16 value (every |x| / (fmax*scale) stays <= 1, nothing saturates)
+    // and take the range that has to fit the format against fmax*scale rather than amax
+    s = as_f32((as_u32(s) + 0xFFFFu) & 0xFFFF0000u);
+    top = (fmax * s) / unit;
+  }
   float k = 1.0f;
   if (md.expand()) {
     // two hardware reciprocals (1 ulp each) are enough here: k moves by ~2 ulp
     // (the max keeps a ratio that rounds below 1 from turning the huge k negative)
-    const float ratio = __builtin_fmaxf(amax * hw_rcp(amin), 1.0f);   // R_X
+    const float ratio = __builtin_fmaxf(top * hw_rcp(amin), 1.0f);    // R_X
     float kk = fmt_log2_range(md) * hw_rcp(hw_log2(ratio));
     kk = __builtin_amdgcn_fmed3f(kk, k_min, k_max);
     k = (amax != amin) ? kk : 1.0f;
@@ -495,8 +518,9 @@ struct RawChunk {
   GroupMeta meta;
 };
 
-template <int G>
-__device__ __forceinline__ void issue_loads(const StepArgs& a, uint64_t chunk, int lane, RawChunk& r) {
+template <int G, class ModeM, class ModeV>
+__device__ __forceinline__ void issue_loads(const StepArgs& a, const ModeM& mm, const ModeV& mv, uint64_t chunk,
+                                            int lane, RawChunk& r) {
   constexpr int LPG = G / kEPL;
   // chunk is uniform over the wavefront: the array bases below are scalar, lanes add 32-bit offsets
   const uint64_t cb = chunk * kChunk;
@@ -512,8 +536,8 @@ __device__ __forceinline__ void issue_loads(const StepArgs& a, uint64_t chunk, i
   for (int j = 0; j < 2; ++j) r.g[j] = ldg<4>(gq + 64 * j + lane);
   r.mc = ldg<1>(mq + lane);
   r.vc = ldg<1>(vq + lane);
-  r.meta.m_scale = a.ms[gb + gl];
-  r.meta.v_scale = a.vs[gb + gl];
+  r.meta.m_scale = load_scale(mm, a.ms, gb + gl);
+  r.meta.v_scale = load_scale(mv, a.vs, gb + gl);
   r.meta.m_k = a.mk[gb + gl];          // written as 1 (and ignored) by a moment stored without expansion
   r.meta.v_k = a.vk[gb + gl];
 }
@@ -543,16 +567,16 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const ModeM& mm
   stg<2>(reinterpret_cast<u32x4*>(a.vq + cb) + lane, vo);
   if ((lane % LPG) == 0) {
     const int gl = lane / LPG;
-    a.ms[gb + gl] = meta.m_scale; a.mk[gb + gl] = meta.m_k;
-    a.vs[gb + gl] = meta.v_scale; a.vk[gb + gl] = meta.v_k;
+    store_scale(mm, a.ms, gb + gl, meta.m_scale); a.mk[gb + gl] = meta.m_k;
+    store_scale(mv, a.vs, gb + gl, meta.v_scale); a.vk[gb + gl] = meta.v_k;
   }
 }
 
 // Admission gate.  Before a wavefront issues the loads of its chunk it reads ONE word that all
 // wavefronts of its neighbourhood (kGateSpan consecutive chunks, i.e. a quarter of that many
 // workgroups, which the dispatcher spreads over all eight XCDs) read as well: the first per-group
-// scale of the neighbourhood's first chunk, a word of the tensor's own metadata that is fetched
-// anyway.  The first reader misses to HBM; the others are served by the memory-side cache as soon
+// exponent k of the neighbourhood's first chunk, a word of the tensor's own metadata that is
+// fetched anyway.  The first reader misses to HBM; the others are served by the memory-side cache as soon
 // as that fill lands.  The wavefronts of a neighbourhood therefore start their bulk loads at about
 // the same moment and HBM sees their adjacent rows together, which keeps DRAM pages open
 // (measured on the 7B set with three resident workgroups per CU: 15.85 -> 15.05 ms; spans of
@@ -609,12 +633,12 @@ __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
 
   RawChunk r;
   const bool have = chunk < a.n_full;
-  if (have) chunk = gate_on_neighbourhood(a.ms, chunk, kChunk / G);
-  if (have) issue_loads<G>(a, chunk, lane, r);
+  if (have) chunk = gate_on_neighbourhood(a.mk, chunk, kChunk / G);
+  if (have) issue_loads<G>(a, mm, mv, chunk, lane, r);
   fill_lut<kTables>(lut);                            // every wavefront of the block reaches this
   if (have) process_chunk<G>(a, mm, mv, lut, tiles, chunk, lane, r);
   for (chunk += stride; chunk < a.n_full; chunk += stride) {
-    issue_loads<G>(a, chunk, lane, r);
+    issue_loads<G>(a, mm, mv, chunk, lane, r);
     process_chunk<G>(a, mm, mv, lut, tiles, chunk, lane, r);
   }
 }
@@ -636,8 +660,8 @@ __device__ __forceinline__ void process_tail_chunk(const StepArgs& a, const Mode
   load_codes16_guarded(a.mq, base, a.n, mc);
   load_codes16_guarded(a.vq, base, a.n, vc);
   GroupMeta meta;
-  meta.m_scale = gvalid ? a.ms[gidx] : 0.0f;
-  meta.v_scale = gvalid ? a.vs[gidx] : 0.0f;
+  meta.m_scale = gvalid ? load_scale(mm, a.ms, gidx) : 0.0f;
+  meta.v_scale = gvalid ? load_scale(mv, a.vs, gidx) : 0.0f;
   meta.m_k = gvalid ? a.mk[gidx] : 1.0f;
   meta.v_k = gvalid ? a.vk[gidx] : 1.0f;
   step_core<G>(a, mm, mv, lut, w, g, mc, vc, meta);
@@ -653,8 +677,8 @@ __device__ __forceinline__ void process_tail_chunk(const StepArgs& a, const Mode
   store_codes16_guarded(a.mq, base, a.n, mc);
   store_codes16_guarded(a.vq, base, a.n, vc);
   if (gvalid && (lane % LPG) == 0) {
-    a.ms[gidx] = meta.m_scale; a.mk[gidx] = meta.m_k;
-    a.vs[gidx] = meta.v_scale; a.vk[gidx] = meta.v_k;
+    store_scale(mm, a.ms, gidx, meta.m_scale); a.mk[gidx] = meta.m_k;
+    store_scale(mv, a.vs, gidx, meta.v_scale); a.vk[gidx] = meta.v_k;
   }
 }
 
@@ -752,8 +776,8 @@ __global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) 
     locate(gc);
     full = chunk < a.n_full;
     if (full) {
-      chunk = gate_on_neighbourhood(a.ms, chunk, kChunk / G);
-      issue_loads<G>(a, chunk, lane, r);
+      chunk = gate_on_neighbourhood(a.mk, chunk, kChunk / G);
+      issue_loads<G>(a, mm, mv, chunk, lane, r);
     }
   }
   fill_lut<kTables>(lut);                            // every wavefront of the block reaches this
@@ -801,7 +825,7 @@ __global__ __launch_bounds__(kBlock) void quant_kernel(QuantArgs a) {
     const GroupQuant q = quant_core<G>(a, x, c);
     const u32x4 co = {c[0], c[1], c[2], c[3]};
     stg<2>(reinterpret_cast<u32x4*>(a.q + cb) + lane, co);
-    if ((lane % LPG) == 0) { a.scale[gb + lane / LPG] = q.scale; a.k[gb + lane / LPG] = q.k; }
+    if ((lane % LPG) == 0) { store_scale(a.mode, a.scale, gb + lane / LPG, q.scale); a.k[gb + lane / LPG] = q.k; }
   }
 }
 
@@ -817,7 +841,7 @@ __global__ __launch_bounds__(kWave) void quant_tail_kernel(QuantArgs a) {
   load_f32x16_guarded(a.x, base, a.n, x);
   const GroupQuant q = quant_core<G>(a, x, c);
   store_codes16_guarded(a.q, base, a.n, c);
-  if (gidx < a.n_groups && (lane % LPG) == 0) { a.scale[gidx] = q.scale; a.k[gidx] = q.k; }
+  if (gidx < a.n_groups && (lane % LPG) == 0) { store_scale(a.mode, a.scale, gidx, q.scale); a.k[gidx] = q.k; }
 }
 
 // The standalone dequantizer always honours the stored k (it is 1 for codes written without
@@ -844,7 +868,7 @@ __global__ __launch_bounds__(kBlock) void dequant_kernel(DequantArgs a) {
     const u32x4 ci = ldg<1>(reinterpret_cast<const u32x4*>(a.q + cb) + lane);
     const uint32_t c[4] = {ci.x, ci.y, ci.z, ci.w};
     float x[kEPL];
-    dequant_core(a, lut, c, a.scale[gb + lane / LPG], a.k[gb + lane / LPG], x);
+    dequant_core(a, lut, c, load_scale(a.mode, a.scale, gb + lane / LPG), a.k[gb + lane / LPG], x);
     tile_lanes_to_rows_store(tile_x + wv * kTileSlotsW, lane, x, a.x + cb);
   }
 }
@@ -861,7 +885,7 @@ __global__ __launch_bounds__(kWave) void dequant_tail_kernel(DequantArgs a) {
   uint32_t c[4];
   float x[kEPL];
   load_codes16_guarded(a.q, base, a.n, c);
-  dequant_core(a, lut, c, gvalid ? a.scale[gidx] : 0.0f, gvalid ? a.k[gidx] : 1.0f, x);
+  dequant_core(a, lut, c, gvalid ? load_scale(a.mode, a.scale, gidx) : 0.0f, gvalid ? a.k[gidx] : 1.0f, x);
   store_f32x16_guarded(a.x, base, a.n, x);
 }
 
@@ -1262,7 +1286,7 @@ int dispatch_step_multi(const MultiArgs& ma, int32_t G, bool generic, hipStream_
 }
 
 constexpr uint32_t kStepFlags = COAT_FLAG_EXPAND | COAT_FLAG_M_E5M2 | COAT_FLAG_V_E5M2 | COAT_FLAG_M_PLAIN |
-                                COAT_FLAG_V_PLAIN;
+                                COAT_FLAG_V_PLAIN | COAT_FLAG_BF16_SCALE;
 
 constexpr uint64_t kMaxPlanChunks = 1ull << 32;     // one launch covers them all (4 per workgroup)
 
@@ -1313,7 +1337,8 @@ int step_constants(const coat_adamw_hparams* hp, StepArgs& a, bool& generic) {
   a.mode_v.e5 = (hp->flags & COAT_FLAG_V_E5M2) != 0;
   a.mode_m.ex = expand && !(hp->flags & COAT_FLAG_M_PLAIN);
   a.mode_v.ex = expand && !(hp->flags & COAT_FLAG_V_PLAIN);
-  generic = a.mode_m.e5 || a.mode_v.e5 || !a.mode_m.ex || !a.mode_v.ex;
+  a.mode_m.s16 = a.mode_v.s16 = (hp->flags & COAT_FLAG_BF16_SCALE) != 0;
+  generic = a.mode_m.e5 || a.mode_v.e5 || !a.mode_m.ex || !a.mode_v.ex || a.mode_m.s16;
   return COAT_OK;
 }
 
@@ -1321,14 +1346,14 @@ int step_constants(const coat_adamw_hparams* hp, StepArgs& a, bool& generic) {
 
 extern "C" {
 
-int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float* m_scale, float* m_k,
-                        uint8_t* v_q, float* v_scale, float* v_k, uint64_t n,
+int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, void* m_scale, float* m_k,
+                        uint8_t* v_q, void* v_scale, float* v_k, uint64_t n,
                         const coat_adamw_hparams* hp, void* hip_stream) {
   return coat_fp8_adamw_step_bf16w(w, nullptr, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, n, hp, hip_stream);
 }
 
 int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_bf16, uint8_t* m_q,
-                              float* m_scale, float* m_k, uint8_t* v_q, float* v_scale, float* v_k,
+                              void* m_scale, float* m_k, uint8_t* v_q, void* v_scale, float* v_k,
                               uint64_t n, const coat_adamw_hparams* hp, void* hip_stream) {
   StepArgs a;
   bool generic = false;
@@ -1339,7 +1364,7 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
       !aligned16(m_scale) || !aligned16(m_k) || !aligned16(v_scale) || !aligned16(v_k) || !aligned16(w_bf16))
     return COAT_ERR_ALIGN;
   if (n > kMaxElements) return COAT_ERR_SIZE;
-  a.w = w; a.wb = w_bf16; a.g = grad_bf16; a.mq = m_q; a.ms = m_scale; a.mk = m_k; a.vq = v_q; a.vs = v_scale; a.vk = v_k;
+  a.w = w; a.wb = w_bf16; a.g = grad_bf16; a.mq = m_q; a.ms = static_cast<float*>(m_scale); a.mk = m_k; a.vq = v_q; a.vs = static_cast<float*>(v_scale); a.vk = v_k;
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(hp->group_size) - 1) / static_cast<uint64_t>(hp->group_size);
   a.neg_lr_wd = static_cast<float>(-static_cast<double>(hp->lr) * static_cast<double>(hp->weight_decay));
@@ -1380,8 +1405,8 @@ int coat_multi_plan_build(const coat_tensor_desc* descs, uint32_t count, void* p
   for (uint32_t t = 0; t < count; ++t) {
     const coat_tensor_desc& d = descs[t];
     TensorDesc o = {};
-    o.w = d.w; o.wb = d.w_bf16; o.g = d.grad_bf16; o.mq = d.m_q; o.ms = d.m_scale; o.mk = d.m_k;
-    o.vq = d.v_q; o.vs = d.v_scale; o.vk = d.v_k; o.n = d.n; o.first_chunk = chunk; o.weight_decay = d.weight_decay;
+    o.w = d.w; o.wb = d.w_bf16; o.g = d.grad_bf16; o.mq = d.m_q; o.ms = static_cast<float*>(d.m_scale); o.mk = d.m_k;
+    o.vq = d.v_q; o.vs = static_cast<float*>(d.v_scale); o.vk = d.v_k; o.n = d.n; o.first_chunk = chunk; o.weight_decay = d.weight_decay;
     __builtin_memcpy(dd + t, &o, sizeof o);
     const uint64_t c = (d.n + kChunk - 1) / kChunk;
     for (uint64_t i = 0; i < c; ++i) map[chunk + i] = t;
@@ -1433,38 +1458,40 @@ int coat_shard_range(uint64_t n, int32_t G, uint32_t rank, uint32_t world, uint6
 }
 
 int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags, float k_min, float k_max,
-                     uint8_t* q, float* scale, float* k, void* hip_stream) {
+                     uint8_t* q, void* scale, float* k, void* hip_stream) {
   if (!group_ok(G)) return COAT_ERR_GROUP;
-  if (flags & ~(COAT_FLAG_EXPAND | COAT_FLAG_E5M2)) return COAT_ERR_HPARAM;
+  if (flags & ~(COAT_FLAG_EXPAND | COAT_FLAG_E5M2 | COAT_FLAG_BF16_SCALE)) return COAT_ERR_HPARAM;
   if (!resolve_k_bounds(k_min, k_max)) return COAT_ERR_HPARAM;
   if (n == 0) return COAT_OK;
   if (!x || !q || !scale || !k) return COAT_ERR_NULL;
   if (!aligned16(x) || !aligned16(q) || !aligned16(scale) || !aligned16(k)) return COAT_ERR_ALIGN;
   if (n > kMaxElements) return COAT_ERR_SIZE;
   QuantArgs a;
-  a.x = x; a.q = q; a.scale = scale; a.k = k;
+  a.x = x; a.q = q; a.scale = static_cast<float*>(scale); a.k = k;
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
   a.k_min = k_min; a.k_max = k_max;
   a.mode.ex = (flags & COAT_FLAG_EXPAND) != 0;
   a.mode.e5 = (flags & COAT_FLAG_E5M2) != 0;
+  a.mode.s16 = (flags & COAT_FLAG_BF16_SCALE) != 0;
   return dispatch_quant(a, G, static_cast<hipStream_t>(hip_stream));
 }
 
-int coat_dequant_group(const uint8_t* q, const float* scale, const float* k, uint64_t n, int32_t G,
+int coat_dequant_group(const uint8_t* q, const void* scale, const float* k, uint64_t n, int32_t G,
                        uint32_t flags, float* x, void* hip_stream) {
   if (!group_ok(G)) return COAT_ERR_GROUP;
-  if (flags & ~(COAT_FLAG_EXPAND | COAT_FLAG_E5M2)) return COAT_ERR_HPARAM;
+  if (flags & ~(COAT_FLAG_EXPAND | COAT_FLAG_E5M2 | COAT_FLAG_BF16_SCALE)) return COAT_ERR_HPARAM;
   if (n == 0) return COAT_OK;
   if (!x || !q || !scale || !k) return COAT_ERR_NULL;
   if (!aligned16(x) || !aligned16(q) || !aligned16(scale) || !aligned16(k)) return COAT_ERR_ALIGN;
   if (n > kMaxElements) return COAT_ERR_SIZE;
   DequantArgs a;
-  a.q = q; a.scale = scale; a.k = k; a.x = x;
+  a.q = q; a.scale = static_cast<const float*>(scale); a.k = k; a.x = x;
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
   a.mode.ex = true;
   a.mode.e5 = (flags & COAT_FLAG_E5M2) != 0;
+  a.mode.s16 = (flags & COAT_FLAG_BF16_SCALE) != 0;
   return dispatch_dequant(a, G, static_cast<hipStream_t>(hip_stream));
 }
 

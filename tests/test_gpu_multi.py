@@ -33,7 +33,7 @@ def make_tensors(G, seed, with_bf16=()):
     return out
 
 
-def to_device(host):
+def to_device(host, bf16_scale=False):
     dev = []
     for h in host:
         n = h["w"].size
@@ -41,6 +41,8 @@ def to_device(host):
                  weight_decay=h["wd"])
         for k, v in h["st"].items():
             d[k] = torch.from_numpy(v.copy()).cuda()
+            if bf16_scale and k.endswith("_scale"):
+                d[k] = d[k].to(torch.bfloat16)
         if h["bf16"]:
             d["w_bf16"] = torch.full((n,), 7.0, dtype=torch.bfloat16, device="cuda")
         dev.append(d)
@@ -73,10 +75,10 @@ def raw(t):
 
 
 @pytest.mark.parametrize("G,flags", [(128, {}), (32, {}), (512, {}), (64, dict(m_e5m2=True, v_plain=True)),
-                                     (128, dict(expand=False))])
+                                     (128, dict(expand=False)), (128, dict(bf16_scale=True))])
 def test_multi_equals_one_call_per_tensor(coat, G, flags):
     host = make_tensors(G, seed=11, with_bf16=(3, 7, 8))
-    a, b = to_device(host), to_device(host)
+    a, b = to_device(host, flags.get("bf16_scale", False)), to_device(host, flags.get("bf16_scale", False))
     plan = coat.MultiPlan(a, G)
     for t in range(1, 4):
         grads = [S.grads_normal(h["w"].size, 50 + i, t, G=G) if i % 2 else S.grads_lognormal(h["w"].size, 50 + i, t)

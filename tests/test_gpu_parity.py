@@ -38,9 +38,15 @@ def gpu_step(coat, w, g_bits, st, G, step, expand=True, **over):
     hp = coat.make_hparams(step=step, group_size=G, expand=expand, **kw)
     tw, tg = dev(w), dev_bf16(g_bits)
     ts = {k: dev(v) for k, v in st.items()}
+    if kw.get("bf16_scale"):
+        # the oracle keeps bf16 scales as floats whose values are bf16: the conversion is exact
+        for k in ("m_scale", "v_scale"):
+            assert np.all(st[k].view(np.uint32) & 0xFFFF == 0)
+            ts[k] = ts[k].to(torch.bfloat16)
     coat.coat_fp8_adamw_step(tw, tg, ts["m_q"], ts["m_scale"], ts["m_k"], ts["v_q"], ts["v_scale"], ts["v_k"], hp)
     torch.cuda.synchronize()
-    return tw.cpu().numpy(), {k: v.cpu().numpy() for k, v in ts.items()}, tg
+    return tw.cpu().numpy(), {k: v.float().cpu().numpy() if v.dtype == torch.bfloat16 else v.cpu().numpy()
+                              for k, v in ts.items()}, tg
 
 
 def ref_step(ref, w, g_bits, st, G, step, expand=True, **over):
@@ -84,15 +90,28 @@ def check_step(ref, tag, w_g, st_g, w_r, st_r, st_old, g_bits, G, expand=True, e
     k_max = over.get("k_max", 0.0) or 1024.0
     hp_only = {k: v for k, v in over.items() if k in HP}
     assert_w(w_g, w_r, tag + " w", extra_w_tol)
-    assert_scale(st_g["m_scale"], st_r["m_scale"], tag + " m scale")
-    assert_scale(st_g["v_scale"], st_r["v_scale"], tag + " v scale")
     m_t, dm, v_t, dv = new_moments(ref, st_old, g_bits, G, over)
     stats = {}
     for name, x, dx in (("m", m_t, dm), ("v", v_t, dv)):
         tol, cl = k_tolerance(st_r[name + "_k"], x, dx, G, k_min, k_max)
+        if over.get("bf16_scale"):
+            # The stored scale is a rounding DECISION (the bf16 ceiling of amax/fmax).  Where the two
+            # sides' amax (fp32 against fp64 arithmetic, within dx of each other) straddle a bf16
+            # boundary they may decide differently, by one bf16 step; such a group's codes are then
+            # all shifted and it is left to the irregular budget.  Everywhere else: EQUAL.
+            near, lo16, hi16 = bf16_scale_candidates(x, dx, G, 57344.0 if over.get(name + "_e5m2") else 448.0)
+            sg, sr = st_g[name + "_scale"], st_r[name + "_scale"]
+            assert np.all(sg.view(np.uint32) & 0xFFFF == 0), tag + ": a stored scale is not a bf16 value"
+            assert np.array_equal(sg[~near], sr[~near]), tag + " %s scale (bf16)" % name
+            assert np.all((sg[near] == lo16[near]) | (sg[near] == hi16[near])), tag + " %s scale near a bf16 boundary" % name
+            other_scale = near & (sg != sr)
+        else:
+            assert_scale(st_g[name + "_scale"], st_r[name + "_scale"], tag + " %s scale" % name)
+            other_scale = np.zeros(tol.shape, dtype=bool)
         if not expand or over.get(name + "_plain"):
             tol = np.full_like(tol, 1e-6)            # k is 1 on both sides
             assert np.all(st_g[name + "_k"] == 1.0)
+        tol = np.where(other_scale, np.inf, tol)
         in_bar = assert_k(st_g[name + "_k"], st_r[name + "_k"], tol, cl, tag + " %s k" % name)
         n_bad, bad_regular, n_irregular = assert_codes(
             ref, st_g[name + "_q"], st_r[name + "_q"], x, dx, st_r[name + "_scale"], st_r[name + "_k"], tol, G,
@@ -100,6 +119,25 @@ def check_step(ref, tag, w_g, st_g, w_r, st_r, st_old, g_bits, G, expand=True, e
         stats[name] = dict(bad=n_bad, bad_regular=bad_regular, irregular=n_irregular, k_in_bar=in_bar)
     assert np.all(st_g["v_q"] < 0x80), tag + ": a second-moment code carries a sign"
     return stats
+
+
+def bf16_ceil(s):
+    s = np.asarray(s, dtype=np.float32)
+    return ((s.view(np.uint32) + np.uint32(0xFFFF)) & np.uint32(0xFFFF0000)).view(np.float32)
+
+
+def bf16_scale_candidates(x, dx, G, fmax):
+    """Per group: the bf16 scales that amax - dx and amax + dx lead to, and whether they differ."""
+    ax = np.abs(np.asarray(x, dtype=np.float64))
+    n = ax.size
+    ng = (n + G - 1) // G
+    pad_lo, pad_hi = np.zeros(ng * G), np.zeros(ng * G)
+    pad_lo[:n] = np.maximum(ax - dx, 0.0)
+    pad_hi[:n] = ax + dx
+    lo = (pad_lo.reshape(ng, G).max(1) / fmax * (1 - 2.0 ** -22)).astype(np.float32)
+    hi = (pad_hi.reshape(ng, G).max(1) / fmax * (1 + 2.0 ** -22)).astype(np.float32)
+    lo16, hi16 = bf16_ceil(lo), bf16_ceil(hi)
+    return lo16 != hi16, lo16, hi16
 
 
 def lockstep(coat, ref, n, G, grads_fn, steps, seed, expand=True, state=None, **over):
@@ -278,6 +316,41 @@ def test_step_from_arbitrary_state(coat, ref, G):
     w_r, st_r = ref_step(ref, w, g, st, G, t)
     extra = update_error_model(ref, st, g, G, t)
     check_step(ref, "random state G=%d" % G, w_g, st_g, w_r, st_r, st, g, G, extra_w_tol=extra)
+
+
+@pytest.mark.parametrize("G", [32, 128, 512])
+def test_step_bf16_scale(coat, ref, G):
+    """Scales stored in BF16 (Sec. 3): lock-step against the oracle's same option."""
+    n = 200 * 1024 + 3 * G + 7
+    lockstep(coat, ref, n, G, lambda t: S.grads_normal(n, 21, t, G=G, outlier_frac=0.01), steps=4, seed=21, bf16_scale=True)
+    lockstep(coat, ref, n, G, lambda t: S.grads_lognormal(n, 22, t), steps=3, seed=22, bf16_scale=True)
+
+
+def test_step_bf16_scale_with_other_cells(coat, ref):
+    n = 64 * 1024 + 50
+    lockstep(coat, ref, n, 128, lambda t: S.grads_normal(n, 23, t), steps=3, seed=23, bf16_scale=True, expand=False)
+    lockstep(coat, ref, n, 128, lambda t: S.grads_normal(n, 24, t), steps=3, seed=24, bf16_scale=True,
+             m_e5m2=True, v_plain=True)
+
+
+@pytest.mark.parametrize("G", [32, 128, 512])
+@pytest.mark.parametrize("kind", ["normal", "square", "lognormal", "zeros_mixed"])
+def test_quant_bf16_scale(coat, ref, G, kind):
+    """Standalone quantizer with BF16 scales: identical inputs, so the stored scales must be EQUAL;
+    then dequantize through the GPU and compare with the oracle's dequantizer."""
+    n = 37 * 1024 + 2 * G + 17
+    x = quant_inputs(kind, n, seed=G + len(kind))
+    q, s, k = coat.coat_quant_group(dev(x), G, bf16_scale=True)
+    assert s.dtype == torch.bfloat16
+    q_g, s_g, k_g = q.cpu().numpy(), s.float().cpu().numpy(), k.cpu().numpy()
+    q_r, s_r, k_r = ref.quant_group(x, G, bf16_scale=True)
+    assert np.array_equal(s_g, s_r)
+    check_quant(ref, "quant bf16 scale %s G=%d" % (kind, G), x, G, (q_g, s_g, k_g), (q_r, s_r, k_r), True)
+    xh_g = coat.coat_dequant_group(q, s, k, G).cpu().numpy().astype(np.float64)
+    xh_r = ref.dequant_group(q_g, s_g, k_g, G, f64=True)
+    ok = np.isfinite(xh_r) & (xh_r != 0)
+    assert np.all(np.abs(xh_g[ok] / xh_r[ok] - 1.0) <= 8 * 2.0 ** -24)
+    assert np.all(xh_g[xh_r == 0] == 0)
 
 
 def test_step_expansion_off(coat, ref):
