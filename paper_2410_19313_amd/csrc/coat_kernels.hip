@@ -121,6 +121,17 @@ __device__ __forceinline__ float load_scale(const Mode& md, const float* p, uint
   if (md.scale16()) return as_f32(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(p)[i]) << 16);
   return p[i];
 }
+// The same for group gl of a FULL chunk whose first group is gb, without control flow: one dword
+// load serves both layouts (a branch here costs the kernel its overlap of loads: the compiler
+// drains the load counter where the two sides meet; measured 17.3 ms against 15.9).  A chunk holds
+// an even number of groups starting at an even index, so the dword is inside the chunk's scales.
+template <class Mode>
+__device__ __forceinline__ float load_scale_full_chunk(const Mode& md, const float* p, uint64_t gb, int gl) {
+  const bool s16 = md.scale16();
+  const uint32_t w = reinterpret_cast<const uint32_t*>(p)[s16 ? (gb + gl) >> 1 : gb + gl];
+  const uint32_t half = (gl & 1) ? (w & 0xffff0000u) : (w << 16);
+  return as_f32(s16 ? half : w);
+}
 template <class Mode>
 __device__ __forceinline__ void store_scale(const Mode& md, float* p, uint64_t i, float s) {
   if (md.scale16()) reinterpret_cast<uint16_t*>(p)[i] = static_cast<uint16_t>(as_u32(s) >> 16);
@@ -536,8 +547,8 @@ __device__ __forceinline__ void issue_loads(const StepArgs& a, const ModeM& mm, 
   for (int j = 0; j < 2; ++j) r.g[j] = ldg<4>(gq + 64 * j + lane);
   r.mc = ldg<1>(mq + lane);
   r.vc = ldg<1>(vq + lane);
-  r.meta.m_scale = load_scale(mm, a.ms, gb + gl);
-  r.meta.v_scale = load_scale(mv, a.vs, gb + gl);
+  r.meta.m_scale = load_scale_full_chunk(mm, a.ms, gb, gl);
+  r.meta.v_scale = load_scale_full_chunk(mv, a.vs, gb, gl);
   r.meta.m_k = a.mk[gb + gl];          // written as 1 (and ignored) by a moment stored without expansion
   r.meta.v_k = a.vk[gb + gl];
 }
@@ -752,7 +763,8 @@ __global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) 
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const StageTiles tiles = {tile_w + wv * kTileSlotsW, tile_g + wv * kTileSlotsG};
-  const uint64_t gc = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv;   // the host sizes the grid to cover every chunk
+  // the host sizes the grid to cover every chunk
+  const uint64_t gc = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv;
 
   StepArgs a = ma.base;
   uint64_t chunk = 0;
