@@ -170,7 +170,7 @@ def main():
     ap.add_argument("--grads", default="normal", choices=["normal", "lognormal"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27)
-    ap.add_argument("--cpu-steps", type=int, default=12)
+    ap.add_argument("--cpu-steps", type=int, default=24)
     ap.add_argument("--op", default="step",
                     choices=["step", "quant", "dequant", "act_group", "act_tensor", "act_tensor_pre"],
                     help="step: the fused optimizer step (the metric); quant / dequant: its two halves alone; "

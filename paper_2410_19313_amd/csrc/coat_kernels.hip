@@ -595,7 +595,8 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const ModeM& mm
 // wavefront reads, or one that hits in L2, gains nothing; the lighter kernels, whose wavefronts
 // live too briefly to wait, gain nothing either, except the quantizer).  The empty asm emits no
 // instruction: it makes the chunk index depend on the probed word so that the compiler keeps the
-// loads behind it.
+// loads behind it.  The probed value itself is never used, so it is harmless that the wavefront
+// owning that chunk may be rewriting the word at the same moment.
 #ifndef COAT_GATE_SHIFT
 #define COAT_GATE_SHIFT 5
 #endif
