@@ -1,12 +1,17 @@
 // coat_kernels.hip -- gfx950 kernels and C ABI of the FP8-state AdamW step of COAT
 // (arxiv 2410.19313: Sec. 3 quantizer and update rule, Sec. 4.2 dynamic range expansion,
-// Appendix A step order, Table 1 format grid).  Hand-written for CDNA4:
+// Appendix A step order, Table 1 format grid) and of the activation quantizers of Sec. 5.2.
+// Hand-written for CDNA4:
 //   * 64-wide wavefronts; every lane owns 16 consecutive elements, a quantization group of G
 //     elements is G/16 adjacent lanes and its max/min are DPP butterflies inside the wavefront;
 //   * every global load/store instruction of a wavefront covers one contiguous 1 KiB row and is
 //     issued as a streaming access; per-wavefront LDS tiles convert between those rows and the
 //     16-elements-per-lane layout the arithmetic wants;
+//   * one 1024-element chunk per wavefront, three resident workgroups per CU, and an admission
+//     gate that lines up the bulk loads of neighbouring wavefronts (gate_on_neighbourhood);
 //   * no atomics, no inter-wave communication: each group is owned by exactly one wavefront.
+// Sections: storage modes, helpers, LDS staging, (de)quantizer arithmetic, the fused step,
+// the multi-tensor step, standalone quantizer / dequantizer, activation quantizers, host side.
 //
 // Arithmetic (fp32 throughout; transcendentals are the hardware log2/exp2/rcp/sqrt), with fmax
 // the largest finite value of the moment's FP8 format (448 for E4M3, 57344 for E5M2):
