@@ -157,7 +157,7 @@ def lockstep(coat, ref, n, G, grads_fn, steps, seed, expand=True, state=None, **
     return total_bad
 
 
-def update_error_model(ref, st, g, G, t):
+def update_error_model(ref, st, g, G, t, m_e5m2=False, v_e5m2=False, **_):
     """Extra weight tolerance for states that come from no optimizer trajectory (random codes,
     scales and exponents): there |m| / sqrt(v) reaches 1e5, the update dwarfs the weight and the
     fp32 error of the update itself shows.  For u = (lr/bc1) m_t / (sqrt(v_t/bc2) + eps) the
@@ -166,12 +166,12 @@ def update_error_model(ref, st, g, G, t):
     from parity import EPS_DQ_M, eps_dq_v
     n = st["m_q"].size
     b1, b2, lr, eps = (float(np.float32(HP[k])) for k in ("beta1", "beta2", "lr", "eps"))
-    m_old = np.abs(ref.dequant_group(st["m_q"], st["m_scale"], st["m_k"], G, f64=True))
-    v_old = ref.dequant_group(st["v_q"], st["v_scale"], st["v_k"], G, f64=True)
+    m_old = np.abs(ref.dequant_group(st["m_q"], st["m_scale"], st["m_k"], G, f64=True, e5m2=m_e5m2))
+    v_old = ref.dequant_group(st["v_q"], st["v_scale"], st["v_k"], G, f64=True, e5m2=v_e5m2)
     gf = S.bf16_bits_to_f32(g).astype(np.float64)
     denom = np.sqrt((b2 * v_old + (1 - b2) * gf * gf) / (1 - b2 ** t)) + eps
     u_scale = lr / (1 - b1 ** t) * (b1 * m_old + (1 - b1) * np.abs(gf)) / denom
-    ev = np.repeat(eps_dq_v(st["v_k"].astype(np.float64)), G)[:n]
+    ev = np.repeat(eps_dq_v(st["v_k"].astype(np.float64), 31.81 if v_e5m2 else 17.81), G)[:n]
     return u_scale * (EPS_DQ_M + 0.5 * ev + 6 * 2.0 ** -24)
 
 
