@@ -1,0 +1,457 @@
+// coat_device.hpp -- types, storage modes, cross-lane and memory helpers, LDS staging and the (de)quantizer arithmetic shared by every kernel
+// Part of the one translation unit coat_kernels.hip (included from there, in this order).
+#pragma once
+
+namespace {
+
+constexpr int kWave = 64;                 // lanes per wavefront
+constexpr int kEPL = 16;                  // consecutive elements owned by one lane
+#ifndef COAT_WPB
+#define COAT_WPB 4
+#endif
+constexpr int kWavesPerBlock = COAT_WPB;
+constexpr int kBlock = kWave * kWavesPerBlock;
+constexpr int kChunk = kWave * kEPL;      // elements one wavefront handles per iteration
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+#include "coat_tables.inc"
+
+// ---------------------------------------------------------------------------------------
+// Storage mode of one moment: FP8 format and whether the dynamic range expansion is applied
+// (the rows / columns of Table 1).  StaticMode folds at compile time (the default E4M3 + expansion
+// fast path); RuntimeMode carries the two switches as wavefront-uniform values, so one kernel per
+// group size serves the other fifteen combinations.
+// ---------------------------------------------------------------------------------------
+template <bool E5M2, bool EXPAND>
+struct StaticMode {
+  __device__ __forceinline__ bool e5m2() const { return E5M2; }
+  __device__ __forceinline__ bool expand() const { return EXPAND; }
+  __device__ __forceinline__ bool scale16() const { return false; }
+};
+struct RuntimeMode {
+  bool e5, ex;
+  bool s16;   // the per-group scales are stored as bf16 (Sec. 3) instead of fp32
+  __device__ __forceinline__ bool e5m2() const { return e5; }
+  __device__ __forceinline__ bool expand() const { return ex; }
+  __device__ __forceinline__ bool scale16() const { return s16; }
+};
+typedef StaticMode<false, true> DefaultMode;
+
+template <class Mode> __device__ __forceinline__ float fmt_max(const Mode& md) { return md.e5m2() ? 57344.0f : 448.0f; }
+template <class Mode> __device__ __forceinline__ float fmt_inv_max(const Mode& md) {
+  return md.e5m2() ? 1.0f / 57344.0f : 1.0f / 448.0f;
+}
+// log2(fmax) and log2(fmax / smallest subnormal): 448 * 2^9 (Sec. 4.1) and 57344 * 2^16
+template <class Mode> __device__ __forceinline__ float fmt_log2_max(const Mode& md) {
+  return md.e5m2() ? 15.807354922057604f : 8.807354922057604f;
+}
+template <class Mode> __device__ __forceinline__ float fmt_log2_range(const Mode& md) {
+  return md.e5m2() ? 31.807354922057604f : 17.807354922057606f;
+}
+
+struct StepArgs {
+  float* w;
+  uint16_t* wb;          // optional bf16 copy of the new weights (nullptr: none)
+  const uint16_t* g;
+  uint8_t* mq; float* ms; float* mk;
+  uint8_t* vq; float* vs; float* vk;
+  uint64_t n;            // elements
+  uint64_t n_full;       // number of full kChunk-sized chunks
+  uint64_t n_groups;     // ceil(n / G)
+  // The kernel carries the new moments divided by (1 - beta): m' = m_t / (1 - beta1) =
+  // (beta1/(1-beta1)) m + g is ONE fma (rounded once, which matters where the two terms cancel),
+  // v' = v_t / (1 - beta2) = (beta2/(1-beta2)) v + g*g one mul and one fma.  The factors are
+  // folded into the constants below and into the per-group scale.
+  float beta1_ratio, beta2_ratio;        // beta / (1 - beta)
+  float one_minus_beta1, one_minus_beta2;
+  float neg_lr_m;        // -lr * (1 - beta1) / (1 - beta1^t)
+  float neg_lr_wd;       // -lr * weight_decay
+  float denom_scale;     // sqrt((1 - beta2) / (1 - beta2^t))
+  float eps;
+  float k_min, k_max;
+  RuntimeMode mode_m, mode_v;
+};
+
+struct QuantArgs {
+  const float* x; uint8_t* q; float* scale; float* k;
+  uint64_t n, n_full, n_groups;
+  float k_min, k_max;
+  RuntimeMode mode;
+};
+
+struct DequantArgs {
+  const uint8_t* q; const float* scale; const float* k; float* x;
+  uint64_t n, n_full, n_groups;
+  RuntimeMode mode;
+};
+
+// ---------------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------------
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// Per-group scale i of an array that holds fp32 or, with scale16, bf16 values (the pointer is typed
+// float* either way).  A stored bf16 scale is exact: the quantizer rounded it before using it.
+template <class Mode>
+__device__ __forceinline__ float load_scale(const Mode& md, const float* p, uint64_t i) {
+  if (md.scale16()) return as_f32(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(p)[i]) << 16);
+  return p[i];
+}
+// The same for group gl of a FULL chunk whose first group is gb, without control flow: one dword
+// load serves both layouts (a branch here costs the kernel its overlap of loads: the compiler
+// drains the load counter where the two sides meet; measured 17.3 ms against 15.9).  A chunk holds
+// an even number of groups starting at an even index, so the dword is inside the chunk's scales.
+template <class Mode>
+__device__ __forceinline__ float load_scale_full_chunk(const Mode& md, const float* p, uint64_t gb, int gl) {
+  const bool s16 = md.scale16();
+  const uint32_t w = reinterpret_cast<const uint32_t*>(p)[s16 ? (gb + gl) >> 1 : gb + gl];
+  const uint32_t half = (gl & 1) ? (w & 0xffff0000u) : (w << 16);
+  return as_f32(s16 ? half : w);
+}
+template <class Mode>
+__device__ __forceinline__ void store_scale(const Mode& md, float* p, uint64_t i, float s) {
+  if (md.scale16()) reinterpret_cast<uint16_t*>(p)[i] = static_cast<uint16_t>(as_u32(s) >> 16);
+  else p[i] = s;
+}
+
+__device__ __forceinline__ float hw_log2(float x) { return __builtin_amdgcn_logf(x); }
+__device__ __forceinline__ float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float hw_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float hw_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+
+// Butterfly all-reduce over LPG adjacent lanes (LPG = lanes per group, a power of two <= 32).
+//   xor 1 / xor 2 : quad_perm, lanes 4..7 / 8..15 : row_half_mirror / row_mirror (after the
+//   previous steps every lane of the smaller block already holds that block's result),
+//   xor 16 : ds_swizzle inside 32 lanes.
+template <int LPG, bool IS_MAX>
+__device__ __forceinline__ float group_allreduce(float x) {
+  auto op = [](float a, float b) { return IS_MAX ? __builtin_fmaxf(a, b) : __builtin_fminf(a, b); };
+  if constexpr (LPG >= 2) x = op(x, dpp_mov<0xB1>(x));    // quad_perm:[1,0,3,2]
+  if constexpr (LPG >= 4) x = op(x, dpp_mov<0x4E>(x));    // quad_perm:[2,3,0,1]
+  if constexpr (LPG >= 8) x = op(x, dpp_mov<0x141>(x));   // row_half_mirror
+  if constexpr (LPG >= 16) x = op(x, dpp_mov<0x140>(x));  // row_mirror
+  if constexpr (LPG >= 32)
+    x = op(x, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, x), 0x401F)));
+  return x;
+}
+
+// Compile-time streaming hints (bit mask): 1 load codes, 2 store codes, 4 load gradients,
+// 8 load fp32, 16 store fp32.  A set bit issues the access as non-temporal.
+#ifndef COAT_NT
+#define COAT_NT 31
+#endif
+template <int BIT, typename T>
+__device__ __forceinline__ T ldg(const T* p) {
+  if constexpr ((COAT_NT & BIT) != 0) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <int BIT, typename T>
+__device__ __forceinline__ void stg(T* p, T v) {
+  if constexpr ((COAT_NT & BIT) != 0) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+// Element-wise guarded accesses straight into the lane layout: only the ragged last chunk
+// (n mod 1024 elements, one wavefront) uses them.
+__device__ __forceinline__ void load_f32x16_guarded(const float* p, uint64_t base, uint64_t n, float (&x)[kEPL]) {
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) x[e] = (base + e < n) ? p[base + e] : 0.0f;
+}
+__device__ __forceinline__ void store_f32x16_guarded(float* p, uint64_t base, uint64_t n, const float (&x)[kEPL]) {
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e)
+    if (base + e < n) p[base + e] = x[e];
+}
+// a bf16 is the upper half of an fp32
+__device__ __forceinline__ void load_bf16x16_guarded(const uint16_t* p, uint64_t base, uint64_t n, float (&x)[kEPL]) {
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e)
+    x[e] = (base + e < n) ? as_f32(static_cast<uint32_t>(p[base + e]) << 16) : 0.0f;
+}
+// 16 code bytes as four dwords, element e in byte (e & 3) of dword (e >> 2)
+__device__ __forceinline__ void load_codes16_guarded(const uint8_t* p, uint64_t base, uint64_t n, uint32_t (&c)[4]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    uint32_t v = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+      if (base + 4 * d + b < n) v |= static_cast<uint32_t>(p[base + 4 * d + b]) << (8 * b);
+    c[d] = v;
+  }
+}
+__device__ __forceinline__ void store_codes16_guarded(uint8_t* p, uint64_t base, uint64_t n, const uint32_t (&c)[4]) {
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e)
+    if (base + e < n) p[base + e] = static_cast<uint8_t>(c[e >> 2] >> (8 * (e & 3)));
+}
+
+// ---------------------------------------------------------------------------------------
+// LDS staging: HBM likes every load/store instruction of a wavefront to cover one contiguous
+// span (and to be issued as a streaming access), the arithmetic wants every lane to own 16
+// consecutive elements.  A per-wavefront LDS tile converts between the two: rows of 64 x 16 B on
+// the memory side, 64 B (fp32) or 32 B (bf16) per lane on the register side.
+// 16-byte slot s lives at s + (s >> 3) (one pad slot after every eight), which makes both access
+// patterns conflict free and keeps every address of a lane a constant offset from one of two
+// per-lane bases: row side 72 j + lane + (lane >> 3), lane side 4 lane + (lane >> 1) + i (fp32)
+// or 2 lane + (lane >> 2) + j (bf16).  A wavefront only ever touches its own tile and LDS
+// executes one wavefront's accesses in order, so no barrier is needed.
+// ---------------------------------------------------------------------------------------
+constexpr int kTileSlotsW = 256 + 32;   // fp32 tile: 1024 elements + padding, in 16-byte slots
+constexpr int kTileSlotsG = 128 + 16;   // bf16 tile
+
+struct StageTiles { f32x4* w; u32x4* g; };
+
+// rows (memory side) -> 16 consecutive fp32 per lane, through the wavefront's fp32 tile
+__device__ __forceinline__ void tile_rows_to_lanes(f32x4* tile, int lane, const f32x4 (&rows)[4], float (&x)[kEPL]) {
+  f32x4* const row = tile + lane + (lane >> 3);            // + 72 j
+  const f32x4* const own = tile + 4 * lane + (lane >> 1);  // + i
+#pragma unroll
+  for (int j = 0; j < 4; ++j) row[72 * j] = rows[j];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f32x4 t = own[i];
+    x[4 * i + 0] = t.x; x[4 * i + 1] = t.y; x[4 * i + 2] = t.z; x[4 * i + 3] = t.w;
+  }
+}
+
+// 16 consecutive fp32 per lane -> rows, written straight to memory (p: start of the chunk)
+__device__ __forceinline__ void tile_lanes_to_rows_store(f32x4* tile, int lane, const float (&x)[kEPL], float* p) {
+  const f32x4* const row = tile + lane + (lane >> 3);
+  f32x4* const own = tile + 4 * lane + (lane >> 1);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f32x4 t = {x[4 * i + 0], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]};
+    own[i] = t;
+  }
+  f32x4* q = reinterpret_cast<f32x4*>(p);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) stg<16>(q + 64 * j + lane, row[72 * j]);
+}
+
+// rows of bf16 -> 16 consecutive gradients per lane as fp32
+__device__ __forceinline__ void tile_rows_to_lanes_bf16(u32x4* tile, int lane, const u32x4 (&rows)[2], float (&g)[kEPL]) {
+  u32x4* const row = tile + lane + (lane >> 3);            // + 72 j
+  const u32x4* const own = tile + 2 * lane + (lane >> 2);  // + j
+#pragma unroll
+  for (int j = 0; j < 2; ++j) row[72 * j] = rows[j];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const u32x4 t = own[j];
+    g[8 * j + 0] = as_f32(t.x << 16); g[8 * j + 1] = as_f32(t.x & 0xffff0000u);
+    g[8 * j + 2] = as_f32(t.y << 16); g[8 * j + 3] = as_f32(t.y & 0xffff0000u);
+    g[8 * j + 4] = as_f32(t.z << 16); g[8 * j + 5] = as_f32(t.z & 0xffff0000u);
+    g[8 * j + 6] = as_f32(t.w << 16); g[8 * j + 7] = as_f32(t.w & 0xffff0000u);
+  }
+}
+
+// two fp32 -> packed bf16 pair (round to nearest even: the native pack convert)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// 16 consecutive fp32 per lane -> bf16 rows written straight to memory (p: start of the chunk)
+__device__ __forceinline__ void tile_lanes_to_rows_store_bf16(u32x4* tile, int lane, const float (&x)[kEPL],
+                                                              uint16_t* p) {
+  const u32x4* const row = tile + lane + (lane >> 3);
+  u32x4* const own = tile + 2 * lane + (lane >> 2);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const u32x4 t = {pack_bf16(x[8 * j + 0], x[8 * j + 1]), pack_bf16(x[8 * j + 2], x[8 * j + 3]),
+                     pack_bf16(x[8 * j + 4], x[8 * j + 5]), pack_bf16(x[8 * j + 6], x[8 * j + 7])};
+    own[j] = t;
+  }
+  u32x4* q = reinterpret_cast<u32x4*>(p);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) stg<16>(q + 64 * j + lane, row[72 * j]);
+}
+
+// The lookup table in LDS: per format 256 entries so that the whole code byte indexes it (the sign
+// bit is ignored).  TABLES = 1 loads E4M3 only, 2 loads E4M3 then E5M2.
+template <int TABLES>
+__device__ __forceinline__ void fill_lut(Log2Entry* lut) {
+  for (int i = threadIdx.x; i < 256 * TABLES; i += blockDim.x) lut[i] = kLog2Code[i >> 8][i & 127];
+  __syncthreads();
+}
+
+constexpr float kLn2 = 0.6931471805599453f;
+
+// |c/fmax|^(1/k) for 16 codes.
+//   ACCURATE = false: exp2(L * (1/k)), good to about |L/k| * 2^-22 relative;
+//   ACCURATE = true : the rounding of the product and of 1/k is recovered with one fma
+//     (r = L - t*k is the exact residual of t = fl(L * fl(1/k)) against L/k, times k), the
+//     table's own rounding is added from its low word, and exp2(t + d) = exp2(t) * (1 + d ln2).
+//     Used for the first moment, whose update beta1*m + (1-beta1)*g cancels and so amplifies
+//     the error of m into the group minimum that fixes the next exponent k.
+//   SIGNED: carry the code's sign bit into the result.
+template <bool SIGNED, bool ACCURATE>
+__device__ __forceinline__ void inverse_expand16(const Log2Entry* lut, const uint32_t (&c)[4], float k,
+                                                 float inv_k, float (&y)[kEPL]) {
+  const float inv_k_ln2 = inv_k * kLn2;
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) {
+    const uint32_t d = c[e >> 2];
+    const int sh = 8 * (e & 3);
+    const uint32_t code = (d >> sh) & 0xffu;
+    float v;
+    if constexpr (ACCURATE) {
+      const Log2Entry l = lut[code];
+      const float t = l.hi * inv_k;
+      const float r = __builtin_fmaf(-t, k, l.hi) + l.lo;
+      const float p = hw_exp2(t);
+      v = __builtin_fmaf(p, r * inv_k_ln2, p);
+    } else {
+      v = hw_exp2(lut[code].hi * inv_k);
+    }
+    if constexpr (SIGNED) v = as_f32(as_u32(v) | ((d << (24 - sh)) & 0x80000000u));
+    y[e] = v;
+  }
+}
+
+// plain dequantizer without expansion: the decoded code itself (to be multiplied by the scale)
+template <bool E5M2>
+__device__ __forceinline__ void decode16(const uint32_t (&c)[4], float (&y)[kEPL]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    if constexpr (E5M2) {
+      y[4 * d + 0] = __builtin_amdgcn_cvt_f32_bf8(c[d], 0);
+      y[4 * d + 1] = __builtin_amdgcn_cvt_f32_bf8(c[d], 1);
+      y[4 * d + 2] = __builtin_amdgcn_cvt_f32_bf8(c[d], 2);
+      y[4 * d + 3] = __builtin_amdgcn_cvt_f32_bf8(c[d], 3);
+    } else {
+      y[4 * d + 0] = __builtin_amdgcn_cvt_f32_fp8(c[d], 0);
+      y[4 * d + 1] = __builtin_amdgcn_cvt_f32_fp8(c[d], 1);
+      y[4 * d + 2] = __builtin_amdgcn_cvt_f32_fp8(c[d], 2);
+      y[4 * d + 3] = __builtin_amdgcn_cvt_f32_fp8(c[d], 3);
+    }
+  }
+}
+
+// Dequantize 16 codes of one moment up to a per-group factor: the stored value is y * factor with
+//   expansion on : y = +-|c/fmax|^(1/k), factor = fmax * scale      (Sec. 4.2, after the DQ of Sec. 3)
+//   expansion off: y = c,               factor = scale              (k is 1 in this mode, not read)
+template <bool SIGNED, bool ACCURATE, class Mode>
+__device__ __forceinline__ float dequant16(const Mode& md, const Log2Entry* lut, const uint32_t (&c)[4],
+                                           float scale, float k, float (&y)[kEPL]) {
+  if (md.expand()) {
+    inverse_expand16<SIGNED, ACCURATE>(lut + (md.e5m2() ? 256 : 0), c, k, hw_rcp(k), y);
+    return fmt_max(md) * scale;
+  }
+  if (md.e5m2()) decode16<true>(c, y);
+  else decode16<false>(c, y);
+  return scale;
+}
+
+struct GroupQuant { float scale, k, inv_a; };
+
+// Per-group scale and exponent from the group's extreme magnitudes (Definition 1, Sec. 4.2).
+// amin is the minimum over NON-ZERO magnitudes (+inf when there is none).  The values reduced
+// over are x / unit (unit = 1 - beta inside the step, 1 otherwise): the stored scale refers to x.
+//   expansion on : inv_a = unit / (fmax * scale), so that (held value) * inv_a = |x| / (fmax*scale)
+//   expansion off: k = 1; inv_a only flags an empty group (the quotient is formed exactly)
+template <class Mode>
+__device__ __forceinline__ GroupQuant group_quant_params(const Mode& md, float amax, float amin, float k_min,
+                                                         float k_max, float unit) {
+  GroupQuant r;
+  // amax / fmax, correctly rounded: multiply by the rounded reciprocal, then one residual step
+  const float inv_fmax = fmt_inv_max(md), fmax = fmt_max(md);
+  const float ax = amax * unit;
+  float s = ax * inv_fmax;
+  s = __builtin_fmaf(__builtin_fmaf(-fmax, s, ax), inv_fmax, s);
+  float top = amax;                                  // what the group is normalized by, in held units
+  if (md.scale16()) {
+    // BF16 scale: round UP to a bf16 value (every |x| / (fmax*scale) stays <= 1, nothing saturates)
+    // and take the range that has to fit the format against fmax*scale rather than amax
+    s = as_f32((as_u32(s) + 0xFFFFu) & 0xFFFF0000u);
+    top = (fmax * s) / unit;
+  }
+  float k = 1.0f;
+  if (md.expand()) {
+    // two hardware reciprocals (1 ulp each) are enough here: k moves by ~2 ulp
+    // (the max keeps a ratio that rounds below 1 from turning the huge k negative)
+    const float ratio = __builtin_fmaxf(top * hw_rcp(amin), 1.0f);    // R_X
+    float kk = fmt_log2_range(md) * hw_rcp(hw_log2(ratio));
+    kk = __builtin_amdgcn_fmed3f(kk, k_min, k_max);
+    k = (amax != amin) ? kk : 1.0f;
+  }
+  const float inv_a = unit * hw_rcp(md.expand() ? fmax * s : s);
+  const bool empty = !(amax > 0.0f);                 // all zero: scale 0, k 1, every code 0
+  r.scale = empty ? 0.0f : s;
+  r.k = empty ? 1.0f : k;
+  r.inv_a = empty ? 0.0f : inv_a;
+  return r;
+}
+
+// max |x| and min non-zero |x| over the lane's 16 values
+__device__ __forceinline__ void lane_extremes(const float (&x)[kEPL], float& amax, float& amin) {
+  float hi = 0.0f, lo = __builtin_huge_valf();
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) {
+    hi = __builtin_fmaxf(hi, __builtin_fabsf(x[e]));
+    lo = __builtin_fminf(lo, __builtin_fabsf(x[e]));
+  }
+  if (__builtin_expect(lo == 0.0f, 0)) {             // rare: some element is exactly zero
+    lo = __builtin_huge_valf();
+#pragma unroll
+    for (int e = 0; e < kEPL; ++e) {
+      const float ax = __builtin_fabsf(x[e]);
+      lo = __builtin_fminf(lo, ax > 0.0f ? ax : __builtin_huge_valf());
+    }
+  }
+  amax = hi; amin = lo;
+}
+
+template <bool E5M2>
+__device__ __forceinline__ uint32_t pack4(const float (&q)[4]) {
+  if constexpr (E5M2) {
+    const uint32_t p = __builtin_amdgcn_cvt_pk_bf8_f32(q[0], q[1], 0u, false);
+    return __builtin_amdgcn_cvt_pk_bf8_f32(q[2], q[3], p, true);
+  } else {
+    const uint32_t p = __builtin_amdgcn_cvt_pk_fp8_f32(q[0], q[1], 0u, false);
+    return __builtin_amdgcn_cvt_pk_fp8_f32(q[2], q[3], p, true);
+  }
+}
+
+// Quantize 16 held values (x / unit) to FP8 codes.  The native converts round to nearest even and
+// round magnitudes up to fmax * (1 + 2^-5) (E4M3: 464) back to fmax; the value converted never
+// exceeds fmax * (1 + 2^-22)^k_max, so no clamp is needed.
+//   expansion on : code = FP8( sign(x) * fmax * (|x| / (fmax*scale))^k ) as one fma in the exponent:
+//                  exp2(k log2 r + log2 fmax), rounded once at magnitude <= log2(range)/2
+//                  (log2 0 = -inf, so a zero stays zero)
+//   expansion off: code = FP8( x / scale ) with the correctly rounded fp32 quotient (the plain
+//                  quantizer of Sec. 3, kept as a baseline; it is not tuned)
+// SIGNED = false (second moment, never negative) skips the sign transfer.
+template <bool SIGNED, class Mode>
+__device__ __forceinline__ void quantize16(const Mode& md, const float (&x)[kEPL], const GroupQuant& gq,
+                                           uint32_t (&c)[4], float unit) {
+  const float log2_fmax = fmt_log2_max(md);
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    float q[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const float xv = x[4 * d + b];
+      if (md.expand()) {
+        const float m = hw_exp2(__builtin_fmaf(hw_log2(__builtin_fabsf(xv) * gq.inv_a), gq.k, log2_fmax));
+        q[b] = SIGNED ? as_f32(as_u32(m) | (as_u32(xv) & 0x80000000u)) : m;
+      } else {
+        q[b] = gq.inv_a != 0.0f ? (xv * unit) / gq.scale : 0.0f;   // IEEE division: correctly rounded
+      }
+    }
+    c[d] = md.e5m2() ? pack4<true>(q) : pack4<false>(q);
+  }
+}
+
+}  // namespace
