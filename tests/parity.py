@@ -26,7 +26,9 @@ groups they reduce to the stated bar.
               1e-4 * max(1, G/128), because boundary crossings are proportional to the deviation
               of k, that to 1/amin, and the minimum of G samples shrinks like 1/G (measured:
               ~4e-5 at G = 128, ~1.2e-4 at G = 512, both for an inverse expansion already within
-              ~1 ulp of fp64);
+              ~1 ulp of fp64).  A test sees a finite sample: the count may exceed rate * n by three
+              Poisson standard deviations (3 * sqrt(rate * n)) + 1; the lock-step drivers also
+              hold the plain rate over all their steps together;
           (b) EVERY mismatch, anywhere, must lie inside the band of codes that x_ref +- dx, the
               k bound and the forward error (log2/exp2 of the hardware, a few ulp) allow.  For a
               well conditioned element that band is the neighbouring code: "at most one step".
@@ -159,7 +161,10 @@ def assert_codes(ref_mod, gpu, ref, x_ref, dx, scale_ref, k_ref, tol_k, G, what=
     n_regular = int(sizes[regular].sum())
     bad_regular = int(regular[grp].sum())
     allowed_rate = CODE_MISMATCH_MAX * max(1.0, G / 128.0)
-    assert bad_regular <= max(1, int(allowed_rate * n_regular)), \
+    # the bar is a RATE; on a finite sample the count of rate * n expected mismatches fluctuates like a
+    # Poisson variable, so the sample is allowed three standard deviations above the expectation
+    expected = allowed_rate * n_regular
+    assert bad_regular <= int(np.ceil(expected + 3.0 * np.sqrt(expected) + 1.0)), \
         "%s: %d of %d codes differ (%.3g %%)" % (what, bad_regular, n_regular, 100.0 * bad_regular / max(1, n_regular))
 
     # (b) every mismatch inside its band

@@ -606,3 +606,35 @@ def test_table1_structure_on_the_gpu_path(coat, ref):
         assert np.all(r[e, :] < r[p, :]) and np.all(r[:, e] < r[:, p])
     assert min(r[1, 1], r[1, 3]) == r.min() and r[1, 1] <= 1.1 * r.min()
     assert r[0, 0] > 1.3 * r[1, 1]                        # the direction of the paper's 1.63x
+
+
+# --- seeded sweep over sizes, group sizes and storage modes ------------------------------------
+
+def test_step_seeded_sweep_of_configurations(coat, ref):
+    """Forty seeded combinations of size (around chunk and group boundaries), group size, storage
+    mode of each moment, BF16 scales and hyper-parameters, two lock-step steps each."""
+    rng = np.random.default_rng(2024)
+    edges = [1, 2, 15, 16, 17, 31, 33, 127, 128, 129, 511, 513, 1023, 1024, 1025, 2047, 2049, 3 * 1024 + 1]
+    for case in range(40):
+        G = int(rng.choice(GROUPS))
+        n = int(rng.choice(edges)) if case % 2 else int(rng.integers(1, 40 * 1024))
+        over = dict(m_e5m2=bool(rng.integers(2)), v_e5m2=bool(rng.integers(2)), m_plain=bool(rng.integers(2)),
+                    v_plain=bool(rng.integers(2)), bf16_scale=bool(rng.integers(2)))
+        if case % 5 == 0:
+            over = {}                                                   # the default kernel gets its share
+        if case % 7 == 0:
+            over.update(lr=1e-3, beta1=0.8, beta2=0.99, weight_decay=0.0)
+        kind = case % 3
+        seed = 1000 + case
+
+        def grads(t, n=n, G=G, kind=kind, seed=seed):
+            if kind == 0:
+                return S.grads_normal(n, seed, t, G=G, outlier_frac=0.05)
+            if kind == 1:
+                return S.grads_lognormal(n, seed, t)
+            return S.grads_normal(n, seed, t, sigma=3e-5)
+
+        try:
+            lockstep(coat, ref, n, G, grads, steps=2, seed=seed, **over)
+        except AssertionError as e:
+            raise AssertionError("case %d: n=%d G=%d %r: %s" % (case, n, G, over, e))
