@@ -124,15 +124,16 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
  * groups); hp->weight_decay is ignored by the multi-tensor step.  n == 0 entries are skipped.
  *
  * Usage: 1. size a HOST buffer with coat_multi_plan_bytes and fill it with coat_multi_plan_build
- * (pure host code: pointers are validated, never dereferenced; the blob holds the descriptors
- * and, per 1024-element chunk, the index of its tensor: 96 bytes per tensor + 4 bytes per chunk);
- * 2. copy the blob to 16-byte-aligned device memory; 3. call coat_fp8_adamw_step_multi every step
- * with both copies (the host copy's 64-byte header gives the launch size, the kernels read the
- * device copy).  The plan stays valid while the tensors' addresses and sizes do; it does not
- * depend on the hyper-parameters or on G.  To step only a shard of a tensor, describe the shard
- * (see coat_shard_range).
+ * (pure host code: pointers are validated, never dereferenced).  The blob is a 128-byte header
+ * followed by one 128-byte record per span of 32 chunks (32768 elements) of every tensor, each
+ * tensor starting a new span: 4 bytes of plan per 1024 elements, plus up to one span of padding
+ * per tensor;  2. copy the blob to device memory (16-byte aligned; 128 keeps every record in one
+ * cache line);  3. call coat_fp8_adamw_step_multi every step with both copies (the host copy's
+ * header gives the launch size, the kernels read the device copy).  The plan stays valid while
+ * the tensors' addresses and sizes do; it does not depend on the hyper-parameters or on G.  To
+ * step only a shard of a tensor, describe the shard (see coat_shard_range).
  * coat_multi_plan_bytes returns 0 on an invalid argument (NULL with count > 0, an n above 2^46, or
- * more than 2^32 chunks in total).
+ * more than 2^27 spans in total).
  */
 typedef struct {
   float*          w;

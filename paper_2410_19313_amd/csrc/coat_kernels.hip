@@ -221,8 +221,8 @@ int act_quant_tensor_impl(const uint16_t* x, uint64_t n, int32_t G, float* group
 }
 
 template <int G, bool GENERIC>
-int launch_step_multi(const MultiArgs& ma, hipStream_t s) {
-  const uint64_t blocks = (ma.total_chunks + kWavesPerBlock - 1) / kWavesPerBlock;
+int launch_step_multi(const MultiArgs& ma, uint64_t total_records, hipStream_t s) {
+  const uint64_t blocks = total_records * (kPlanSpan / kWavesPerBlock);
   size_t lds = kMultiLdsPad;
 #ifdef COAT_TUNING
   if (g_tune_lds_pad >= 0) lds = static_cast<size_t>(g_tune_lds_pad);
@@ -231,18 +231,20 @@ int launch_step_multi(const MultiArgs& ma, hipStream_t s) {
   return launch_status();
 }
 
-int dispatch_step_multi(const MultiArgs& ma, int32_t G, bool generic, hipStream_t s) {
-  if (!generic) { COAT_DISPATCH_G(G, (launch_step_multi<kG, false>(ma, s))); }
-  COAT_DISPATCH_G(G, (launch_step_multi<kG, true>(ma, s)));
+int dispatch_step_multi(const MultiArgs& ma, uint64_t total_records, int32_t G, bool generic, hipStream_t s) {
+  if (!generic) { COAT_DISPATCH_G(G, (launch_step_multi<kG, false>(ma, total_records, s))); }
+  COAT_DISPATCH_G(G, (launch_step_multi<kG, true>(ma, total_records, s)));
 }
 
 constexpr uint32_t kStepFlags = COAT_FLAG_EXPAND | COAT_FLAG_M_E5M2 | COAT_FLAG_V_E5M2 | COAT_FLAG_M_PLAIN |
                                 COAT_FLAG_V_PLAIN | COAT_FLAG_BF16_SCALE;
 
-constexpr uint64_t kMaxPlanChunks = 1ull << 32;     // one launch covers them all (4 per workgroup)
+constexpr uint64_t kPlanRecordOffset = 128;          // records start one cache line into the blob
+constexpr uint64_t kMaxPlanRecords = 1ull << 27;    // one launch covers them all (8 workgroups per record)
 
-size_t plan_map_offset(uint32_t count) {
-  return sizeof(PlanHeader) + ((static_cast<size_t>(count) * sizeof(TensorDesc) + 63) / 64) * 64;
+uint64_t plan_records_of(uint64_t n) {               // spans of 32 chunks a tensor of n elements occupies
+  const uint64_t chunks = (n + kChunk - 1) / kChunk;
+  return (chunks + kPlanSpan - 1) / kPlanSpan;
 }
 
 // Validates the hyper-parameters and fills every field of StepArgs that does not depend on the
@@ -324,13 +326,13 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
 
 size_t coat_multi_plan_bytes(const coat_tensor_desc* descs, uint32_t count) {
   if (count && !descs) return 0;
-  uint64_t chunks = 0;
+  uint64_t records = 0;
   for (uint32_t t = 0; t < count; ++t) {
     if (descs[t].n > kMaxElements) return 0;
-    chunks += (descs[t].n + kChunk - 1) / kChunk;
+    records += plan_records_of(descs[t].n);
   }
-  if (chunks > kMaxPlanChunks) return 0;
-  return plan_map_offset(count) + static_cast<size_t>(chunks) * sizeof(uint32_t);
+  if (records > kMaxPlanRecords) return 0;
+  return kPlanRecordOffset + static_cast<size_t>(records) * sizeof(PlanRecord);
 }
 
 int coat_multi_plan_build(const coat_tensor_desc* descs, uint32_t count, void* plan_host, size_t plan_bytes) {
@@ -348,22 +350,21 @@ int coat_multi_plan_build(const coat_tensor_desc* descs, uint32_t count, void* p
   }
   unsigned char* blob = static_cast<unsigned char*>(plan_host);
   PlanHeader h = {};
-  h.magic = kPlanMagic; h.version = 1; h.count = count;
-  h.desc_offset = sizeof(PlanHeader); h.map_offset = plan_map_offset(count); h.bytes = need;
-  TensorDesc* dd = reinterpret_cast<TensorDesc*>(blob + h.desc_offset);
-  uint32_t* map = reinterpret_cast<uint32_t*>(blob + h.map_offset);
-  uint64_t chunk = 0;
+  h.magic = kPlanMagic; h.version = 2; h.count = count;
+  h.record_offset = kPlanRecordOffset; h.bytes = need;
+  uint64_t rec = 0;
   for (uint32_t t = 0; t < count; ++t) {
     const coat_tensor_desc& d = descs[t];
-    TensorDesc o = {};
-    o.w = d.w; o.wb = d.w_bf16; o.g = d.grad_bf16; o.mq = d.m_q; o.ms = static_cast<float*>(d.m_scale); o.mk = d.m_k;
-    o.vq = d.v_q; o.vs = static_cast<float*>(d.v_scale); o.vk = d.v_k; o.n = d.n; o.first_chunk = chunk; o.weight_decay = d.weight_decay;
-    __builtin_memcpy(dd + t, &o, sizeof o);
-    const uint64_t c = (d.n + kChunk - 1) / kChunk;
-    for (uint64_t i = 0; i < c; ++i) map[chunk + i] = t;
-    chunk += c;
+    const uint64_t spans = plan_records_of(d.n);
+    for (uint64_t i = 0; i < spans; ++i, ++rec) {
+      PlanRecord o = {};
+      o.w = d.w; o.wb = d.w_bf16; o.g = d.grad_bf16; o.mq = d.m_q; o.ms = static_cast<float*>(d.m_scale); o.mk = d.m_k;
+      o.vq = d.v_q; o.vs = static_cast<float*>(d.v_scale); o.vk = d.v_k; o.n = d.n;
+      o.chunk_base = i * kPlanSpan; o.weight_decay = d.weight_decay; o.tensor = t;
+      __builtin_memcpy(blob + h.record_offset + rec * sizeof(PlanRecord), &o, sizeof o);
+    }
   }
-  h.total_chunks = chunk;
+  h.total_records = rec;
   __builtin_memcpy(blob, &h, sizeof h);
   return COAT_OK;
 }
@@ -376,22 +377,19 @@ int coat_fp8_adamw_step_multi(const void* plan_host, const void* plan_device, co
   if (!plan_host) return COAT_ERR_NULL;
   PlanHeader h;
   __builtin_memcpy(&h, plan_host, sizeof h);
-  if (h.magic != kPlanMagic || h.version != 1 || h.desc_offset != sizeof(PlanHeader) ||
-      h.map_offset != plan_map_offset(h.count) || h.total_chunks > kMaxPlanChunks)
+  if (h.magic != kPlanMagic || h.version != 2 || h.record_offset != kPlanRecordOffset ||
+      h.total_records > kMaxPlanRecords || h.bytes != kPlanRecordOffset + h.total_records * sizeof(PlanRecord))
     return COAT_ERR_PLAN;
-  if (h.total_chunks == 0) return COAT_OK;
+  if (h.total_records == 0) return COAT_OK;
   if (!plan_device) return COAT_ERR_NULL;
   if (!aligned16(plan_device)) return COAT_ERR_ALIGN;
   const unsigned char* dev = static_cast<const unsigned char*>(plan_device);
   ma.base.w = nullptr; ma.base.wb = nullptr; ma.base.g = nullptr; ma.base.mq = nullptr; ma.base.ms = nullptr;
   ma.base.mk = nullptr; ma.base.vq = nullptr; ma.base.vs = nullptr; ma.base.vk = nullptr;
   ma.base.n = 0; ma.base.n_full = 0; ma.base.n_groups = 0; ma.base.neg_lr_wd = 0.0f;
-  ma.descs = reinterpret_cast<const TensorDesc*>(dev + h.desc_offset);
-  ma.chunk_tensor = reinterpret_cast<const uint32_t*>(dev + h.map_offset);
-  ma.total_chunks = h.total_chunks;
+  ma.records = reinterpret_cast<const PlanRecord*>(dev + h.record_offset);
   ma.neg_lr = -static_cast<double>(hp->lr);
-  ma.group_size = hp->group_size;
-  return dispatch_step_multi(ma, hp->group_size, generic, static_cast<hipStream_t>(hip_stream));
+  return dispatch_step_multi(ma, h.total_records, hp->group_size, generic, static_cast<hipStream_t>(hip_stream));
 }
 
 int coat_shard_range(uint64_t n, int32_t G, uint32_t rank, uint32_t world, uint64_t* begin, uint64_t* end) {

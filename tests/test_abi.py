@@ -120,29 +120,29 @@ def fake_desc(coat, n, wd=0.0, base=0x10000, **over):
 
 def test_multi_plan_layout_is_what_the_header_documents(coat):
     """The plan is host-built data: check it against the documented layout with an independent
-    reconstruction (chunk -> tensor map by brute force)."""
+    reconstruction (one record per span of 32 chunks, every tensor starting a new span)."""
     import numpy as np
-    sizes = [5000, 0, 1024, 7, 1 << 20, 1023, 1025]
+    sizes = [5000, 0, 1024, 7, 1 << 20, 1023, 1025, 32 * 1024, 32 * 1024 + 1]
     descs = [fake_desc(coat, n, wd=0.01 * i, base=0x10000 * (i + 1)) for i, n in enumerate(sizes)]
     blob = coat.coat_multi_plan_build(descs)
-    chunks = [(n + 1023) // 1024 for n in sizes]
-    desc_bytes = (96 * len(sizes) + 63) // 64 * 64
-    assert len(blob) == 64 + desc_bytes + 4 * sum(chunks)
-    magic, = np.frombuffer(blob[:8], np.uint64)
-    assert bytes(blob[:8]) == b"COATPLN1" and magic != 0
+    spans = [((n + 1023) // 1024 + 31) // 32 for n in sizes]
+    assert spans == [1, 0, 1, 1, 32, 1, 1, 1, 2]
+    assert len(blob) == 128 + 128 * sum(spans)
+    assert bytes(blob[:8]) == b"COATPLN2"
     version, count = np.frombuffer(blob[8:16], np.uint32)
-    total, d_off, m_off, nbytes = np.frombuffer(blob[16:48], np.uint64)
-    assert (version, count, total, d_off, m_off, nbytes) == (1, len(sizes), sum(chunks), 64, 64 + desc_bytes, len(blob))
-    cmap = np.frombuffer(blob[m_off:], np.uint32)
-    expect = np.concatenate([np.full(c, t, np.uint32) for t, c in enumerate(chunks)])
-    assert np.array_equal(cmap, expect)
-    first = np.cumsum([0] + chunks[:-1])
+    total, r_off, nbytes = np.frombuffer(blob[16:40], np.uint64)
+    assert (version, count, total, r_off, nbytes) == (2, len(sizes), sum(spans), 128, len(blob))
+    rec = 0
     for t, n in enumerate(sizes):
-        rec = blob[64 + 96 * t: 64 + 96 * (t + 1)]
-        ptrs = np.frombuffer(rec[:72], np.uint64)
-        assert ptrs[0] == 0x10000 * (t + 1) and ptrs[1] == 0 and np.all(ptrs[2:] == 0x10000 * (t + 1))
-        assert np.frombuffer(rec[72:88], np.uint64).tolist() == [n, first[t]]
-        assert np.frombuffer(rec[88:92], np.float32)[0] == np.float32(0.01 * t)
+        for i in range(spans[t]):
+            raw = blob[128 + 128 * rec: 128 + 128 * (rec + 1)]
+            ptrs = np.frombuffer(raw[:72], np.uint64)
+            assert ptrs[0] == 0x10000 * (t + 1) and ptrs[1] == 0 and np.all(ptrs[2:] == 0x10000 * (t + 1))
+            assert np.frombuffer(raw[72:88], np.uint64).tolist() == [n, 32 * i]          # n, chunk_base
+            assert np.frombuffer(raw[88:92], np.float32)[0] == np.float32(0.01 * t)
+            assert np.frombuffer(raw[92:96], np.uint32)[0] == t
+            rec += 1
+    assert rec == total
 
 
 def test_multi_plan_and_step_reject_bad_arguments(coat):
@@ -150,10 +150,10 @@ def test_multi_plan_and_step_reject_bad_arguments(coat):
     good = [fake_desc(coat, 4096)]
     arr = (coat.TensorDesc * 1)(*good)
     size = L.coat_multi_plan_bytes(arr, 1)
-    assert size == 64 + 128 + 16
+    assert size == 128 + 128
     buf = ctypes.create_string_buffer(size)
     assert L.coat_multi_plan_bytes(None, 1) == 0
-    assert L.coat_multi_plan_bytes(None, 0) == 64                     # an empty plan is legal
+    assert L.coat_multi_plan_bytes(None, 0) == 128                    # an empty plan is legal
     assert L.coat_multi_plan_build(arr, 1, None, size) == -1
     assert L.coat_multi_plan_build(arr, 1, buf, size - 1) == -7
     for field, bad, code in (("w", 0, -1), ("v_k", 0, -1), ("w", 0x10004, -2), ("m_q", 0x10008, -2), ("w_bf16", 0x10002, -2)):
@@ -174,8 +174,8 @@ def test_multi_plan_and_step_reject_bad_arguments(coat):
     assert L.coat_fp8_adamw_step_multi(buf, dev, ctypes.byref(coat.make_hparams(step=0)), None) == -4
     junk = ctypes.create_string_buffer(b"\x01" * size, size)
     assert L.coat_fp8_adamw_step_multi(junk, dev, ctypes.byref(hp), None) == -8
-    empty = ctypes.create_string_buffer(64)
-    assert L.coat_multi_plan_build(None, 0, empty, 64) == 0
+    empty = ctypes.create_string_buffer(128)
+    assert L.coat_multi_plan_build(None, 0, empty, 128) == 0
     assert L.coat_fp8_adamw_step_multi(empty, None, ctypes.byref(hp), None) == 0      # nothing to do
 
 
