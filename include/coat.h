@@ -152,6 +152,28 @@ int coat_fp8_adamw_step_multi(const void* plan_host, const void* plan_device,
                               const coat_adamw_hparams* hp, void* hip_stream);
 
 /*
+ * The multi-tensor step for callers that REPLAY a captured graph across steps.  Kernel arguments
+ * are frozen at capture, but three numbers change every step (Sec. 3, Eq. 1: the learning rate of
+ * the schedule and the two bias corrections 1 - beta^t).  This variant reads them from
+ * consts_device, a coat_step_consts in device memory (16-byte aligned) that the caller rewrites
+ * between replays with what coat_step_consts_compute (pure host code) returns for the new step;
+ * hp->lr and hp->step are validated but not used by the kernels, every other field of hp is
+ * frozen into the launch as usual.  Results are bit-identical to coat_fp8_adamw_step_multi with
+ * the same hyper-parameters.
+ */
+typedef struct {
+  float    neg_lr_m;      /* -lr * (1 - beta1) / (1 - beta1^t) */
+  float    denom_scale;   /* sqrt((1 - beta2) / (1 - beta2^t)) */
+  double   neg_lr;        /* -lr */
+  uint64_t reserved[2];
+} coat_step_consts;
+
+int coat_step_consts_compute(const coat_adamw_hparams* hp, coat_step_consts* out_host);
+int coat_fp8_adamw_step_multi_consts(const void* plan_host, const void* plan_device,
+                                     const coat_adamw_hparams* hp,
+                                     const coat_step_consts* consts_device, void* hip_stream);
+
+/*
  * The part of a flat tensor of n elements that rank `rank` of `world` owns when optimizer states
  * are sharded (ZeRO / FSDP style; Sec. 3: every rank quantizes its own shard with its own
  * statistics): shards are contiguous, cut at multiples of G so that no group spans two ranks, and

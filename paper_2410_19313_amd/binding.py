@@ -21,6 +21,7 @@ ACT_WORKSPACE_FLOATS = 64
 EXPORTS = ("coat_fp8_adamw_step", "coat_fp8_adamw_step_bf16w", "coat_quant_group", "coat_dequant_group",
            "coat_act_quant_group", "coat_act_quant_tensor", "coat_act_quant_tensor_from_group_amax",
            "coat_multi_plan_bytes", "coat_multi_plan_build", "coat_fp8_adamw_step_multi", "coat_shard_range",
+           "coat_step_consts_compute", "coat_fp8_adamw_step_multi_consts",
            "coat_strerror", "coat_version")
 
 
@@ -56,6 +57,13 @@ class TensorDesc(ctypes.Structure):
         ("v_q", ctypes.c_void_p), ("v_scale", ctypes.c_void_p), ("v_k", ctypes.c_void_p),
         ("n", ctypes.c_uint64), ("weight_decay", ctypes.c_float), ("reserved", ctypes.c_uint32),
     ]
+
+
+class StepConsts(ctypes.Structure):
+    """Mirror of coat_step_consts."""
+
+    _fields_ = [("neg_lr_m", ctypes.c_float), ("denom_scale", ctypes.c_float), ("neg_lr", ctypes.c_double),
+                ("reserved", ctypes.c_uint64 * 2)]
 
 
 def step_flags(expand=True, m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False) -> int:
@@ -108,6 +116,10 @@ def lib():
         L.coat_multi_plan_build.argtypes = [ctypes.POINTER(TensorDesc), ctypes.c_uint32, vp, ctypes.c_size_t]
         L.coat_fp8_adamw_step_multi.restype = ctypes.c_int
         L.coat_fp8_adamw_step_multi.argtypes = [vp, vp, ctypes.POINTER(HParams), vp]
+        L.coat_step_consts_compute.restype = ctypes.c_int
+        L.coat_step_consts_compute.argtypes = [ctypes.POINTER(HParams), ctypes.POINTER(StepConsts)]
+        L.coat_fp8_adamw_step_multi_consts.restype = ctypes.c_int
+        L.coat_fp8_adamw_step_multi_consts.argtypes = [vp, vp, ctypes.POINTER(HParams), vp, vp]
         L.coat_shard_range.restype = ctypes.c_int
         L.coat_shard_range.argtypes = [ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_uint32,
                                        ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
@@ -326,3 +338,33 @@ def coat_fp8_adamw_step_multi(plan: MultiPlan, hp: HParams) -> None:
         raise ValueError("COAT_FLAG_BF16_SCALE must match the dtype of the plan's scale tensors")
     _check(lib().coat_fp8_adamw_step_multi(ctypes.cast(plan._host_buf, ctypes.c_void_p),
                                            ctypes.c_void_p(plan.device.data_ptr()), ctypes.byref(hp), _stream()))
+
+
+def coat_step_consts_compute(hp: HParams) -> bytes:
+    """The 32 bytes of step-dependent constants for hp (host side; copy them into the device block)."""
+    c = StepConsts()
+    _check(lib().coat_step_consts_compute(ctypes.byref(hp), ctypes.byref(c)))
+    return bytes(c)
+
+
+def step_consts_tensor(hp: HParams, device, out=None):
+    """A device uint8[32] tensor holding coat_step_consts for hp (written into `out` when given)."""
+    import torch
+    host = torch.frombuffer(bytearray(coat_step_consts_compute(hp)), dtype=torch.uint8)
+    if out is None:
+        return host.to(device)
+    out.copy_(host)
+    return out
+
+
+def coat_fp8_adamw_step_multi_consts(plan: MultiPlan, hp: HParams, consts) -> None:
+    """coat_fp8_adamw_step_multi with the step-dependent constants read from `consts` (device uint8[32]),
+    so that a captured graph can be replayed across steps."""
+    import torch
+    if hp.group_size != plan.group_size:
+        raise ValueError("the plan's metadata buffers were sized for G=%d" % plan.group_size)
+    if bool(hp.flags & FLAG_BF16_SCALE) != plan.bf16_scale:
+        raise ValueError("COAT_FLAG_BF16_SCALE must match the dtype of the plan's scale tensors")
+    _check(lib().coat_fp8_adamw_step_multi_consts(ctypes.cast(plan._host_buf, ctypes.c_void_p),
+                                                  ctypes.c_void_p(plan.device.data_ptr()), ctypes.byref(hp),
+                                                  _dev_ptr(consts, torch.uint8, ctypes.sizeof(StepConsts)), _stream()))

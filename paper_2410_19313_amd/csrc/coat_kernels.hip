@@ -295,6 +295,33 @@ int step_constants(const coat_adamw_hparams* hp, StepArgs& a, bool& generic) {
   return COAT_OK;
 }
 
+
+int step_multi_impl(const void* plan_host, const void* plan_device, const coat_adamw_hparams* hp,
+                    const coat_step_consts* consts_device, bool want_consts, void* hip_stream) {
+  MultiArgs ma;
+  bool generic = false;
+  if (int rc = step_constants(hp, ma.base, generic)) return rc;
+  if (!plan_host) return COAT_ERR_NULL;
+  PlanHeader h;
+  __builtin_memcpy(&h, plan_host, sizeof h);
+  if (h.magic != kPlanMagic || h.version != 2 || h.record_offset != kPlanRecordOffset ||
+      h.total_records > kMaxPlanRecords || h.bytes != kPlanRecordOffset + h.total_records * sizeof(PlanRecord))
+    return COAT_ERR_PLAN;
+  if (want_consts && !consts_device) return COAT_ERR_NULL;
+  if (want_consts && !aligned16(consts_device)) return COAT_ERR_ALIGN;
+  if (h.total_records == 0) return COAT_OK;
+  if (!plan_device) return COAT_ERR_NULL;
+  if (!aligned16(plan_device)) return COAT_ERR_ALIGN;
+  const unsigned char* dev = static_cast<const unsigned char*>(plan_device);
+  ma.base.w = nullptr; ma.base.wb = nullptr; ma.base.g = nullptr; ma.base.mq = nullptr; ma.base.ms = nullptr;
+  ma.base.mk = nullptr; ma.base.vq = nullptr; ma.base.vs = nullptr; ma.base.vk = nullptr;
+  ma.base.n = 0; ma.base.n_full = 0; ma.base.n_groups = 0; ma.base.neg_lr_wd = 0.0f;
+  ma.records = reinterpret_cast<const PlanRecord*>(dev + h.record_offset);
+  ma.neg_lr = -static_cast<double>(hp->lr);
+  ma.consts = reinterpret_cast<const StepConsts*>(consts_device);
+  return dispatch_step_multi(ma, h.total_records, hp->group_size, generic, static_cast<hipStream_t>(hip_stream));
+}
+
 }  // namespace
 
 extern "C" {
@@ -369,27 +396,27 @@ int coat_multi_plan_build(const coat_tensor_desc* descs, uint32_t count, void* p
   return COAT_OK;
 }
 
+int coat_step_consts_compute(const coat_adamw_hparams* hp, coat_step_consts* out) {
+  if (!out) return COAT_ERR_NULL;
+  StepArgs a;
+  bool generic = false;
+  if (int rc = step_constants(hp, a, generic)) return rc;
+  coat_step_consts c = {};
+  c.neg_lr_m = a.neg_lr_m;
+  c.denom_scale = a.denom_scale;
+  c.neg_lr = -static_cast<double>(hp->lr);
+  *out = c;
+  return COAT_OK;
+}
+
 int coat_fp8_adamw_step_multi(const void* plan_host, const void* plan_device, const coat_adamw_hparams* hp,
                               void* hip_stream) {
-  MultiArgs ma;
-  bool generic = false;
-  if (int rc = step_constants(hp, ma.base, generic)) return rc;
-  if (!plan_host) return COAT_ERR_NULL;
-  PlanHeader h;
-  __builtin_memcpy(&h, plan_host, sizeof h);
-  if (h.magic != kPlanMagic || h.version != 2 || h.record_offset != kPlanRecordOffset ||
-      h.total_records > kMaxPlanRecords || h.bytes != kPlanRecordOffset + h.total_records * sizeof(PlanRecord))
-    return COAT_ERR_PLAN;
-  if (h.total_records == 0) return COAT_OK;
-  if (!plan_device) return COAT_ERR_NULL;
-  if (!aligned16(plan_device)) return COAT_ERR_ALIGN;
-  const unsigned char* dev = static_cast<const unsigned char*>(plan_device);
-  ma.base.w = nullptr; ma.base.wb = nullptr; ma.base.g = nullptr; ma.base.mq = nullptr; ma.base.ms = nullptr;
-  ma.base.mk = nullptr; ma.base.vq = nullptr; ma.base.vs = nullptr; ma.base.vk = nullptr;
-  ma.base.n = 0; ma.base.n_full = 0; ma.base.n_groups = 0; ma.base.neg_lr_wd = 0.0f;
-  ma.records = reinterpret_cast<const PlanRecord*>(dev + h.record_offset);
-  ma.neg_lr = -static_cast<double>(hp->lr);
-  return dispatch_step_multi(ma, h.total_records, hp->group_size, generic, static_cast<hipStream_t>(hip_stream));
+  return step_multi_impl(plan_host, plan_device, hp, nullptr, false, hip_stream);
+}
+
+int coat_fp8_adamw_step_multi_consts(const void* plan_host, const void* plan_device, const coat_adamw_hparams* hp,
+                                     const coat_step_consts* consts_device, void* hip_stream) {
+  return step_multi_impl(plan_host, plan_device, hp, consts_device, true, hip_stream);
 }
 
 int coat_shard_range(uint64_t n, int32_t G, uint32_t rank, uint32_t world, uint64_t* begin, uint64_t* end) {
@@ -485,7 +512,7 @@ const char* coat_strerror(int code) {
   return "unknown error code";
 }
 
-int coat_version(void) { return 220; }
+int coat_version(void) { return 230; }
 
 #ifdef COAT_TUNING
 // development builds only: launch-shape knobs for sweeps

@@ -55,10 +55,22 @@ constexpr uint64_t kPlanMagic = 0x324e4c5054414f43ull;     // "COATPLN2"
 constexpr int kPlanSpan = kGateSpan;                        // virtual chunks per record
 static_assert(kPlanSpan % kWavesPerBlock == 0, "a workgroup never straddles two records");
 
+// The three numbers of a step that change from one step to the next (learning-rate schedule, bias
+// corrections).  Normally they travel as kernel arguments; a caller that replays a captured graph
+// keeps them in device memory instead and rewrites these 32 bytes between replays.
+struct StepConsts {
+  float neg_lr_m;            // -lr * (1 - beta1) / (1 - beta1^t)
+  float denom_scale;         // sqrt((1 - beta2) / (1 - beta2^t))
+  double neg_lr;             // -lr
+  uint64_t reserved[2];
+};
+static_assert(sizeof(StepConsts) == sizeof(coat_step_consts), "C ABI mirror");
+
 struct MultiArgs {
   StepArgs base;             // the shared hyper-parameter constants; pointers and sizes are per tensor
   const PlanRecord* records;
   double neg_lr;             // -lr: the decay factor -lr * lambda is formed per tensor, in fp64 like the host does
+  const StepConsts* consts;  // nullptr: the step's constants are the arguments above
 };
 
 template <int G, bool GENERIC>
@@ -77,12 +89,18 @@ __global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) 
   // everything here is uniform over the wavefront (gc is), so the record travels in scalar registers
   const PlanRecordDev& d = reinterpret_cast<const PlanRecordDev*>(ma.records)[gc / kPlanSpan];
   StepArgs a = ma.base;
+  double neg_lr = ma.neg_lr;
+  if (ma.consts) {                                   // uniform: three scalar loads beside the record's
+    a.neg_lr_m = ma.consts->neg_lr_m;
+    a.denom_scale = ma.consts->denom_scale;
+    neg_lr = ma.consts->neg_lr;
+  }
   a.w = (float*)d.w; a.wb = (uint16_t*)d.wb; a.g = (const uint16_t*)d.g;
   a.mq = (uint8_t*)d.mq; a.ms = (float*)d.ms; a.mk = (float*)d.mk;
   a.vq = (uint8_t*)d.vq; a.vs = (float*)d.vs; a.vk = (float*)d.vk;
   a.n = d.n; a.n_full = d.n / kChunk;
   a.n_groups = (d.n + G - 1) / G;
-  a.neg_lr_wd = static_cast<float>(ma.neg_lr * static_cast<double>(d.weight_decay));
+  a.neg_lr_wd = static_cast<float>(neg_lr * static_cast<double>(d.weight_decay));
   const uint64_t chunk = d.chunk_base + (gc % kPlanSpan);
   const bool full = chunk < a.n_full;
   const bool tail = !full && chunk * kChunk < a.n;     // the tensor's ragged last chunk; beyond it: padding

@@ -179,6 +179,32 @@ def test_multi_plan_and_step_reject_bad_arguments(coat):
     assert L.coat_fp8_adamw_step_multi(empty, None, ctypes.byref(hp), None) == 0      # nothing to do
 
 
+def test_step_consts_are_the_documented_formulas(coat):
+    import math
+    import struct
+    for lr, b1, b2, t in ((3e-4, 0.9, 0.95, 1), (1e-3, 0.8, 0.999, 17), (0.0, 0.9, 0.95, 1000000)):
+        hp = coat.make_hparams(lr=lr, beta1=b1, beta2=b2, step=t)
+        neg_lr_m, denom_scale, neg_lr = struct.unpack("<ffd", coat.coat_step_consts_compute(hp)[:16])
+        f = lambda x: struct.unpack("<f", struct.pack("<f", x))[0]      # what the fp32 fields hold
+        lr32, b1f, b2f = f(lr), f(b1), f(b2)
+        omb1, omb2 = f(1.0 - b1f), f(1.0 - b2f)
+        assert neg_lr == -lr32
+        assert neg_lr_m == f(-lr32 * omb1 / (1.0 - b1f ** t))
+        assert denom_scale == f(math.sqrt(omb2 / (1.0 - b2f ** t)))
+    L = coat.lib()
+    c = coat.StepConsts()
+    assert L.coat_step_consts_compute(None, ctypes.byref(c)) == -1
+    assert L.coat_step_consts_compute(ctypes.byref(coat.make_hparams()), None) == -1
+    assert L.coat_step_consts_compute(ctypes.byref(coat.make_hparams(step=0)), ctypes.byref(c)) == -4
+    buf = ctypes.create_string_buffer(256)
+    arr = (coat.TensorDesc * 1)(fake_desc(coat, 4096))
+    assert L.coat_multi_plan_build(arr, 1, buf, 256) == 0
+    dev = ctypes.c_void_p(0x20000)
+    hp = coat.make_hparams()
+    assert L.coat_fp8_adamw_step_multi_consts(buf, dev, ctypes.byref(hp), None, None) == -1
+    assert L.coat_fp8_adamw_step_multi_consts(buf, dev, ctypes.byref(hp), ctypes.c_void_p(0x30004), None) == -2
+
+
 def test_shard_range_partitions_at_group_boundaries(coat):
     for n, G, world in ((0, 128, 4), (1, 128, 4), (1000, 128, 3), (4096, 128, 8), (4097, 32, 5), (10 ** 9 + 7, 512, 64),
                         (300, 128, 8)):

@@ -141,3 +141,58 @@ def test_training_trajectory_tracks_fp32_adamw(coat):
         assert l_ref < 1e-3 * first and torch.all(torch.isfinite(w_fp8))
     assert abs(final[True][0] / final[True][1] - 1.0) <= 0.02
     assert final[False][0] > 10.0 * final[True][0]
+
+
+def test_one_captured_graph_replayed_across_steps(coat):
+    """A training loop under a graph: the multi-tensor step is captured ONCE (with the step-dependent
+    constants in a device block) and replayed for steps 1..5 with a changing learning rate, the host
+    rewriting the 32-byte block and the gradients between replays.  Every step must equal the
+    eager multi-tensor step with that step's hyper-parameters, bit for bit."""
+    G = 128
+    dev = torch.device("cuda:0")
+    sizes = [70 * 1024 + 3, 4096, 129, 33 * 1024]
+
+    def make():
+        tens = []
+        for i, n in enumerate(sizes):
+            st = S.torch_zero_state(n, G, dev)
+            d = dict(w=torch.from_numpy(S.weights(n, 40 + i)).to(dev), grad=torch.empty(n, dtype=torch.bfloat16, device=dev),
+                     weight_decay=0.1 if i % 2 else 0.0)
+            d.update(st)
+            tens.append(d)
+        return tens
+
+    def set_grads(tens, t):
+        for i, d in enumerate(tens):
+            d["grad"].copy_(torch.from_numpy(S.grads_normal(sizes[i], 60 + i, t, G=G, outlier_frac=0.02).view(np.int16)).to(dev)
+                            .view(torch.bfloat16))
+
+    def hp_of(t):
+        return coat.make_hparams(step=t, group_size=G, **{**HP, "lr": 3e-4 * (1.0 - 0.1 * t)})
+
+    eager, graphed = make(), make()
+    plan_e, plan_g = coat.MultiPlan(eager, G), coat.MultiPlan(graphed, G)
+    consts = coat.step_consts_tensor(hp_of(1), dev)
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    set_grads(graphed, 1)
+    snapshot = [{k: v.clone() for k, v in d.items() if torch.is_tensor(v)} for d in graphed]
+    with torch.cuda.stream(cap):
+        with torch.cuda.graph(graph, stream=cap):
+            coat.coat_fp8_adamw_step_multi_consts(plan_g, hp_of(1), consts)
+    torch.cuda.synchronize()
+    for d, s in zip(graphed, snapshot):            # capture does not execute; make sure of the start state anyway
+        for k, v in s.items():
+            d[k].copy_(v)
+    for t in range(1, 6):
+        set_grads(eager, t)
+        set_grads(graphed, t)
+        coat.coat_fp8_adamw_step_multi(plan_e, hp_of(t))
+        coat.step_consts_tensor(hp_of(t), dev, out=consts)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (de, dg) in enumerate(zip(eager, graphed)):
+            for k in ("w", "m_q", "m_scale", "m_k", "v_q", "v_scale", "v_k"):
+                assert same(de[k], dg[k]), "step %d tensor %d: %s differs" % (t, i, k)
