@@ -61,6 +61,20 @@ def test_group_scaling_two_stage_max_and_per_tensor_codes(ref, G):
     assert ts2 == ts and np.array_equal(q2, q)
 
 
+@pytest.mark.parametrize("where", ["first", "last_ragged", "middle"])
+def test_group_scaling_finds_the_maximum_wherever_it_is(ref, where):
+    # the tensor's largest element in the first group, in the short last group, or in between
+    G, n = 16, 40 * 16 + 5
+    x = (np.random.default_rng(9).standard_normal(n) * 0.1).astype(np.float32)
+    pos = {"first": 3, "last_ragged": n - 2, "middle": 17 * G + 9}[where]
+    x[pos] = -7.0
+    xb = S.f32_to_bf16_bits(x)
+    q, ts, gmax = ref.act_quant_tensor(xb, G)
+    assert ts == np.float32(7.0) / np.float32(448.0)
+    assert gmax[pos // G] == 7.0 and q[pos] == 0xFE                   # -448
+    assert np.all(gmax[np.arange(gmax.size) != pos // G] < 7.0)
+
+
 def test_per_group_beats_per_tensor_on_spiky_activations(ref):
     # the reason for the mixed granularity (Sec. 5.2): with outliers a single scale wastes the range
     n, G = 64 * 1024, 16
