@@ -63,37 +63,58 @@ __global__ __launch_bounds__(kWave) void quant_tail_kernel(QuantArgs a) {
 
 // The standalone dequantizer always honours the stored k (it is 1 for codes written without
 // expansion), with the compensated exponent.
-__device__ __forceinline__ void dequant_core(const DequantArgs& a, const Log2Entry* lut, const uint32_t (&c)[4],
-                                             float scale, float k, float (&x)[kEPL]) {
-  inverse_expand16<true, true>(lut + (a.mode.e5m2() ? 256 : 0), c, k, hw_rcp(k), x);
+// The dequantizer needs one format's table only; it sits at the front of the LDS array.
+__device__ __forceinline__ void fill_lut_one(Log2Entry* lut, bool e5m2) {
+  for (int i = threadIdx.x; i < 256; i += blockDim.x) lut[i] = kLog2Code[e5m2 ? 1 : 0][i & 127];
+  __syncthreads();
+}
+
+__device__ __forceinline__ void dequant_core(const DequantArgs& a, const Log2Entry* lut, const u32x4& ci, float scale,
+                                             float k, float (&x)[kEPL]) {
+  const uint32_t c[4] = {ci.x, ci.y, ci.z, ci.w};
+  inverse_expand16<true, true>(lut, c, k, hw_rcp(k), x);
   const float amag = fmt_max(a.mode) * scale;
 #pragma unroll
   for (int e = 0; e < kEPL; ++e) x[e] *= amag;
 }
 
+// One chunk per wavefront; the first chunk's codes and metadata are requested before the block
+// fills its table, so the table's latency hides behind them.
 template <int G>
 __global__ __launch_bounds__(kBlock) void dequant_kernel(DequantArgs a) {
-  __shared__ Log2Entry lut[512];
+  __shared__ Log2Entry lut[256];
   __shared__ f32x4 tile_x[kWavesPerBlock * kTileSlotsW];
-  fill_lut<2>(lut);
   constexpr int LPG = G / kEPL;
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
-  for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
-    const uint64_t cb = chunk * kChunk, gb = chunk * (kChunk / G);
-    const u32x4 ci = ldg<1>(reinterpret_cast<const u32x4*>(a.q + cb) + lane);
-    const uint32_t c[4] = {ci.x, ci.y, ci.z, ci.w};
-    float x[kEPL];
-    dequant_core(a, lut, c, load_scale(a.mode, a.scale, gb + lane / LPG), a.k[gb + lane / LPG], x);
-    tile_lanes_to_rows_store(tile_x + wv * kTileSlotsW, lane, x, a.x + cb);
+  uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv;
+  const bool have = chunk < a.n_full;
+  u32x4 ci = {0u, 0u, 0u, 0u};
+  float scale = 0.0f, k = 1.0f;
+  if (have) {
+    ci = ldg<1>(reinterpret_cast<const u32x4*>(a.q + chunk * kChunk) + lane);
+    scale = load_scale_full_chunk(a.mode, a.scale, chunk * (kChunk / G), lane / LPG);
+    k = a.k[chunk * (kChunk / G) + lane / LPG];
+  }
+  fill_lut_one(lut, a.mode.e5m2());                  // every wavefront of the block reaches this
+  float x[kEPL];
+  if (have) {
+    dequant_core(a, lut, ci, scale, k, x);
+    tile_lanes_to_rows_store(tile_x + wv * kTileSlotsW, lane, x, a.x + chunk * kChunk);
+  }
+  for (chunk += stride; chunk < a.n_full; chunk += stride) {
+    const uint64_t gb = chunk * (kChunk / G);
+    ci = ldg<1>(reinterpret_cast<const u32x4*>(a.q + chunk * kChunk) + lane);
+    dequant_core(a, lut, ci, load_scale_full_chunk(a.mode, a.scale, gb, lane / LPG), a.k[gb + lane / LPG], x);
+    tile_lanes_to_rows_store(tile_x + wv * kTileSlotsW, lane, x, a.x + chunk * kChunk);
   }
 }
 
 template <int G>
 __global__ __launch_bounds__(kWave) void dequant_tail_kernel(DequantArgs a) {
-  __shared__ Log2Entry lut[512];
-  fill_lut<2>(lut);
+  __shared__ Log2Entry lut[256];
+  fill_lut_one(lut, a.mode.e5m2());
   constexpr int LPG = G / kEPL;
   const int lane = threadIdx.x;
   const uint64_t base = a.n_full * kChunk + static_cast<uint64_t>(lane) * kEPL;
@@ -102,7 +123,8 @@ __global__ __launch_bounds__(kWave) void dequant_tail_kernel(DequantArgs a) {
   uint32_t c[4];
   float x[kEPL];
   load_codes16_guarded(a.q, base, a.n, c);
-  dequant_core(a, lut, c, gvalid ? load_scale(a.mode, a.scale, gidx) : 0.0f, gvalid ? a.k[gidx] : 1.0f, x);
+  const u32x4 ci = {c[0], c[1], c[2], c[3]};
+  dequant_core(a, lut, ci, gvalid ? load_scale(a.mode, a.scale, gidx) : 0.0f, gvalid ? a.k[gidx] : 1.0f, x);
   store_f32x16_guarded(a.x, base, a.n, x);
 }
 
