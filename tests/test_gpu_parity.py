@@ -606,6 +606,10 @@ def test_table1_structure_on_the_gpu_path(coat, ref):
         assert np.all(r[e, :] < r[p, :]) and np.all(r[:, e] < r[:, p])
     assert min(r[1, 1], r[1, 3]) == r.min() and r[1, 1] <= 1.1 * r.min()
     assert r[0, 0] > 1.3 * r[1, 1]                        # the direction of the paper's 1.63x
+    # and the order the paper's own sixteen values establish (tests/golden/table1_mse.txt)
+    from test_oracle_formats import concordance, paper_table1
+    pairs, wrong = concordance(paper_table1(), r)
+    assert len(pairs) == 110 and not wrong, wrong
 
 
 # --- seeded sweep over sizes, group sizes and storage modes ------------------------------------
