@@ -33,6 +33,14 @@ def test_header_symbols_are_exported(coat):
     assert coat.lib().coat_version() >= 100
 
 
+def test_header_is_plain_c_and_cplusplus():
+    """The boundary is a C ABI: the header must compile on its own as C99 and as C++."""
+    import subprocess
+    h = os.path.join(ROOT, "include", "coat.h")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", h], check=True)
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", h], check=True)
+
+
 def test_error_codes_have_text(coat):
     for code in range(0, -9, -1):
         assert coat.strerror(code) and "unknown" not in coat.strerror(code)
