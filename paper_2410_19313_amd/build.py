@@ -41,5 +41,24 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+NATIVE_TEST_SRC = os.path.join(ROOT, "tests", "native", "abi_smoke.cpp")
+NATIVE_TEST_BIN = os.path.join(ROOT, "tests", "native", "abi_smoke")
+
+
+def build_native_test(force: bool = True) -> str:
+    """Compile the plain-HIP host program that uses the C ABI without Python (tests/native)."""
+    if not force and os.path.exists(NATIVE_TEST_BIN) and \
+            os.path.getmtime(NATIVE_TEST_BIN) >= max(os.path.getmtime(NATIVE_TEST_SRC), os.path.getmtime(LIB)):
+        return NATIVE_TEST_BIN
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), NATIVE_TEST_SRC,
+           "-L", _HERE, "-lcoat", "-Wl,-rpath,$ORIGIN/../../paper_2410_19313_amd", "-o", NATIVE_TEST_BIN]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    return NATIVE_TEST_BIN
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
+    print(build_native_test(force=True))
