@@ -154,16 +154,17 @@ int coat_fp8_adamw_step_multi(const void* plan_host, const void* plan_device,
 /*
  * The multi-tensor step for callers that REPLAY a captured graph across steps.  Kernel arguments
  * are frozen at capture, but three numbers change every step (Sec. 3, Eq. 1: the learning rate of
- * the schedule and the two bias corrections 1 - beta^t).  This variant reads them from
+ * the schedule and the two bias corrections 1 - beta^t; the kernels use them folded into the
+ * denominator of the update, see the fields below).  This variant reads them from
  * consts_device, a coat_step_consts in device memory (16-byte aligned) that the caller rewrites
  * between replays with what coat_step_consts_compute (pure host code) returns for the new step;
- * hp->lr and hp->step are validated but not used by the kernels, every other field of hp is
- * frozen into the launch as usual.  Results are bit-identical to coat_fp8_adamw_step_multi with
+ * hp->lr, hp->step and hp->eps are validated but not used by the kernels, every other field of hp
+ * is frozen into the launch as usual.  Results are bit-identical to coat_fp8_adamw_step_multi with
  * the same hyper-parameters.
  */
 typedef struct {
-  float    neg_lr_m;      /* -lr * (1 - beta1) / (1 - beta1^t) */
-  float    denom_scale;   /* sqrt((1 - beta2) / (1 - beta2^t)) */
+  float    denom_mul;     /* sqrt((1 - beta2) / (1 - beta2^t)) / c,  c = -lr (1 - beta1) / (1 - beta1^t) */
+  float    denom_add;     /* eps / c;  lr == 0 gives denom_mul = 0 and denom_add = +inf (no update) */
   double   neg_lr;        /* -lr */
   uint64_t reserved[2];
 } coat_step_consts;

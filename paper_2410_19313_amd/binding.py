@@ -62,7 +62,7 @@ class TensorDesc(ctypes.Structure):
 class StepConsts(ctypes.Structure):
     """Mirror of coat_step_consts."""
 
-    _fields_ = [("neg_lr_m", ctypes.c_float), ("denom_scale", ctypes.c_float), ("neg_lr", ctypes.c_double),
+    _fields_ = [("denom_mul", ctypes.c_float), ("denom_add", ctypes.c_float), ("neg_lr", ctypes.c_double),
                 ("reserved", ctypes.c_uint64 * 2)]
 
 

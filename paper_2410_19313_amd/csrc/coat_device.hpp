@@ -68,12 +68,19 @@ struct StepArgs {
   // folded into the constants below and into the per-group scale.
   float beta1_ratio, beta2_ratio;        // beta / (1 - beta)
   float one_minus_beta1, one_minus_beta2;
-  float neg_lr_m;        // -lr * (1 - beta1) / (1 - beta1^t)
-  float neg_lr_wd;       // -lr * weight_decay
-  float denom_scale;     // sqrt((1 - beta2) / (1 - beta2^t))
-  float eps;
+  // Eq. (1) as  w <- w_keep * w + m' / (denom_mul * sqrt(v') + denom_add)  with the step size folded
+  // into the denominator: with c = -lr (1 - beta1) / (1 - beta1^t) (the factor that turns m' / D into
+  // the update), denom_mul = sqrt((1 - beta2) / (1 - beta2^t)) / c and denom_add = eps / c; lr == 0
+  // gives denom_mul = 0 and denom_add = +inf, i.e. no update.  w_keep = 1 - lr * weight_decay.
+  float denom_mul, denom_add;
+  float w_keep;
   float k_min, k_max;
   RuntimeMode mode_m, mode_v;
+  // the same first-moment update in fp64, for the one element per lane that is recomputed exactly
+  // (exact_candidate): m_t / (1 - beta1) = m_ratio64 * m + g_coef64 * g, with beta1 the fp32
+  // hyper-parameter taken as a double; g_coef64 = (1 - beta1) / one_minus_beta1 is 1 whenever the
+  // fp32 difference 1 - beta1 is exact (beta1 >= 0.5)
+  double m_ratio64, g_coef64;
 };
 
 struct QuantArgs {
@@ -278,11 +285,34 @@ __device__ __forceinline__ void tile_lanes_to_rows_store_bf16(u32x4* tile, int l
   for (int j = 0; j < 2; ++j) stg<16>(q + 64 * j + lane, row[72 * j]);
 }
 
-// The lookup table in LDS: per format 256 entries so that the whole code byte indexes it (the sign
-// bit is ignored).  TABLES = 1 loads E4M3 only, 2 loads E4M3 then E5M2.
-template <int TABLES>
-__device__ __forceinline__ void fill_lut(Log2Entry* lut) {
-  for (int i = threadIdx.x; i < 256 * TABLES; i += blockDim.x) lut[i] = kLog2Code[i >> 8][i & 127];
+// The tables a step kernel keeps in LDS: the logarithms of the code magnitudes (per format 256
+// entries so that the whole code byte indexes it; the sign bit is ignored) and the fractional
+// powers 2^(j/512) that exp2_f64 looks up.  TABLES = 1 loads E4M3 only, 2 loads E4M3 then E5M2.
+constexpr int kExp2Frac = kExp2FracSize;
+struct StepTables { const Log2Entry* lut; const double* frac; };
+
+// THREADS: the (compile-time) size of the block.  Every load is issued before the first LDS write,
+// so that the fill costs ONE trip to memory, which the chunk's own loads (issued before it) hide;
+// a loop that waits per iteration adds a full memory latency to the wavefront's life each time
+// (measured on the 7B set: about +0.6 ms per extra trip).
+template <int TABLES, int THREADS>
+__device__ __forceinline__ void fill_lut(Log2Entry* lut, double* frac) {
+  constexpr int kLutIters = (256 * TABLES + THREADS - 1) / THREADS, kFracIters = (kExp2Frac + THREADS - 1) / THREADS;
+  Log2Entry e[kLutIters];
+  double f[kFracIters];
+#pragma unroll
+  for (int r = 0; r < kLutIters; ++r) {
+    const int i = threadIdx.x + r * THREADS;
+    e[r] = kLog2Code[(i >> 8) & 1][i & 127];
+  }
+#pragma unroll
+  for (int r = 0; r < kFracIters; ++r) f[r] = kExp2Frac512[(threadIdx.x + r * THREADS) & (kExp2Frac - 1)];
+#pragma unroll
+  for (int r = 0; r < kLutIters; ++r)
+    if (threadIdx.x + r * THREADS < 256 * TABLES) lut[threadIdx.x + r * THREADS] = e[r];
+#pragma unroll
+  for (int r = 0; r < kFracIters; ++r)
+    if (threadIdx.x + r * THREADS < kExp2Frac) frac[threadIdx.x + r * THREADS] = f[r];
   __syncthreads();
 }
 
@@ -344,9 +374,9 @@ __device__ __forceinline__ void decode16(const uint32_t (&c)[4], float (&y)[kEPL
 //   expansion off: y = c,               factor = scale              (k is 1 in this mode, not read)
 template <bool SIGNED, bool ACCURATE, class Mode>
 __device__ __forceinline__ float dequant16(const Mode& md, const Log2Entry* lut, const uint32_t (&c)[4],
-                                           float scale, float k, float (&y)[kEPL]) {
+                                           float scale, float k, float inv_k, float (&y)[kEPL]) {
   if (md.expand()) {
-    inverse_expand16<SIGNED, ACCURATE>(lut + (md.e5m2() ? 256 : 0), c, k, hw_rcp(k), y);
+    inverse_expand16<SIGNED, ACCURATE>(lut + (md.e5m2() ? 256 : 0), c, k, inv_k, y);
     return fmt_max(md) * scale;
   }
   if (md.e5m2()) decode16<true>(c, y);
@@ -413,6 +443,120 @@ __device__ __forceinline__ void lane_extremes(const float (&x)[kEPL], float& ama
   amax = hi; amin = lo;
 }
 
+// max |x| over the lane's 16 new first moments and, in one word, the smallest magnitude that may
+// be the lane's non-zero minimum together with the index of the element that holds it:
+// key = (bits of |x|, low four mantissa bits cleared) | index, so that one unsigned minimum finds
+// both.  ~0 when the lane has no candidate.  An fp32 zero is a candidate too (magnitude 0, so it
+// wins) when its gradient is not zero: then beta1 m and (1 - beta1) g cancelled to the last bit
+// in fp32 while the exact value need not be zero; a zero with a zero gradient is a true zero
+// (the old moment is zero as well) and leaves the minimum, as Definition 1 is read here.
+__device__ __forceinline__ void lane_extremes_keyed(const float (&x)[kEPL], const float (&g)[kEPL], float& amax,
+                                                    uint32_t& min_key) {
+  float hi = 0.0f;
+  uint32_t lo = 0xffffffffu;
+  uint32_t mask;                                     // in a scalar register: one v_and_or_b32 per key
+  asm("s_mov_b32 %0, 0x7ffffff0" : "=s"(mask));
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) {
+    hi = __builtin_fmaxf(hi, __builtin_fabsf(x[e]));
+    const uint32_t key = (as_u32(x[e]) & mask) | static_cast<uint32_t>(e);
+    lo = key < lo ? key : lo;
+  }
+  if (__builtin_expect(lo < 16u, 0)) {               // rare: some element is exactly zero in fp32
+    lo = 0xffffffffu;
+#pragma unroll
+    for (int e = 0; e < kEPL; ++e) {
+      const uint32_t mag = as_u32(x[e]) & mask;
+      const bool cancelled = (as_u32(g[e]) & 0x7fffffffu) != 0u;
+      const uint32_t key = (mag || cancelled) ? (mag | static_cast<uint32_t>(e)) : 0xffffffffu;
+      lo = key < lo ? key : lo;
+    }
+  }
+  amax = hi; min_key = lo;
+}
+
+// 2^t in fp64 for t <= 0: 512 t = i + r with i an integer and |r| <= 1/2, so that
+// 2^t = 2^(i >> 9) * 2^((i & 511) / 512) * 2^(r / 512): the middle factor from the table in LDS,
+// the last one as 1 + x + x^2/2 + x^3/6 in x = r ln2 / 512 (|x| < 6.8e-4, remainder below 1e-14).
+// Below -1100 the result is 0 either way.
+__device__ __forceinline__ double exp2_f64(const double* frac, double t) {
+  const double u = __builtin_fmax(t, -1100.0) * static_cast<double>(kExp2Frac);
+  const double ni = __builtin_rint(u);
+  const double x = (u - ni) * (0x1.62e42fefa39efp-1 / kExp2Frac);
+  const int i = static_cast<int>(ni);
+  const double p = __builtin_fma(x, __builtin_fma(x, __builtin_fma(x, 1.0 / 6.0, 0.5), 1.0), 1.0);
+  return __builtin_ldexp(frac[i & (kExp2Frac - 1)] * p, i >> 9);
+}
+
+// Where the lane keeps, in LDS, what the refinement below looks up by a run-time index: the 16
+// first-moment codes the step started from and the 16 bf16 gradients.
+typedef uint16_t __attribute__((may_alias)) lds_u16;
+struct LaneScratch { const uint8_t* codes; const lds_u16* g; };
+
+// The lane's smallest |m_t| recomputed in fp64 (with or without the expansion; without it k is 1
+// and only the replacement in apply_exact_min matters).
+// m_t = beta1 m + (1 - beta1) g cancels; the element where it cancels most is the group minimum,
+// which fixes the exponent k = log2(range) / log2(amax / amin) (Sec. 4.2) and through k every code
+// of the group.  In fp32 that element keeps the absolute error of the dequantized m but not its
+// size, so the fp32 pass only NAMES the candidate (min_key, from lane_extremes_keyed) and this
+// function recomputes that one element exactly: the table logarithm as hi + lo, 1/k by a Newton
+// step, 2^(L/k) by exp2_f64, the update as one fp64 fma, rounded to fp32 at the end.  About fifty
+// instructions per lane (three per element), and no branch: the caller places independent work
+// (the second moment's quantization) beside this long dependent chain.
+template <class Mode>
+__device__ __forceinline__ float exact_candidate(const StepArgs& a, const Mode& md, const StepTables& tb,
+                                                 const LaneScratch& ls, uint32_t min_key, float scale, float k,
+                                                 float inv_k) {
+  const uint32_t idx = min_key & 15u;                // also in range when there is no candidate (~0)
+  const uint32_t code = ls.codes[idx];
+  const float g = as_f32(static_cast<uint32_t>(ls.g[idx]) << 16);
+  double old_m;                                      // the element's old first moment, exactly
+  if (md.expand()) {
+    const Log2Entry l = tb.lut[(md.e5m2() ? 256u : 0u) + code];
+    const double kd = static_cast<double>(k);
+    double r = static_cast<double>(inv_k);
+    r = __builtin_fma(r, __builtin_fma(-kd, r, 1.0), r);
+    const double t = (static_cast<double>(l.hi) + static_cast<double>(l.lo)) * r;
+    const double mag = exp2_f64(tb.frac, t) * (static_cast<double>(fmt_max(md)) * static_cast<double>(scale));
+    // the code's sign bit goes onto the (non-negative) magnitude
+    old_m = __builtin_bit_cast(double, __builtin_bit_cast(uint64_t, mag) | (static_cast<uint64_t>(code & 0x80u) << 56));
+  } else {
+    // stored without expansion: the decoded code times the scale, exact in fp64
+    const float c = md.e5m2() ? __builtin_amdgcn_cvt_f32_bf8(code, 0) : __builtin_amdgcn_cvt_f32_fp8(code, 0);
+    old_m = static_cast<double>(c) * static_cast<double>(scale);
+  }
+  return static_cast<float>(__builtin_fma(a.m_ratio64, old_m, a.g_coef64 * static_cast<double>(g)));
+}
+
+// The lane's smallest non-zero |m_t| given the exact value of its candidate.  Where the fp32 value
+// of that element is off by more than 2^-9 of its size (deep cancellation: a few lanes in 10^4)
+// `replace` is set: the minimum is then taken again with the exact value in the element's place
+// (an exact zero leaves it; another element may now be the smallest) and the caller re-encodes that
+// one element from the exact value (requantize_one), so that its code comes out right, sign
+// included.  x itself is never written: a conditional write to the register array would cost the
+// straight-line path a copy of all sixteen.  amax: the lane's maximum from the fp32 pass (in/out).
+__device__ __forceinline__ float apply_exact_min(float exact, uint32_t min_key, const float (&x)[kEPL], float& amax,
+                                                 bool& replace) {
+  float res = __builtin_fabsf(exact);
+  const bool have = min_key != 0xffffffffu;          // false: nothing but true zeros in this lane
+  const uint32_t seen_bits = min_key & 0x7ffffff0u;  // what the fp32 pass had (low mantissa bits cleared)
+  replace = have && !(__builtin_fabsf(res - as_f32(seen_bits)) <= 0x1p-9f * res);
+  if (__builtin_expect(replace, 0)) {
+    uint32_t idx = min_key & 15u;
+    asm volatile("" : "+v"(idx));                    // keeps the loop's arithmetic inside this rare block
+    res = res > 0.0f ? res : __builtin_huge_valf();
+#pragma unroll
+    for (int e = 0; e < kEPL; ++e) {
+      const float ax = __builtin_fabsf(x[e]);
+      res = __builtin_fminf(res, (static_cast<uint32_t>(e) != idx && ax > 0.0f) ? ax : __builtin_huge_valf());
+    }
+  }
+  // a lane whose magnitudes are all the same (one element, or +-c throughout): the exact value is
+  // its maximum as well, so that a group of equal magnitudes has amax == amin on this side too
+  if (have && (as_u32(amax) & 0x7ffffff0u) == seen_bits && seen_bits != 0u) amax = res;
+  return have ? res : __builtin_huge_valf();
+}
+
 template <bool E5M2>
 __device__ __forceinline__ uint32_t pack4(const float (&q)[4]) {
   if constexpr (E5M2) {
@@ -452,6 +596,26 @@ __device__ __forceinline__ void quantize16(const Mode& md, const float (&x)[kEPL
     }
     c[d] = md.e5m2() ? pack4<true>(q) : pack4<false>(q);
   }
+}
+
+// Re-encode element idx of the lane from the value xv (the exact one, see apply_exact_min) and put
+// its code in place among the sixteen.  Rare path; same arithmetic as quantize16.
+template <class Mode>
+__device__ __forceinline__ void requantize_one(const Mode& md, float xv, const GroupQuant& gq, uint32_t idx,
+                                               uint32_t (&c)[4], float unit) {
+  float q;
+  if (md.expand()) {
+    const float m = hw_exp2(__builtin_fmaf(hw_log2(__builtin_fabsf(xv) * gq.inv_a), gq.k, fmt_log2_max(md)));
+    q = as_f32(as_u32(m) | (as_u32(xv) & 0x80000000u));
+  } else {
+    q = gq.inv_a != 0.0f ? (xv * unit) / gq.scale : 0.0f;
+  }
+  const uint32_t code = (md.e5m2() ? __builtin_amdgcn_cvt_pk_bf8_f32(q, q, 0u, false)
+                                   : __builtin_amdgcn_cvt_pk_fp8_f32(q, q, 0u, false)) & 0xffu;
+  const uint32_t sh = 8u * (idx & 3u);
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+    c[d] = (idx >> 2) == static_cast<uint32_t>(d) ? ((c[d] & ~(0xffu << sh)) | (code << sh)) : c[d];
 }
 
 }  // namespace

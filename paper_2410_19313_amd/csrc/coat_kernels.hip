@@ -280,10 +280,17 @@ int step_constants(const coat_adamw_hparams* hp, StepArgs& a, bool& generic) {
   a.one_minus_beta2 = 1.0f - hp->beta2;
   const double omb1 = a.one_minus_beta1, omb2 = a.one_minus_beta2;
   a.beta1_ratio = static_cast<float>(b1 / omb1);
+  a.m_ratio64 = b1 / omb1;
+  a.g_coef64 = (1.0 - b1) / omb1;
   a.beta2_ratio = static_cast<float>(b2 / omb2);
-  a.neg_lr_m = static_cast<float>(-static_cast<double>(hp->lr) * omb1 / bc1);
-  a.denom_scale = static_cast<float>(__builtin_sqrt(omb2 / bc2));
-  a.eps = hp->eps;
+  const double c = -static_cast<double>(hp->lr) * omb1 / bc1;      // m' / D times this is the update
+  if (c != 0.0) {
+    a.denom_mul = static_cast<float>(__builtin_sqrt(omb2 / bc2) / c);
+    a.denom_add = static_cast<float>(static_cast<double>(hp->eps) / c);
+  } else {                                                          // lr == 0: 1 / (0 * sqrt(v') + inf) = 0
+    a.denom_mul = 0.0f;
+    a.denom_add = __builtin_huge_valf();
+  }
   a.k_min = k_min; a.k_max = k_max;
   const bool expand = (hp->flags & COAT_FLAG_EXPAND) != 0;
   a.mode_m.e5 = (hp->flags & COAT_FLAG_M_E5M2) != 0;
@@ -315,7 +322,7 @@ int step_multi_impl(const void* plan_host, const void* plan_device, const coat_a
   const unsigned char* dev = static_cast<const unsigned char*>(plan_device);
   ma.base.w = nullptr; ma.base.wb = nullptr; ma.base.g = nullptr; ma.base.mq = nullptr; ma.base.ms = nullptr;
   ma.base.mk = nullptr; ma.base.vq = nullptr; ma.base.vs = nullptr; ma.base.vk = nullptr;
-  ma.base.n = 0; ma.base.n_full = 0; ma.base.n_groups = 0; ma.base.neg_lr_wd = 0.0f;
+  ma.base.n = 0; ma.base.n_full = 0; ma.base.n_groups = 0; ma.base.w_keep = 1.0f;
   ma.records = reinterpret_cast<const PlanRecord*>(dev + h.record_offset);
   ma.neg_lr = -static_cast<double>(hp->lr);
   ma.consts = reinterpret_cast<const StepConsts*>(consts_device);
@@ -347,7 +354,7 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
   a.w = w; a.wb = w_bf16; a.g = grad_bf16; a.mq = m_q; a.ms = static_cast<float*>(m_scale); a.mk = m_k; a.vq = v_q; a.vs = static_cast<float*>(v_scale); a.vk = v_k;
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(hp->group_size) - 1) / static_cast<uint64_t>(hp->group_size);
-  a.neg_lr_wd = static_cast<float>(-static_cast<double>(hp->lr) * static_cast<double>(hp->weight_decay));
+  a.w_keep = static_cast<float>(1.0 - static_cast<double>(hp->lr) * static_cast<double>(hp->weight_decay));
   return dispatch_step(a, hp->group_size, generic, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -402,8 +409,8 @@ int coat_step_consts_compute(const coat_adamw_hparams* hp, coat_step_consts* out
   bool generic = false;
   if (int rc = step_constants(hp, a, generic)) return rc;
   coat_step_consts c = {};
-  c.neg_lr_m = a.neg_lr_m;
-  c.denom_scale = a.denom_scale;
+  c.denom_mul = a.denom_mul;
+  c.denom_add = a.denom_add;
   c.neg_lr = -static_cast<double>(hp->lr);
   *out = c;
   return COAT_OK;

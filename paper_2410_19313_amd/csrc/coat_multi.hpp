@@ -55,12 +55,12 @@ constexpr uint64_t kPlanMagic = 0x324e4c5054414f43ull;     // "COATPLN2"
 constexpr int kPlanSpan = kGateSpan;                        // virtual chunks per record
 static_assert(kPlanSpan % kWavesPerBlock == 0, "a workgroup never straddles two records");
 
-// The three numbers of a step that change from one step to the next (learning-rate schedule, bias
+// The numbers of a step that change from one step to the next (learning-rate schedule, bias
 // corrections).  Normally they travel as kernel arguments; a caller that replays a captured graph
 // keeps them in device memory instead and rewrites these 32 bytes between replays.
 struct StepConsts {
-  float neg_lr_m;            // -lr * (1 - beta1) / (1 - beta1^t)
-  float denom_scale;         // sqrt((1 - beta2) / (1 - beta2^t))
+  float denom_mul;           // sqrt((1 - beta2) / (1 - beta2^t)) / c,  c = -lr (1 - beta1) / (1 - beta1^t)
+  float denom_add;           // eps / c   (lr == 0: denom_mul = 0, denom_add = +inf)
   double neg_lr;             // -lr
   uint64_t reserved[2];
 };
@@ -77,6 +77,7 @@ template <int G, bool GENERIC>
 __global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) {
   constexpr int kTables = GENERIC ? 2 : 1;
   __shared__ Log2Entry lut[256 * kTables];
+  __shared__ double frac[kExp2Frac];
   __shared__ f32x4 tile_w[kWavesPerBlock * kTileSlotsW];
   __shared__ u32x4 tile_g[kWavesPerBlock * kTileSlotsG];
   const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(ma.base), mv = ModesOf<GENERIC>::v(ma.base);
@@ -91,8 +92,8 @@ __global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) 
   StepArgs a = ma.base;
   double neg_lr = ma.neg_lr;
   if (ma.consts) {                                   // uniform: three scalar loads beside the record's
-    a.neg_lr_m = ma.consts->neg_lr_m;
-    a.denom_scale = ma.consts->denom_scale;
+    a.denom_mul = ma.consts->denom_mul;
+    a.denom_add = ma.consts->denom_add;
     neg_lr = ma.consts->neg_lr;
   }
   a.w = (float*)d.w; a.wb = (uint16_t*)d.wb; a.g = (const uint16_t*)d.g;
@@ -100,16 +101,17 @@ __global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) 
   a.vq = (uint8_t*)d.vq; a.vs = (float*)d.vs; a.vk = (float*)d.vk;
   a.n = d.n; a.n_full = d.n / kChunk;
   a.n_groups = (d.n + G - 1) / G;
-  a.neg_lr_wd = static_cast<float>(neg_lr * static_cast<double>(d.weight_decay));
+  a.w_keep = static_cast<float>(1.0 + neg_lr * static_cast<double>(d.weight_decay));
   const uint64_t chunk = d.chunk_base + (gc % kPlanSpan);
   const bool full = chunk < a.n_full;
   const bool tail = !full && chunk * kChunk < a.n;     // the tensor's ragged last chunk; beyond it: padding
 
   RawChunk r;
   if (full) issue_loads<G>(a, mm, mv, chunk, lane, r);
-  fill_lut<kTables>(lut);                            // every wavefront of the block reaches this
-  if (full) process_chunk<G>(a, mm, mv, lut, tiles, chunk, lane, r);
-  else if (tail) process_tail_chunk<G>(a, mm, mv, lut, lane);
+  fill_lut<kTables, kBlock>(lut, frac);              // every wavefront of the block reaches this
+  const StepTables tb = {lut, frac};
+  if (full) process_chunk<G>(a, mm, mv, tb, tiles, chunk, lane, r);
+  else if (tail) process_tail_chunk<G>(a, mm, mv, tb, reinterpret_cast<u32x4*>(tiles.w + 4 * lane + (lane >> 1)), lane);
 }
 
 }  // namespace

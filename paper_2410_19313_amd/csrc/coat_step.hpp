@@ -13,41 +13,54 @@ struct GroupMeta { float m_scale, m_k, v_scale, v_k; };
 
 // The arithmetic of the step on one lane's 16 elements, registers in, registers out:
 // w (in/out), g, codes (in/out), metadata (in/out).  Cross-lane traffic: the group reductions.
+// ls: the lane's old first-moment codes and its gradients once more, in LDS, for the one element
+// per lane that is looked up by a run-time index (exact_candidate).
 template <int G, class ModeM, class ModeV>
 __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, const ModeV& mv,
-                                          const Log2Entry* lut, float (&w)[kEPL], const float (&g)[kEPL],
-                                          uint32_t (&mc)[4], uint32_t (&vc)[4], GroupMeta& meta) {
+                                          const StepTables& tb, const LaneScratch& ls, float (&w)[kEPL],
+                                          const float (&g)[kEPL], uint32_t (&mc)[4], uint32_t (&vc)[4],
+                                          GroupMeta& meta) {
   constexpr int LPG = G / kEPL;                      // lanes per group
   float m[kEPL], v[kEPL];
+  const float m_inv_k = hw_rcp(meta.m_k);
   // beta/(1-beta) * (magnitude of the decoded unit)
-  const float m_fac = a.beta1_ratio * dequant16<true, true>(mm, lut, mc, meta.m_scale, meta.m_k, m);
-  const float v_fac = a.beta2_ratio * dequant16<false, false>(mv, lut, vc, meta.v_scale, meta.v_k, v);
+  const float m_fac = a.beta1_ratio * dequant16<true, false>(mm, tb.lut, mc, meta.m_scale, meta.m_k, m_inv_k, m);
+  const float v_fac = a.beta2_ratio * dequant16<false, false>(mv, tb.lut, vc, meta.v_scale, meta.v_k, hw_rcp(meta.v_k), v);
 
 #pragma unroll
   for (int e = 0; e < kEPL; ++e) {
     const float ge = g[e];
     const float m_t = __builtin_fmaf(m[e], m_fac, ge);              // m_t / (1 - beta1), Sec. 3
     const float v_t = __builtin_fmaf(ge, ge, v[e] * v_fac);         // v_t / (1 - beta2)
-    // Eq. (1) with the unquantized new moments; sqrt(v_t / bc2) = sqrt(v') * sqrt((1-beta2)/bc2)
-    const float denom = __builtin_fmaf(hw_sqrt(v_t), a.denom_scale, a.eps);
-    const float upd = m_t * hw_rcp(denom);
-    const float wt = __builtin_fmaf(upd, a.neg_lr_m, w[e]);
-    w[e] = __builtin_fmaf(w[e], a.neg_lr_wd, wt);
+    // Eq. (1) with the unquantized new moments, step size and bias corrections inside the denominator
+    const float denom = __builtin_fmaf(hw_sqrt(v_t), a.denom_mul, a.denom_add);
+    w[e] = __builtin_fmaf(w[e], a.w_keep, m_t * hw_rcp(denom));
     m[e] = m_t;
     v[e] = v_t;
   }
 
-  float m_max, m_min, v_max, v_min;
-  lane_extremes(m, m_max, m_min);
+  // Extremes.  The first moment's minimum fixes k and is where the update cancels: its element is
+  // recomputed exactly (exact_candidate), a long dependent chain beside which the second moment
+  // is quantized; the rare branches stay outside that stretch of straight-line code.
+  float m_max, v_max, v_min;
+  uint32_t m_key;
+  lane_extremes_keyed(m, g, m_max, m_key);
   lane_extremes(v, v_max, v_min);
-  m_max = group_allreduce<LPG, true>(m_max);
-  m_min = group_allreduce<LPG, false>(m_min);
+  float m_exact = exact_candidate(a, mm, tb, ls, m_key, meta.m_scale, meta.m_k, m_inv_k);
   v_max = group_allreduce<LPG, true>(v_max);
   v_min = group_allreduce<LPG, false>(v_min);
-  const GroupQuant qm = group_quant_params(mm, m_max, m_min, a.k_min, a.k_max, a.one_minus_beta1);
   const GroupQuant qv = group_quant_params(mv, v_max, v_min, a.k_min, a.k_max, a.one_minus_beta2);
-  quantize16<true>(mm, m, qm, mc, a.one_minus_beta1);
   quantize16<false>(mv, v, qv, vc, a.one_minus_beta2);
+  // (empty asm: holds the second moment's codes and the exact value at one point of the program, so
+  // that the compiler does not sink the quantization above past the rare branch that follows)
+  asm volatile("" : "+v"(vc[0]), "+v"(vc[1]), "+v"(vc[2]), "+v"(vc[3]), "+v"(m_exact));
+  bool m_replace;
+  float m_min = apply_exact_min(m_exact, m_key, m, m_max, m_replace);
+  m_max = group_allreduce<LPG, true>(m_max);
+  m_min = group_allreduce<LPG, false>(m_min);
+  const GroupQuant qm = group_quant_params(mm, m_max, m_min, a.k_min, a.k_max, a.one_minus_beta1);
+  quantize16<true>(mm, m, qm, mc, a.one_minus_beta1);
+  if (__builtin_expect(m_replace, 0)) requantize_one(mm, m_exact, qm, m_key & 15u, mc, a.one_minus_beta1);
   meta.m_scale = qm.scale; meta.m_k = qm.k;
   meta.v_scale = qv.scale; meta.v_k = qv.k;
 }
@@ -88,7 +101,7 @@ __device__ __forceinline__ void issue_loads(const StepArgs& a, const ModeM& mm, 
 // One full chunk: rows -> lane layout through the LDS tiles, the arithmetic, and back out.
 template <int G, class ModeM, class ModeV>
 __device__ __forceinline__ void process_chunk(const StepArgs& a, const ModeM& mm, const ModeV& mv,
-                                              const Log2Entry* lut, const StageTiles& tiles, uint64_t chunk,
+                                              const StepTables& tb, const StageTiles& tiles, uint64_t chunk,
                                               int lane, RawChunk& r) {
   constexpr int LPG = G / kEPL;
   const uint64_t cb = chunk * kChunk;
@@ -97,11 +110,18 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const ModeM& mm
   float w[kEPL], g[kEPL];
   tile_rows_to_lanes_bf16(tiles.g, lane, r.g, g);
   tile_rows_to_lanes(tiles.w, lane, r.w, w);
+  // The weights are in registers now and the fp32 tile is free until they are staged back: the
+  // first of this lane's own slots keeps the old first-moment codes; the gradient tile still holds
+  // the lane's 16 gradients as consecutive bf16.
+  f32x4* const own_w = tiles.w + 4 * lane + (lane >> 1);
+  *own_w = __builtin_bit_cast(f32x4, r.mc);          // same type as the tile's other accesses: kept in order
+  const LaneScratch ls = {reinterpret_cast<const uint8_t*>(own_w),
+                          reinterpret_cast<const lds_u16*>(tiles.g + 2 * lane + (lane >> 2))};
   uint32_t mc[4] = {r.mc.x, r.mc.y, r.mc.z, r.mc.w};
   uint32_t vc[4] = {r.vc.x, r.vc.y, r.vc.z, r.vc.w};
   GroupMeta meta = r.meta;
 
-  step_core<G>(a, mm, mv, lut, w, g, mc, vc, meta);
+  step_core<G>(a, mm, mv, tb, ls, w, g, mc, vc, meta);
 
   tile_lanes_to_rows_store(tiles.w, lane, w, a.w + cb);
   if (a.wb) tile_lanes_to_rows_store_bf16(tiles.g, lane, w, a.wb + cb);   // the gradient tile is free by now
@@ -166,6 +186,7 @@ template <int G, bool GENERIC>
 __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
   constexpr int kTables = GENERIC ? 2 : 1;
   __shared__ Log2Entry lut[256 * kTables];
+  __shared__ double frac[kExp2Frac];
   __shared__ f32x4 tile_w[kWavesPerBlock * kTileSlotsW];
   __shared__ u32x4 tile_g[kWavesPerBlock * kTileSlotsG];
   const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(a), mv = ModesOf<GENERIC>::v(a);
@@ -179,19 +200,21 @@ __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
   const bool have = chunk < a.n_full;
   if (have) chunk = gate_on_neighbourhood(a.mk, chunk, kChunk / G);
   if (have) issue_loads<G>(a, mm, mv, chunk, lane, r);
-  fill_lut<kTables>(lut);                            // every wavefront of the block reaches this
-  if (have) process_chunk<G>(a, mm, mv, lut, tiles, chunk, lane, r);
+  fill_lut<kTables, kBlock>(lut, frac);              // every wavefront of the block reaches this
+  const StepTables tb = {lut, frac};
+  if (have) process_chunk<G>(a, mm, mv, tb, tiles, chunk, lane, r);
   for (chunk += stride; chunk < a.n_full; chunk += stride) {
     issue_loads<G>(a, mm, mv, chunk, lane, r);
-    process_chunk<G>(a, mm, mv, lut, tiles, chunk, lane, r);
+    process_chunk<G>(a, mm, mv, tb, tiles, chunk, lane, r);
   }
 }
 
 // The ragged last chunk (n % 1024 elements): one wavefront, element-wise guarded accesses
-// straight into the lane layout.
+// straight into the lane layout.  slots: three 16-byte LDS slots of this lane's own (old codes,
+// gradients as bf16) for step_core's indexed lookup.
 template <int G, class ModeM, class ModeV>
 __device__ __forceinline__ void process_tail_chunk(const StepArgs& a, const ModeM& mm, const ModeV& mv,
-                                                   const Log2Entry* lut, int lane) {
+                                                   const StepTables& tb, u32x4* slots, int lane) {
   constexpr int LPG = G / kEPL;
   const uint64_t chunk = a.n_full;
   const uint64_t base = chunk * kChunk + static_cast<uint64_t>(lane) * kEPL;
@@ -208,7 +231,17 @@ __device__ __forceinline__ void process_tail_chunk(const StepArgs& a, const Mode
   meta.v_scale = gvalid ? load_scale(mv, a.vs, gidx) : 0.0f;
   meta.m_k = gvalid ? a.mk[gidx] : 1.0f;
   meta.v_k = gvalid ? a.vk[gidx] : 1.0f;
-  step_core<G>(a, mm, mv, lut, w, g, mc, vc, meta);
+  {
+    const u32x4 c = {mc[0], mc[1], mc[2], mc[3]};
+    slots[0] = c;
+    uint32_t gb[8];                                  // a bf16 gradient is the upper half of its fp32
+#pragma unroll
+    for (int i = 0; i < 8; ++i) gb[i] = (as_u32(g[2 * i + 1]) & 0xffff0000u) | (as_u32(g[2 * i]) >> 16);
+    const u32x4 g0 = {gb[0], gb[1], gb[2], gb[3]}, g1 = {gb[4], gb[5], gb[6], gb[7]};
+    slots[1] = g0; slots[2] = g1;
+  }
+  const LaneScratch ls = {reinterpret_cast<const uint8_t*>(slots), reinterpret_cast<const lds_u16*>(slots + 1)};
+  step_core<G>(a, mm, mv, tb, ls, w, g, mc, vc, meta);
   store_f32x16_guarded(a.w, base, a.n, w);
   if (a.wb) {
 #pragma unroll
@@ -230,9 +263,12 @@ template <int G, bool GENERIC>
 __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
   constexpr int kTables = GENERIC ? 2 : 1;
   __shared__ Log2Entry lut[256 * kTables];
-  fill_lut<kTables>(lut);
+  __shared__ double frac[kExp2Frac];
+  __shared__ u32x4 slots[3 * kWave];
+  fill_lut<kTables, kWave>(lut, frac);
+  const StepTables tb = {lut, frac};
   const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(a), mv = ModesOf<GENERIC>::v(a);
-  process_tail_chunk<G>(a, mm, mv, lut, threadIdx.x);
+  process_tail_chunk<G>(a, mm, mv, tb, slots + 3 * threadIdx.x, threadIdx.x);
 }
 
 }  // namespace

@@ -192,13 +192,17 @@ def test_step_consts_are_the_documented_formulas(coat):
     import struct
     for lr, b1, b2, t in ((3e-4, 0.9, 0.95, 1), (1e-3, 0.8, 0.999, 17), (0.0, 0.9, 0.95, 1000000)):
         hp = coat.make_hparams(lr=lr, beta1=b1, beta2=b2, step=t)
-        neg_lr_m, denom_scale, neg_lr = struct.unpack("<ffd", coat.coat_step_consts_compute(hp)[:16])
+        denom_mul, denom_add, neg_lr = struct.unpack("<ffd", coat.coat_step_consts_compute(hp)[:16])
         f = lambda x: struct.unpack("<f", struct.pack("<f", x))[0]      # what the fp32 fields hold
-        lr32, b1f, b2f = f(lr), f(b1), f(b2)
+        lr32, b1f, b2f, eps32 = f(lr), f(b1), f(b2), f(hp.eps)
         omb1, omb2 = f(1.0 - b1f), f(1.0 - b2f)
         assert neg_lr == -lr32
-        assert neg_lr_m == f(-lr32 * omb1 / (1.0 - b1f ** t))
-        assert denom_scale == f(math.sqrt(omb2 / (1.0 - b2f ** t)))
+        c = -lr32 * omb1 / (1.0 - b1f ** t)
+        if lr == 0.0:
+            assert denom_mul == 0.0 and denom_add == math.inf
+        else:
+            assert denom_mul == f(math.sqrt(omb2 / (1.0 - b2f ** t)) / c)
+            assert denom_add == f(eps32 / c)
     L = coat.lib()
     c = coat.StepConsts()
     assert L.coat_step_consts_compute(None, ctypes.byref(c)) == -1

@@ -115,7 +115,7 @@ def test_multi_against_oracle(coat, ref):
             w_r, st_r = ref_step(ref, h["w"], g, h["st"], G, t, weight_decay=h["wd"])
             st_g = {k: d[k].cpu().numpy() for k in h["st"]}
             check_step(ref, "multi tensor %d n=%d step %d" % (i, n, t), d["w"].cpu().numpy(), st_g, w_r, st_r, h["st"],
-                       g, G, w_old=h["w"], weight_decay=h["wd"])
+                       g, G, weight_decay=h["wd"])
             h["w"], h["st"] = w_r, st_r
 
 

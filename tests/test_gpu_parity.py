@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import synth_inputs as S
-from parity import EPS_DQ_M, assert_codes, assert_k, assert_scale, assert_w, eps_dq_v, k_tolerance
+from parity import allowed_mismatches, assert_codes, assert_k, assert_scale, assert_w, eps_dq, k_bar, k_tolerance
 
 pytestmark = pytest.mark.gpu
 
@@ -62,7 +62,8 @@ def ref_step(ref, w, g_bits, st, G, step, expand=True, **over):
 
 def new_moments(ref, st_old, g_bits, G, hp_over):
     """The fp64 new moments of the reference side and the bound dx on how far the fp32 side's
-    moments may be from them (see parity.py).  Used for tolerances only, never as expected values."""
+    moments may be from them (see parity.py).  Used for the k bar (ln R) and for the bound that
+    exception groups must obey, never as expected values."""
     kw = dict(HP)
     kw.update({k: v for k, v in hp_over.items() if k in HP})
     b1, b2 = float(np.float32(kw["beta1"])), float(np.float32(kw["beta2"]))
@@ -73,50 +74,51 @@ def new_moments(ref, st_old, g_bits, G, hp_over):
     g = S.bf16_bits_to_f32(g_bits).astype(np.float64)
     m_t = b1 * m_old + (1 - b1) * g
     v_t = b2 * v_old + (1 - b2) * g * g
-    dm = EPS_DQ_M * b1 * np.abs(m_old) + 2.0 ** -22 * np.abs(m_t)
-    ev = eps_dq_v(st_old["v_k"].astype(np.float64), 31.81 if v_e5 else 17.81)
+    em = eps_dq(st_old["m_k"].astype(np.float64), 31.81 if m_e5 else 17.81)
+    ev = eps_dq(st_old["v_k"].astype(np.float64), 31.81 if v_e5 else 17.81)
+    dm = np.repeat(em, G)[:n] * b1 * np.abs(m_old) + 2.0 ** -22 * np.abs(m_t)
     dv = np.repeat(ev, G)[:n] * b2 * v_old + 2.0 ** -22 * v_t
     return m_t, dm, v_t, dv
 
 
-def check_step(ref, tag, w_g, st_g, w_r, st_r, st_old, g_bits, G, expand=True, extra_w_tol=None, w_old=None,
-               **over):
-    """st_old, w_old: the state both sides started from (it conditions the tolerances)."""
-    if w_old is not None:
-        # the update term itself goes through sqrt, fma, rcp, mul, fma in fp32: <= 8 ulp of its size
-        upd = 8 * 2.0 ** -24 * np.abs(w_r.astype(np.float64) - w_old.astype(np.float64))
-        extra_w_tol = upd if extra_w_tol is None else extra_w_tol + upd
+def check_step(ref, tag, w_g, st_g, w_r, st_r, st_old, g_bits, G, expand=True, extra_w_tol=None, **over):
+    """The parity bar of tests/parity.py on one step.  st_old: the state both sides started from.
+    Returns per-moment statistics (mismatches, mismatches of more than a step, exception groups)."""
     k_min = over.get("k_min", 0.0) or 0.0625
     k_max = over.get("k_max", 0.0) or 1024.0
-    hp_only = {k: v for k, v in over.items() if k in HP}
-    assert_w(w_g, w_r, tag + " w", extra_w_tol)
+    stats = {"w": assert_w(w_g, w_r, tag + " w", extra_w_tol)}
     m_t, dm, v_t, dv = new_moments(ref, st_old, g_bits, G, over)
-    stats = {}
     for name, x, dx in (("m", m_t, dm), ("v", v_t, dv)):
-        tol, cl = k_tolerance(st_r[name + "_k"], x, dx, G, k_min, k_max)
+        x32 = x.astype(np.float32).astype(np.float64)     # both sides hold the new moments as fp32
+        bound, _ = k_tolerance(st_r[name + "_k"], x32, dx, G, k_min, k_max)
+        bar = k_bar(x32, G)
+        excused = None
         if over.get("bf16_scale"):
             # The stored scale is a rounding DECISION (the bf16 ceiling of amax/fmax).  Where the two
             # sides' amax (fp32 against fp64 arithmetic, within dx of each other) straddle a bf16
-            # boundary they may decide differently, by one bf16 step; such a group's codes are then
-            # all shifted and it is left to the irregular budget.  Everywhere else: EQUAL.
+            # boundary they may decide differently, by one bf16 step; such a group's k and codes then
+            # all shift and it is an exception group.  Everywhere else: EQUAL.
             near, lo16, hi16 = bf16_scale_candidates(x, dx, G, 57344.0 if over.get(name + "_e5m2") else 448.0)
             sg, sr = st_g[name + "_scale"], st_r[name + "_scale"]
             assert np.all(sg.view(np.uint32) & 0xFFFF == 0), tag + ": a stored scale is not a bf16 value"
             assert np.array_equal(sg[~near], sr[~near]), tag + " %s scale (bf16)" % name
             assert np.all((sg[near] == lo16[near]) | (sg[near] == hi16[near])), tag + " %s scale near a bf16 boundary" % name
-            other_scale = near & (sg != sr)
+            excused = near & (sg != sr)
+            assert int(excused.sum()) <= int(np.ceil(5e-3 * excused.size)), \
+                tag + ": %d of %d bf16 scale decisions differ" % (int(excused.sum()), excused.size)
+            bound = np.where(excused, np.inf, bound)
         else:
             assert_scale(st_g[name + "_scale"], st_r[name + "_scale"], tag + " %s scale" % name)
-            other_scale = np.zeros(tol.shape, dtype=bool)
         if not expand or over.get(name + "_plain"):
-            tol = np.full_like(tol, 1e-6)            # k is 1 on both sides
-            assert np.all(st_g[name + "_k"] == 1.0)
-        tol = np.where(other_scale, np.inf, tol)
-        in_bar = assert_k(st_g[name + "_k"], st_r[name + "_k"], tol, cl, tag + " %s k" % name)
-        n_bad, bad_regular, n_irregular = assert_codes(
-            ref, st_g[name + "_q"], st_r[name + "_q"], x, dx, st_r[name + "_scale"], st_r[name + "_k"], tol, G,
-            tag + " %s codes" % name, e5m2=bool(over.get(name + "_e5m2")))
-        stats[name] = dict(bad=n_bad, bad_regular=bad_regular, irregular=n_irregular, k_in_bar=in_bar)
+            assert np.all(st_g[name + "_k"] == 1.0) and np.all(st_r[name + "_k"] == 1.0)   # k is 1 on both sides
+        exc, kstats = assert_k(st_g[name + "_k"], st_r[name + "_k"], bar, tag + " %s k" % name, bound=bound, excused=excused)
+        n_bad, n_far = assert_codes(ref, st_g[name + "_q"], st_r[name + "_q"], G, tag + " %s codes" % name, exception=exc,
+                                    x_ref=x, dx=dx, scale_ref=st_r[name + "_scale"], k_ref=st_r[name + "_k"], bound=bound,
+                                    e5m2=bool(over.get(name + "_e5m2")), other_scale=excused)
+        stats[name] = dict(bad=n_bad, far=n_far, n=int(x.size), groups=int(bar.size), **kstats)
+    # the second moment has no cancellation and takes no exception: plain bar everywhere
+    if not over.get("bf16_scale"):
+        assert stats["v"]["k_out"] == 0, tag + ": v k outside the bar in %d groups" % stats["v"]["k_out"]
     assert np.all(st_g["v_q"] < 0x80), tag + ": a second-moment code carries a sign"
     return stats
 
@@ -140,21 +142,37 @@ def bf16_scale_candidates(x, dx, G, fmax):
     return lo16 != hi16, lo16, hi16
 
 
-def lockstep(coat, ref, n, G, grads_fn, steps, seed, expand=True, state=None, **over):
+TOTALS = {}     # tag -> accumulated statistics of the lock-step runs, printed at the end of the module
+
+
+def lockstep(coat, ref, n, G, grads_fn, steps, seed, expand=True, state=None, update_model=False, **over):
+    """update_model: add the fp32 error model of the update itself to the weight tolerance.  Only for
+    cells in which the second moment is stored WITHOUT expansion under log-normal gradients: its small
+    entries flush to zero, the update m / (sqrt(v) + eps) reaches 1e4 times the weight, and 1e-6 of
+    the weight is then below the fp32 resolution of the update."""
     w = S.weights(n, seed)
     st = state if state is not None else S.zero_state(n, G)
-    total_bad = 0
+    tot = dict(bad=0, far=0, k_out=0, elems=0, groups=0, w=0.0)
     for t in range(1, steps + 1):
         g = grads_fn(t)
         w_g, st_g, _ = gpu_step(coat, w, g, st, G, t, expand, **over)
-        st_old, w_old = st, w
+        st_old = st
         w, st = ref_step(ref, w, g, st, G, t, expand, **over)
+        extra = update_error_model(ref, st_old, g, G, t, **over) if update_model else None
         stats = check_step(ref, "n=%d G=%d step %d" % (n, G, t), w_g, st_g, w, st, st_old, g, G, expand,
-                           w_old=w_old, **over)
-        total_bad += stats["m"]["bad_regular"] + stats["v"]["bad_regular"]
-    # over the whole run the match rate must hold too
-    assert total_bad <= max(2, int(1e-4 * 2 * n * steps)), total_bad
-    return total_bad
+                           extra_w_tol=extra, **over)
+        for name in ("m", "v"):
+            tot["bad"] += stats[name]["bad"]; tot["far"] += stats[name]["far"]; tot["k_out"] += stats[name]["k_out"]
+            tot["elems"] += stats[name]["n"]; tot["groups"] += stats[name]["groups"]
+        tot["w"] = max(tot["w"], stats["w"])
+    # over the whole run the rate must hold too
+    assert tot["bad"] <= allowed_mismatches(tot["elems"]), tot
+    key = "G=%d%s" % (G, "" if not over and expand else " other")
+    acc = TOTALS.setdefault(key, dict(bad=0, far=0, k_out=0, elems=0, groups=0, w=0.0))
+    for k_ in ("bad", "far", "k_out", "elems", "groups"):
+        acc[k_] += tot[k_]
+    acc["w"] = max(acc["w"], tot["w"])
+    return tot
 
 
 def update_error_model(ref, st, g, G, t, m_e5m2=False, v_e5m2=False, **_):
@@ -163,7 +181,6 @@ def update_error_model(ref, st, g, G, t, m_e5m2=False, v_e5m2=False, **_):
     fp32 error of the update itself shows.  For u = (lr/bc1) m_t / (sqrt(v_t/bc2) + eps) the
     dequantized m carries EPS_DQ_M, the dequantized v eps_dq_v (halved by the square root), the
     remaining operations a few ulp."""
-    from parity import EPS_DQ_M, eps_dq_v
     n = st["m_q"].size
     b1, b2, lr, eps = (float(np.float32(HP[k])) for k in ("beta1", "beta2", "lr", "eps"))
     m_old = np.abs(ref.dequant_group(st["m_q"], st["m_scale"], st["m_k"], G, f64=True, e5m2=m_e5m2))
@@ -171,8 +188,9 @@ def update_error_model(ref, st, g, G, t, m_e5m2=False, v_e5m2=False, **_):
     gf = S.bf16_bits_to_f32(g).astype(np.float64)
     denom = np.sqrt((b2 * v_old + (1 - b2) * gf * gf) / (1 - b2 ** t)) + eps
     u_scale = lr / (1 - b1 ** t) * (b1 * m_old + (1 - b1) * np.abs(gf)) / denom
-    ev = np.repeat(eps_dq_v(st["v_k"].astype(np.float64), 31.81 if v_e5m2 else 17.81), G)[:n]
-    return u_scale * (EPS_DQ_M + 0.5 * ev + 6 * 2.0 ** -24)
+    em = np.repeat(eps_dq(st["m_k"].astype(np.float64), 31.81 if m_e5m2 else 17.81), G)[:n]
+    ev = np.repeat(eps_dq(st["v_k"].astype(np.float64), 31.81 if v_e5m2 else 17.81), G)[:n]
+    return u_scale * (em + 0.5 * ev + 6 * 2.0 ** -24)
 
 
 # --- dequantizer -------------------------------------------------------------------------------
@@ -227,16 +245,14 @@ def quant_inputs(kind, n, seed):
 
 
 def check_quant(ref, tag, x, G, gpu, expect, expand, e5m2=False):
-    """Standalone quantizer: both sides see the same fp32 inputs, so dx = 0 and the stated bar
-    applies as it stands (k: 1e-6, widened only by 1/ln R for groups narrower than e)."""
+    """Standalone quantizer: both sides see the same fp32 inputs, so the stated bar applies as it
+    stands and no exception is allowed (k: 1e-6, on ln R for groups narrower than e)."""
     (q_g, s_g, k_g), (q_r, s_r, k_r) = gpu, expect
-    zero = np.zeros(x.size)
-    tol, cl = k_tolerance(k_r, x, zero, G)
-    if not expand:
-        tol = np.full_like(tol, 1e-6)
     assert_scale(s_g, s_r, tag)
-    assert_k(k_g, k_r, tol, cl, tag)
-    assert_codes(ref, q_g, q_r, x, zero, s_r, k_r, tol, G, tag, e5m2=e5m2)
+    if not expand:
+        assert np.all(k_g == 1.0) and np.all(k_r == 1.0)
+    assert_k(k_g, k_r, k_bar(x, G), tag)
+    assert_codes(ref, q_g, q_r, G, tag, e5m2=e5m2)
 
 
 @pytest.mark.parametrize("G", GROUPS)
@@ -523,7 +539,8 @@ def test_step_format_grid(coat, ref, m_e5m2, m_plain, v_e5m2, v_plain):
 @pytest.mark.parametrize("G", [32, 64, 256, 512])
 def test_step_format_grid_other_group_sizes(coat, ref, G):
     n = 64 * 1024 + G + 1
-    lockstep(coat, ref, n, G, lambda t: S.grads_lognormal(n, 14, t), steps=2, seed=14, m_e5m2=True, v_plain=True)
+    lockstep(coat, ref, n, G, lambda t: S.grads_lognormal(n, 14, t), steps=2, seed=14, m_e5m2=True, v_plain=True,
+             update_model=True)
     lockstep(coat, ref, n, G, lambda t: S.grads_normal(n, 15, t), steps=2, seed=15, m_plain=True, v_e5m2=True)
 
 
@@ -639,6 +656,14 @@ def test_step_seeded_sweep_of_configurations(coat, ref):
             return S.grads_normal(n, seed, t, sigma=3e-5)
 
         try:
-            lockstep(coat, ref, n, G, grads, steps=2, seed=seed, **over)
+            lockstep(coat, ref, n, G, grads, steps=2, seed=seed, update_model=bool(kind == 1 and over.get("v_plain")), **over)
         except AssertionError as e:
             raise AssertionError("case %d: n=%d G=%d %r: %s" % (case, n, G, over, e))
+
+
+def test_zz_print_totals():
+    """Not a check: prints what the lock-step runs of this module measured (run with -s)."""
+    for key in sorted(TOTALS):
+        t = TOTALS[key]
+        print("%-12s mismatch rate %.2e (%d of %d), more than one step %d, k outside the bar %d of %d groups, w err/tol %.3f" % (
+            key, t["bad"] / max(1, t["elems"]), t["bad"], t["elems"], t["far"], t["k_out"], t["groups"], t["w"]))
