@@ -234,6 +234,24 @@ int coat_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G,
                           float* tensor_scale, uint8_t* q, void* hip_stream);
 
 /*
+ * coat_act_quant_tensor for callers that cannot hand over a workspace and cannot allocate one:
+ * code under graph capture, tight serving loops, harnesses that forbid allocation.  Same
+ * arguments, results and launches, but the COAT_ACT_WORKSPACE_FLOATS partial maxima live in a
+ * device array of the library's own (256 bytes per GPU, held until the process ends) instead of a
+ * caller buffer.  The call allocates and frees nothing, on the host or on the device; its first
+ * use on a device looks the array's address up (hipGetSymbolAddress) and caches it.
+ * Limits and errors: n above 2^46 elements returns COAT_ERR_SIZE (the scratch itself does not grow
+ * with n); COAT_ERR_LAUNCH if the runtime cannot name the current device or the array; the other
+ * codes as for coat_act_quant_tensor.  Every call on one GPU shares that GPU's array: calls that
+ * overlap in time on one GPU (two streams, two threads) race on it and must be serialized by the
+ * caller; calls in stream order are fine, nothing needs clearing between them (every entry that
+ * is read has been written by the same call).
+ */
+int coat_act_quant_tensor_static(const uint16_t* x_bf16, uint64_t n, int32_t G,
+                                 float* group_amax, float* tensor_amax, float* tensor_scale,
+                                 uint8_t* q, void* hip_stream);
+
+/*
  * The same with stage 1 already done: group_amax [ceil(n/G)] is an INPUT (non-negative group
  * maxima), as when the operator that produced x emitted them in its epilogue, which is how the
  * paper removes the cost of the first stage (Sec. 5.2).  Runs stage 2 and the quantization.

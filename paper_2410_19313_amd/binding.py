@@ -20,6 +20,7 @@ ACT_WORKSPACE_FLOATS = 64
 
 EXPORTS = ("coat_fp8_adamw_step", "coat_fp8_adamw_step_bf16w", "coat_quant_group", "coat_dequant_group",
            "coat_act_quant_group", "coat_act_quant_tensor", "coat_act_quant_tensor_from_group_amax",
+           "coat_act_quant_tensor_static",
            "coat_multi_plan_bytes", "coat_multi_plan_build", "coat_fp8_adamw_step_multi", "coat_shard_range",
            "coat_step_consts_compute", "coat_fp8_adamw_step_multi_consts",
            "coat_strerror", "coat_version")
@@ -110,6 +111,8 @@ def lib():
         for f in (L.coat_act_quant_tensor, L.coat_act_quant_tensor_from_group_amax):
             f.restype = ctypes.c_int
             f.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
+        L.coat_act_quant_tensor_static.restype = ctypes.c_int
+        L.coat_act_quant_tensor_static.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, vp, vp, vp, vp, vp]
         L.coat_multi_plan_bytes.restype = ctypes.c_size_t
         L.coat_multi_plan_bytes.argtypes = [ctypes.POINTER(TensorDesc), ctypes.c_uint32]
         L.coat_multi_plan_build.restype = ctypes.c_int
@@ -257,6 +260,20 @@ def coat_act_quant_tensor(x_bf16, G: int = 16, out=None, workspace=None):
                                        _dev_ptr(workspace, torch.float32, ACT_WORKSPACE_FLOATS),
                                        _dev_ptr(tamax, torch.float32, 1), _dev_ptr(tscale, torch.float32, 1),
                                        _dev_ptr(q, torch.uint8, n), _stream()))
+    return q, tscale, gamax, tamax
+
+
+def coat_act_quant_tensor_static(x_bf16, G: int, out):
+    """coat_act_quant_tensor without a workspace (the library's own static device scratch) and without
+    any allocation: `out` = (codes uint8 [n], tensor_scale fp32 [1], group_amax fp32 [ng], tensor_amax fp32 [1])
+    must be given."""
+    import torch
+    n = x_bf16.numel()
+    ng = n_groups(n, G) if G > 0 else 0
+    q, tscale, gamax, tamax = out
+    _check(lib().coat_act_quant_tensor_static(_dev_ptr(x_bf16, torch.bfloat16), n, G, _dev_ptr(gamax, torch.float32, ng),
+                                              _dev_ptr(tamax, torch.float32, 1), _dev_ptr(tscale, torch.float32, 1),
+                                              _dev_ptr(q, torch.uint8, n), _stream()))
     return q, tscale, gamax, tamax
 
 

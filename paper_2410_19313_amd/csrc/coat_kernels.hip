@@ -25,7 +25,15 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "coat.h"
+
+// Scratch of coat_act_quant_tensor_static: the partial maxima of Group Scaling's second stage in a
+// device array of the library's own instead of a caller workspace.  Every GPU holds its own copy
+// of the array at its own address (looked up once per device, below); the name itself is only a
+// host-side handle and is never passed to a kernel.
+static __device__ __align__(256) float g_act_scratch[COAT_ACT_WORKSPACE_FLOATS];
 
 #include "coat_device.hpp"
 #include "coat_step.hpp"
@@ -199,6 +207,22 @@ int launch_act_tensor_rest(ActArgs a, hipStream_t s) {
   hipLaunchKernelGGL((act_tensor_amax_kernel<kStage2Block, kStage2Unroll>), dim3(grid), dim3(kStage2Block), 0, s, a);
   if (int rc = launch_status()) return rc;
   return launch_act_quant<16, true>(a, s);   // the group size plays no part once the scale is per tensor
+}
+
+constexpr int kMaxDevices = 64;
+std::atomic<float*> g_act_scratch_ptr[kMaxDevices];
+
+// The device address of g_act_scratch on the current device (nullptr on failure).  The first call
+// on a device asks the runtime for it; later calls read the cached pointer.  Nothing is allocated.
+float* act_scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  float* p = g_act_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  void* sym = nullptr;
+  if (hipGetSymbolAddress(&sym, HIP_SYMBOL(g_act_scratch)) != hipSuccess || !sym) return nullptr;
+  g_act_scratch_ptr[dev].store(static_cast<float*>(sym), std::memory_order_release);   // same value from any thread
+  return static_cast<float*>(sym);
 }
 
 int act_quant_tensor_impl(const uint16_t* x, uint64_t n, int32_t G, float* group_amax, bool have_group_amax,
@@ -497,6 +521,14 @@ int coat_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G, float* 
   return act_quant_tensor_impl(x_bf16, n, G, group_amax, false, workspace, tensor_amax, tensor_scale, q, hip_stream);
 }
 
+int coat_act_quant_tensor_static(const uint16_t* x_bf16, uint64_t n, int32_t G, float* group_amax,
+                                 float* tensor_amax, float* tensor_scale, uint8_t* q, void* hip_stream) {
+  if (n > kMaxElements) return COAT_ERR_SIZE;       // before anything else: this variant's size limit
+  float* scratch = act_scratch_on_current_device();
+  if (!scratch) return COAT_ERR_LAUNCH;
+  return act_quant_tensor_impl(x_bf16, n, G, group_amax, false, scratch, tensor_amax, tensor_scale, q, hip_stream);
+}
+
 int coat_act_quant_tensor_from_group_amax(const uint16_t* x_bf16, uint64_t n, int32_t G,
                                           const float* group_amax, float* workspace, float* tensor_amax,
                                           float* tensor_scale, uint8_t* q, void* hip_stream) {
@@ -513,7 +545,7 @@ const char* coat_strerror(int code) {
     case COAT_ERR_STEP: return "step must be >= 1";
     case COAT_ERR_HPARAM: return "hyper-parameter or flag is non-finite, unsupported or out of its domain";
     case COAT_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
-    case COAT_ERR_SIZE: return "n is too large, or the plan buffer is too small";
+    case COAT_ERR_SIZE: return "n is too large (above 2^46 elements), or the plan buffer is too small";
     case COAT_ERR_PLAN: return "the plan blob is not one that coat_multi_plan_build wrote";
   }
   return "unknown error code";
