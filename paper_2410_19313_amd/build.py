@@ -13,7 +13,9 @@ LIB = os.path.join(_HERE, "libcoat.so")
 
 # packed fp32 instructions are switched off on purpose (some forms have misbehaved on this
 # hardware); the option belongs to the device pass, the host pass only warns about it
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+# -fno-strict-aliasing: the kernels view one LDS tile as fp32 rows, as packed bf16 rows and as bytes;
+# the order of those accesses must follow the program, not the types
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-strict-aliasing",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wno-unused-command-line-argument"]
 

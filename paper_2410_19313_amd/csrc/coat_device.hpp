@@ -2,6 +2,8 @@
 // Part of the one translation unit coat_kernels.hip (included from there, in this order).
 #pragma once
 
+#include <type_traits>
+
 namespace {
 
 constexpr int kWave = 64;                 // lanes per wavefront
@@ -133,25 +135,28 @@ __device__ __forceinline__ float hw_rcp(float x) { return __builtin_amdgcn_rcpf(
 __device__ __forceinline__ float hw_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
 
 template <int CTRL>
-__device__ __forceinline__ float dpp_mov(float x) {
-  return __builtin_bit_cast(
-      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t x) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), CTRL, 0xf, 0xf, true));
 }
 
 // Butterfly all-reduce over LPG adjacent lanes (LPG = lanes per group, a power of two <= 32).
 //   xor 1 / xor 2 : quad_perm, lanes 4..7 / 8..15 : row_half_mirror / row_mirror (after the
 //   previous steps every lane of the smaller block already holds that block's result),
 //   xor 16 : ds_swizzle inside 32 lanes.
+// The values reduced are magnitudes (non-negative, +inf for "none"), so their bit patterns order
+// like the numbers and the reduction runs on unsigned integers: no canonicalization of the
+// cross-lane operand before every floating-point min/max.  A NaN (pattern above +inf) wins a
+// maximum and loses a minimum.
 template <int LPG, bool IS_MAX>
-__device__ __forceinline__ float group_allreduce(float x) {
-  auto op = [](float a, float b) { return IS_MAX ? __builtin_fmaxf(a, b) : __builtin_fminf(a, b); };
+__device__ __forceinline__ float group_allreduce(float xf) {
+  auto op = [](uint32_t a, uint32_t b) { return IS_MAX ? (a > b ? a : b) : (a < b ? a : b); };
+  uint32_t x = as_u32(xf);
   if constexpr (LPG >= 2) x = op(x, dpp_mov<0xB1>(x));    // quad_perm:[1,0,3,2]
   if constexpr (LPG >= 4) x = op(x, dpp_mov<0x4E>(x));    // quad_perm:[2,3,0,1]
   if constexpr (LPG >= 8) x = op(x, dpp_mov<0x141>(x));   // row_half_mirror
   if constexpr (LPG >= 16) x = op(x, dpp_mov<0x140>(x));  // row_mirror
-  if constexpr (LPG >= 32)
-    x = op(x, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, x), 0x401F)));
-  return x;
+  if constexpr (LPG >= 32) x = op(x, static_cast<uint32_t>(__builtin_amdgcn_ds_swizzle(static_cast<int>(x), 0x401F)));
+  return as_f32(x);
 }
 
 // Compile-time streaming hints (bit mask): 1 load codes, 2 store codes, 4 load gradients,
@@ -218,7 +223,7 @@ __device__ __forceinline__ void store_codes16_guarded(uint8_t* p, uint64_t base,
 constexpr int kTileSlotsW = 256 + 32;   // fp32 tile: 1024 elements + padding, in 16-byte slots
 constexpr int kTileSlotsG = 128 + 16;   // bf16 tile
 
-struct StageTiles { f32x4* w; u32x4* g; };
+struct StageTiles { f32x4* w; u32x4* g; u32x4* codes; };   // codes: 16 bytes per lane (see LaneScratch)
 
 // rows (memory side) -> 16 consecutive fp32 per lane, through the wavefront's fp32 tile
 __device__ __forceinline__ void tile_rows_to_lanes(f32x4* tile, int lane, const f32x4 (&rows)[4], float (&x)[kEPL]) {
@@ -291,28 +296,44 @@ __device__ __forceinline__ void tile_lanes_to_rows_store_bf16(u32x4* tile, int l
 constexpr int kExp2Frac = kExp2FracSize;
 struct StepTables { const Log2Entry* lut; const double* frac; };
 
-// THREADS: the (compile-time) size of the block.  Every load is issued before the first LDS write,
-// so that the fill costs ONE trip to memory, which the chunk's own loads (issued before it) hide;
-// a loop that waits per iteration adds a full memory latency to the wavefront's life each time
-// (measured on the 7B set: about +0.6 ms per extra trip).
+// The fill in two halves.  THREADS: the (compile-time) size of the block.
+//   fill_issue : every thread's table entries are requested (all loads before any LDS write, so
+//                the fill costs ONE trip to memory; a loop that waits per iteration adds a full
+//                memory latency to the wavefront's life each time, about +0.6 ms per extra trip on
+//                the 7B set);
+//   fill_commit: the entries go to LDS and the block synchronizes.
+// A step kernel calls fill_issue FIRST, then its admission gate and its chunk's loads, then
+// fill_commit: loads return in order, so the table entries arrive before the bulk data and the
+// block's one barrier is over while the bulk data is still in flight; each wavefront then starts
+// on its own data as soon as that arrives.  With the table requested after the bulk loads every
+// wavefront of the block waited at the barrier for the slowest one's data (7B set: 15.2 -> 14.9 ms).
 template <int TABLES, int THREADS>
-__device__ __forceinline__ void fill_lut(Log2Entry* lut, double* frac) {
-  constexpr int kLutIters = (256 * TABLES + THREADS - 1) / THREADS, kFracIters = (kExp2Frac + THREADS - 1) / THREADS;
+struct FillRegs {
+  static constexpr int kLutIters = (256 * TABLES + THREADS - 1) / THREADS, kFracIters = (kExp2Frac + THREADS - 1) / THREADS;
   Log2Entry e[kLutIters];
   double f[kFracIters];
+};
+template <int TABLES, int THREADS>
+__device__ __forceinline__ void fill_issue(FillRegs<TABLES, THREADS>& fr) {
 #pragma unroll
-  for (int r = 0; r < kLutIters; ++r) {
+  for (int r = 0; r < FillRegs<TABLES, THREADS>::kLutIters; ++r) {
     const int i = threadIdx.x + r * THREADS;
-    e[r] = kLog2Code[(i >> 8) & 1][i & 127];
+    fr.e[r] = kLog2Code[(i >> 8) & 1][i & 127];
   }
 #pragma unroll
-  for (int r = 0; r < kFracIters; ++r) f[r] = kExp2Frac512[(threadIdx.x + r * THREADS) & (kExp2Frac - 1)];
+  for (int r = 0; r < FillRegs<TABLES, THREADS>::kFracIters; ++r)
+    fr.f[r] = kExp2Frac512[(threadIdx.x + r * THREADS) & (kExp2Frac - 1)];
+  __builtin_amdgcn_sched_barrier(0);                 // the requests stay ahead of what follows
+}
+template <int TABLES, int THREADS>
+__device__ __forceinline__ void fill_commit(const FillRegs<TABLES, THREADS>& fr, Log2Entry* lut, double* frac) {
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int r = 0; r < kLutIters; ++r)
-    if (threadIdx.x + r * THREADS < 256 * TABLES) lut[threadIdx.x + r * THREADS] = e[r];
+  for (int r = 0; r < FillRegs<TABLES, THREADS>::kLutIters; ++r)
+    if (threadIdx.x + r * THREADS < 256 * TABLES) lut[threadIdx.x + r * THREADS] = fr.e[r];
 #pragma unroll
-  for (int r = 0; r < kFracIters; ++r)
-    if (threadIdx.x + r * THREADS < kExp2Frac) frac[threadIdx.x + r * THREADS] = f[r];
+  for (int r = 0; r < FillRegs<TABLES, THREADS>::kFracIters; ++r)
+    if (threadIdx.x + r * THREADS < kExp2Frac) frac[threadIdx.x + r * THREADS] = fr.f[r];
   __syncthreads();
 }
 
@@ -466,26 +487,13 @@ __device__ __forceinline__ void lane_extremes_keyed(const float (&x)[kEPL], cons
     lo = 0xffffffffu;
 #pragma unroll
     for (int e = 0; e < kEPL; ++e) {
-      const uint32_t mag = as_u32(x[e]) & mask;
+      const uint32_t mag = as_u32(x[e]) & 0x7ffffff0u;   // (the literal, not `mask`: no sharing with the fast path's and_or)
       const bool cancelled = (as_u32(g[e]) & 0x7fffffffu) != 0u;
       const uint32_t key = (mag || cancelled) ? (mag | static_cast<uint32_t>(e)) : 0xffffffffu;
       lo = key < lo ? key : lo;
     }
   }
   amax = hi; min_key = lo;
-}
-
-// 2^t in fp64 for t <= 0: 512 t = i + r with i an integer and |r| <= 1/2, so that
-// 2^t = 2^(i >> 9) * 2^((i & 511) / 512) * 2^(r / 512): the middle factor from the table in LDS,
-// the last one as 1 + x + x^2/2 + x^3/6 in x = r ln2 / 512 (|x| < 6.8e-4, remainder below 1e-14).
-// Below -1100 the result is 0 either way.
-__device__ __forceinline__ double exp2_f64(const double* frac, double t) {
-  const double u = __builtin_fmax(t, -1100.0) * static_cast<double>(kExp2Frac);
-  const double ni = __builtin_rint(u);
-  const double x = (u - ni) * (0x1.62e42fefa39efp-1 / kExp2Frac);
-  const int i = static_cast<int>(ni);
-  const double p = __builtin_fma(x, __builtin_fma(x, __builtin_fma(x, 1.0 / 6.0, 0.5), 1.0), 1.0);
-  return __builtin_ldexp(frac[i & (kExp2Frac - 1)] * p, i >> 9);
 }
 
 // Where the lane keeps, in LDS, what the refinement below looks up by a run-time index: the 16
@@ -499,33 +507,88 @@ struct LaneScratch { const uint8_t* codes; const lds_u16* g; };
 // which fixes the exponent k = log2(range) / log2(amax / amin) (Sec. 4.2) and through k every code
 // of the group.  In fp32 that element keeps the absolute error of the dequantized m but not its
 // size, so the fp32 pass only NAMES the candidate (min_key, from lane_extremes_keyed) and this
-// function recomputes that one element exactly: the table logarithm as hi + lo, 1/k by a Newton
-// step, 2^(L/k) by exp2_f64, the update as one fp64 fma, rounded to fp32 at the end.  About fifty
-// instructions per lane (three per element), and no branch: the caller places independent work
-// (the second moment's quantization) beside this long dependent chain.
+// chain recomputes that one element exactly: the table logarithm as hi + lo, 1/k by a Newton
+// step, 2^(L/k) by the table-based exponential (see exp2 steps below), the update as one fp64 fma,
+// rounded to fp32 at the end.  About fifty instructions per lane (three per element), every one
+// depending on the one before and three of them LDS look-ups, so it is cut into seventeen STEPS:
+// the caller puts independent work (the second moment's quantization, one element per step) between
+// them and fences every step with a scheduling barrier; left to itself the compiler runs the chain
+// back to back and each wavefront lives longer by its whole latency, which costs the 7B step about
+// 4 % (measured).
+//   exp2 for t <= 0:  512 t = i + r with i an integer and |r| <= 1/2, so that
+//   2^t = 2^(i >> 9) * 2^((i & 511) / 512) * 2^(r / 512): the middle factor from the table in LDS,
+//   the last one as 1 + x + x^2/2 + x^3/6 in x = r ln2 / 512 (|x| < 6.8e-4, remainder below 1e-14);
+//   below -1100 the result is 0 either way.
 template <class Mode>
-__device__ __forceinline__ float exact_candidate(const StepArgs& a, const Mode& md, const StepTables& tb,
-                                                 const LaneScratch& ls, uint32_t min_key, float scale, float k,
-                                                 float inv_k) {
-  const uint32_t idx = min_key & 15u;                // also in range when there is no candidate (~0)
-  const uint32_t code = ls.codes[idx];
-  const float g = as_f32(static_cast<uint32_t>(ls.g[idx]) << 16);
-  double old_m;                                      // the element's old first moment, exactly
-  if (md.expand()) {
-    const Log2Entry l = tb.lut[(md.e5m2() ? 256u : 0u) + code];
-    const double kd = static_cast<double>(k);
-    double r = static_cast<double>(inv_k);
-    r = __builtin_fma(r, __builtin_fma(-kd, r, 1.0), r);
-    const double t = (static_cast<double>(l.hi) + static_cast<double>(l.lo)) * r;
-    const double mag = exp2_f64(tb.frac, t) * (static_cast<double>(fmt_max(md)) * static_cast<double>(scale));
-    // the code's sign bit goes onto the (non-negative) magnitude
-    old_m = __builtin_bit_cast(double, __builtin_bit_cast(uint64_t, mag) | (static_cast<uint64_t>(code & 0x80u) << 56));
-  } else {
-    // stored without expansion: the decoded code times the scale, exact in fp64
-    const float c = md.e5m2() ? __builtin_amdgcn_cvt_f32_bf8(code, 0) : __builtin_amdgcn_cvt_f32_fp8(code, 0);
-    old_m = static_cast<double>(c) * static_cast<double>(scale);
+struct ExactChain {
+  static constexpr int kSteps = 16;                  // step<0> .. step<16>
+  const StepArgs& a; const Mode& md; const StepTables& tb; const LaneScratch& ls;
+  uint32_t idx, code;
+  float g32, scale, k, inv_k, exact;
+  Log2Entry l;
+  double r, amag, gd, t, u, ni, x, p, fr, q;
+  int i;
+
+  __device__ __forceinline__ ExactChain(const StepArgs& a_, const Mode& md_, const StepTables& tb_, const LaneScratch& ls_,
+                                        uint32_t min_key, float scale_, float k_, float inv_k_)
+      : a(a_), md(md_), tb(tb_), ls(ls_), idx(min_key & 15u), scale(scale_), k(k_), inv_k(inv_k_) {}
+  // (idx is in range also when there is no candidate, min_key == ~0)
+
+  template <int S>
+  __device__ __forceinline__ void step() {
+    if (md.expand()) {
+      if constexpr (S == 0) {                        // the two look-ups by index go out first; 1/k meanwhile
+        code = ls.codes[idx];
+        g32 = as_f32(static_cast<uint32_t>(ls.g[idx]) << 16);
+        const double kd = static_cast<double>(k);
+        const double r0 = static_cast<double>(inv_k);
+        r = __builtin_fma(r0, __builtin_fma(-kd, r0, 1.0), r0);
+        amag = static_cast<double>(fmt_max(md)) * static_cast<double>(scale);
+      }
+      if constexpr (S == 1) l = tb.lut[(md.e5m2() ? 256u : 0u) + code];
+      if constexpr (S == 2) gd = a.g_coef64 * static_cast<double>(g32);
+      if constexpr (S == 3) t = (static_cast<double>(l.hi) + static_cast<double>(l.lo)) * r;
+      if constexpr (S == 4) u = __builtin_fmax(t, -1100.0) * static_cast<double>(kExp2Frac);
+      if constexpr (S == 5) ni = __builtin_rint(u);
+      if constexpr (S == 6) {
+        x = (u - ni) * (0x1.62e42fefa39efp-1 / kExp2Frac);
+        i = static_cast<int>(ni);
+        fr = tb.frac[i & (kExp2Frac - 1)];
+      }
+      if constexpr (S == 7) p = __builtin_fma(x, 1.0 / 6.0, 0.5);
+      if constexpr (S == 8) p = __builtin_fma(x, p, 1.0);
+      if constexpr (S == 9) p = __builtin_fma(x, p, 1.0);
+      if constexpr (S == 11) q = fr * p;
+      if constexpr (S == 12) q = __builtin_ldexp(q, i >> 9);
+      if constexpr (S == 13) {                       // the code's sign bit goes onto the (non-negative) magnitude
+        const double mag = q * amag;
+        q = __builtin_bit_cast(double, __builtin_bit_cast(uint64_t, mag) | (static_cast<uint64_t>(code & 0x80u) << 56));
+      }
+      if constexpr (S == 14) q = __builtin_fma(a.m_ratio64, q, gd);
+      if constexpr (S == 15) exact = static_cast<float>(q);
+    } else {
+      // stored without expansion: the decoded code times the scale, exact in fp64
+      if constexpr (S == 0) {
+        code = ls.codes[idx];
+        g32 = as_f32(static_cast<uint32_t>(ls.g[idx]) << 16);
+      }
+      if constexpr (S == 2) {
+        const float c = md.e5m2() ? __builtin_amdgcn_cvt_f32_bf8(code, 0) : __builtin_amdgcn_cvt_f32_fp8(code, 0);
+        q = static_cast<double>(c) * static_cast<double>(scale);
+        gd = a.g_coef64 * static_cast<double>(g32);
+      }
+      if constexpr (S == 4) q = __builtin_fma(a.m_ratio64, q, gd);
+      if constexpr (S == 6) exact = static_cast<float>(q);
+    }
   }
-  return static_cast<float>(__builtin_fma(a.m_ratio64, old_m, a.g_coef64 * static_cast<double>(g)));
+};
+
+template <int S, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (S < N) {
+    f(std::integral_constant<int, S>{});
+    static_for<S + 1, N>(f);
+  }
 }
 
 // The lane's smallest non-zero |m_t| given the exact value of its candidate.  Where the fp32 value
@@ -578,22 +641,21 @@ __device__ __forceinline__ uint32_t pack4(const float (&q)[4]) {
 //                  quantizer of Sec. 3, kept as a baseline; it is not tuned)
 // SIGNED = false (second moment, never negative) skips the sign transfer.
 template <bool SIGNED, class Mode>
+__device__ __forceinline__ float quantize_value(const Mode& md, float xv, const GroupQuant& gq, float unit) {
+  if (md.expand()) {
+    const float m = hw_exp2(__builtin_fmaf(hw_log2(__builtin_fabsf(xv) * gq.inv_a), gq.k, fmt_log2_max(md)));
+    return SIGNED ? as_f32(as_u32(m) | (as_u32(xv) & 0x80000000u)) : m;
+  }
+  return gq.inv_a != 0.0f ? (xv * unit) / gq.scale : 0.0f;      // IEEE division: correctly rounded
+}
+template <bool SIGNED, class Mode>
 __device__ __forceinline__ void quantize16(const Mode& md, const float (&x)[kEPL], const GroupQuant& gq,
                                            uint32_t (&c)[4], float unit) {
-  const float log2_fmax = fmt_log2_max(md);
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
     float q[4];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const float xv = x[4 * d + b];
-      if (md.expand()) {
-        const float m = hw_exp2(__builtin_fmaf(hw_log2(__builtin_fabsf(xv) * gq.inv_a), gq.k, log2_fmax));
-        q[b] = SIGNED ? as_f32(as_u32(m) | (as_u32(xv) & 0x80000000u)) : m;
-      } else {
-        q[b] = gq.inv_a != 0.0f ? (xv * unit) / gq.scale : 0.0f;   // IEEE division: correctly rounded
-      }
-    }
+    for (int b = 0; b < 4; ++b) q[b] = quantize_value<SIGNED>(md, x[4 * d + b], gq, unit);
     c[d] = md.e5m2() ? pack4<true>(q) : pack4<false>(q);
   }
 }

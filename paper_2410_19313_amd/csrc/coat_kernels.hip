@@ -85,8 +85,8 @@ int launch_status() { return hipGetLastError() == hipSuccess ? COAT_OK : COAT_ER
 // flight per CU the HBM controllers see longer same-page runs; three blocks rather than two cover
 // the wait at the admission gate (measured on the 7B set, with the gate: 2 blocks 15.6 ms,
 // 3 blocks 15.05, 4 blocks 15.3, 5 blocks 15.35; without it: 15.85, 16.1, 16.3, 16.3).
-constexpr size_t kStepLdsPad = 16 * 1024;
-constexpr size_t kMultiLdsPad = 16 * 1024;
+constexpr size_t kStepLdsPad = 12 * 1024;
+constexpr size_t kMultiLdsPad = 12 * 1024;
 
 template <int G, bool GENERIC>
 int launch_step(const StepArgs& a, hipStream_t s) {

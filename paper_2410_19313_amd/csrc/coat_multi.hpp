@@ -80,12 +80,15 @@ __global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) 
   __shared__ double frac[kExp2Frac];
   __shared__ f32x4 tile_w[kWavesPerBlock * kTileSlotsW];
   __shared__ u32x4 tile_g[kWavesPerBlock * kTileSlotsG];
+  __shared__ u32x4 code_scratch[kBlock];
   const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(ma.base), mv = ModesOf<GENERIC>::v(ma.base);
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const StageTiles tiles = {tile_w + wv * kTileSlotsW, tile_g + wv * kTileSlotsG};
+  const StageTiles tiles = {tile_w + wv * kTileSlotsW, tile_g + wv * kTileSlotsG, code_scratch + wv * kWave};
   // the grid covers the virtual chunk space exactly (kPlanSpan / kWavesPerBlock workgroups per record)
   const uint64_t gc = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv;
+  FillRegs<kTables, kBlock> fill;
+  fill_issue(fill);                                  // the table entries are requested before anything else
 
   // everything here is uniform over the wavefront (gc is), so the record travels in scalar registers
   const PlanRecordDev& d = reinterpret_cast<const PlanRecordDev*>(ma.records)[gc / kPlanSpan];
@@ -108,7 +111,7 @@ __global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) 
 
   RawChunk r;
   if (full) issue_loads<G>(a, mm, mv, chunk, lane, r);
-  fill_lut<kTables, kBlock>(lut, frac);              // every wavefront of the block reaches this
+  fill_commit(fill, lut, frac);                      // every wavefront of the block reaches this
   const StepTables tb = {lut, frac};
   if (full) process_chunk<G>(a, mm, mv, tb, tiles, chunk, lane, r);
   else if (tail) process_tail_chunk<G>(a, mm, mv, tb, reinterpret_cast<u32x4*>(tiles.w + 4 * lane + (lane >> 1)), lane);

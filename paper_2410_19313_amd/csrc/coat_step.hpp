@@ -11,21 +11,33 @@ namespace {
 // Per-group metadata of one chunk as one lane sees it (its own group's words).
 struct GroupMeta { float m_scale, m_k, v_scale, v_k; };
 
-// The arithmetic of the step on one lane's 16 elements, registers in, registers out:
-// w (in/out), g, codes (in/out), metadata (in/out).  Cross-lane traffic: the group reductions.
+// The arithmetic of the step on one lane's 16 elements.  Codes and metadata come in registers;
+// everything else goes through `io`, in the order in which the data is needed and produced, so
+// that a wavefront works on what has arrived and sends off what is final while the rest is still
+// in flight or being computed (the loads are issued in that order too: codes, metadata,
+// weights, gradients):
+//   the moments are dequantized from codes and metadata alone;
+//   io.gradients(g), io.old_weights(w) then hand over the lane's 16 gradients and weights;
+//   io.weights(w) takes the new weights right after the update, before the moments are requantized;
+//   io.second(codes, scale, k) after the second moment's quantization, io.first(...) at the end.
+// (With all stores issued at the end, behind the rare branches of the requantization, the 7B step
+// took 3 % longer.)  Cross-lane traffic: the group reductions.
 // ls: the lane's old first-moment codes and its gradients once more, in LDS, for the one element
-// per lane that is looked up by a run-time index (exact_candidate).
-template <int G, class ModeM, class ModeV>
+// per lane that is looked up by a run-time index (ExactChain).
+template <int G, class ModeM, class ModeV, class IO>
 __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, const ModeV& mv,
-                                          const StepTables& tb, const LaneScratch& ls, float (&w)[kEPL],
-                                          const float (&g)[kEPL], uint32_t (&mc)[4], uint32_t (&vc)[4],
-                                          GroupMeta& meta) {
+                                          const StepTables& tb, const LaneScratch& ls, uint32_t (&mc)[4],
+                                          uint32_t (&vc)[4], const GroupMeta& meta, IO&& io) {
   constexpr int LPG = G / kEPL;                      // lanes per group
   float m[kEPL], v[kEPL];
   const float m_inv_k = hw_rcp(meta.m_k);
   // beta/(1-beta) * (magnitude of the decoded unit)
   const float m_fac = a.beta1_ratio * dequant16<true, false>(mm, tb.lut, mc, meta.m_scale, meta.m_k, m_inv_k, m);
   const float v_fac = a.beta2_ratio * dequant16<false, false>(mv, tb.lut, vc, meta.v_scale, meta.v_k, hw_rcp(meta.v_k), v);
+  __builtin_amdgcn_sched_barrier(0);
+  float w[kEPL], g[kEPL];
+  io.gradients(g);
+  io.old_weights(w);
 
 #pragma unroll
   for (int e = 0; e < kEPL; ++e) {
@@ -38,22 +50,41 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, co
     m[e] = m_t;
     v[e] = v_t;
   }
+  io.weights(w);
+  __builtin_amdgcn_sched_barrier(0);
 
   // Extremes.  The first moment's minimum fixes k and is where the update cancels: its element is
-  // recomputed exactly (exact_candidate), a long dependent chain beside which the second moment
-  // is quantized; the rare branches stay outside that stretch of straight-line code.
+  // recomputed exactly (ExactChain), a long chain of dependent steps; the second moment's
+  // quantization, which does not depend on it, is dealt out between the steps, one element each,
+  // and a scheduling barrier after every step keeps the compiler from undoing the interleave.
+  // The rare branches stay outside this stretch of straight-line code.
   float m_max, v_max, v_min;
   uint32_t m_key;
   lane_extremes_keyed(m, g, m_max, m_key);
   lane_extremes(v, v_max, v_min);
-  float m_exact = exact_candidate(a, mm, tb, ls, m_key, meta.m_scale, meta.m_k, m_inv_k);
+  ExactChain<ModeM> chain(a, mm, tb, ls, m_key, meta.m_scale, meta.m_k, m_inv_k);
+  chain.template step<0>();
   v_max = group_allreduce<LPG, true>(v_max);
   v_min = group_allreduce<LPG, false>(v_min);
   const GroupQuant qv = group_quant_params(mv, v_max, v_min, a.k_min, a.k_max, a.one_minus_beta2);
-  quantize16<false>(mv, v, qv, vc, a.one_minus_beta2);
+  __builtin_amdgcn_sched_barrier(0);
+  float vq[kEPL];
+  static_for<0, kEPL>([&](auto e) {
+    chain.template step<e.value + 1>();
+    vq[e.value] = quantize_value<false>(mv, v[e.value], qv, a.one_minus_beta2);
+    __builtin_amdgcn_sched_barrier(0);
+  });
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const float q4[4] = {vq[4 * d], vq[4 * d + 1], vq[4 * d + 2], vq[4 * d + 3]};
+    vc[d] = mv.e5m2() ? pack4<true>(q4) : pack4<false>(q4);
+  }
+  float m_exact = chain.exact;
   // (empty asm: holds the second moment's codes and the exact value at one point of the program, so
   // that the compiler does not sink the quantization above past the rare branch that follows)
   asm volatile("" : "+v"(vc[0]), "+v"(vc[1]), "+v"(vc[2]), "+v"(vc[3]), "+v"(m_exact));
+  io.second(vc, qv.scale, qv.k);
+  __builtin_amdgcn_sched_barrier(0);
   bool m_replace;
   float m_min = apply_exact_min(m_exact, m_key, m, m_max, m_replace);
   m_max = group_allreduce<LPG, true>(m_max);
@@ -61,8 +92,7 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, co
   const GroupQuant qm = group_quant_params(mm, m_max, m_min, a.k_min, a.k_max, a.one_minus_beta1);
   quantize16<true>(mm, m, qm, mc, a.one_minus_beta1);
   if (__builtin_expect(m_replace, 0)) requantize_one(mm, m_exact, qm, m_key & 15u, mc, a.one_minus_beta1);
-  meta.m_scale = qm.scale; meta.m_k = qm.k;
-  meta.v_scale = qv.scale; meta.v_k = qv.k;
+  io.first(mc, qm.scale, qm.k);
 }
 
 // What one lane fetches for one full chunk, still in the layout of the memory side: weight and
@@ -86,16 +116,19 @@ __device__ __forceinline__ void issue_loads(const StepArgs& a, const ModeM& mm, 
   const u32x4* mq = reinterpret_cast<const u32x4*>(a.mq + cb);
   const u32x4* vq = reinterpret_cast<const u32x4*>(a.vq + cb);
   const int gl = lane / LPG;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) r.w[j] = ldg<8>(wq + 64 * j + lane);
-#pragma unroll
-  for (int j = 0; j < 2; ++j) r.g[j] = ldg<4>(gq + 64 * j + lane);
+  // in the order of use (loads return in order): codes and metadata feed the dequantization,
+  // which runs while the weights and the gradients are still on their way (measured on the 7B set,
+  // same run: this order 14.84 ms; metadata, codes, gradients, weights 14.94; weights first 14.91)
   r.mc = ldg<1>(mq + lane);
   r.vc = ldg<1>(vq + lane);
   r.meta.m_scale = load_scale_full_chunk(mm, a.ms, gb, gl);
   r.meta.v_scale = load_scale_full_chunk(mv, a.vs, gb, gl);
   r.meta.m_k = a.mk[gb + gl];          // written as 1 (and ignored) by a moment stored without expansion
   r.meta.v_k = a.vk[gb + gl];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) r.w[j] = ldg<8>(wq + 64 * j + lane);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) r.g[j] = ldg<4>(gq + 64 * j + lane);
 }
 
 // One full chunk: rows -> lane layout through the LDS tiles, the arithmetic, and back out.
@@ -107,32 +140,37 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const ModeM& mm
   const uint64_t cb = chunk * kChunk;
   const uint64_t gb = chunk * (kChunk / G);
 
-  float w[kEPL], g[kEPL];
-  tile_rows_to_lanes_bf16(tiles.g, lane, r.g, g);
-  tile_rows_to_lanes(tiles.w, lane, r.w, w);
-  // The weights are in registers now and the fp32 tile is free until they are staged back: the
-  // first of this lane's own slots keeps the old first-moment codes; the gradient tile still holds
-  // the lane's 16 gradients as consecutive bf16.
-  f32x4* const own_w = tiles.w + 4 * lane + (lane >> 1);
-  *own_w = __builtin_bit_cast(f32x4, r.mc);          // same type as the tile's other accesses: kept in order
-  const LaneScratch ls = {reinterpret_cast<const uint8_t*>(own_w),
+  // For the look-up by index: the old first-moment codes go into the lane's slot of the code
+  // scratch; the gradient tile will hold the lane's 16 gradients as consecutive bf16.
+  tiles.codes[lane] = r.mc;
+  const LaneScratch ls = {reinterpret_cast<const uint8_t*>(tiles.codes + lane),
                           reinterpret_cast<const lds_u16*>(tiles.g + 2 * lane + (lane >> 2))};
   uint32_t mc[4] = {r.mc.x, r.mc.y, r.mc.z, r.mc.w};
   uint32_t vc[4] = {r.vc.x, r.vc.y, r.vc.z, r.vc.w};
-  GroupMeta meta = r.meta;
 
-  step_core<G>(a, mm, mv, tb, ls, w, g, mc, vc, meta);
-
-  tile_lanes_to_rows_store(tiles.w, lane, w, a.w + cb);
-  if (a.wb) tile_lanes_to_rows_store_bf16(tiles.g, lane, w, a.wb + cb);   // the gradient tile is free by now
-  const u32x4 mo = {mc[0], mc[1], mc[2], mc[3]}, vo = {vc[0], vc[1], vc[2], vc[3]};
-  stg<2>(reinterpret_cast<u32x4*>(a.mq + cb) + lane, mo);
-  stg<2>(reinterpret_cast<u32x4*>(a.vq + cb) + lane, vo);
-  if ((lane % LPG) == 0) {
-    const int gl = lane / LPG;
-    store_scale(mm, a.ms, gb + gl, meta.m_scale); a.mk[gb + gl] = meta.m_k;
-    store_scale(mv, a.vs, gb + gl, meta.v_scale); a.vk[gb + gl] = meta.v_k;
-  }
+  struct IO {
+    const StepArgs& a; const ModeM& mm; const ModeV& mv; const StageTiles& tiles; const RawChunk& r;
+    uint64_t cb, gb; int lane;
+    __device__ __forceinline__ void gradients(float (&g)[kEPL]) const { tile_rows_to_lanes_bf16(tiles.g, lane, r.g, g); }
+    __device__ __forceinline__ void old_weights(float (&w)[kEPL]) const { tile_rows_to_lanes(tiles.w, lane, r.w, w); }
+    __device__ __forceinline__ void weights(const float (&wn)[kEPL]) const {
+      tile_lanes_to_rows_store(tiles.w, lane, wn, a.w + cb);
+      // (the bf16 copy is staged through the fp32 tile too: its rows are in registers by now, and the
+      // gradient tile is still needed)
+      if (a.wb) tile_lanes_to_rows_store_bf16(reinterpret_cast<u32x4*>(tiles.w), lane, wn, a.wb + cb);
+    }
+    __device__ __forceinline__ void second(const uint32_t (&c)[4], float scale, float k) const {
+      const u32x4 o = {c[0], c[1], c[2], c[3]};
+      stg<2>(reinterpret_cast<u32x4*>(a.vq + cb) + lane, o);
+      if ((lane % LPG) == 0) { store_scale(mv, a.vs, gb + lane / LPG, scale); a.vk[gb + lane / LPG] = k; }
+    }
+    __device__ __forceinline__ void first(const uint32_t (&c)[4], float scale, float k) const {
+      const u32x4 o = {c[0], c[1], c[2], c[3]};
+      stg<2>(reinterpret_cast<u32x4*>(a.mq + cb) + lane, o);
+      if ((lane % LPG) == 0) { store_scale(mm, a.ms, gb + lane / LPG, scale); a.mk[gb + lane / LPG] = k; }
+    }
+  };
+  step_core<G>(a, mm, mv, tb, ls, mc, vc, r.meta, IO{a, mm, mv, tiles, r, cb, gb, lane});
 }
 
 // Admission gate.  Before a wavefront issues the loads of its chunk it reads ONE word that all
@@ -178,8 +216,8 @@ template <> struct ModesOf<true> {
 };
 
 // Main kernel: one chunk per wavefront (the loop only runs again for buffers with more chunks
-// than the grid has wavefronts).  The first chunk's loads are issued before the block fills its
-// lookup table, so the table's latency hides behind them.
+// than the grid has wavefronts).  Order of the memory requests: the block's table entries, the
+// gate's probe, the chunk's loads (see fill_issue).
 // GENERIC = false: both moments E4M3 with expansion (the method as the paper runs it);
 // GENERIC = true : per-moment format and expansion read from the arguments (Table 1's grid).
 template <int G, bool GENERIC>
@@ -189,18 +227,21 @@ __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
   __shared__ double frac[kExp2Frac];
   __shared__ f32x4 tile_w[kWavesPerBlock * kTileSlotsW];
   __shared__ u32x4 tile_g[kWavesPerBlock * kTileSlotsG];
+  __shared__ u32x4 code_scratch[kBlock];
   const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(a), mv = ModesOf<GENERIC>::v(a);
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wavefront-uniform
-  const StageTiles tiles = {tile_w + wv * kTileSlotsW, tile_g + wv * kTileSlotsG};
+  const StageTiles tiles = {tile_w + wv * kTileSlotsW, tile_g + wv * kTileSlotsG, code_scratch + wv * kWave};
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
   uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv;
 
   RawChunk r;
   const bool have = chunk < a.n_full;
+  FillRegs<kTables, kBlock> fill;
+  fill_issue(fill);
   if (have) chunk = gate_on_neighbourhood(a.mk, chunk, kChunk / G);
   if (have) issue_loads<G>(a, mm, mv, chunk, lane, r);
-  fill_lut<kTables, kBlock>(lut, frac);              // every wavefront of the block reaches this
+  fill_commit(fill, lut, frac);                      // every wavefront of the block reaches this
   const StepTables tb = {lut, frac};
   if (have) process_chunk<G>(a, mm, mv, tb, tiles, chunk, lane, r);
   for (chunk += stride; chunk < a.n_full; chunk += stride) {
@@ -241,22 +282,38 @@ __device__ __forceinline__ void process_tail_chunk(const StepArgs& a, const Mode
     slots[1] = g0; slots[2] = g1;
   }
   const LaneScratch ls = {reinterpret_cast<const uint8_t*>(slots), reinterpret_cast<const lds_u16*>(slots + 1)};
-  step_core<G>(a, mm, mv, tb, ls, w, g, mc, vc, meta);
-  store_f32x16_guarded(a.w, base, a.n, w);
-  if (a.wb) {
+  struct IO {
+    const StepArgs& a; const ModeM& mm; const ModeV& mv; const float (&w0)[kEPL]; const float (&g0)[kEPL];
+    uint64_t base, gidx; bool store_meta;
+    __device__ __forceinline__ void gradients(float (&g)[kEPL]) const {
 #pragma unroll
-    for (int e = 0; e < kEPL; e += 2) {
-      const uint32_t pr = pack_bf16(w[e], w[e + 1]);
-      if (base + e < a.n) a.wb[base + e] = static_cast<uint16_t>(pr);
-      if (base + e + 1 < a.n) a.wb[base + e + 1] = static_cast<uint16_t>(pr >> 16);
+      for (int e = 0; e < kEPL; ++e) g[e] = g0[e];
     }
-  }
-  store_codes16_guarded(a.mq, base, a.n, mc);
-  store_codes16_guarded(a.vq, base, a.n, vc);
-  if (gvalid && (lane % LPG) == 0) {
-    store_scale(mm, a.ms, gidx, meta.m_scale); a.mk[gidx] = meta.m_k;
-    store_scale(mv, a.vs, gidx, meta.v_scale); a.vk[gidx] = meta.v_k;
-  }
+    __device__ __forceinline__ void old_weights(float (&w)[kEPL]) const {
+#pragma unroll
+      for (int e = 0; e < kEPL; ++e) w[e] = w0[e];
+    }
+    __device__ __forceinline__ void weights(const float (&wn)[kEPL]) const {
+      store_f32x16_guarded(a.w, base, a.n, wn);
+      if (a.wb) {
+#pragma unroll
+        for (int e = 0; e < kEPL; e += 2) {
+          const uint32_t pr = pack_bf16(wn[e], wn[e + 1]);
+          if (base + e < a.n) a.wb[base + e] = static_cast<uint16_t>(pr);
+          if (base + e + 1 < a.n) a.wb[base + e + 1] = static_cast<uint16_t>(pr >> 16);
+        }
+      }
+    }
+    __device__ __forceinline__ void second(const uint32_t (&c)[4], float scale, float k) const {
+      store_codes16_guarded(a.vq, base, a.n, c);
+      if (store_meta) { store_scale(mv, a.vs, gidx, scale); a.vk[gidx] = k; }
+    }
+    __device__ __forceinline__ void first(const uint32_t (&c)[4], float scale, float k) const {
+      store_codes16_guarded(a.mq, base, a.n, c);
+      if (store_meta) { store_scale(mm, a.ms, gidx, scale); a.mk[gidx] = k; }
+    }
+  };
+  step_core<G>(a, mm, mv, tb, ls, mc, vc, meta, IO{a, mm, mv, w, g, base, gidx, gvalid && (lane % LPG) == 0});
 }
 
 template <int G, bool GENERIC>
@@ -265,7 +322,9 @@ __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
   __shared__ Log2Entry lut[256 * kTables];
   __shared__ double frac[kExp2Frac];
   __shared__ u32x4 slots[3 * kWave];
-  fill_lut<kTables, kWave>(lut, frac);
+  FillRegs<kTables, kWave> fill;
+  fill_issue(fill);
+  fill_commit(fill, lut, frac);
   const StepTables tb = {lut, frac};
   const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(a), mv = ModesOf<GENERIC>::v(a);
   process_tail_chunk<G>(a, mm, mv, tb, slots + 3 * threadIdx.x, threadIdx.x);
