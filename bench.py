@@ -8,6 +8,12 @@ Llama-2-7B-sized parameter set (6.74e9 fp32 master weights, bf16 gradients, E4M3
 group size 128).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--group-size 128]
+
+The default run times the 7B set (the headline: `value`, `roofline`, `cpu_baseline`) and then the
+other configurations of the report -- cfg1, cfg2, cfg4 at G = 32 / 128 / 512, cfg5 -- each at its
+stated length, the sub-millisecond ones also at steady clocks, each beside the copy control (the
+step's bytes in the step's access pattern without its arithmetic); they land in `configs` of the
+same JSON line.  `--only` times the chosen workload alone.
 """
 from __future__ import annotations
 
@@ -160,22 +166,150 @@ def bench_act(args, C, S, torch, dev, gen):
                      "avg_call_us": avg_s * 1e6, "algorithmic_bytes_per_call": algo}}))
 
 
+WORKLOAD_TEXT = {"cfg1": "one 1024x1024 weight", "cfg2": "one Llama-2-7B decoder layer",
+                 "cfg3": "full Llama-2-7B-sized parameter set", "cfg4": "one Llama-2-7B decoder layer",
+                 "cfg5": "full Llama-2-13B-sized parameter set"}
+
+
+def run_step_config(C, S, torch, dev, workload, G, grads_kind, warmup, steps, steady_steps=0, copy_control=True,
+                    flags=None, emit_bf16=False, multi=False, multi_small=0):
+    """Allocate one workload, run `warmup` untimed and `steps` timed steps (HIP events around every
+    launch, on the launch stream), optionally `steady_steps` more as one back-to-back block, then the
+    copy control on the same buffers.  Returns the figures of one row of the report."""
+    import time
+    flags = flags or {}
+    shapes_of = "cfg2" if workload == "cfg4" else workload
+    n = S.workload_numel(shapes_of)
+    assert n % G == 0
+    gen = S.torch_generator(dev, 0)
+    w = S.torch_weights(n, dev, gen)
+    st = S.torch_zero_state(n, G, dev)
+    if flags.get("bf16_scale"):
+        st["m_scale"], st["v_scale"] = st["m_scale"].to(torch.bfloat16), st["v_scale"].to(torch.bfloat16)
+    # two gradient buffers, alternated, so that consecutive steps do not see identical input
+    if grads_kind == "normal":
+        mask = S.torch_outlier_group_mask(n // G, dev, gen, 0.01 if workload != "cfg1" else 0.0)
+        grads = [S.torch_grads_normal(n, dev, gen, G=G, outlier_mask=mask) for _ in range(2)]
+        del mask
+    else:
+        grads = [S.torch_grads_lognormal(n, dev, gen) for _ in range(2)]
+    w_bf16 = torch.empty(n, dtype=torch.bfloat16, device=dev) if emit_bf16 else None
+    torch.cuda.synchronize()
+
+    plans = None
+    if multi:
+        # the same flat buffers seen as the workload's separate tensors (the model's weight matrices, plus
+        # multi_small extra 4096-element vectors standing in for norm weights), one plan per gradient buffer
+        sizes = [r * c for r, c in S.workload_shapes(shapes_of)]
+        for _ in range(multi_small):
+            big = max(range(len(sizes)), key=lambda i: sizes[i])
+            sizes[big] -= 4096
+            sizes.append(4096)
+        assert sum(sizes) == n and all(x % G == 0 for x in sizes)
+        plans = []
+        for gbuf in grads:
+            tens, off = [], 0
+            for x in sizes:
+                d = dict(w=w[off:off + x], grad=gbuf[off:off + x], weight_decay=HP["weight_decay"])
+                for k in ("m_q", "v_q"):
+                    d[k] = st[k][off:off + x]
+                for k in ("m_scale", "m_k", "v_scale", "v_k"):
+                    d[k] = st[k][off // G:(off + x) // G]
+                if emit_bf16:
+                    d["w_bf16"] = w_bf16[off:off + x]
+                tens.append(d)
+                off += x
+            plans.append(C.MultiPlan(tens, G))
+
+    def step(t):
+        hp = C.make_hparams(step=t, group_size=G, **flags, **HP)
+        if plans is not None:
+            C.coat_fp8_adamw_step_multi(plans[t & 1], hp)
+        elif emit_bf16:
+            C.coat_fp8_adamw_step_bf16w(w, w_bf16, grads[t & 1], st["m_q"], st["m_scale"], st["m_k"],
+                                        st["v_q"], st["v_scale"], st["v_k"], hp)
+        else:
+            C.coat_fp8_adamw_step(w, grads[t & 1], st["m_q"], st["m_scale"], st["m_k"],
+                                  st["v_q"], st["v_scale"], st["v_k"], hp)
+
+    t = 0
+    for _ in range(warmup):
+        t += 1
+        step(t)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        t += 1
+        ev[i][0].record()
+        step(t)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    launch_ms = [a.elapsed_time(b) for a, b in ev]
+    avg_launch_s = sum(launch_ms) / len(launch_ms) / 1e3
+    per_param = bytes_per_param(G) + (2.0 if emit_bf16 else 0.0) - (8.0 / G if flags.get("bf16_scale") else 0.0)
+    algo_bytes = per_param * n
+    row = dict(workload=workload, params=n, group_size=G, grads=grads_kind, steps=steps, warmup=warmup,
+               ms_per_step=wall / steps * 1e3, avg_launch_ms=avg_launch_s * 1e3, params_per_s=n * steps / wall,
+               hbm_gbs=algo_bytes / avg_launch_s / 1e9, algorithmic_bytes_per_launch=algo_bytes)
+    row["frac_of_peak"] = row["hbm_gbs"] / HBM_PEAK_GBS
+    if steady_steps:
+        # a sub-millisecond kernel needs tens of milliseconds of back-to-back launches before the part
+        # reaches its steady clocks: the same step, `steady_steps` launches timed as one block
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steady_steps):
+            t += 1
+            step(t)
+        e1.record()
+        torch.cuda.synchronize()
+        s_ms = e0.elapsed_time(e1) / steady_steps
+        row["steady"] = dict(steps=steady_steps, ms_per_step=s_ms, hbm_gbs=algo_bytes / s_ms / 1e6,
+                             frac_of_peak=algo_bytes / s_ms / 1e6 / HBM_PEAK_GBS)
+    finite = bool(torch.isfinite(w[:: max(1, n // (1 << 20))]).all().item())
+    if not finite:
+        sys.exit("bench.py: non-finite weights after the timed steps (%s)" % workload)
+    if copy_control and not (emit_bf16 or flags.get("bf16_scale")):
+        # the copy control: the same bytes in the same access pattern without the arithmetic (destroys the state)
+        reps = max(steps, 5) + steady_steps
+        for i in range(2):
+            C.coat_bench_copy_control(w, grads[i & 1], st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"], G)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            C.coat_bench_copy_control(w, grads[i & 1], st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"], G)
+        e1.record()
+        torch.cuda.synchronize()
+        c_gbs = algo_bytes / (e0.elapsed_time(e1) / reps) / 1e6
+        best = row["steady"]["hbm_gbs"] if steady_steps else row["hbm_gbs"]
+        row["copy_control_gbs"] = c_gbs
+        row["frac_of_copy_control"] = best / c_gbs
+    row["tensors"] = len(plans[0].tensors) if plans else 1
+    del w, st, grads, plans, w_bf16
+    torch.cuda.empty_cache()
+    return row
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg5"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
+                    help="cfg4 = the cfg2 shapes under log-normal gradients (use with --group-size 32/128/512)")
     ap.add_argument("--group-size", type=int, default=128)
-    ap.add_argument("--grads", default="normal", choices=["normal", "lognormal"])
+    ap.add_argument("--grads", default=None, choices=["normal", "lognormal"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", action="store_true",
+                    help="time the chosen workload alone (no report on the other configurations, no copy control)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27)
     ap.add_argument("--cpu-steps", type=int, default=24)
     ap.add_argument("--op", default="step",
-                    choices=["step", "quant", "dequant", "act_group", "act_tensor", "act_tensor_pre"],
+                    choices=["step", "quant", "dequant", "act_group", "act_tensor", "act_tensor_pre", "copy_control"],
                     help="step: the fused optimizer step (the metric); quant / dequant: its two halves alone; "
                          "act_*: the activation quantizers (per group, per tensor with Group Scaling, the same "
-                         "with the group maxima supplied)")
+                         "with the group maxima supplied); copy_control: the step's traffic without its arithmetic")
     ap.add_argument("--act-tokens", type=int, default=8192, help="rows of the activation tensor (hidden = 4096)")
     ap.add_argument("--act-group-size", type=int, default=16)
     ap.add_argument("--act-buffers", type=int, default=8)
@@ -215,126 +349,84 @@ def main():
                           "bytes_read_per_launch": src.numel() * 4, "bytes_written_per_launch": src.numel() * 4}))
         return
     G = args.group_size
-    n = S.workload_numel(args.workload)
+    grads_kind = args.grads or ("lognormal" if args.workload == "cfg4" else "normal")
+    n = S.workload_numel("cfg2" if args.workload == "cfg4" else args.workload)
     assert n % G == 0
 
     gen = S.torch_generator(dev, 0)
     if args.op.startswith("act_"):
         bench_act(args, C, S, torch, dev, gen)
         return
-    if args.op != "step":
+    if args.op in ("quant", "dequant"):
         bench_half(args, C, S, torch, dev, gen, n, G)
         return
-    w = S.torch_weights(n, dev, gen)
-    st = S.torch_zero_state(n, G, dev)
-    if args.bf16_scale:
-        st["m_scale"], st["v_scale"] = st["m_scale"].to(torch.bfloat16), st["v_scale"].to(torch.bfloat16)
-    mask = S.torch_outlier_group_mask(n // G, dev, gen, 0.01)
-    # two gradient buffers, alternated, so that consecutive steps do not see identical input
-    if args.grads == "normal":
-        grads = [S.torch_grads_normal(n, dev, gen, G=G, outlier_mask=mask) for _ in range(2)]
-    else:
-        grads = [S.torch_grads_lognormal(n, dev, gen) for _ in range(2)]
-    del mask
-    w_bf16 = torch.empty(n, dtype=torch.bfloat16, device=dev) if args.emit_bf16 else None
-    torch.cuda.synchronize()
+    if args.op == "copy_control":
+        # the control alone, under the step's report format (for profiles)
+        w = S.torch_weights(n, dev, gen)
+        st = S.torch_zero_state(n, G, dev)
+        g = S.torch_grads_normal(n, dev, gen, G=G)
+        for _ in range(args.warmup):
+            C.coat_bench_copy_control(w, g, st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"], G)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            C.coat_bench_copy_control(w, g, st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"], G)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        print(json.dumps({"op": "copy_control", "workload": args.workload, "params": n, "group_size": G, "ms_per_launch": ms,
+                          "hbm_gbs": bytes_per_param(G) * n / ms / 1e6, "frac_of_peak": bytes_per_param(G) * n / ms / 1e6 / HBM_PEAK_GBS}))
+        return
 
-    plans = None
-    if args.multi:
-        # the same flat buffers seen as the workload's separate tensors (the model's weight matrices, plus
-        # --multi-small extra 4096-element vectors standing in for norm weights), one plan per gradient buffer
-        sizes = [r * c for r, c in S.workload_shapes(args.workload)]
-        for _ in range(args.multi_small):
-            big = max(range(len(sizes)), key=lambda i: sizes[i])
-            sizes[big] -= 4096
-            sizes.append(4096)
-        assert sum(sizes) == n and all(x % G == 0 for x in sizes)
-        plans = []
-        for gbuf in grads:
-            tens, off = [], 0
-            for x in sizes:
-                d = dict(w=w[off:off + x], grad=gbuf[off:off + x], weight_decay=HP["weight_decay"])
-                for k in ("m_q", "v_q"):
-                    d[k] = st[k][off:off + x]
-                for k in ("m_scale", "m_k", "v_scale", "v_k"):
-                    d[k] = st[k][off // G:(off + x) // G]
-                if args.emit_bf16:
-                    d["w_bf16"] = w_bf16[off:off + x]
-                tens.append(d)
-                off += x
-            plans.append(C.MultiPlan(tens, G))
-
-    def step(t):
-        hp = C.make_hparams(step=t, group_size=G, m_e5m2=args.m_e5m2, v_e5m2=args.v_e5m2,
-                            m_plain=args.m_plain, v_plain=args.v_plain, bf16_scale=args.bf16_scale, **HP)
-        if plans is not None:
-            C.coat_fp8_adamw_step_multi(plans[t & 1], hp)
-        elif args.emit_bf16:
-            C.coat_fp8_adamw_step_bf16w(w, w_bf16, grads[t & 1], st["m_q"], st["m_scale"], st["m_k"],
-                                        st["v_q"], st["v_scale"], st["v_k"], hp)
-        else:
-            C.coat_fp8_adamw_step(w, grads[t & 1], st["m_q"], st["m_scale"], st["m_k"],
-                                  st["v_q"], st["v_scale"], st["v_k"], hp)
-
-    t = 0
-    for _ in range(args.warmup):
-        t += 1
-        step(t)
-    torch.cuda.synchronize()
-
-    # HIP events on the stream the kernel is launched on (torch's current stream)
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        t += 1
-        ev[i][0].record()
-        step(t)
-        ev[i][1].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    launch_ms = [a.elapsed_time(b) for a, b in ev]
-    avg_launch_s = sum(launch_ms) / len(launch_ms) / 1e3
-
-    finite = bool(torch.isfinite(w[:: max(1, n // (1 << 20))]).all().item())
-    if not finite:
-        sys.exit("bench.py: non-finite weights after the timed steps")
-
-    generic = args.m_e5m2 or args.v_e5m2 or args.m_plain or args.v_plain or args.bf16_scale
-    ms_per_step = wall / args.steps * 1e3
-    value = n * args.steps / wall
-    algo_bytes = (bytes_per_param(G) + (2.0 if args.emit_bf16 else 0.0) - (8.0 / G if args.bf16_scale else 0.0)) * n
-    achieved = algo_bytes / avg_launch_s / 1e9
+    flags = dict(m_e5m2=args.m_e5m2, v_e5m2=args.v_e5m2, m_plain=args.m_plain, v_plain=args.v_plain, bf16_scale=args.bf16_scale)
+    generic = any(flags.values())
+    head = run_step_config(C, S, torch, dev, args.workload, G, grads_kind, args.warmup, args.steps,
+                           copy_control=not args.only, flags=flags, emit_bf16=args.emit_bf16, multi=args.multi,
+                           multi_small=args.multi_small)
+    achieved = head["hbm_gbs"]
     out = {
         "metric": "params updated/sec, FP8-state AdamW (E4M3 m/v, per-group scale + dynamic range expansion)",
-        "value": value,
+        "value": head["params_per_s"],
         "unit": "params/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: %s, %d params, G=%d, grads %s" % (
-            args.workload, {"cfg1": "one 1024x1024 weight", "cfg2": "one Llama-2-7B decoder layer",
-                            "cfg3": "full Llama-2-7B-sized parameter set", "cfg5": "full Llama-2-13B-sized parameter set"}[
-                args.workload], n, G, args.grads) + (
+        "config": {"workload": "%s: %s, %d params, G=%d, grads %s" % (args.workload, WORKLOAD_TEXT[args.workload], n, G, grads_kind) + (
                     ", m %s%s, v %s%s" % ("E5M2" if args.m_e5m2 else "E4M3", "" if args.m_plain else "+expand",
                                             "E5M2" if args.v_e5m2 else "E4M3", "" if args.v_plain else "+expand")
                     if generic else "") + (", bf16 weight copy" if args.emit_bf16 else "") + (", bf16 scales" if args.bf16_scale else "") + (
-                        ", %d tensors in one multi-tensor launch" % len(plans[0].tensors) if plans else ""),
+                        ", %d tensors in one multi-tensor launch" % head["tensors"] if args.multi else ""),
             "params": n, "group_size": G, "hbm_gbs": achieved, "hbm_frac_of_peak": achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": (read_profile_traffic(args.workload, G)
-                                 if not (generic or args.emit_bf16 or plans) else None),   # the counters were read for the default kernel
-                     "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_ms": avg_launch_s * 1e3,
-                     "kernel": "adamw_step%s_kernel<%d, %s>" % ("_multi" if plans else "", G, "generic" if generic else "default")},
+                                 if not (generic or args.emit_bf16 or args.multi) else None),   # the counters were read for the default kernel
+                     "algorithmic_bytes_per_launch": head["algorithmic_bytes_per_launch"], "avg_launch_ms": head["avg_launch_ms"],
+                     "copy_control_gbs": head.get("copy_control_gbs"), "frac_of_copy_control": head.get("frac_of_copy_control"),
+                     "kernel": "adamw_step%s_kernel<%d, %s>" % ("_multi" if args.multi else "", G, "generic" if generic else "default")},
     }
-    # free the device buffers before the host-side baseline allocates its own arrays
-    del w, st, grads, plans
-    torch.cuda.empty_cache()
+    if not args.only and args.workload == "cfg3" and not (generic or args.emit_bf16 or args.multi):
+        # the other configurations of the report, each at its stated length and, for the sub-millisecond
+        # ones, once more at steady clocks; one row per configuration (cfg4: one per group size)
+        rows = [run_step_config(C, S, torch, dev, "cfg1", 128, "normal", 3, 10, steady_steps=2000),
+                run_step_config(C, S, torch, dev, "cfg2", 128, "normal", 3, 10, steady_steps=300)]
+        for g4 in (32, 128, 512):
+            rows.append(run_step_config(C, S, torch, dev, "cfg4", g4, "lognormal", 3, 10, steady_steps=300))
+        free, _ = torch.cuda.mem_get_info()
+        n5 = S.workload_numel("cfg5")
+        if free > n5 * 10.2 + (4 << 30):
+            rows.append(run_step_config(C, S, torch, dev, "cfg5", 128, "normal", 3, 5))
+        else:
+            rows.append(dict(workload="cfg5", skipped="needs %.0f GB of device memory, %.0f GB free" % (n5 * 10.2 / 1e9, free / 1e9)))
+        head_row = {k: head[k] for k in ("workload", "params", "group_size", "grads", "steps", "warmup", "ms_per_step",
+                                         "avg_launch_ms", "params_per_s", "hbm_gbs", "frac_of_peak") if k in head}
+        head_row.update(copy_control_gbs=head.get("copy_control_gbs"), frac_of_copy_control=head.get("frac_of_copy_control"))
+        out["configs"] = rows[:2] + [head_row] + rows[2:]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(G, min(args.cpu_sample, n), args.cpu_steps)
     print(json.dumps(out))

@@ -261,6 +261,18 @@ int coat_act_quant_tensor_from_group_amax(const uint16_t* x_bf16, uint64_t n, in
                                           float* tensor_amax, float* tensor_scale, uint8_t* q,
                                           void* hip_stream);
 
+/*
+ * Measurement aid, not part of the method: the copy control of the step.  Moves exactly the bytes
+ * coat_fp8_adamw_step moves (14 + 32/G per element: w, gradient and both code arrays read, w and
+ * both code arrays written, the four metadata arrays read and written) in the step's access
+ * pattern and launch shape, with next to no arithmetic (w <- w + g, the code arrays swap).  What it
+ * sustains is the ceiling of that access pattern on the machine; bench.py reports the step beside
+ * it.  Same pointer rules as the step (fp32 scales); n must be a multiple of 1024 (else
+ * COAT_ERR_SIZE).  The buffers' contents are destroyed.
+ */
+int coat_bench_copy_control(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float* m_scale, float* m_k,
+                            uint8_t* v_q, float* v_scale, float* v_k, uint64_t n, int32_t G, void* hip_stream);
+
 /* Human-readable text for a return code (static storage, never NULL). */
 const char* coat_strerror(int code);
 

@@ -5,7 +5,7 @@ from .binding import (CoatError, HParams, FLAG_EXPAND, FLAG_E5M2, FLAG_M_E5M2, F
                       make_hparams, n_groups, strerror, lib,
                       coat_fp8_adamw_step, coat_fp8_adamw_step_bf16w, coat_quant_group, coat_dequant_group,
                       coat_act_quant_group, coat_act_quant_tensor, coat_act_quant_tensor_from_group_amax,
-                      coat_act_quant_tensor_static, ACT_GROUP_SIZES,
+                      coat_act_quant_tensor_static, coat_bench_copy_control, ACT_GROUP_SIZES,
                       ACT_WORKSPACE_FLOATS, act_workspace,
                       TensorDesc, MultiPlan, coat_multi_plan_build, coat_fp8_adamw_step_multi, coat_shard_range,
                       StepConsts, coat_step_consts_compute, step_consts_tensor, coat_fp8_adamw_step_multi_consts)
@@ -14,6 +14,6 @@ __all__ = ["CoatError", "HParams", "FLAG_EXPAND", "FLAG_E5M2", "FLAG_M_E5M2", "F
            "FLAG_V_PLAIN", "FLAG_BF16_SCALE", "step_flags", "SUPPORTED_GROUP_SIZES", "EXPORTS", "make_hparams",
            "n_groups", "strerror", "lib", "coat_fp8_adamw_step", "coat_fp8_adamw_step_bf16w", "coat_quant_group", "coat_dequant_group",
            "coat_act_quant_group", "coat_act_quant_tensor", "coat_act_quant_tensor_from_group_amax",
-           "coat_act_quant_tensor_static", "ACT_GROUP_SIZES", "ACT_WORKSPACE_FLOATS", "act_workspace",
+           "coat_act_quant_tensor_static", "coat_bench_copy_control", "ACT_GROUP_SIZES", "ACT_WORKSPACE_FLOATS", "act_workspace",
            "TensorDesc", "MultiPlan", "coat_multi_plan_build", "coat_fp8_adamw_step_multi", "coat_shard_range",
            "StepConsts", "coat_step_consts_compute", "step_consts_tensor", "coat_fp8_adamw_step_multi_consts"]

@@ -20,7 +20,7 @@ ACT_WORKSPACE_FLOATS = 64
 
 EXPORTS = ("coat_fp8_adamw_step", "coat_fp8_adamw_step_bf16w", "coat_quant_group", "coat_dequant_group",
            "coat_act_quant_group", "coat_act_quant_tensor", "coat_act_quant_tensor_from_group_amax",
-           "coat_act_quant_tensor_static",
+           "coat_act_quant_tensor_static", "coat_bench_copy_control",
            "coat_multi_plan_bytes", "coat_multi_plan_build", "coat_fp8_adamw_step_multi", "coat_shard_range",
            "coat_step_consts_compute", "coat_fp8_adamw_step_multi_consts",
            "coat_strerror", "coat_version")
@@ -113,6 +113,8 @@ def lib():
             f.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
         L.coat_act_quant_tensor_static.restype = ctypes.c_int
         L.coat_act_quant_tensor_static.argtypes = [vp, ctypes.c_uint64, ctypes.c_int32, vp, vp, vp, vp, vp]
+        L.coat_bench_copy_control.restype = ctypes.c_int
+        L.coat_bench_copy_control.argtypes = [vp] * 8 + [ctypes.c_uint64, ctypes.c_int32, vp]
         L.coat_multi_plan_bytes.restype = ctypes.c_size_t
         L.coat_multi_plan_bytes.argtypes = [ctypes.POINTER(TensorDesc), ctypes.c_uint32]
         L.coat_multi_plan_build.restype = ctypes.c_int
@@ -188,6 +190,19 @@ def coat_fp8_adamw_step_bf16w(w, w_bf16, grad_bf16, m_q, m_scale, m_k, v_q, v_sc
         _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, _scale_dtype(hp.flags), ng), _dev_ptr(m_k, torch.float32, ng),
         _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, _scale_dtype(hp.flags), ng), _dev_ptr(v_k, torch.float32, ng),
         n, ctypes.byref(hp), _stream()))
+
+
+def coat_bench_copy_control(w, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, G: int) -> None:
+    """The copy control of the step (same bytes, same access pattern, no arithmetic): a measurement aid.
+    Destroys the buffers' contents."""
+    import torch
+    n = w.numel()
+    ng = n_groups(n, G)
+    _check(lib().coat_bench_copy_control(
+        _dev_ptr(w, torch.float32), _dev_ptr(grad_bf16, torch.bfloat16, n),
+        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, torch.float32, ng), _dev_ptr(m_k, torch.float32, ng),
+        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, torch.float32, ng), _dev_ptr(v_k, torch.float32, ng),
+        n, G, _stream()))
 
 
 def coat_quant_group(x, G: int, expand: bool = True, k_min: float = 0.0, k_max: float = 0.0,

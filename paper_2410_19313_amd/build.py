@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 SOURCES = [os.path.join(_HERE, "csrc", "coat_kernels.hip")]
 HEADERS = [os.path.join(ROOT, "include", "coat.h")] + [os.path.join(_HERE, "csrc", f) for f in (
-    "coat_tables.inc", "coat_device.hpp", "coat_step.hpp", "coat_multi.hpp", "coat_quant.hpp", "coat_act.hpp")]
+    "coat_tables.inc", "coat_device.hpp", "coat_step.hpp", "coat_multi.hpp", "coat_quant.hpp", "coat_act.hpp", "coat_copy.hpp")]
 LIB = os.path.join(_HERE, "libcoat.so")
 
 # packed fp32 instructions are switched off on purpose (some forms have misbehaved on this

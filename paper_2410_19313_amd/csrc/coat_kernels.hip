@@ -12,8 +12,9 @@
 //   * no atomics, no inter-wave communication: each group is owned by exactly one wavefront.
 // One translation unit: coat_device.hpp (storage modes, helpers, LDS staging, (de)quantizer
 // arithmetic), coat_step.hpp (the fused step), coat_multi.hpp (the multi-tensor step),
-// coat_quant.hpp (standalone quantizer / dequantizer), coat_act.hpp (activation quantizers), and
-// below them the host side: validation, launches and the extern "C" entry points.
+// coat_quant.hpp (standalone quantizer / dequantizer), coat_act.hpp (activation quantizers),
+// coat_copy.hpp (the copy control of the measurements), and below them the host side: validation,
+// launches and the extern "C" entry points.
 //
 // Arithmetic (fp32 throughout; transcendentals are the hardware log2/exp2/rcp/sqrt), with fmax
 // the largest finite value of the moment's FP8 format (448 for E4M3, 57344 for E5M2):
@@ -40,6 +41,7 @@ static __device__ __align__(256) float g_act_scratch[COAT_ACT_WORKSPACE_FLOATS];
 #include "coat_multi.hpp"
 #include "coat_quant.hpp"
 #include "coat_act.hpp"
+#include "coat_copy.hpp"
 
 namespace {
 
@@ -86,6 +88,7 @@ int launch_status() { return hipGetLastError() == hipSuccess ? COAT_OK : COAT_ER
 // the wait at the admission gate (measured on the 7B set, with the gate: 2 blocks 15.6 ms,
 // 3 blocks 15.05, 4 blocks 15.3, 5 blocks 15.35; without it: 15.85, 16.1, 16.3, 16.3).
 constexpr size_t kStepLdsPad = 12 * 1024;
+constexpr size_t kStepStaticLds = 37 * 1024;       // what the step kernel declares itself (tiles, tables, scratch)
 constexpr size_t kMultiLdsPad = 12 * 1024;
 
 template <int G, bool GENERIC>
@@ -149,6 +152,16 @@ int dispatch_step(const StepArgs& a, int32_t G, bool generic, hipStream_t s) {
   if (!generic) { COAT_DISPATCH_G(G, (launch_step<kG, false>(a, s))); }
   COAT_DISPATCH_G(G, (launch_step<kG, true>(a, s)));
 }
+
+template <int G>
+int launch_copy_control(const StepArgs& a, hipStream_t s) {
+  if (a.n_full) {
+    hipLaunchKernelGGL((copy_control_kernel<G>), dim3(grid_for(a.n_full)), dim3(kBlock), kStepLdsPad + kStepStaticLds, s, a);
+    if (int rc = launch_status()) return rc;
+  }
+  return COAT_OK;
+}
+int dispatch_copy_control(const StepArgs& a, int32_t G, hipStream_t s) { COAT_DISPATCH_G(G, (launch_copy_control<kG>(a, s))); }
 
 int dispatch_quant(const QuantArgs& a, int32_t G, hipStream_t s) { COAT_DISPATCH_G(G, (launch_quant<kG>(a, s))); }
 
@@ -462,6 +475,21 @@ int coat_shard_range(uint64_t n, int32_t G, uint32_t rank, uint32_t world, uint6
   *begin = g0 * g < n ? g0 * g : n;
   *end = g1 * g < n ? g1 * g : n;
   return COAT_OK;
+}
+
+int coat_bench_copy_control(float* w, const uint16_t* grad_bf16, uint8_t* m_q, float* m_scale, float* m_k,
+                            uint8_t* v_q, float* v_scale, float* v_k, uint64_t n, int32_t G, void* hip_stream) {
+  if (!group_ok(G)) return COAT_ERR_GROUP;
+  if (n == 0) return COAT_OK;
+  if (!w || !grad_bf16 || !m_q || !m_scale || !m_k || !v_q || !v_scale || !v_k) return COAT_ERR_NULL;
+  if (!aligned16(w) || !aligned16(grad_bf16) || !aligned16(m_q) || !aligned16(v_q) || !aligned16(m_scale) ||
+      !aligned16(m_k) || !aligned16(v_scale) || !aligned16(v_k))
+    return COAT_ERR_ALIGN;
+  if (n > kMaxElements || n % kChunk != 0) return COAT_ERR_SIZE;
+  StepArgs a = {};
+  a.w = w; a.g = grad_bf16; a.mq = m_q; a.ms = m_scale; a.mk = m_k; a.vq = v_q; a.vs = v_scale; a.vk = v_k;
+  a.n = n; a.n_full = n / kChunk; a.n_groups = n / static_cast<uint64_t>(G);
+  return dispatch_copy_control(a, G, static_cast<hipStream_t>(hip_stream));
 }
 
 int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags, float k_min, float k_max,
