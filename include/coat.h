@@ -133,7 +133,8 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
  * the tensors' addresses and sizes do; it does not depend on the hyper-parameters or on G.  To
  * step only a shard of a tensor, describe the shard (see coat_shard_range).
  * coat_multi_plan_bytes returns 0 on an invalid argument (NULL with count > 0, an n above 2^46, or
- * more than 2^27 spans in total).
+ * 2^21 or more spans in total: one launch covers every span with eight workgroups and a launch
+ * holds fewer than 2^24 workgroups).
  */
 typedef struct {
   float*          w;
@@ -173,6 +174,14 @@ int coat_step_consts_compute(const coat_adamw_hparams* hp, coat_step_consts* out
 int coat_fp8_adamw_step_multi_consts(const void* plan_host, const void* plan_device,
                                      const coat_adamw_hparams* hp,
                                      const coat_step_consts* consts_device, void* hip_stream);
+
+/*
+ * The shape of the main launch of a single-tensor step over n elements (pure host code): one
+ * 1024-element chunk per wavefront, 256 threads per workgroup, and at most 2^24 - 1 workgroups (a
+ * dispatch counts its work-items in 32 bits); beyond that many chunks the kernels loop.  For callers
+ * that size graphs or occupancy estimates; the ragged last chunk is a second one-wavefront launch.
+ */
+int coat_launch_shape(uint64_t n, uint32_t* blocks, uint32_t* threads_per_block);
 
 /*
  * The part of a flat tensor of n elements that rank `rank` of `world` owns when optimizer states

@@ -20,7 +20,7 @@ ACT_WORKSPACE_FLOATS = 64
 
 EXPORTS = ("coat_fp8_adamw_step", "coat_fp8_adamw_step_bf16w", "coat_quant_group", "coat_dequant_group",
            "coat_act_quant_group", "coat_act_quant_tensor", "coat_act_quant_tensor_from_group_amax",
-           "coat_act_quant_tensor_static", "coat_bench_copy_control",
+           "coat_act_quant_tensor_static", "coat_bench_copy_control", "coat_launch_shape",
            "coat_multi_plan_bytes", "coat_multi_plan_build", "coat_fp8_adamw_step_multi", "coat_shard_range",
            "coat_step_consts_compute", "coat_fp8_adamw_step_multi_consts",
            "coat_strerror", "coat_version")
@@ -125,6 +125,8 @@ def lib():
         L.coat_step_consts_compute.argtypes = [ctypes.POINTER(HParams), ctypes.POINTER(StepConsts)]
         L.coat_fp8_adamw_step_multi_consts.restype = ctypes.c_int
         L.coat_fp8_adamw_step_multi_consts.argtypes = [vp, vp, ctypes.POINTER(HParams), vp, vp]
+        L.coat_launch_shape.restype = ctypes.c_int
+        L.coat_launch_shape.argtypes = [ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32)]
         L.coat_shard_range.restype = ctypes.c_int
         L.coat_shard_range.argtypes = [ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_uint32,
                                        ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]

@@ -8,10 +8,7 @@ namespace {
 
 constexpr int kWave = 64;                 // lanes per wavefront
 constexpr int kEPL = 16;                  // consecutive elements owned by one lane
-#ifndef COAT_WPB
-#define COAT_WPB 4
-#endif
-constexpr int kWavesPerBlock = COAT_WPB;
+constexpr int kWavesPerBlock = 4;
 constexpr int kBlock = kWave * kWavesPerBlock;
 constexpr int kChunk = kWave * kEPL;      // elements one wavefront handles per iteration
 
@@ -159,21 +156,13 @@ __device__ __forceinline__ float group_allreduce(float xf) {
   return as_f32(x);
 }
 
-// Compile-time streaming hints (bit mask): 1 load codes, 2 store codes, 4 load gradients,
-// 8 load fp32, 16 store fp32.  A set bit issues the access as non-temporal.
-#ifndef COAT_NT
-#define COAT_NT 31
-#endif
-template <int BIT, typename T>
-__device__ __forceinline__ T ldg(const T* p) {
-  if constexpr ((COAT_NT & BIT) != 0) return __builtin_nontemporal_load(p);
-  else return *p;
-}
-template <int BIT, typename T>
-__device__ __forceinline__ void stg(T* p, T v) {
-  if constexpr ((COAT_NT & BIT) != 0) __builtin_nontemporal_store(v, p);
-  else *p = v;
-}
+// Bulk accesses: every array is streamed through once per step, so every bulk load and store is
+// issued as non-temporal (measured best for all five kinds of access).  KIND only names the access
+// at the call site: 1 load codes, 2 store codes, 4 load gradients, 8 load fp32, 16 store fp32.
+template <int KIND, typename T>
+__device__ __forceinline__ T ldg(const T* p) { return __builtin_nontemporal_load(p); }
+template <int KIND, typename T>
+__device__ __forceinline__ void stg(T* p, T v) { __builtin_nontemporal_store(v, p); }
 
 // Element-wise guarded accesses straight into the lane layout: only the ragged last chunk
 // (n mod 1024 elements, one wavefront) uses them.

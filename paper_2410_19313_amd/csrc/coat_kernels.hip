@@ -54,21 +54,15 @@ bool finite_f(float x) { return x == x && x - x == 0.0f; }
 constexpr uint64_t kMaxElements = 1ull << 46;
 bool group_ok(int32_t G) { return G == 32 || G == 64 || G == 128 || G == 256 || G == 512; }
 
-#ifdef COAT_TUNING
-int g_tune_cap_mult = 0;      // blocks per CU cap; 0 = one wavefront per chunk (no loop)
-int g_tune_lds_pad = -1;      // dynamic LDS bytes per block (limits occupancy); -1 = the default
-#endif
 
 // Blocks of the main launch.  One chunk per wavefront measured best (the hardware dispatcher then
-// walks memory in address order and few bytes are in flight per CU); the kernels still loop,
-// which covers buffers with more chunks than a grid can hold blocks.
+// walks memory in address order and few bytes are in flight per CU).  A dispatch counts its
+// work-items in 32 bits, so a grid holds fewer than 2^32 / 256 blocks; the kernels loop, which
+// covers buffers with more chunks than that (above 6.8e10 elements).
+constexpr uint64_t kMaxGridBlocks = (1ull << 32) / kBlock - 1;
 unsigned grid_for(uint64_t n_full) {
   const uint64_t need = (n_full + kWavesPerBlock - 1) / kWavesPerBlock;
-  uint64_t cap = 1ull << 30;
-#ifdef COAT_TUNING
-  if (g_tune_cap_mult > 0) cap = 256ull * static_cast<uint64_t>(g_tune_cap_mult);
-#endif
-  return static_cast<unsigned>(need < cap ? need : cap);
+  return static_cast<unsigned>(need < kMaxGridBlocks ? need : kMaxGridBlocks);
 }
 
 // k bounds: 0,0 selects the defaults; the kernels assume 2^-6 <= k <= 2^16 (finite table
@@ -96,12 +90,6 @@ int launch_step(const StepArgs& a, hipStream_t s) {
   if (a.n_full) {
     const unsigned grid = grid_for(a.n_full);
     size_t lds = kStepLdsPad;
-#ifdef COAT_TUNING
-    if (g_tune_lds_pad >= 0) lds = static_cast<size_t>(g_tune_lds_pad);
-    if (lds > 32 * 1024)
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&adamw_step_kernel<G, GENERIC>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-#endif
     hipLaunchKernelGGL((adamw_step_kernel<G, GENERIC>), dim3(grid), dim3(kBlock), lds, s, a);
     if (int rc = launch_status()) return rc;
   }
@@ -261,9 +249,6 @@ template <int G, bool GENERIC>
 int launch_step_multi(const MultiArgs& ma, uint64_t total_records, hipStream_t s) {
   const uint64_t blocks = total_records * (kPlanSpan / kWavesPerBlock);
   size_t lds = kMultiLdsPad;
-#ifdef COAT_TUNING
-  if (g_tune_lds_pad >= 0) lds = static_cast<size_t>(g_tune_lds_pad);
-#endif
   hipLaunchKernelGGL((adamw_step_multi_kernel<G, GENERIC>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), lds, s, ma);
   return launch_status();
 }
@@ -277,7 +262,9 @@ constexpr uint32_t kStepFlags = COAT_FLAG_EXPAND | COAT_FLAG_M_E5M2 | COAT_FLAG_
                                 COAT_FLAG_V_PLAIN | COAT_FLAG_BF16_SCALE;
 
 constexpr uint64_t kPlanRecordOffset = 128;          // records start one cache line into the blob
-constexpr uint64_t kMaxPlanRecords = 1ull << 27;    // one launch covers them all (8 workgroups per record)
+// one launch covers all records with kPlanSpan / kWavesPerBlock = 8 workgroups each, and a grid holds
+// fewer than 2^24 workgroups
+constexpr uint64_t kMaxPlanRecords = kMaxGridBlocks / (kPlanSpan / kWavesPerBlock);
 
 uint64_t plan_records_of(uint64_t n) {               // spans of 32 chunks a tensor of n elements occupies
   const uint64_t chunks = (n + kChunk - 1) / kChunk;
@@ -463,6 +450,14 @@ int coat_fp8_adamw_step_multi_consts(const void* plan_host, const void* plan_dev
   return step_multi_impl(plan_host, plan_device, hp, consts_device, true, hip_stream);
 }
 
+int coat_launch_shape(uint64_t n, uint32_t* blocks, uint32_t* threads_per_block) {
+  if (!blocks || !threads_per_block) return COAT_ERR_NULL;
+  if (n > kMaxElements) return COAT_ERR_SIZE;
+  *blocks = grid_for(n / kChunk);
+  *threads_per_block = kBlock;
+  return COAT_OK;
+}
+
 int coat_shard_range(uint64_t n, int32_t G, uint32_t rank, uint32_t world, uint64_t* begin, uint64_t* end) {
   if (!begin || !end) return COAT_ERR_NULL;
   if (G < 1) return COAT_ERR_GROUP;
@@ -581,11 +576,5 @@ const char* coat_strerror(int code) {
 
 int coat_version(void) { return 230; }
 
-#ifdef COAT_TUNING
-// development builds only: launch-shape knobs for sweeps
-void coat_tune_set(int cap_mult, int lds_pad, int unused) {
-  g_tune_cap_mult = cap_mult; g_tune_lds_pad = lds_pad; (void)unused;
-}
-#endif
 
 }  // extern "C"

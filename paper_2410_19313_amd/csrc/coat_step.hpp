@@ -187,15 +187,9 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const ModeM& mm
 // instruction: it makes the chunk index depend on the probed word so that the compiler keeps the
 // loads behind it.  The probed value itself is never used, so it is harmless that the wavefront
 // owning that chunk may be rewriting the word at the same moment.
-#ifndef COAT_GATE_SHIFT
-#define COAT_GATE_SHIFT 5
-#endif
-constexpr int kGateSpan = 1 << COAT_GATE_SHIFT;
+constexpr int kGateSpan = 32;
 // `words`: any array of the operand with a fixed number of 32-bit words per chunk.
 __device__ __forceinline__ uint64_t gate_on_neighbourhood(const void* words, uint64_t chunk, int words_per_chunk) {
-#ifdef COAT_NO_GATE
-  return chunk;
-#endif
   const uint64_t first = chunk & ~static_cast<uint64_t>(kGateSpan - 1);
   const uint32_t probe = __builtin_amdgcn_readfirstlane(static_cast<const uint32_t*>(words)[first * words_per_chunk]);
   uint32_t lo = static_cast<uint32_t>(chunk);

@@ -10,7 +10,7 @@ cells have E4M3+Expand for the first moment and an expanded second moment (whose
 hardly matters, in the paper too), and plain E5M2 for the first moment is the worst row.  Every quantize / dequantize runs in the HIP kernels
 through the C ABI (coat_quant_group, coat_dequant_group); torch only forms the ratio and the mean.
 
-    python -m paper_2410_19313_amd.table1 [--n 16777216] [--group-size 128] [--seed 0]
+    python table1_experiment.py [--n 16777216] [--group-size 128] [--seed 0]
 """
 from __future__ import annotations
 
@@ -26,7 +26,7 @@ def table1(n: int, G: int, seed: int, eps: float = 1e-8):
     """-> (labels, 4 x 4 list of MSE values: rows = first moment, columns = second moment)."""
     import torch
     import paper_2410_19313_amd as C
-    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
     import synth_inputs as S
 
     dev = torch.device("cuda:0")

@@ -245,3 +245,24 @@ def test_binding_refuses_host_tensors(coat):
     x = torch.zeros(1024)
     with pytest.raises(TypeError):
         coat.coat_quant_group(x, 128)
+
+
+def test_launch_shape_and_plan_limits(coat):
+    """A dispatch counts its work-items in 32 bits: the main launch stays below 2^32 / 256 workgroups
+    whatever n is (the kernels loop beyond), and a plan whose spans would need more than one launch
+    is refused.  Host logic only: nothing is launched and no pointer is dereferenced."""
+    L = coat.lib()
+    b, t = ctypes.c_uint32(), ctypes.c_uint32()
+    for n, want in ((0, 0), (1023, 0), (1024, 1), (4096, 1), (4097, 1), (8192, 2), (6738149376, 1645056),
+                    (13015449600, 3177600), (1 << 36, (1 << 24) - 1), (1 << 46, (1 << 24) - 1)):
+        assert L.coat_launch_shape(n, ctypes.byref(b), ctypes.byref(t)) == 0
+        assert (b.value, t.value) == (want, 256), (n, b.value)
+        assert b.value * t.value < 1 << 32
+    assert L.coat_launch_shape((1 << 46) + 1, ctypes.byref(b), ctypes.byref(t)) == -7
+    assert L.coat_launch_shape(4096, None, ctypes.byref(t)) == -1
+    # plan limit: 2^21 - 1 spans of 32768 elements fit one launch, one more does not
+    span = 32 * 1024
+    fits = (coat.TensorDesc * 1)(fake_desc(coat, span * ((1 << 21) - 1)))
+    assert L.coat_multi_plan_bytes(fits, 1) == 128 + 128 * ((1 << 21) - 1)
+    too_many = (coat.TensorDesc * 2)(fake_desc(coat, span * ((1 << 21) - 1)), fake_desc(coat, 1))
+    assert L.coat_multi_plan_bytes(too_many, 2) == 0

@@ -601,7 +601,7 @@ def test_table1_structure_on_the_gpu_path(coat, ref):
     those with E4M3+Expand for the first moment and an expanded second moment, whose two formats
     differ by about a percent in the paper as well).  The paper's absolute values need its real
     optimizer states: unpinned."""
-    from paper_2410_19313_amd.table1 import CELLS, table1
+    from table1_experiment import CELLS, table1
     n, G, seed = 1 << 18, 128, 4
     labels, rows = table1(n, G, seed)
     gen = S.torch_generator(torch.device("cuda:0"), seed)
