@@ -12,8 +12,10 @@
  *   - A tensor is a flat buffer of n elements.  Every G consecutive elements form one
  *     quantization group (Sec. 3, optimizer state quantization); the last group is short
  *     when n % G != 0.  Per-group arrays have ceil(n/G) entries.
- *   - Base pointers must be 16-byte aligned.  n is 64-bit (the 7B and 13B parameter sets
- *     exceed 2^32 elements).
+ *   - Base pointers of per-element arrays must be 16-byte aligned; the per-group arrays of the
+ *     optimizer state (scale, k) need 4-byte alignment only, so that a shard may start at any even
+ *     group (see coat_shard_range).  n is 64-bit (the 7B and 13B parameter sets exceed 2^32
+ *     elements).
  *   - Return value: COAT_OK (0) or a negative COAT_ERR_* code.  Arguments are validated on
  *     the host before anything is launched, so a failing call has touched no memory.
  *     n == 0 is a successful no-op.  No exception or abort crosses this boundary.
@@ -34,7 +36,7 @@ extern "C" {
 
 #define COAT_OK            0
 #define COAT_ERR_NULL     -1  /* a required pointer is NULL */
-#define COAT_ERR_ALIGN    -2  /* a base pointer is not 16-byte aligned */
+#define COAT_ERR_ALIGN    -2  /* a base pointer is not aligned as required (16 bytes; 4 for scale and k) */
 #define COAT_ERR_GROUP    -3  /* group size not one of 32, 64, 128, 256, 512 (activation quantizers: or 16) */
 #define COAT_ERR_STEP     -4  /* step < 1 */
 #define COAT_ERR_HPARAM   -5  /* non-finite or out-of-domain hyper-parameter, unknown flag bit */
@@ -92,7 +94,11 @@ typedef struct {
  * round(x/scale), x = scale*code), writes k = 1 and does not read k.
  * The valid start state (m0 = v0 = 0) is: all codes 0, scale 0, k 1.
  * Gradients that are NaN/Inf poison their own element of w and their own group's
- * moments; other groups are unaffected.  Moments that are fp32-subnormal are flushed.
+ * moments; other groups are unaffected.  Magnitudes below the smallest normal fp32 number (a squared
+ * gradient of 1e-20, say) are outside the domain the results are specified for: such an element may
+ * count as zero or not; its group's stored state stays valid (finite scale, k within its bounds, no
+ * NaN code) and no other group is affected.  A group whose scale amax / fmax would itself fall below
+ * the smallest normal fp32 number is stored as the zero state (codes 0, scale 0, k 1).
  */
 int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
                         uint8_t* m_q, void* m_scale, float* m_k,
@@ -186,10 +192,12 @@ int coat_launch_shape(uint64_t n, uint32_t* blocks, uint32_t* threads_per_block)
 /*
  * The part of a flat tensor of n elements that rank `rank` of `world` owns when optimizer states
  * are sharded (ZeRO / FSDP style; Sec. 3: every rank quantizes its own shard with its own
- * statistics): shards are contiguous, cut at multiples of G so that no group spans two ranks, and
- * differ by at most one group.  Pure host code.  Writes [*begin, *end); an empty shard has
+ * statistics): shards are contiguous, cut at multiples of 2 G (pairs of groups: no group spans two
+ * ranks, and a shard's per-group arrays start on a 32-bit word also when the scales are bf16), and
+ * differ by at most one pair of groups.  Pure host code.  Writes [*begin, *end); an empty shard has
  * *begin == *end.  Offsetting the element pointers by *begin and the per-group pointers by
- * *begin / G describes the shard to any entry point here.
+ * *begin / G describes the shard to the optimizer step, the multi-tensor plan, coat_quant_group and
+ * coat_dequant_group (whose per-group arrays need 4-byte alignment only).
  */
 int coat_shard_range(uint64_t n, int32_t G, uint32_t rank, uint32_t world, uint64_t* begin, uint64_t* end);
 

@@ -427,7 +427,9 @@ __device__ __forceinline__ GroupQuant group_quant_params(const Mode& md, float a
     k = (amax != amin) ? kk : 1.0f;
   }
   const float inv_a = unit * hw_rcp(md.expand() ? fmax * s : s);
-  const bool empty = !(amax > 0.0f);                 // all zero: scale 0, k 1, every code 0
+  // all zero, or so small that amax / fmax is no normal fp32 number (the hardware reciprocal of a
+  // subnormal is infinite and every code would be NaN): stored as the zero state, scale 0, k 1, codes 0
+  const bool empty = !(s >= 0x1.0p-126f);
   r.scale = empty ? 0.0f : s;
   r.k = empty ? 1.0f : k;
   r.inv_a = empty ? 0.0f : inv_a;
@@ -607,6 +609,28 @@ __device__ __forceinline__ float apply_exact_min(float exact, uint32_t min_key, 
   // its maximum as well, so that a group of equal magnitudes has amax == amin on this side too
   if (have && (as_u32(amax) & 0x7ffffff0u) == seen_bits && seen_bits != 0u) amax = res;
   return have ? res : __builtin_huge_valf();
+}
+
+// The lane's largest |m_t| recomputed exactly, for the groups whose maximum FELL: rare path, the
+// chain run back to back.  The fp32 value of m_t = beta1 m + (1 - beta1) g carries the error of the
+// dequantized m, at most about 2.1e-7 of beta1 * (old group maximum) whichever element it is (the
+// inverse expansion's error grows with |log2(c/fmax) / k| while the element shrinks as 2 to minus
+// that).  Against a new maximum of at least 3/8 of beta1 * (old maximum) that is below 6e-7 and the
+// scale amax / fmax keeps six digits; only a group whose largest elements all cancelled falls below
+// (a few in 10^4 under heavy-tailed gradients), and for those the maximum is taken from exact values.
+template <class Mode>
+__device__ __forceinline__ float exact_lane_max(const StepArgs& a, const Mode& md, const StepTables& tb,
+                                                const LaneScratch& ls, const float (&x)[kEPL], float scale, float k,
+                                                float inv_k) {
+  uint32_t hi = 0u;
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) {
+    const uint32_t key = (as_u32(x[e]) & 0x7ffffff0u) | static_cast<uint32_t>(e);
+    hi = key > hi ? key : hi;
+  }
+  ExactChain<Mode> chain(a, md, tb, ls, hi, scale, k, inv_k);
+  static_for<0, ExactChain<Mode>::kSteps + 1>([&](auto s) { chain.template step<s.value>(); });
+  return __builtin_fabsf(chain.exact);
 }
 
 template <bool E5M2>

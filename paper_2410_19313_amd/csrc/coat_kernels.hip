@@ -50,6 +50,8 @@ namespace {
 // ---------------------------------------------------------------------------------------
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+// per-group arrays (scale, k) are read and written one 32-bit word at a time
+bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 bool finite_f(float x) { return x == x && x - x == 0.0f; }
 constexpr uint64_t kMaxElements = 1ull << 46;
 bool group_ok(int32_t G) { return G == 32 || G == 64 || G == 128 || G == 256 || G == 512; }
@@ -372,7 +374,7 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
   if (n == 0) return COAT_OK;
   if (!w || !grad_bf16 || !m_q || !m_scale || !m_k || !v_q || !v_scale || !v_k) return COAT_ERR_NULL;
   if (!aligned16(w) || !aligned16(grad_bf16) || !aligned16(m_q) || !aligned16(v_q) ||
-      !aligned16(m_scale) || !aligned16(m_k) || !aligned16(v_scale) || !aligned16(v_k) || !aligned16(w_bf16))
+      !aligned4(m_scale) || !aligned4(m_k) || !aligned4(v_scale) || !aligned4(v_k) || !aligned16(w_bf16))
     return COAT_ERR_ALIGN;
   if (n > kMaxElements) return COAT_ERR_SIZE;
   a.w = w; a.wb = w_bf16; a.g = grad_bf16; a.mq = m_q; a.ms = static_cast<float*>(m_scale); a.mk = m_k; a.vq = v_q; a.vs = static_cast<float*>(v_scale); a.vk = v_k;
@@ -401,8 +403,8 @@ int coat_multi_plan_build(const coat_tensor_desc* descs, uint32_t count, void* p
     const coat_tensor_desc& d = descs[t];
     if (d.n == 0) continue;
     if (!d.w || !d.grad_bf16 || !d.m_q || !d.m_scale || !d.m_k || !d.v_q || !d.v_scale || !d.v_k) return COAT_ERR_NULL;
-    if (!aligned16(d.w) || !aligned16(d.grad_bf16) || !aligned16(d.m_q) || !aligned16(d.v_q) || !aligned16(d.m_scale) ||
-        !aligned16(d.m_k) || !aligned16(d.v_scale) || !aligned16(d.v_k) || !aligned16(d.w_bf16))
+    if (!aligned16(d.w) || !aligned16(d.grad_bf16) || !aligned16(d.m_q) || !aligned16(d.v_q) || !aligned4(d.m_scale) ||
+        !aligned4(d.m_k) || !aligned4(d.v_scale) || !aligned4(d.v_k) || !aligned16(d.w_bf16))
       return COAT_ERR_ALIGN;
     if (!finite_f(d.weight_decay)) return COAT_ERR_HPARAM;
   }
@@ -462,9 +464,11 @@ int coat_shard_range(uint64_t n, int32_t G, uint32_t rank, uint32_t world, uint6
   if (!begin || !end) return COAT_ERR_NULL;
   if (G < 1) return COAT_ERR_GROUP;
   if (world == 0 || rank >= world) return COAT_ERR_HPARAM;
-  const uint64_t g = static_cast<uint64_t>(G);
+  // cuts fall on PAIRS of groups: with scales stored as bf16 a shard's scale array then still starts
+  // on a 32-bit word, which is how the kernels read it
+  const uint64_t g = 2 * static_cast<uint64_t>(G);
   const uint64_t groups = n / g + (n % g != 0);
-  const uint64_t base = groups / world, extra = groups % world;           // the first `extra` ranks own one more
+  const uint64_t base = groups / world, extra = groups % world;           // the first `extra` ranks own one more pair
   const uint64_t g0 = rank * base + (rank < extra ? rank : extra);
   const uint64_t g1 = g0 + base + (rank < extra ? 1 : 0);
   *begin = g0 * g < n ? g0 * g : n;
@@ -477,8 +481,8 @@ int coat_bench_copy_control(float* w, const uint16_t* grad_bf16, uint8_t* m_q, f
   if (!group_ok(G)) return COAT_ERR_GROUP;
   if (n == 0) return COAT_OK;
   if (!w || !grad_bf16 || !m_q || !m_scale || !m_k || !v_q || !v_scale || !v_k) return COAT_ERR_NULL;
-  if (!aligned16(w) || !aligned16(grad_bf16) || !aligned16(m_q) || !aligned16(v_q) || !aligned16(m_scale) ||
-      !aligned16(m_k) || !aligned16(v_scale) || !aligned16(v_k))
+  if (!aligned16(w) || !aligned16(grad_bf16) || !aligned16(m_q) || !aligned16(v_q) || !aligned4(m_scale) ||
+      !aligned4(m_k) || !aligned4(v_scale) || !aligned4(v_k))
     return COAT_ERR_ALIGN;
   if (n > kMaxElements || n % kChunk != 0) return COAT_ERR_SIZE;
   StepArgs a = {};
@@ -494,7 +498,7 @@ int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags, floa
   if (!resolve_k_bounds(k_min, k_max)) return COAT_ERR_HPARAM;
   if (n == 0) return COAT_OK;
   if (!x || !q || !scale || !k) return COAT_ERR_NULL;
-  if (!aligned16(x) || !aligned16(q) || !aligned16(scale) || !aligned16(k)) return COAT_ERR_ALIGN;
+  if (!aligned16(x) || !aligned16(q) || !aligned4(scale) || !aligned4(k)) return COAT_ERR_ALIGN;
   if (n > kMaxElements) return COAT_ERR_SIZE;
   QuantArgs a;
   a.x = x; a.q = q; a.scale = static_cast<float*>(scale); a.k = k;
@@ -513,7 +517,7 @@ int coat_dequant_group(const uint8_t* q, const void* scale, const float* k, uint
   if (flags & ~(COAT_FLAG_EXPAND | COAT_FLAG_E5M2 | COAT_FLAG_BF16_SCALE)) return COAT_ERR_HPARAM;
   if (n == 0) return COAT_OK;
   if (!x || !q || !scale || !k) return COAT_ERR_NULL;
-  if (!aligned16(x) || !aligned16(q) || !aligned16(scale) || !aligned16(k)) return COAT_ERR_ALIGN;
+  if (!aligned16(x) || !aligned16(q) || !aligned4(scale) || !aligned4(k)) return COAT_ERR_ALIGN;
   if (n > kMaxElements) return COAT_ERR_SIZE;
   DequantArgs a;
   a.q = q; a.scale = static_cast<const float*>(scale); a.k = k; a.x = x;

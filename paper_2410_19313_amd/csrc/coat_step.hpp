@@ -89,6 +89,16 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, co
   float m_min = apply_exact_min(m_exact, m_key, m, m_max, m_replace);
   m_max = group_allreduce<LPG, true>(m_max);
   m_min = group_allreduce<LPG, false>(m_min);
+  if (mm.expand()) {
+    // a group whose maximum fell below 3/8 of beta1 * (its old maximum): see exact_lane_max.  The
+    // branch is taken by whole wavefronts (the butterflies inside need every lane); only the groups
+    // concerned adopt the result, so a group's outcome does not depend on its neighbours.
+    const bool fell = m_max < 0.375f * m_fac;
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(fell) != 0ull, 0)) {
+      const float ex = group_allreduce<LPG, true>(exact_lane_max(a, mm, tb, ls, m, meta.m_scale, meta.m_k, m_inv_k));
+      m_max = fell ? ex : m_max;
+    }
+  }
   const GroupQuant qm = group_quant_params(mm, m_max, m_min, a.k_min, a.k_max, a.one_minus_beta1);
   quantize16<true>(mm, m, qm, mc, a.one_minus_beta1);
   if (__builtin_expect(m_replace, 0)) requantize_one(mm, m_exact, qm, m_key & 15u, mc, a.one_minus_beta1);

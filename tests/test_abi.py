@@ -89,7 +89,10 @@ def test_quant_dequant_reject_bad_arguments(coat):
     assert L.coat_quant_group(ok, 1024, 128, 64, 0.0, 0.0, ok, ok, ok, None) == -5     # unknown flag bit
     assert L.coat_dequant_group(ok, ok, ok, 1024, 7, 0, ok, None) == -3
     assert L.coat_dequant_group(ok, None, ok, 1024, 128, 0, ok, None) == -1
-    assert L.coat_dequant_group(ok, ok, bad, 1024, 128, 0, ok, None) == -2
+    assert L.coat_dequant_group(bad, ok, ok, 1024, 128, 0, ok, None) == -2
+    # per-group arrays need 4-byte alignment only (a shard may start at any even group)
+    assert L.coat_dequant_group(ok, ok, ctypes.c_void_p(0x1002), 1024, 128, 0, ok, None) == -2
+    assert L.coat_quant_group(ok, 1024, 128, 1, 0.0, 0.0, ok, ctypes.c_void_p(0x1002), ok, None) == -2
     assert L.coat_dequant_group(ok, ok, ok, 1024, 128, 8, ok, None) == -5
     assert L.coat_dequant_group(None, None, None, 0, 128, 2, None, None) == 0
 
@@ -164,7 +167,8 @@ def test_multi_plan_and_step_reject_bad_arguments(coat):
     assert L.coat_multi_plan_bytes(None, 0) == 128                    # an empty plan is legal
     assert L.coat_multi_plan_build(arr, 1, None, size) == -1
     assert L.coat_multi_plan_build(arr, 1, buf, size - 1) == -7
-    for field, bad, code in (("w", 0, -1), ("v_k", 0, -1), ("w", 0x10004, -2), ("m_q", 0x10008, -2), ("w_bf16", 0x10002, -2)):
+    for field, bad, code in (("w", 0, -1), ("v_k", 0, -1), ("w", 0x10004, -2), ("m_q", 0x10008, -2), ("w_bf16", 0x10002, -2),
+                             ("m_k", 0x10002, -2), ("v_scale", 0x10006, -2)):
         arr2 = (coat.TensorDesc * 1)(fake_desc(coat, 4096, **{field: bad}))
         assert L.coat_multi_plan_build(arr2, 1, buf, size) == code, field
     arr3 = (coat.TensorDesc * 1)(fake_desc(coat, 4096, wd=float("nan")))
@@ -225,12 +229,12 @@ def test_shard_range_partitions_at_group_boundaries(coat):
         for r in range(world):
             b, e = coat.coat_shard_range(n, G, r, world)
             assert b == prev and b <= e <= n
-            assert b % G == 0 or b == n
-            assert e % G == 0 or e == n
-            sizes.append((e - b + G - 1) // G)
+            assert b % (2 * G) == 0 or b == n                    # cut at pairs of groups
+            assert e % (2 * G) == 0 or e == n
+            sizes.append((e - b + 2 * G - 1) // (2 * G))
             prev = e
         assert prev == n                                         # the shards tile [0, n)
-        assert max(sizes) - min(sizes) <= 1                      # in groups: balanced to one group
+        assert max(sizes) - min(sizes) <= 1                      # in pairs of groups: balanced to one pair
         assert sizes == sorted(sizes, reverse=True)              # the larger shards come first
     L = coat.lib()
     b, e = ctypes.c_uint64(), ctypes.c_uint64()
