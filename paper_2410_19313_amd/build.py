@@ -43,24 +43,39 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
-NATIVE_TEST_SRC = os.path.join(ROOT, "tests", "native", "abi_smoke.cpp")
-NATIVE_TEST_BIN = os.path.join(ROOT, "tests", "native", "abi_smoke")
+NATIVE_DIR = os.path.join(ROOT, "tests", "native")
+NATIVE_TEST_SRC = os.path.join(NATIVE_DIR, "abi_smoke.cpp")
+NATIVE_TEST_BIN = os.path.join(NATIVE_DIR, "abi_smoke")
+CONVERT_TEST_SRC = os.path.join(NATIVE_DIR, "convert_band.cpp")
+CONVERT_TEST_BIN = os.path.join(NATIVE_DIR, "convert_band")
+
+
+def _hipcc_program(src: str, out: str, force: bool, link_lib: bool) -> str:
+    newest = max([os.path.getmtime(src)] + ([os.path.getmtime(LIB)] if link_lib else []))
+    if not force and os.path.exists(out) and os.path.getmtime(out) >= newest:
+        return out
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), src]
+    if link_lib:
+        cmd += ["-L", _HERE, "-lcoat", "-Wl,-rpath,$ORIGIN/../../paper_2410_19313_amd"]
+    res = subprocess.run(cmd + ["-o", out], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    return out
 
 
 def build_native_test(force: bool = True) -> str:
     """Compile the plain-HIP host program that uses the C ABI without Python (tests/native)."""
-    if not force and os.path.exists(NATIVE_TEST_BIN) and \
-            os.path.getmtime(NATIVE_TEST_BIN) >= max(os.path.getmtime(NATIVE_TEST_SRC), os.path.getmtime(LIB)):
-        return NATIVE_TEST_BIN
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), NATIVE_TEST_SRC,
-           "-L", _HERE, "-lcoat", "-Wl,-rpath,$ORIGIN/../../paper_2410_19313_amd", "-o", NATIVE_TEST_BIN]
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout)
-    return NATIVE_TEST_BIN
+    return _hipcc_program(NATIVE_TEST_SRC, NATIVE_TEST_BIN, force, link_lib=True)
+
+
+def build_convert_test(force: bool = True) -> str:
+    """Compile the program that pins the hardware FP32 -> FP8 converts around the largest finite value
+    (tests/native); it does not use the library."""
+    return _hipcc_program(CONVERT_TEST_SRC, CONVERT_TEST_BIN, force, link_lib=False)
 
 
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
     print(build_native_test(force=True))
+    print(build_convert_test(force=True))

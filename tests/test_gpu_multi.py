@@ -96,6 +96,57 @@ def test_multi_equals_one_call_per_tensor(coat, G, flags):
                         "G=%d step %d tensor %d (n=%d): %s differs" % (G, t, i, SIZES[i], k)
 
 
+def shard_views(coat, dev, G, world):
+    """Every tensor cut into `world` contiguous shards at multiples of G (coat_shard_range), as views
+    of the same device memory: what the ranks of a ZeRO-style partition would each hand to the step."""
+    out = []
+    for d in dev:
+        n = d["w"].numel()
+        covered = 0
+        for rank in range(world):
+            b, e = coat.coat_shard_range(n, G, rank, world)
+            assert b == covered and (b % (2 * G) == 0 or b == n) and (e % (2 * G) == 0 or e == n)
+            covered = e
+            gb, ge = (b // G, (e + G - 1) // G) if e > b else (0, 0)
+            v = dict(weight_decay=d["weight_decay"])
+            for k in ("w", "grad", "m_q", "v_q", "w_bf16"):
+                if k in d:
+                    v[k] = d[k][b:e]
+            for k in ("m_scale", "m_k", "v_scale", "v_k"):
+                v[k] = d[k][gb:ge]
+            out.append(v)
+        assert covered == n
+    return out
+
+
+@pytest.mark.parametrize("world", [2, 3, 8])
+@pytest.mark.parametrize("G,bf16_scale", [(32, False), (128, False), (512, False), (64, True)])
+def test_sharded_plan_equals_unsharded(coat, G, bf16_scale, world):
+    """The optimizer state partitioned over `world` ranks (Sec. 2 places this step next to ZeRO-style
+    sharding): all shards of all tensors as entries of ONE plan, one launch, against the unsharded
+    plan, bit for bit, over three steps.  Groups never straddle a cut, so nothing else is acceptable."""
+    host = make_tensors(G, seed=31, with_bf16=(4, 7))
+    a, b = to_device(host, bf16_scale), to_device(host, bf16_scale)
+    whole = coat.MultiPlan(a, G)
+    shards = shard_views(coat, b, G, world)
+    assert len(shards) == world * len(SIZES)
+    cut = coat.MultiPlan(shards, G)
+    for t in (1, 2, 3):
+        grads = [S.grads_lognormal(h["w"].size, 90 + i, t) if i % 3 == 0 else S.grads_normal(h["w"].size, 90 + i, t, G=G)
+                 for i, h in enumerate(host)]
+        set_grads(a, grads)
+        set_grads(b, grads)
+        hp = coat.make_hparams(step=t, group_size=G, bf16_scale=bf16_scale, **HP)
+        coat.coat_fp8_adamw_step_multi(whole, hp)
+        coat.coat_fp8_adamw_step_multi(cut, hp)
+        torch.cuda.synchronize()
+        for i, (da, db) in enumerate(zip(a, b)):
+            for k in KEYS:
+                if k in da:
+                    assert raw(da[k]) == raw(db[k]), "G=%d world=%d step %d tensor %d (n=%d): %s differs" % (
+                        G, world, t, i, SIZES[i], k)
+
+
 def test_multi_against_oracle(coat, ref):
     """Three lock-step steps from the zero state (both sides restart every step from the oracle's
     state), every tensor checked against the oracle with the rules of the single-tensor parity tests."""
@@ -169,7 +220,7 @@ def test_full_size_multi_equals_flat(coat, workload):
     n = sum(sizes)
     free, _ = torch.cuda.mem_get_info()
     if free < n * 18 + (1 << 31):
-        pytest.skip("needs %.0f GB of device memory" % (n * 18 / 1e9))
+        pytest.fail("needs %.0f GB of device memory, %.0f GB free" % (n * 18 / 1e9, free / 1e9))
     gen = S.torch_generator(dev, 3)
     w = S.torch_weights(n, dev, gen)
     g = S.torch_grads_normal(n, dev, gen, G=G, outlier_mask=S.torch_outlier_group_mask(n // G, dev, gen, 0.01))

@@ -57,3 +57,26 @@ def test_log2_tables_match_the_formats():
     assert math.isnan(t43[0x7F][0])
     check(t52, e5m2, 57344.0, 0x7B)
     assert t52[0x7C][0] == math.inf and all(math.isnan(t52[c][0]) for c in (0x7D, 0x7E, 0x7F))
+
+
+def test_committed_tables_are_what_the_generator_writes():
+    import importlib.util
+    path = os.path.join(ROOT, "paper_2410_19313_amd", "csrc", "make_tables.py")
+    spec = importlib.util.spec_from_file_location("make_tables", path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    assert open(mod.OUT).read() == mod.render(), "coat_tables.inc is stale: run make_tables.py"
+
+
+def test_exp2_fraction_table_is_correctly_rounded():
+    # kExp2Frac512[j] is the double nearest to 2^(j/512): with h half an ulp of v, exactly,
+    # (v - h)^512 <= 2^j <= (v + h)^512 in rational arithmetic
+    from fractions import Fraction
+    text = open(os.path.join(ROOT, "paper_2410_19313_amd", "csrc", "coat_tables.inc")).read()
+    body = text[text.index("kExp2Frac512[kExp2FracSize]"):]
+    vals = [float.fromhex(t) for t in re.findall(r"-?0x[0-9a-f.]+p[+-]?\d+", body)]
+    assert len(vals) == 512 and vals[0] == 1.0
+    for j, v in enumerate(vals):
+        assert 1.0 <= v < 2.0
+        h = Fraction(1, 2 ** 53)                          # half an ulp of a double in [1, 2)
+        assert (Fraction(v) - h) ** 512 <= Fraction(2) ** j <= (Fraction(v) + h) ** 512, j
