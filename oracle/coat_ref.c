@@ -126,7 +126,19 @@ static float bf16_ceil(float s) {
   return cvt.f;
 }
 
-static void quant_one_group(const float* x, uint64_t len, int expand, fmt_t f, int scale16,
+/* Largest bf16 value that is not above k (k > 0 and finite): the exponent "stored in BF16" like the
+ * scale.  Rounding DOWN keeps R_X^k <= R_format: the expanded group stays inside the format's range,
+ * its smallest element at or above the smallest subnormal (rounding up would put it below). */
+static float bf16_floor(float k) {
+  /* bf16 keeps 8 significant bits: for k = m * 2^e with 1/2 <= m < 1 its values are the multiples of 2^(e-8) */
+  int e;
+  double quantum;
+  (void)frexp((double)k, &e);
+  quantum = ldexp(1.0, e - 8);
+  return (float)(floor((double)k / quantum) * quantum);
+}
+
+static void quant_one_group(const float* x, uint64_t len, int expand, fmt_t f, int scale16, int k16,
                             float k_min, float k_max,
                             uint8_t* q, float* scale_out, float* k_out) {
   double amax = 0.0, amin = INFINITY, top;
@@ -162,6 +174,7 @@ static void quant_one_group(const float* x, uint64_t len, int expand, fmt_t f, i
     if (kd < (double)k_min) kd = (double)k_min;
     if (kd > (double)k_max) kd = (double)k_max;
     k = (float)kd;
+    if (k16) k = bf16_floor(k);                  /* after the clamp; the quantizer below uses the stored value */
   }
   /* Quantize with the STORED scale and k so that Q and DQ agree.  The expanded group is
    * f(x / a) with a = fmax * scale ~= amax, whose largest element is 1, so the plain
@@ -204,7 +217,8 @@ void coat_ref_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags,
     uint64_t lo = (uint64_t)gi * (uint64_t)G;
     uint64_t len = (n - lo < (uint64_t)G) ? n - lo : (uint64_t)G;
     quant_one_group(x + lo, len, (flags & COAT_REF_FLAG_EXPAND) != 0, fmt_of((flags & COAT_REF_FLAG_E5M2) != 0),
-                    (flags & COAT_REF_FLAG_BF16_SCALE) != 0, k_min, k_max, q + lo, scale + gi, k + gi);
+                    (flags & COAT_REF_FLAG_BF16_SCALE) != 0, (flags & COAT_REF_FLAG_BF16_K) != 0, k_min, k_max,
+                    q + lo, scale + gi, k + gi);
   }
 }
 
@@ -334,7 +348,7 @@ int coat_ref_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* gr
   float k_min, k_max;
   int32_t G;
   int64_t ng, gi;
-  int failed = 0, expand_m, expand_v, scale16;
+  int failed = 0, expand_m, expand_v, scale16, k16;
   fmt_t fm, fv;
 
   if (!hp) return -1;
@@ -355,6 +369,7 @@ int coat_ref_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* gr
   expand_m = (hp->flags & COAT_REF_FLAG_EXPAND) && !(hp->flags & COAT_REF_FLAG_M_PLAIN);
   expand_v = (hp->flags & COAT_REF_FLAG_EXPAND) && !(hp->flags & COAT_REF_FLAG_V_PLAIN);
   scale16 = (hp->flags & COAT_REF_FLAG_BF16_SCALE) != 0;
+  k16 = (hp->flags & COAT_REF_FLAG_BF16_K) != 0;
 
 #pragma omp parallel for schedule(static)
   for (gi = 0; gi < ng; ++gi) {
@@ -391,8 +406,8 @@ int coat_ref_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* gr
     }
 
     /* m^q_t, S = Q(m_t);  v^q_t, S = Q(v_t) */
-    quant_one_group(mt, len, expand_m, fm, scale16, k_min, k_max, m_q + lo, m_scale + gi, m_k + gi);
-    quant_one_group(vt, len, expand_v, fv, scale16, k_min, k_max, v_q + lo, v_scale + gi, v_k + gi);
+    quant_one_group(mt, len, expand_m, fm, scale16, k16, k_min, k_max, m_q + lo, m_scale + gi, m_k + gi);
+    quant_one_group(vt, len, expand_v, fv, scale16, k16, k_min, k_max, v_q + lo, v_scale + gi, v_k + gi);
     free(m); free(mt);
   }
   return failed ? -1 : 0;

@@ -42,6 +42,11 @@ typedef struct {
 #define COAT_REF_FLAG_BF16_SCALE 32u /* scales are stored in BF16 (Sec. 3): rounded UP to a bf16 value, which
                                         the quantizer then uses; k from (fmax * scale) / amin.  The arrays
                                         stay float here; every value in them is a bf16. */
+#define COAT_REF_FLAG_BF16_K 64u     /* the exponents k are stored in BF16 as well (Sec. 4.2 computes k per group
+                                        and step and keeps it beside the scale, whose storage Sec. 3 gives as BF16):
+                                        rounded DOWN to a bf16 value after the clamp, so that R_X^k <= R_format still
+                                        holds (the smallest element stays at or above the smallest subnormal); the
+                                        quantizer uses the stored value.  The arrays stay float here; every value in them is a bf16. */
 
 /* OCP FP8 E4M3 ("FN"): 1-4-3 bits, bias 7, no infinity, 0x7F/0xFF are NaN, largest
  * finite 448 and smallest positive 2^-9 (the two constants Sec. 3 prints). */

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "coat_ref.c")
 _LIB = os.path.join(_HERE, "libcoat_ref.so")
 
-FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN, FLAG_BF16_SCALE = 1, 2, 2, 4, 8, 16, 32
+FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN, FLAG_BF16_SCALE, FLAG_BF16_K = 1, 2, 2, 4, 8, 16, 32, 64
 
 
 class HParams(ctypes.Structure):
@@ -125,9 +125,9 @@ def e5m2_encode(q: float) -> int:
 
 
 def quant_group(x: np.ndarray, G: int, expand: bool = True, k_min: float = 0.0, k_max: float = 0.0,
-                e5m2: bool = False, bf16_scale: bool = False):
+                e5m2: bool = False, bf16_scale: bool = False, bf16_k: bool = False):
     """x: fp32 array (flattened).  Returns (codes u8 [n], scale f32 [ng], k f32 [ng]).
-    bf16_scale: the scales are bf16 values (held in the float array)."""
+    bf16_scale / bf16_k: the scales / exponents are bf16 values (held in the float arrays)."""
     x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
     n = x.size
     ng = n_groups(n, G)
@@ -137,7 +137,8 @@ def quant_group(x: np.ndarray, G: int, expand: bool = True, k_min: float = 0.0, 
     if n:
         lib().coat_ref_quant_group(_ptr(x, np.float32, ctypes.c_float), n, G,
                                    (FLAG_EXPAND if expand else 0) | (FLAG_E5M2 if e5m2 else 0)
-                                   | (FLAG_BF16_SCALE if bf16_scale else 0), k_min, k_max,
+                                   | (FLAG_BF16_SCALE if bf16_scale else 0) | (FLAG_BF16_K if bf16_k else 0),
+                                   k_min, k_max,
                                    _ptr(q, np.uint8, ctypes.c_uint8),
                                    _ptr(scale, np.float32, ctypes.c_float),
                                    _ptr(k, np.float32, ctypes.c_float))
@@ -195,17 +196,18 @@ def act_quant_tensor(x_bf16: np.ndarray, G: int):
     return q, float(ts[0]), amax
 
 
-def step_flags(expand=True, m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False) -> int:
+def step_flags(expand=True, m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False,
+               bf16_k=False) -> int:
     return ((FLAG_EXPAND if expand else 0) | (FLAG_M_E5M2 if m_e5m2 else 0) | (FLAG_V_E5M2 if v_e5m2 else 0)
             | (FLAG_M_PLAIN if m_plain else 0) | (FLAG_V_PLAIN if v_plain else 0)
-            | (FLAG_BF16_SCALE if bf16_scale else 0))
+            | (FLAG_BF16_SCALE if bf16_scale else 0) | (FLAG_BF16_K if bf16_k else 0))
 
 
 def make_hparams(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1,
                  group_size=128, expand=True, k_min=0.0, k_max=0.0,
-                 m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False) -> HParams:
+                 m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False, bf16_k=False) -> HParams:
     return HParams(lr, beta1, beta2, eps, weight_decay, int(step), int(group_size),
-                   step_flags(expand, m_e5m2, v_e5m2, m_plain, v_plain, bf16_scale), k_min, k_max)
+                   step_flags(expand, m_e5m2, v_e5m2, m_plain, v_plain, bf16_scale, bf16_k), k_min, k_max)
 
 
 def fp8_adamw_step(w, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, hp: HParams, w_bf16=None) -> int:

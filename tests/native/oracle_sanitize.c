@@ -48,7 +48,7 @@ static int one_size(uint64_t n, int32_t G, uint32_t flags) {
     w[i] = rnd_float(0.05f);
   }
   for (i = 0; i < ng; ++i) mk[i] = vk[i] = 1.0f;
-  coat_ref_quant_group(x, n, G, flags & (COAT_REF_FLAG_EXPAND | COAT_REF_FLAG_E5M2 | COAT_REF_FLAG_BF16_SCALE), 0.0f, 0.0f, q, s, k);
+  coat_ref_quant_group(x, n, G, flags & (COAT_REF_FLAG_EXPAND | COAT_REF_FLAG_E5M2 | COAT_REF_FLAG_BF16_SCALE | COAT_REF_FLAG_BF16_K), 0.0f, 0.0f, q, s, k);
   coat_ref_dequant_group(q, s, k, n, G, flags & COAT_REF_FLAG_E5M2, x);
   coat_ref_dequant_group_f64(q, s, k, n, G, flags & COAT_REF_FLAG_E5M2, x64);
   for (t = 1; t <= 3; ++t) {
@@ -72,7 +72,7 @@ int main(void) {
   static const uint32_t flag_sets[] = {
       COAT_REF_FLAG_EXPAND, 0u, COAT_REF_FLAG_EXPAND | COAT_REF_FLAG_M_E5M2 | COAT_REF_FLAG_V_E5M2,
       COAT_REF_FLAG_EXPAND | COAT_REF_FLAG_M_PLAIN, COAT_REF_FLAG_EXPAND | COAT_REF_FLAG_V_PLAIN | COAT_REF_FLAG_V_E5M2,
-      COAT_REF_FLAG_EXPAND | COAT_REF_FLAG_BF16_SCALE};
+      COAT_REF_FLAG_EXPAND | COAT_REF_FLAG_BF16_SCALE, COAT_REF_FLAG_EXPAND | COAT_REF_FLAG_BF16_SCALE | COAT_REF_FLAG_BF16_K};
   size_t a, b, c;
   int code;
   for (code = 0; code < 256; ++code) {

@@ -1,0 +1,129 @@
+"""Pins for the oracle's BF16-exponent option.  Sec. 4.2 computes the expansion exponent k for every
+group at every step and keeps it with the group's scale, whose storage Sec. 3 gives as BF16.
+Reading taken: the stored k is the clamped fp32 exponent rounded DOWN to a bf16 value, and the
+quantizer and the dequantizer both use that stored value.  Rounding down keeps R_X^k <= R_format: the
+expanded group stays inside the format's range, its smallest element at or above the smallest
+subnormal.  No GPU needed."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+
+HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+FMT = {False: (448.0, 2.0 ** -9), True: (57344.0, 2.0 ** -16)}
+
+
+def groups(n, G, seed, spread=3.0):
+    rng = np.random.default_rng(seed)
+    scale = np.exp(rng.normal(0.0, 2.0, n // G))[:, None]
+    x = scale * 1e-3 * np.exp(rng.uniform(0.0, spread, (n // G, G))) * rng.choice([-1.0, 1.0], (n // G, G))
+    return x.astype(np.float32).reshape(-1)
+
+
+def bf16_floor_by_torch(k):
+    """Independent route to 'the largest bf16 that is not above k' (k > 0): torch's nearest-even cast,
+    lowered by one bf16 step where it came out above."""
+    t = torch.from_numpy(np.asarray(k, dtype=np.float32))
+    b = t.to(torch.bfloat16)
+    high = b.to(torch.float32) > t
+    bits = b.view(torch.int16).to(torch.int32) - high.to(torch.int32)     # positive values: next bf16 down
+    return bits.to(torch.int16).view(torch.bfloat16).to(torch.float32).numpy()
+
+
+def test_closed_form_two_magnitudes(ref):
+    # a group of a and a * 2^-j: R_X = 2^j, k = log2(448 * 512) / j, stored as its bf16 floor
+    G = 32
+    for j, a in ((1, 3e-4), (3, 1.0), (7, 2e-6), (17, 5.0), (30, 1e-2)):
+        x = np.full(G, a, np.float32)
+        x[5::2] = np.float32(a) * np.float32(2.0 ** -j)
+        q, s, k = ref.quant_group(x, G, bf16_k=True)
+        exact = math.log2(448.0 * 512.0) / j
+        assert k[0] == bf16_floor_by_torch([np.float32(exact)])[0]
+        assert exact * (1 - 2.0 ** -7) < k[0] <= exact
+        # the largest elements get the largest code, the smallest a non-zero code
+        assert np.all((q[x == x.max()] & 0x7F) == 0x7E) and np.all((q[x == x.min()] & 0x7F) >= 1)
+
+
+@pytest.mark.parametrize("e5m2", [False, True])
+@pytest.mark.parametrize("bf16_scale", [False, True])
+def test_stored_k_is_the_bf16_floor_and_nothing_flushes(ref, e5m2, bf16_scale):
+    fmax, fmin = FMT[e5m2]
+    n, G = 512 * 128, 128
+    x = groups(n, G, 2, spread=6.0)
+    q, s, k = ref.quant_group(x, G, e5m2=e5m2, bf16_scale=bf16_scale, bf16_k=True)
+    q0, s0, k0 = ref.quant_group(x, G, e5m2=e5m2, bf16_scale=bf16_scale)
+    assert np.array_equal(s, s0)                                          # the scale does not depend on how k is stored
+    assert np.all(k.view(np.uint32) & 0xFFFF == 0)                        # a bf16 value
+    assert np.array_equal(k, bf16_floor_by_torch(k0))                     # ... the floor of the fp32 exponent
+    assert np.all(k <= k0) and np.all(k > k0 * (1 - 2.0 ** -7))
+    # no flush: every non-zero input keeps a non-zero code (k is not on its lower clamp here)
+    assert np.all(k0 > 0.0625)
+    assert np.all((q & 0x7F) != 0)
+    # while rounding UP would overshoot the format's range: with the next bf16 above, the smallest
+    # element of most groups falls below the smallest subnormal
+    k_up = (k.view(np.uint32) + np.uint32(0x10000)).view(np.float32).astype(np.float64)
+    ax = np.abs(x.astype(np.float64)).reshape(-1, G)
+    top = fmax * s.astype(np.float64)
+    low = fmax * (ax.min(1) / top) ** k_up
+    assert np.mean(low < fmin) > 0.5
+    assert np.all(fmax * (ax.min(1) / top) ** k.astype(np.float64) >= fmin * (1 - 1e-6))
+
+
+@pytest.mark.parametrize("G", [32, 128])
+def test_round_trip_with_the_stored_exponent(ref, G):
+    # DQ(Q(x)) with the stored (bf16) k: a value between two normal codes (3 mantissa bits) moves by at
+    # most half a code step, 2^-4 relative, in the expanded domain: 1 - (1 - 2^-4)^(1/k) on the way back
+    n = 256 * G
+    x = groups(n, G, 3)
+    q, s, k = ref.quant_group(x, G, bf16_k=True)
+    back = ref.dequant_group(q, s, k, G, f64=True)
+    kk = np.repeat(k.astype(np.float64), G)
+    normal = (q & 0x7F) >= 9                                            # the value itself was at or above the smallest normal
+    rel = np.abs(back / x.astype(np.float64) - 1.0)
+    assert np.all(rel[normal] <= (1.0 - (1.0 - 2.0 ** -4) ** (1.0 / kk[normal])) * (1 + 1e-6) + 1e-6)
+    assert np.all(np.sign(back) == np.sign(x))
+    # the same codes dequantized with the unrounded exponent would be off by the rounding of k
+    q0, s0, k0 = ref.quant_group(x, G)
+    moved = ref.dequant_group(q, s, k0, G, f64=True)
+    assert np.mean(np.abs(moved / x.astype(np.float64) - 1.0)[normal]) > 1.05 * np.mean(rel[normal])
+
+
+def test_clamped_and_trivial_groups(ref):
+    G = 32
+    x = np.full(3 * G, 1e-3, np.float32)
+    x[G + 1] = np.nextafter(np.float32(1e-3), np.float32(1))             # R barely above 1: k on its upper clamp
+    x[2 * G: 3 * G] = 0.0
+    x[2 * G + 3] = 7.0
+    x[2 * G + 4] = 7.0e-30                                                # R = 1e30: k = 0.1786, below a lower clamp of 0.3
+    q, s, k = ref.quant_group(x, G, bf16_k=True)
+    assert k[0] == 1.0 and k[1] == 1024.0                                 # 1 and the default upper clamp: bf16 values already
+    assert k[2] == bf16_floor_by_torch([np.float32(math.log2(448.0 * 512.0) / math.log2(1e30))])[0]
+    q, s, k = ref.quant_group(x, G, bf16_k=True, k_min=0.3, k_max=777.7)  # bounds that are no bf16 values
+    assert k[1] == bf16_floor_by_torch([np.float32(777.7)])[0] and k[2] == bf16_floor_by_torch([np.float32(0.3)])[0]
+    # without expansion k is 1 whatever the flag says
+    q, s, k = ref.quant_group(x, G, expand=False, bf16_k=True)
+    assert np.all(k == 1.0)
+
+
+def test_step_stores_bf16_exponents_for_both_moments(ref):
+    n, G = 64 * 128 + 40, 128
+    w = S.weights(n, 1)
+    st = S.zero_state(n, G)
+    st0 = {key: v.copy() for key, v in st.items()}
+    w0 = w.copy()
+    for t in (1, 2, 3):
+        g = S.grads_normal(n, 1, t, G=G, outlier_frac=0.02)
+        assert ref.fp8_adamw_step(w, g, st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"],
+                                  ref.make_hparams(step=t, group_size=G, bf16_k=True, **HP)) == 0
+        assert ref.fp8_adamw_step(w0, g, st0["m_q"], st0["m_scale"], st0["m_k"], st0["v_q"], st0["v_scale"], st0["v_k"],
+                                  ref.make_hparams(step=t, group_size=G, **HP)) == 0
+        for name in ("m_k", "v_k"):
+            assert np.all(st[name].view(np.uint32) & 0xFFFF == 0)
+            if t == 1:                                                    # same inputs on both sides at the first step
+                assert np.array_equal(st[name], bf16_floor_by_torch(st0[name]))
+        assert np.all(st["v_q"] < 0x80)
+    # the trajectories stay close: the stored exponent moves a dequantized value by less than its own quantization step
+    assert np.max(np.abs(w - w0)) < 1e-4
