@@ -57,8 +57,13 @@ extern "C" {
                                     fp32, as Sec. 3 stores them.  The scale is amax/fmax rounded UP to
                                     a bf16 value, quantizer and dequantizer both use the stored value,
                                     and k is chosen from (fmax*scale)/amin, the range the normalized
-                                    group really spans.  k stays fp32.  Resident state: 8 + 12/G
-                                    bytes per parameter instead of 8 + 16/G. */
+                                    group really spans.  Resident state: 8 + 12/G bytes per parameter
+                                    instead of 8 + 16/G. */
+#define COAT_FLAG_BF16_K  64u  /* the per-group exponent arrays hold bf16 (uint16_t) values too: Sec. 4.2
+                                  computes k per group and step and keeps it beside the scale.  The
+                                  stored k is the clamped exponent rounded DOWN to a bf16 value (so that
+                                  R_X^k <= R_format still holds) and quantizer and dequantizer both use
+                                  the stored value.  With both flags: 8 + 8/G bytes per parameter. */
 
 /* Hyper-parameters of one step: symbols of Sec. 3, Eq. (1). */
 typedef struct {
@@ -88,7 +93,8 @@ typedef struct {
  * grad_bf16  [n]   bf16 gradients (raw 16-bit patterns), read only.
  * m_q, v_q   [n]   E4M3 codes of the first and second moment, updated in place.
  * m_scale, m_k, v_scale, v_k  [ceil(n/G)]  per-group scale and exponent, in place: fp32, except that
- *              with COAT_FLAG_BF16_SCALE the two scale arrays hold bf16 (uint16_t) values.
+ *              with COAT_FLAG_BF16_SCALE the two scale arrays, and with COAT_FLAG_BF16_K the two
+ *              exponent arrays, hold bf16 (uint16_t) values.
  * With COAT_FLAG_*_E5M2 the constants 448 and 448*512 become 57344 and 57344*65536 for that
  * moment; a moment stored without expansion uses the plain quantizer of Sec. 3 (code =
  * round(x/scale), x = scale*code), writes k = 1 and does not read k.
@@ -101,8 +107,8 @@ typedef struct {
  * the smallest normal fp32 number is stored as the zero state (codes 0, scale 0, k 1).
  */
 int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
-                        uint8_t* m_q, void* m_scale, float* m_k,
-                        uint8_t* v_q, void* v_scale, float* v_k,
+                        uint8_t* m_q, void* m_scale, void* m_k,
+                        uint8_t* v_q, void* v_scale, void* v_k,
                         uint64_t n, const coat_adamw_hparams* hp, void* hip_stream);
 
 /*
@@ -113,8 +119,8 @@ int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16,
  * and must not overlap the other buffers; NULL makes this call identical to coat_fp8_adamw_step.
  */
 int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_bf16,
-                              uint8_t* m_q, void* m_scale, float* m_k,
-                              uint8_t* v_q, void* v_scale, float* v_k,
+                              uint8_t* m_q, void* m_scale, void* m_k,
+                              uint8_t* v_q, void* v_scale, void* v_k,
                               uint64_t n, const coat_adamw_hparams* hp, void* hip_stream);
 
 /*
@@ -146,8 +152,8 @@ typedef struct {
   float*          w;
   uint16_t*       w_bf16;        /* optional bf16 copy of the new weights, or NULL */
   const uint16_t* grad_bf16;
-  uint8_t*        m_q;  void*  m_scale;  float* m_k;   /* scales: float[], or uint16_t[] with COAT_FLAG_BF16_SCALE */
-  uint8_t*        v_q;  void*  v_scale;  float* v_k;
+  uint8_t*        m_q;  void*  m_scale;  void*  m_k;   /* float[]; uint16_t[] (bf16) with COAT_FLAG_BF16_SCALE / _K */
+  uint8_t*        v_q;  void*  v_scale;  void*  v_k;
   uint64_t        n;
   float           weight_decay;  /* lambda of this tensor */
   uint32_t        reserved;      /* set to 0 */
@@ -205,20 +211,21 @@ int coat_shard_range(uint64_t n, int32_t G, uint32_t rank, uint32_t world, uint6
  * Per-group quantizer with dynamic range expansion (Sec. 3 quantizer Q applied to f(X),
  * Sec. 4.2): the second half of the step on its own.
  * x [n] fp32 in;  q [n] codes, scale/k [ceil(n/G)] out.  All-zero group: scale 0, k 1.
- * flags: COAT_FLAG_EXPAND, COAT_FLAG_E5M2, COAT_FLAG_BF16_SCALE (scale then is uint16_t[]).
+ * flags: COAT_FLAG_EXPAND, COAT_FLAG_E5M2, COAT_FLAG_BF16_SCALE (scale then is uint16_t[]),
+ * COAT_FLAG_BF16_K (k then is uint16_t[]).
  */
 int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags,
                      float k_min, float k_max,
-                     uint8_t* q, void* scale, float* k, void* hip_stream);
+                     uint8_t* q, void* scale, void* k, void* hip_stream);
 
 /*
  * Dequantizer followed by the inverse expansion (Sec. 3 DQ, Sec. 4.2 f^-1): the first half
  * of the step on its own.  x = sign(c) * (448*scale) * (|c|/448)^(1/k), c = decode(code).
  * The stored k is always honoured (it is 1 for codes written without expansion).
  * flags: COAT_FLAG_E5M2 selects the format (57344 replaces 448); COAT_FLAG_BF16_SCALE says that
- * scale is uint16_t[] (bf16); COAT_FLAG_EXPAND is accepted and ignored.
+ * scale is uint16_t[] (bf16), COAT_FLAG_BF16_K the same of k; COAT_FLAG_EXPAND is accepted and ignored.
  */
-int coat_dequant_group(const uint8_t* q, const void* scale, const float* k,
+int coat_dequant_group(const uint8_t* q, const void* scale, const void* k,
                        uint64_t n, int32_t G, uint32_t flags, float* x, void* hip_stream);
 
 /*

@@ -12,7 +12,7 @@ import os
 
 from . import build as _build
 
-FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN, FLAG_BF16_SCALE = 1, 2, 2, 4, 8, 16, 32
+FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN, FLAG_BF16_SCALE, FLAG_BF16_K = 1, 2, 2, 4, 8, 16, 32, 64
 SUPPORTED_GROUP_SIZES = (32, 64, 128, 256, 512)
 
 ACT_GROUP_SIZES = (16,) + SUPPORTED_GROUP_SIZES
@@ -67,10 +67,11 @@ class StepConsts(ctypes.Structure):
                 ("reserved", ctypes.c_uint64 * 2)]
 
 
-def step_flags(expand=True, m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False) -> int:
+def step_flags(expand=True, m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False,
+               bf16_k=False) -> int:
     return ((FLAG_EXPAND if expand else 0) | (FLAG_M_E5M2 if m_e5m2 else 0) | (FLAG_V_E5M2 if v_e5m2 else 0)
             | (FLAG_M_PLAIN if m_plain else 0) | (FLAG_V_PLAIN if v_plain else 0)
-            | (FLAG_BF16_SCALE if bf16_scale else 0))
+            | (FLAG_BF16_SCALE if bf16_scale else 0) | (FLAG_BF16_K if bf16_k else 0))
 
 
 def _scale_dtype(flags: int):
@@ -78,11 +79,16 @@ def _scale_dtype(flags: int):
     return torch.bfloat16 if flags & FLAG_BF16_SCALE else torch.float32
 
 
+def _k_dtype(flags: int):
+    import torch
+    return torch.bfloat16 if flags & FLAG_BF16_K else torch.float32
+
+
 def make_hparams(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1,
                  group_size=128, expand=True, k_min=0.0, k_max=0.0,
-                 m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False) -> HParams:
+                 m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False, bf16_k=False) -> HParams:
     return HParams(lr, beta1, beta2, eps, weight_decay, int(step), int(group_size),
-                   step_flags(expand, m_e5m2, v_e5m2, m_plain, v_plain, bf16_scale), k_min, k_max)
+                   step_flags(expand, m_e5m2, v_e5m2, m_plain, v_plain, bf16_scale, bf16_k), k_min, k_max)
 
 
 _lib = None
@@ -177,8 +183,8 @@ def coat_fp8_adamw_step(w, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, hp: 
     ng = n_groups(n, hp.group_size) if hp.group_size > 0 else 0
     _check(lib().coat_fp8_adamw_step(
         _dev_ptr(w, torch.float32), _dev_ptr(grad_bf16, torch.bfloat16, n),
-        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, _scale_dtype(hp.flags), ng), _dev_ptr(m_k, torch.float32, ng),
-        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, _scale_dtype(hp.flags), ng), _dev_ptr(v_k, torch.float32, ng),
+        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, _scale_dtype(hp.flags), ng), _dev_ptr(m_k, _k_dtype(hp.flags), ng),
+        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, _scale_dtype(hp.flags), ng), _dev_ptr(v_k, _k_dtype(hp.flags), ng),
         n, ctypes.byref(hp), _stream()))
 
 
@@ -189,8 +195,8 @@ def coat_fp8_adamw_step_bf16w(w, w_bf16, grad_bf16, m_q, m_scale, m_k, v_q, v_sc
     ng = n_groups(n, hp.group_size) if hp.group_size > 0 else 0
     _check(lib().coat_fp8_adamw_step_bf16w(
         _dev_ptr(w, torch.float32), _dev_ptr(w_bf16, torch.bfloat16, n), _dev_ptr(grad_bf16, torch.bfloat16, n),
-        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, _scale_dtype(hp.flags), ng), _dev_ptr(m_k, torch.float32, ng),
-        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, _scale_dtype(hp.flags), ng), _dev_ptr(v_k, torch.float32, ng),
+        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, _scale_dtype(hp.flags), ng), _dev_ptr(m_k, _k_dtype(hp.flags), ng),
+        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, _scale_dtype(hp.flags), ng), _dev_ptr(v_k, _k_dtype(hp.flags), ng),
         n, ctypes.byref(hp), _stream()))
 
 
@@ -202,26 +208,28 @@ def coat_bench_copy_control(w, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, 
     ng = n_groups(n, G)
     _check(lib().coat_bench_copy_control(
         _dev_ptr(w, torch.float32), _dev_ptr(grad_bf16, torch.bfloat16, n),
-        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, torch.float32, ng), _dev_ptr(m_k, torch.float32, ng),
-        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, torch.float32, ng), _dev_ptr(v_k, torch.float32, ng),
+        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, torch.float32, ng), _dev_ptr(m_k, _k_dtype(hp.flags), ng),
+        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, torch.float32, ng), _dev_ptr(v_k, _k_dtype(hp.flags), ng),
         n, G, _stream()))
 
 
 def coat_quant_group(x, G: int, expand: bool = True, k_min: float = 0.0, k_max: float = 0.0,
-                     out=None, e5m2: bool = False, bf16_scale: bool = False):
-    """x fp32 [n] -> (codes uint8 [n], scale fp32 (bfloat16 with bf16_scale) [ng], k fp32 [ng]) on the device."""
+                     out=None, e5m2: bool = False, bf16_scale: bool = False, bf16_k: bool = False):
+    """x fp32 [n] -> (codes uint8 [n], scale fp32 (bfloat16 with bf16_scale) [ng], k fp32 (bfloat16 with bf16_k)
+    [ng]) on the device."""
     import torch
     n = x.numel()
     ng = n_groups(n, G) if G > 0 else 0
-    flags = (FLAG_EXPAND if expand else 0) | (FLAG_E5M2 if e5m2 else 0) | (FLAG_BF16_SCALE if bf16_scale else 0)
+    flags = ((FLAG_EXPAND if expand else 0) | (FLAG_E5M2 if e5m2 else 0) | (FLAG_BF16_SCALE if bf16_scale else 0)
+             | (FLAG_BF16_K if bf16_k else 0))
     if out is None:
         out = (torch.empty(n, dtype=torch.uint8, device=x.device),
                torch.empty(ng, dtype=_scale_dtype(flags), device=x.device),
-               torch.empty(ng, dtype=torch.float32, device=x.device))
+               torch.empty(ng, dtype=_k_dtype(flags), device=x.device))
     q, scale, k = out
     _check(lib().coat_quant_group(_dev_ptr(x, torch.float32), n, G, flags,
                                   k_min, k_max, _dev_ptr(q, torch.uint8, n),
-                                  _dev_ptr(scale, _scale_dtype(flags), ng), _dev_ptr(k, torch.float32, ng),
+                                  _dev_ptr(scale, _scale_dtype(flags), ng), _dev_ptr(k, _k_dtype(flags), ng),
                                   _stream()))
     return q, scale, k
 
@@ -233,9 +241,10 @@ def coat_dequant_group(q, scale, k, G: int, out=None, e5m2: bool = False):
     ng = n_groups(n, G) if G > 0 else 0
     if out is None:
         out = torch.empty(n, dtype=torch.float32, device=q.device)
-    flags = (FLAG_E5M2 if e5m2 else 0) | (FLAG_BF16_SCALE if scale.dtype == torch.bfloat16 else 0)
+    flags = ((FLAG_E5M2 if e5m2 else 0) | (FLAG_BF16_SCALE if scale.dtype == torch.bfloat16 else 0)
+             | (FLAG_BF16_K if k.dtype == torch.bfloat16 else 0))
     _check(lib().coat_dequant_group(_dev_ptr(q, torch.uint8), _dev_ptr(scale, _scale_dtype(flags), ng),
-                                    _dev_ptr(k, torch.float32, ng), n, G, flags,
+                                    _dev_ptr(k, _k_dtype(flags), ng), n, G, flags,
                                     _dev_ptr(out, torch.float32, n), _stream()))
     return out
 
@@ -342,6 +351,8 @@ class MultiPlan:
         descs = []
         sdt = tensors[0]["m_scale"].dtype if tensors else torch.float32     # fp32, or bfloat16 for COAT_FLAG_BF16_SCALE
         self.bf16_scale = sdt == torch.bfloat16
+        kdt = tensors[0]["m_k"].dtype if tensors else torch.float32         # the same for COAT_FLAG_BF16_K
+        self.bf16_k = kdt == torch.bfloat16
         for t in tensors:
             n = t["w"].numel()
             ng = n_groups(n, G)
@@ -351,9 +362,9 @@ class MultiPlan:
                 (_dev_ptr(wb, torch.bfloat16, n).value or 0) if wb is not None else 0,
                 _dev_ptr(t["grad"], torch.bfloat16, n).value or 0,
                 _dev_ptr(t["m_q"], torch.uint8, n).value or 0, _dev_ptr(t["m_scale"], sdt, ng).value or 0,
-                _dev_ptr(t["m_k"], torch.float32, ng).value or 0,
+                _dev_ptr(t["m_k"], kdt, ng).value or 0,
                 _dev_ptr(t["v_q"], torch.uint8, n).value or 0, _dev_ptr(t["v_scale"], sdt, ng).value or 0,
-                _dev_ptr(t["v_k"], torch.float32, ng).value or 0,
+                _dev_ptr(t["v_k"], kdt, ng).value or 0,
                 n, float(t.get("weight_decay", 0.0)), 0))
         self.tensors = list(tensors)
         self.group_size = G
@@ -368,8 +379,8 @@ def coat_fp8_adamw_step_multi(plan: MultiPlan, hp: HParams) -> None:
     each tensor carries its own)."""
     if hp.group_size != plan.group_size:
         raise ValueError("the plan's metadata buffers were sized for G=%d" % plan.group_size)
-    if bool(hp.flags & FLAG_BF16_SCALE) != plan.bf16_scale:
-        raise ValueError("COAT_FLAG_BF16_SCALE must match the dtype of the plan's scale tensors")
+    if bool(hp.flags & FLAG_BF16_SCALE) != plan.bf16_scale or bool(hp.flags & FLAG_BF16_K) != plan.bf16_k:
+        raise ValueError("COAT_FLAG_BF16_SCALE / _K must match the dtypes of the plan's scale and k tensors")
     _check(lib().coat_fp8_adamw_step_multi(ctypes.cast(plan._host_buf, ctypes.c_void_p),
                                            ctypes.c_void_p(plan.device.data_ptr()), ctypes.byref(hp), _stream()))
 
@@ -397,8 +408,8 @@ def coat_fp8_adamw_step_multi_consts(plan: MultiPlan, hp: HParams, consts) -> No
     import torch
     if hp.group_size != plan.group_size:
         raise ValueError("the plan's metadata buffers were sized for G=%d" % plan.group_size)
-    if bool(hp.flags & FLAG_BF16_SCALE) != plan.bf16_scale:
-        raise ValueError("COAT_FLAG_BF16_SCALE must match the dtype of the plan's scale tensors")
+    if bool(hp.flags & FLAG_BF16_SCALE) != plan.bf16_scale or bool(hp.flags & FLAG_BF16_K) != plan.bf16_k:
+        raise ValueError("COAT_FLAG_BF16_SCALE / _K must match the dtypes of the plan's scale and k tensors")
     _check(lib().coat_fp8_adamw_step_multi_consts(ctypes.cast(plan._host_buf, ctypes.c_void_p),
                                                   ctypes.c_void_p(plan.device.data_ptr()), ctypes.byref(hp),
                                                   _dev_ptr(consts, torch.uint8, ctypes.sizeof(StepConsts)), _stream()))

@@ -30,13 +30,16 @@ struct StaticMode {
   __device__ __forceinline__ bool e5m2() const { return E5M2; }
   __device__ __forceinline__ bool expand() const { return EXPAND; }
   __device__ __forceinline__ bool scale16() const { return false; }
+  __device__ __forceinline__ bool k16() const { return false; }
 };
 struct RuntimeMode {
   bool e5, ex;
   bool s16;   // the per-group scales are stored as bf16 (Sec. 3) instead of fp32
+  bool kh;    // the per-group exponents k are stored as bf16 as well
   __device__ __forceinline__ bool e5m2() const { return e5; }
   __device__ __forceinline__ bool expand() const { return ex; }
   __device__ __forceinline__ bool scale16() const { return s16; }
+  __device__ __forceinline__ bool k16() const { return kh; }
 };
 typedef StaticMode<false, true> DefaultMode;
 
@@ -102,29 +105,42 @@ struct DequantArgs {
 __device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
 
-// Per-group scale i of an array that holds fp32 or, with scale16, bf16 values (the pointer is typed
-// float* either way).  A stored bf16 scale is exact: the quantizer rounded it before using it.
-template <class Mode>
-__device__ __forceinline__ float load_scale(const Mode& md, const float* p, uint64_t i) {
-  if (md.scale16()) return as_f32(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(p)[i]) << 16);
+// Per-group word i of an array that holds fp32 or, with `half16`, bf16 values (the pointer is typed
+// float* either way): the scales and the exponents k.  A stored bf16 value is exact: the quantizer
+// rounded it before using it.
+__device__ __forceinline__ float load_meta(bool half16, const float* p, uint64_t i) {
+  if (half16) return as_f32(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(p)[i]) << 16);
   return p[i];
 }
 // The same for group gl of a FULL chunk whose first group is gb, without control flow: one dword
 // load serves both layouts (a branch here costs the kernel its overlap of loads: the compiler
 // drains the load counter where the two sides meet; measured 17.3 ms against 15.9).  A chunk holds
-// an even number of groups starting at an even index, so the dword is inside the chunk's scales.
-template <class Mode>
-__device__ __forceinline__ float load_scale_full_chunk(const Mode& md, const float* p, uint64_t gb, int gl) {
-  const bool s16 = md.scale16();
-  const uint32_t w = reinterpret_cast<const uint32_t*>(p)[s16 ? (gb + gl) >> 1 : gb + gl];
+// an even number of groups starting at an even index, so the dword is inside the chunk's words.
+__device__ __forceinline__ float load_meta_full_chunk(bool half16, const float* p, uint64_t gb, int gl) {
+  const uint32_t w = reinterpret_cast<const uint32_t*>(p)[half16 ? (gb + gl) >> 1 : gb + gl];
   const uint32_t half = (gl & 1) ? (w & 0xffff0000u) : (w << 16);
-  return as_f32(s16 ? half : w);
+  return as_f32(half16 ? half : w);
 }
-template <class Mode>
-__device__ __forceinline__ void store_scale(const Mode& md, float* p, uint64_t i, float s) {
-  if (md.scale16()) reinterpret_cast<uint16_t*>(p)[i] = static_cast<uint16_t>(as_u32(s) >> 16);
+__device__ __forceinline__ void store_meta(bool half16, float* p, uint64_t i, float s) {
+  if (half16) reinterpret_cast<uint16_t*>(p)[i] = static_cast<uint16_t>(as_u32(s) >> 16);
   else p[i] = s;
 }
+template <class Mode>
+__device__ __forceinline__ float load_scale(const Mode& md, const float* p, uint64_t i) { return load_meta(md.scale16(), p, i); }
+template <class Mode>
+__device__ __forceinline__ float load_scale_full_chunk(const Mode& md, const float* p, uint64_t gb, int gl) {
+  return load_meta_full_chunk(md.scale16(), p, gb, gl);
+}
+template <class Mode>
+__device__ __forceinline__ void store_scale(const Mode& md, float* p, uint64_t i, float s) { store_meta(md.scale16(), p, i, s); }
+template <class Mode>
+__device__ __forceinline__ float load_k(const Mode& md, const float* p, uint64_t i) { return load_meta(md.k16(), p, i); }
+template <class Mode>
+__device__ __forceinline__ float load_k_full_chunk(const Mode& md, const float* p, uint64_t gb, int gl) {
+  return load_meta_full_chunk(md.k16(), p, gb, gl);
+}
+template <class Mode>
+__device__ __forceinline__ void store_k(const Mode& md, float* p, uint64_t i, float k) { store_meta(md.k16(), p, i, k); }
 
 __device__ __forceinline__ float hw_log2(float x) { return __builtin_amdgcn_logf(x); }
 __device__ __forceinline__ float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -424,6 +440,9 @@ __device__ __forceinline__ GroupQuant group_quant_params(const Mode& md, float a
     const float ratio = __builtin_fmaxf(top * hw_rcp(amin), 1.0f);    // R_X
     float kk = fmt_log2_range(md) * hw_rcp(hw_log2(ratio));
     kk = __builtin_amdgcn_fmed3f(kk, k_min, k_max);
+    // BF16-stored exponent: rounded DOWN after the clamp (R_X^k stays within the format's range);
+    // the codes below are computed with the stored value
+    if (md.k16()) kk = as_f32(as_u32(kk) & 0xFFFF0000u);
     k = (amax != amin) ? kk : 1.0f;
   }
   const float inv_a = unit * hw_rcp(md.expand() ? fmax * s : s);

@@ -261,7 +261,7 @@ int dispatch_step_multi(const MultiArgs& ma, uint64_t total_records, int32_t G, 
 }
 
 constexpr uint32_t kStepFlags = COAT_FLAG_EXPAND | COAT_FLAG_M_E5M2 | COAT_FLAG_V_E5M2 | COAT_FLAG_M_PLAIN |
-                                COAT_FLAG_V_PLAIN | COAT_FLAG_BF16_SCALE;
+                                COAT_FLAG_V_PLAIN | COAT_FLAG_BF16_SCALE | COAT_FLAG_BF16_K;
 
 constexpr uint64_t kPlanRecordOffset = 128;          // records start one cache line into the blob
 // one launch covers all records with kPlanSpan / kWavesPerBlock = 8 workgroups each, and a grid holds
@@ -324,7 +324,8 @@ int step_constants(const coat_adamw_hparams* hp, StepArgs& a, bool& generic) {
   a.mode_m.ex = expand && !(hp->flags & COAT_FLAG_M_PLAIN);
   a.mode_v.ex = expand && !(hp->flags & COAT_FLAG_V_PLAIN);
   a.mode_m.s16 = a.mode_v.s16 = (hp->flags & COAT_FLAG_BF16_SCALE) != 0;
-  generic = a.mode_m.e5 || a.mode_v.e5 || !a.mode_m.ex || !a.mode_v.ex || a.mode_m.s16;
+  a.mode_m.kh = a.mode_v.kh = (hp->flags & COAT_FLAG_BF16_K) != 0;
+  generic = a.mode_m.e5 || a.mode_v.e5 || !a.mode_m.ex || !a.mode_v.ex || a.mode_m.s16 || a.mode_m.kh;
   return COAT_OK;
 }
 
@@ -359,14 +360,14 @@ int step_multi_impl(const void* plan_host, const void* plan_device, const coat_a
 
 extern "C" {
 
-int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, void* m_scale, float* m_k,
-                        uint8_t* v_q, void* v_scale, float* v_k, uint64_t n,
+int coat_fp8_adamw_step(float* w, const uint16_t* grad_bf16, uint8_t* m_q, void* m_scale, void* m_k,
+                        uint8_t* v_q, void* v_scale, void* v_k, uint64_t n,
                         const coat_adamw_hparams* hp, void* hip_stream) {
   return coat_fp8_adamw_step_bf16w(w, nullptr, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, n, hp, hip_stream);
 }
 
 int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_bf16, uint8_t* m_q,
-                              void* m_scale, float* m_k, uint8_t* v_q, void* v_scale, float* v_k,
+                              void* m_scale, void* m_k, uint8_t* v_q, void* v_scale, void* v_k,
                               uint64_t n, const coat_adamw_hparams* hp, void* hip_stream) {
   StepArgs a;
   bool generic = false;
@@ -377,7 +378,7 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
       !aligned4(m_scale) || !aligned4(m_k) || !aligned4(v_scale) || !aligned4(v_k) || !aligned16(w_bf16))
     return COAT_ERR_ALIGN;
   if (n > kMaxElements) return COAT_ERR_SIZE;
-  a.w = w; a.wb = w_bf16; a.g = grad_bf16; a.mq = m_q; a.ms = static_cast<float*>(m_scale); a.mk = m_k; a.vq = v_q; a.vs = static_cast<float*>(v_scale); a.vk = v_k;
+  a.w = w; a.wb = w_bf16; a.g = grad_bf16; a.mq = m_q; a.ms = static_cast<float*>(m_scale); a.mk = static_cast<float*>(m_k); a.vq = v_q; a.vs = static_cast<float*>(v_scale); a.vk = static_cast<float*>(v_k);
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(hp->group_size) - 1) / static_cast<uint64_t>(hp->group_size);
   a.w_keep = static_cast<float>(1.0 - static_cast<double>(hp->lr) * static_cast<double>(hp->weight_decay));
@@ -418,8 +419,8 @@ int coat_multi_plan_build(const coat_tensor_desc* descs, uint32_t count, void* p
     const uint64_t spans = plan_records_of(d.n);
     for (uint64_t i = 0; i < spans; ++i, ++rec) {
       PlanRecord o = {};
-      o.w = d.w; o.wb = d.w_bf16; o.g = d.grad_bf16; o.mq = d.m_q; o.ms = static_cast<float*>(d.m_scale); o.mk = d.m_k;
-      o.vq = d.v_q; o.vs = static_cast<float*>(d.v_scale); o.vk = d.v_k; o.n = d.n;
+      o.w = d.w; o.wb = d.w_bf16; o.g = d.grad_bf16; o.mq = d.m_q; o.ms = static_cast<float*>(d.m_scale); o.mk = static_cast<float*>(d.m_k);
+      o.vq = d.v_q; o.vs = static_cast<float*>(d.v_scale); o.vk = static_cast<float*>(d.v_k); o.n = d.n;
       o.chunk_base = i * kPlanSpan; o.weight_decay = d.weight_decay; o.tensor = t;
       __builtin_memcpy(blob + h.record_offset + rec * sizeof(PlanRecord), &o, sizeof o);
     }
@@ -492,40 +493,42 @@ int coat_bench_copy_control(float* w, const uint16_t* grad_bf16, uint8_t* m_q, f
 }
 
 int coat_quant_group(const float* x, uint64_t n, int32_t G, uint32_t flags, float k_min, float k_max,
-                     uint8_t* q, void* scale, float* k, void* hip_stream) {
+                     uint8_t* q, void* scale, void* k, void* hip_stream) {
   if (!group_ok(G)) return COAT_ERR_GROUP;
-  if (flags & ~(COAT_FLAG_EXPAND | COAT_FLAG_E5M2 | COAT_FLAG_BF16_SCALE)) return COAT_ERR_HPARAM;
+  if (flags & ~(COAT_FLAG_EXPAND | COAT_FLAG_E5M2 | COAT_FLAG_BF16_SCALE | COAT_FLAG_BF16_K)) return COAT_ERR_HPARAM;
   if (!resolve_k_bounds(k_min, k_max)) return COAT_ERR_HPARAM;
   if (n == 0) return COAT_OK;
   if (!x || !q || !scale || !k) return COAT_ERR_NULL;
   if (!aligned16(x) || !aligned16(q) || !aligned4(scale) || !aligned4(k)) return COAT_ERR_ALIGN;
   if (n > kMaxElements) return COAT_ERR_SIZE;
   QuantArgs a;
-  a.x = x; a.q = q; a.scale = static_cast<float*>(scale); a.k = k;
+  a.x = x; a.q = q; a.scale = static_cast<float*>(scale); a.k = static_cast<float*>(k);
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
   a.k_min = k_min; a.k_max = k_max;
   a.mode.ex = (flags & COAT_FLAG_EXPAND) != 0;
   a.mode.e5 = (flags & COAT_FLAG_E5M2) != 0;
   a.mode.s16 = (flags & COAT_FLAG_BF16_SCALE) != 0;
+  a.mode.kh = (flags & COAT_FLAG_BF16_K) != 0;
   return dispatch_quant(a, G, static_cast<hipStream_t>(hip_stream));
 }
 
-int coat_dequant_group(const uint8_t* q, const void* scale, const float* k, uint64_t n, int32_t G,
+int coat_dequant_group(const uint8_t* q, const void* scale, const void* k, uint64_t n, int32_t G,
                        uint32_t flags, float* x, void* hip_stream) {
   if (!group_ok(G)) return COAT_ERR_GROUP;
-  if (flags & ~(COAT_FLAG_EXPAND | COAT_FLAG_E5M2 | COAT_FLAG_BF16_SCALE)) return COAT_ERR_HPARAM;
+  if (flags & ~(COAT_FLAG_EXPAND | COAT_FLAG_E5M2 | COAT_FLAG_BF16_SCALE | COAT_FLAG_BF16_K)) return COAT_ERR_HPARAM;
   if (n == 0) return COAT_OK;
   if (!x || !q || !scale || !k) return COAT_ERR_NULL;
   if (!aligned16(x) || !aligned16(q) || !aligned4(scale) || !aligned4(k)) return COAT_ERR_ALIGN;
   if (n > kMaxElements) return COAT_ERR_SIZE;
   DequantArgs a;
-  a.q = q; a.scale = static_cast<const float*>(scale); a.k = k; a.x = x;
+  a.q = q; a.scale = static_cast<const float*>(scale); a.k = static_cast<const float*>(k); a.x = x;
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
   a.mode.ex = true;
   a.mode.e5 = (flags & COAT_FLAG_E5M2) != 0;
   a.mode.s16 = (flags & COAT_FLAG_BF16_SCALE) != 0;
+  a.mode.kh = (flags & COAT_FLAG_BF16_K) != 0;
   return dispatch_dequant(a, G, static_cast<hipStream_t>(hip_stream));
 }
 

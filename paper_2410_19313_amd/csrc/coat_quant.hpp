@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kBlock) void quant_kernel(QuantArgs a) {
     const GroupQuant q = quant_core<G>(a, x, c);
     const u32x4 co = {c[0], c[1], c[2], c[3]};
     stg<2>(reinterpret_cast<u32x4*>(a.q + cb) + lane, co);
-    if ((lane % LPG) == 0) { store_scale(a.mode, a.scale, gb + lane / LPG, q.scale); a.k[gb + lane / LPG] = q.k; }
+    if ((lane % LPG) == 0) { store_scale(a.mode, a.scale, gb + lane / LPG, q.scale); store_k(a.mode, a.k, gb + lane / LPG, q.k); }
   }
 }
 
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kWave) void quant_tail_kernel(QuantArgs a) {
   load_f32x16_guarded(a.x, base, a.n, x);
   const GroupQuant q = quant_core<G>(a, x, c);
   store_codes16_guarded(a.q, base, a.n, c);
-  if (gidx < a.n_groups && (lane % LPG) == 0) { store_scale(a.mode, a.scale, gidx, q.scale); a.k[gidx] = q.k; }
+  if (gidx < a.n_groups && (lane % LPG) == 0) { store_scale(a.mode, a.scale, gidx, q.scale); store_k(a.mode, a.k, gidx, q.k); }
 }
 
 // The standalone dequantizer always honours the stored k (it is 1 for codes written without
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kBlock) void dequant_kernel(DequantArgs a) {
   if (have) {
     ci = ldg<1>(reinterpret_cast<const u32x4*>(a.q + chunk * kChunk) + lane);
     scale = load_scale_full_chunk(a.mode, a.scale, chunk * (kChunk / G), lane / LPG);
-    k = a.k[chunk * (kChunk / G) + lane / LPG];
+    k = load_k_full_chunk(a.mode, a.k, chunk * (kChunk / G), lane / LPG);
   }
   fill_lut_one(lut, a.mode.e5m2());                  // every wavefront of the block reaches this
   float x[kEPL];
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(kBlock) void dequant_kernel(DequantArgs a) {
   for (chunk += stride; chunk < a.n_full; chunk += stride) {
     const uint64_t gb = chunk * (kChunk / G);
     ci = ldg<1>(reinterpret_cast<const u32x4*>(a.q + chunk * kChunk) + lane);
-    dequant_core(a, lut, ci, load_scale_full_chunk(a.mode, a.scale, gb, lane / LPG), a.k[gb + lane / LPG], x);
+    dequant_core(a, lut, ci, load_scale_full_chunk(a.mode, a.scale, gb, lane / LPG), load_k_full_chunk(a.mode, a.k, gb, lane / LPG), x);
     tile_lanes_to_rows_store(tile_x + wv * kTileSlotsW, lane, x, a.x + chunk * kChunk);
   }
 }
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(kWave) void dequant_tail_kernel(DequantArgs a) {
   float x[kEPL];
   load_codes16_guarded(a.q, base, a.n, c);
   const u32x4 ci = {c[0], c[1], c[2], c[3]};
-  dequant_core(a, lut, ci, gvalid ? load_scale(a.mode, a.scale, gidx) : 0.0f, gvalid ? a.k[gidx] : 1.0f, x);
+  dequant_core(a, lut, ci, gvalid ? load_scale(a.mode, a.scale, gidx) : 0.0f, gvalid ? load_k(a.mode, a.k, gidx) : 1.0f, x);
   store_f32x16_guarded(a.x, base, a.n, x);
 }
 

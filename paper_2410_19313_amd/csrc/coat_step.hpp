@@ -133,8 +133,8 @@ __device__ __forceinline__ void issue_loads(const StepArgs& a, const ModeM& mm, 
   r.vc = ldg<1>(vq + lane);
   r.meta.m_scale = load_scale_full_chunk(mm, a.ms, gb, gl);
   r.meta.v_scale = load_scale_full_chunk(mv, a.vs, gb, gl);
-  r.meta.m_k = a.mk[gb + gl];          // written as 1 (and ignored) by a moment stored without expansion
-  r.meta.v_k = a.vk[gb + gl];
+  r.meta.m_k = load_k_full_chunk(mm, a.mk, gb, gl);          // written as 1 (and ignored) by a moment stored without expansion
+  r.meta.v_k = load_k_full_chunk(mv, a.vk, gb, gl);
 #pragma unroll
   for (int j = 0; j < 4; ++j) r.w[j] = ldg<8>(wq + 64 * j + lane);
 #pragma unroll
@@ -172,12 +172,12 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const ModeM& mm
     __device__ __forceinline__ void second(const uint32_t (&c)[4], float scale, float k) const {
       const u32x4 o = {c[0], c[1], c[2], c[3]};
       stg<2>(reinterpret_cast<u32x4*>(a.vq + cb) + lane, o);
-      if ((lane % LPG) == 0) { store_scale(mv, a.vs, gb + lane / LPG, scale); a.vk[gb + lane / LPG] = k; }
+      if ((lane % LPG) == 0) { store_scale(mv, a.vs, gb + lane / LPG, scale); store_k(mv, a.vk, gb + lane / LPG, k); }
     }
     __device__ __forceinline__ void first(const uint32_t (&c)[4], float scale, float k) const {
       const u32x4 o = {c[0], c[1], c[2], c[3]};
       stg<2>(reinterpret_cast<u32x4*>(a.mq + cb) + lane, o);
-      if ((lane % LPG) == 0) { store_scale(mm, a.ms, gb + lane / LPG, scale); a.mk[gb + lane / LPG] = k; }
+      if ((lane % LPG) == 0) { store_scale(mm, a.ms, gb + lane / LPG, scale); store_k(mm, a.mk, gb + lane / LPG, k); }
     }
   };
   step_core<G>(a, mm, mv, tb, ls, mc, vc, r.meta, IO{a, mm, mv, tiles, r, cb, gb, lane});
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
   const bool have = chunk < a.n_full;
   FillRegs<kTables, kBlock> fill;
   fill_issue(fill);
-  if (have) chunk = gate_on_neighbourhood(a.mk, chunk, kChunk / G);
+  if (have) chunk = gate_on_neighbourhood(a.mk, chunk, mm.k16() ? kChunk / G / 2 : kChunk / G);
   if (have) issue_loads<G>(a, mm, mv, chunk, lane, r);
   fill_commit(fill, lut, frac);                      // every wavefront of the block reaches this
   const StepTables tb = {lut, frac};
@@ -274,8 +274,8 @@ __device__ __forceinline__ void process_tail_chunk(const StepArgs& a, const Mode
   GroupMeta meta;
   meta.m_scale = gvalid ? load_scale(mm, a.ms, gidx) : 0.0f;
   meta.v_scale = gvalid ? load_scale(mv, a.vs, gidx) : 0.0f;
-  meta.m_k = gvalid ? a.mk[gidx] : 1.0f;
-  meta.v_k = gvalid ? a.vk[gidx] : 1.0f;
+  meta.m_k = gvalid ? load_k(mm, a.mk, gidx) : 1.0f;
+  meta.v_k = gvalid ? load_k(mv, a.vk, gidx) : 1.0f;
   {
     const u32x4 c = {mc[0], mc[1], mc[2], mc[3]};
     slots[0] = c;
@@ -310,11 +310,11 @@ __device__ __forceinline__ void process_tail_chunk(const StepArgs& a, const Mode
     }
     __device__ __forceinline__ void second(const uint32_t (&c)[4], float scale, float k) const {
       store_codes16_guarded(a.vq, base, a.n, c);
-      if (store_meta) { store_scale(mv, a.vs, gidx, scale); a.vk[gidx] = k; }
+      if (store_meta) { store_scale(mv, a.vs, gidx, scale); store_k(mv, a.vk, gidx, k); }
     }
     __device__ __forceinline__ void first(const uint32_t (&c)[4], float scale, float k) const {
       store_codes16_guarded(a.mq, base, a.n, c);
-      if (store_meta) { store_scale(mm, a.ms, gidx, scale); a.mk[gidx] = k; }
+      if (store_meta) { store_scale(mm, a.ms, gidx, scale); store_k(mm, a.mk, gidx, k); }
     }
   };
   step_core<G>(a, mm, mv, tb, ls, mc, vc, meta, IO{a, mm, mv, w, g, base, gidx, gvalid && (lane % LPG) == 0});

@@ -68,7 +68,7 @@ def test_step_rejects_bad_arguments_before_launch(coat):
     assert call(coat.make_hparams(k_min=1e-3, k_max=2.0)) == -5
     assert call(coat.make_hparams(k_min=1.0, k_max=1e6)) == -5
     hp = coat.make_hparams()
-    hp.flags = 1 | 64
+    hp.flags = 1 | 128
     assert call(hp) == -5                               # unknown flag bit
     assert call(coat.make_hparams(), ptrs=[ok, ok, 0, ok, ok, ok, ok, ok]) == -1
     assert call(coat.make_hparams(), ptrs=[ok + 4, ok, ok, ok, ok, ok, ok, ok]) == -2
@@ -86,7 +86,7 @@ def test_quant_dequant_reject_bad_arguments(coat):
     assert L.coat_quant_group(ok, 1024, 128, 1, 0.0, 0.0, bad, ok, ok, None) == -2
     assert L.coat_quant_group(ok, 1024, 128, 1, 2.0, 1.0, ok, ok, ok, None) == -5
     assert L.coat_quant_group(None, 0, 128, 1, 0.0, 0.0, None, None, None, None) == 0
-    assert L.coat_quant_group(ok, 1024, 128, 64, 0.0, 0.0, ok, ok, ok, None) == -5     # unknown flag bit
+    assert L.coat_quant_group(ok, 1024, 128, 128, 0.0, 0.0, ok, ok, ok, None) == -5     # unknown flag bit
     assert L.coat_dequant_group(ok, ok, ok, 1024, 7, 0, ok, None) == -3
     assert L.coat_dequant_group(ok, None, ok, 1024, 128, 0, ok, None) == -1
     assert L.coat_dequant_group(bad, ok, ok, 1024, 128, 0, ok, None) == -2

@@ -153,6 +153,7 @@ def gather(t, idx_dev, G):
 @pytest.mark.parametrize("workload,G,grads,flags", [
     ("cfg3", 128, "normal", {}), ("cfg5", 128, "normal", {}),
     ("cfg3", 128, "normal", dict(bf16_scale=True)),                 # scales stored in BF16 (Sec. 3)
+    ("cfg3", 128, "normal", dict(bf16_scale=True, bf16_k=True)),    # ... and the exponents too: 8 + 8/G bytes per parameter
     ("cfg3", 128, "normal", dict(m_e5m2=True, v_e5m2=True)),        # a cell of Table 1 through the generic kernel
 ])
 def test_full_size_sampled(coat, ref, workload, G, grads, flags):
@@ -163,10 +164,11 @@ def test_full_size_sampled(coat, ref, workload, G, grads, flags):
     gen = S.torch_generator(dev, 100 + G)
     w = S.torch_weights(n, dev, gen)
     scale_dtype = torch.bfloat16 if flags.get("bf16_scale") else torch.float32
+    k_dtype = torch.bfloat16 if flags.get("bf16_k") else torch.float32
     st = dict(m_q=torch.zeros(n, dtype=torch.uint8, device=dev), m_scale=torch.zeros(ng, dtype=scale_dtype, device=dev),
-              m_k=torch.ones(ng, dtype=torch.float32, device=dev),
+              m_k=torch.ones(ng, dtype=k_dtype, device=dev),
               v_q=torch.zeros(n, dtype=torch.uint8, device=dev), v_scale=torch.zeros(ng, dtype=scale_dtype, device=dev),
-              v_k=torch.ones(ng, dtype=torch.float32, device=dev))
+              v_k=torch.ones(ng, dtype=k_dtype, device=dev))
     g = torch.empty(n, dtype=torch.bfloat16, device=dev)
     idx = sample_groups(ng, 4096, seed=G)
     idx_dev = torch.from_numpy(idx).to(dev)

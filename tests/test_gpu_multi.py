@@ -33,7 +33,7 @@ def make_tensors(G, seed, with_bf16=()):
     return out
 
 
-def to_device(host, bf16_scale=False):
+def to_device(host, bf16_scale=False, bf16_k=False):
     dev = []
     for h in host:
         n = h["w"].size
@@ -41,7 +41,7 @@ def to_device(host, bf16_scale=False):
                  weight_decay=h["wd"])
         for k, v in h["st"].items():
             d[k] = torch.from_numpy(v.copy()).cuda()
-            if bf16_scale and k.endswith("_scale"):
+            if (bf16_scale and k.endswith("_scale")) or (bf16_k and k.endswith("_k")):
                 d[k] = d[k].to(torch.bfloat16)
         if h["bf16"]:
             d["w_bf16"] = torch.full((n,), 7.0, dtype=torch.bfloat16, device="cuda")
@@ -75,10 +75,12 @@ def raw(t):
 
 
 @pytest.mark.parametrize("G,flags", [(128, {}), (32, {}), (512, {}), (64, dict(m_e5m2=True, v_plain=True)),
-                                     (128, dict(expand=False)), (128, dict(bf16_scale=True))])
+                                     (128, dict(expand=False)), (128, dict(bf16_scale=True)),
+                                     (32, dict(bf16_scale=True, bf16_k=True)), (512, dict(bf16_k=True))])
 def test_multi_equals_one_call_per_tensor(coat, G, flags):
     host = make_tensors(G, seed=11, with_bf16=(3, 7, 8))
-    a, b = to_device(host, flags.get("bf16_scale", False)), to_device(host, flags.get("bf16_scale", False))
+    a = to_device(host, flags.get("bf16_scale", False), flags.get("bf16_k", False))
+    b = to_device(host, flags.get("bf16_scale", False), flags.get("bf16_k", False))
     plan = coat.MultiPlan(a, G)
     for t in range(1, 4):
         grads = [S.grads_normal(h["w"].size, 50 + i, t, G=G) if i % 2 else S.grads_lognormal(h["w"].size, 50 + i, t)
@@ -120,13 +122,14 @@ def shard_views(coat, dev, G, world):
 
 
 @pytest.mark.parametrize("world", [2, 3, 8])
-@pytest.mark.parametrize("G,bf16_scale", [(32, False), (128, False), (512, False), (64, True)])
-def test_sharded_plan_equals_unsharded(coat, G, bf16_scale, world):
+@pytest.mark.parametrize("G,bf16_scale,bf16_k", [(32, False, False), (128, False, False), (512, False, False),
+                                                 (64, True, False), (32, True, True)])
+def test_sharded_plan_equals_unsharded(coat, G, bf16_scale, bf16_k, world):
     """The optimizer state partitioned over `world` ranks (Sec. 2 places this step next to ZeRO-style
     sharding): all shards of all tensors as entries of ONE plan, one launch, against the unsharded
     plan, bit for bit, over three steps.  Groups never straddle a cut, so nothing else is acceptable."""
     host = make_tensors(G, seed=31, with_bf16=(4, 7))
-    a, b = to_device(host, bf16_scale), to_device(host, bf16_scale)
+    a, b = to_device(host, bf16_scale, bf16_k), to_device(host, bf16_scale, bf16_k)
     whole = coat.MultiPlan(a, G)
     shards = shard_views(coat, b, G, world)
     assert len(shards) == world * len(SIZES)
@@ -136,7 +139,7 @@ def test_sharded_plan_equals_unsharded(coat, G, bf16_scale, world):
                  for i, h in enumerate(host)]
         set_grads(a, grads)
         set_grads(b, grads)
-        hp = coat.make_hparams(step=t, group_size=G, bf16_scale=bf16_scale, **HP)
+        hp = coat.make_hparams(step=t, group_size=G, bf16_scale=bf16_scale, bf16_k=bf16_k, **HP)
         coat.coat_fp8_adamw_step_multi(whole, hp)
         coat.coat_fp8_adamw_step_multi(cut, hp)
         torch.cuda.synchronize()

@@ -7,7 +7,8 @@ import pytest
 import torch
 
 import synth_inputs as S
-from parity import allowed_mismatches, assert_codes, assert_k, assert_scale, assert_w, eps_dq, k_bar, k_tolerance
+from parity import (K_EXCEPTION_MAX, allowed_mismatches, assert_codes, assert_k, assert_scale, assert_w, eps_dq, k_bar,
+                    k_tolerance)
 
 pytestmark = pytest.mark.gpu
 
@@ -38,11 +39,12 @@ def gpu_step(coat, w, g_bits, st, G, step, expand=True, **over):
     hp = coat.make_hparams(step=step, group_size=G, expand=expand, **kw)
     tw, tg = dev(w), dev_bf16(g_bits)
     ts = {k: dev(v) for k, v in st.items()}
-    if kw.get("bf16_scale"):
-        # the oracle keeps bf16 scales as floats whose values are bf16: the conversion is exact
-        for k in ("m_scale", "v_scale"):
-            assert np.all(st[k].view(np.uint32) & 0xFFFF == 0)
-            ts[k] = ts[k].to(torch.bfloat16)
+    # the oracle keeps bf16 scales / exponents as floats whose values are bf16: the conversion is exact
+    for flag, keys in (("bf16_scale", ("m_scale", "v_scale")), ("bf16_k", ("m_k", "v_k"))):
+        if kw.get(flag):
+            for k in keys:
+                assert np.all(st[k].view(np.uint32) & 0xFFFF == 0)
+                ts[k] = ts[k].to(torch.bfloat16)
     coat.coat_fp8_adamw_step(tw, tg, ts["m_q"], ts["m_scale"], ts["m_k"], ts["v_q"], ts["v_scale"], ts["v_k"], hp)
     torch.cuda.synchronize()
     return tw.cpu().numpy(), {k: v.float().cpu().numpy() if v.dtype == torch.bfloat16 else v.cpu().numpy()
@@ -88,6 +90,12 @@ def check_step(ref, tag, w_g, st_g, w_r, st_r, st_old, g_bits, G, expand=True, e
     k_max = over.get("k_max", 0.0) or 1024.0
     stats = {"w": assert_w(w_g, w_r, tag + " w", extra_w_tol)}
     m_t, dm, v_t, dv = new_moments(ref, st_old, g_bits, G, over)
+    k_unrounded = None
+    if over.get("bf16_k"):
+        # the reference exponents BEFORE their rounding to bf16: the same oracle step without that flag
+        # (scales and moments do not depend on how k is stored)
+        _, k_unrounded = ref_step(ref, np.zeros(st_old["m_q"].size, np.float32), g_bits, st_old, G, 1, expand,
+                                  **{**over, "bf16_k": False})
     for name, x, dx in (("m", m_t, dm), ("v", v_t, dv)):
         x32 = x.astype(np.float32).astype(np.float64)     # both sides hold the new moments as fp32
         bound, _ = k_tolerance(st_r[name + "_k"], x32, dx, G, k_min, k_max)
@@ -111,16 +119,55 @@ def check_step(ref, tag, w_g, st_g, w_r, st_r, st_old, g_bits, G, expand=True, e
             assert_scale(st_g[name + "_scale"], st_r[name + "_scale"], tag + " %s scale" % name)
         if not expand or over.get(name + "_plain"):
             assert np.all(st_g[name + "_k"] == 1.0) and np.all(st_r[name + "_k"] == 1.0)   # k is 1 on both sides
-        exc, kstats = assert_k(st_g[name + "_k"], st_r[name + "_k"], bar, tag + " %s k" % name, bound=bound, excused=excused)
+        if over.get("bf16_k"):
+            exc, kstats = check_bf16_k(tag + " %s k" % name, st_g[name + "_k"], st_r[name + "_k"], k_unrounded[name + "_k"],
+                                       bar, bound, excused)
+            excused = exc                                     # their codes are relative to another exponent
+        else:
+            exc, kstats = assert_k(st_g[name + "_k"], st_r[name + "_k"], bar, tag + " %s k" % name, bound=bound, excused=excused)
         n_bad, n_far = assert_codes(ref, st_g[name + "_q"], st_r[name + "_q"], G, tag + " %s codes" % name, exception=exc,
                                     x_ref=x, dx=dx, scale_ref=st_r[name + "_scale"], k_ref=st_r[name + "_k"], bound=bound,
                                     e5m2=bool(over.get(name + "_e5m2")), other_scale=excused)
         stats[name] = dict(bad=n_bad, far=n_far, n=int(x.size), groups=int(bar.size), **kstats)
     # the second moment has no cancellation and takes no exception: plain bar everywhere
-    if not over.get("bf16_scale"):
+    if not over.get("bf16_scale") and not over.get("bf16_k"):
         assert stats["v"]["k_out"] == 0, tag + ": v k outside the bar in %d groups" % stats["v"]["k_out"]
     assert np.all(st_g["v_q"] < 0x80), tag + ": a second-moment code carries a sign"
     return stats
+
+
+def bf16_floor(k):
+    k = np.asarray(k, dtype=np.float32)
+    return (k.view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32)
+
+
+def check_bf16_k(tag, k_gpu, k_ref, k_exact, bar, bound, excused):
+    """BF16-stored exponents: the stored k is a rounding DECISION (the bf16 floor of the clamped
+    exponent).  k_exact: the reference exponent before that rounding.  Where k_exact is further than
+    the plain bar from a bf16 boundary both sides must store the SAME value; nearer than that either
+    neighbour is right.  The "two candidates" exception of parity.py keeps its own limit (1e-4 of
+    the groups, each within its bound plus one bf16 step).  Returns (groups whose stored k differs,
+    statistics)."""
+    assert np.all(k_gpu.view(np.uint32) & 0xFFFF == 0), tag + ": a stored k is not a bf16 value"
+    assert np.array_equal(k_ref, bf16_floor(k_exact)), tag + ": the reference k is not the floor of its own exponent"
+    k64 = k_exact.astype(np.float64)
+    lo16, hi16 = bf16_floor(k64 * (1.0 - 2.0 * bar)), bf16_floor(k64 * (1.0 + 2.0 * bar))
+    near = lo16 != hi16
+    differ = k_gpu != k_ref
+    if excused is not None:
+        differ_own = differ & ~excused                         # a different bf16 scale moves k as a whole
+    else:
+        differ_own = differ
+    decided = differ_own & near
+    assert np.all((k_gpu[decided] == lo16[decided]) | (k_gpu[decided] == hi16[decided])), tag + ": near a bf16 boundary"
+    assert int(decided.sum()) <= int(np.ceil(5e-3 * differ.size)), tag + ": %d bf16 exponent decisions differ" % int(decided.sum())
+    out = differ_own & ~near
+    assert int(out.sum()) <= int(np.ceil(K_EXCEPTION_MAX * differ.size)), \
+        tag + ": stored k differs away from a bf16 boundary in %d of %d groups" % (int(out.sum()), differ.size)
+    rel = np.abs(k_gpu.astype(np.float64) / k_ref - 1.0)
+    assert np.all(rel[out] <= bound[out] + 2.0 ** -7), tag + ": an exception group's k outside its bound"
+    return (differ if excused is None else differ | excused), dict(k_out=int(out.sum()), k_in_bar=float(1.0 - out.mean()),
+                                                                    k_max_rel=float(rel.max()), k_decisions=int(decided.sum()))
 
 
 def bf16_ceil(s):
@@ -362,6 +409,41 @@ def test_quant_bf16_scale(coat, ref, G, kind):
     q_r, s_r, k_r = ref.quant_group(x, G, bf16_scale=True)
     assert np.array_equal(s_g, s_r)
     check_quant(ref, "quant bf16 scale %s G=%d" % (kind, G), x, G, (q_g, s_g, k_g), (q_r, s_r, k_r), True)
+    xh_g = coat.coat_dequant_group(q, s, k, G).cpu().numpy().astype(np.float64)
+    xh_r = ref.dequant_group(q_g, s_g, k_g, G, f64=True)
+    ok = np.isfinite(xh_r) & (xh_r != 0)
+    assert np.all(np.abs(xh_g[ok] / xh_r[ok] - 1.0) <= 8 * 2.0 ** -24)
+    assert np.all(xh_g[xh_r == 0] == 0)
+
+
+@pytest.mark.parametrize("G", [32, 128, 512])
+@pytest.mark.parametrize("bf16_scale", [False, True])
+def test_step_bf16_k(coat, ref, G, bf16_scale):
+    """Exponents stored in BF16 (with fp32 and with BF16 scales: 8 + 12/G and 8 + 8/G bytes per parameter)."""
+    n = 96 * 1024 + 3 * G + 5
+    tot = lockstep(coat, ref, n, G, lambda t: S.grads_normal(n, 12, t, G=G, outlier_frac=0.02), steps=4, seed=12,
+                   bf16_k=True, bf16_scale=bf16_scale)
+    tot2 = lockstep(coat, ref, n, G, lambda t: S.grads_lognormal(n, 13, t), steps=3, seed=13, bf16_k=True, bf16_scale=bf16_scale)
+    print("bf16 k G=%d bf16_scale=%s:" % (G, bf16_scale), tot, tot2)
+
+
+@pytest.mark.parametrize("G", [32, 128, 512])
+@pytest.mark.parametrize("kind", ["normal", "square", "lognormal", "zeros_mixed"])
+def test_quant_bf16_k(coat, ref, G, kind):
+    """Standalone quantizer with BF16 exponents: identical inputs, so the scales are equal to 1e-6 and
+    the stored exponents are EQUAL except where the exponent sits within the plain bar of a bf16
+    boundary; then the dequantizer reads the bf16 exponents back."""
+    n = 37 * 1024 + 2 * G + 17
+    x = quant_inputs(kind, n, seed=G + len(kind))
+    q, s, k = coat.coat_quant_group(dev(x), G, bf16_k=True)
+    assert k.dtype == torch.bfloat16 and s.dtype == torch.float32
+    q_g, s_g, k_g = q.cpu().numpy(), s.cpu().numpy(), k.float().cpu().numpy()
+    q_r, s_r, k_r = ref.quant_group(x, G, bf16_k=True)
+    _, _, k_exact = ref.quant_group(x, G)
+    assert_scale(s_g, s_r, "quant bf16 k")
+    differ, stats = check_bf16_k("quant bf16 k %s G=%d" % (kind, G), k_g, k_r, k_exact, k_bar(x, G), np.zeros(k_r.size), None)
+    assert stats["k_out"] == 0
+    assert_codes(ref, q_g, q_r, G, "quant bf16 k codes", other_scale=differ)
     xh_g = coat.coat_dequant_group(q, s, k, G).cpu().numpy().astype(np.float64)
     xh_r = ref.dequant_group(q_g, s_g, k_g, G, f64=True)
     ok = np.isfinite(xh_r) & (xh_r != 0)
