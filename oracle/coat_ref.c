@@ -391,6 +391,9 @@ int coat_ref_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* gr
     dequant_one_group(m_q + lo, m_scale[gi], m_k[gi], fm, len, m);
     dequant_one_group(v_q + lo, v_scale[gi], v_k[gi], fv, len, v);
 
+    if (hp->flags & COAT_REF_FLAG_DQ_FP32)        /* the other reading of "dequantize to FP32" (see the header) */
+      for (i = 0; i < len; ++i) { m[i] = (double)(float)m[i]; v[i] = (double)(float)v[i]; }
+
     for (i = 0; i < len; ++i) {
       double g = bf16_to_double(grad_bf16[lo + i]);
       double wi = (double)w[lo + i];

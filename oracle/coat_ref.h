@@ -48,6 +48,13 @@ typedef struct {
                                         holds (the smallest element stays at or above the smallest subnormal); the
                                         quantizer uses the stored value.  The arrays stay float here; every value in them is a bf16. */
 
+#define COAT_REF_FLAG_DQ_FP32 128u   /* step only, NOT the default: round the dequantized moments to fp32 before the
+                                        update.  Appendix A says "dequantize to FP32"; the default reading takes the
+                                        dequantizer as the real function a * (|c| / fmax)^(1/k) and rounds to fp32 only
+                                        what the method stores or decides on (new moments before Q, scale, k, the value
+                                        handed to the FP8 rounding).  This flag exists to MEASURE what the other reading
+                                        would change (tests/test_oracle_step.py); nothing else uses it. */
+
 /* OCP FP8 E4M3 ("FN"): 1-4-3 bits, bias 7, no infinity, 0x7F/0xFF are NaN, largest
  * finite 448 and smallest positive 2^-9 (the two constants Sec. 3 prints). */
 double  coat_ref_e4m3_decode(uint8_t code);

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "coat_ref.c")
 _LIB = os.path.join(_HERE, "libcoat_ref.so")
 
-FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN, FLAG_BF16_SCALE, FLAG_BF16_K = 1, 2, 2, 4, 8, 16, 32, 64
+FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN, FLAG_BF16_SCALE, FLAG_BF16_K, FLAG_DQ_FP32 = 1, 2, 2, 4, 8, 16, 32, 64, 128
 
 
 class HParams(ctypes.Structure):
