@@ -115,7 +115,7 @@ def bench_act(args, C, S, torch, dev, gen):
     input / output buffer sets are cycled so that the working set (far) exceeds the 256 MB of
     last-level cache and the figure is an HBM figure.  Algorithmic bytes per element:
       act_group        2 in + 1 out + 4/G scales                              = 3 + 4/G
-      act_tensor       stage 1: 2 in + 4/G out; stage 2: 4/G in; then 2 in + 1 out = 5 + 8/G
+      act_tensor       stage 1: 2 in + 4/G out (the reduction rides along); then 2 in + 1 out = 5 + 4/G
       act_tensor_pre   (group maxima supplied) 4/G in + 2 in + 1 out           = 3 + 4/G"""
     G = args.act_group_size
     hidden = 4096
@@ -153,7 +153,7 @@ def bench_act(args, C, S, torch, dev, gen):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     avg_s = e0.elapsed_time(e1) / args.steps / 1e3
-    per = {"act_group": 3.0 + 4.0 / G, "act_tensor": 5.0 + 8.0 / G, "act_tensor_pre": 3.0 + 4.0 / G}[args.op]
+    per = {"act_group": 3.0 + 4.0 / G, "act_tensor": 5.0 + 4.0 / G, "act_tensor_pre": 3.0 + 4.0 / G}[args.op]
     algo = per * n
     print(json.dumps({
         "metric": "elements/sec, %s (bf16 -> E4M3, Sec. 5.2)" % args.op,
@@ -186,6 +186,8 @@ def run_step_config(C, S, torch, dev, workload, G, grads_kind, warmup, steps, st
     st = S.torch_zero_state(n, G, dev)
     if flags.get("bf16_scale"):
         st["m_scale"], st["v_scale"] = st["m_scale"].to(torch.bfloat16), st["v_scale"].to(torch.bfloat16)
+    if flags.get("bf16_k"):
+        st["m_k"], st["v_k"] = st["m_k"].to(torch.bfloat16), st["v_k"].to(torch.bfloat16)
     # two gradient buffers, alternated, so that consecutive steps do not see identical input
     if grads_kind == "normal":
         mask = S.torch_outlier_group_mask(n // G, dev, gen, 0.01 if workload != "cfg1" else 0.0)
@@ -248,7 +250,8 @@ def run_step_config(C, S, torch, dev, workload, G, grads_kind, warmup, steps, st
     wall = time.perf_counter() - t0
     launch_ms = [a.elapsed_time(b) for a, b in ev]
     avg_launch_s = sum(launch_ms) / len(launch_ms) / 1e3
-    per_param = bytes_per_param(G) + (2.0 if emit_bf16 else 0.0) - (8.0 / G if flags.get("bf16_scale") else 0.0)
+    per_param = (bytes_per_param(G) + (2.0 if emit_bf16 else 0.0) - (8.0 / G if flags.get("bf16_scale") else 0.0)
+                 - (8.0 / G if flags.get("bf16_k") else 0.0))
     algo_bytes = per_param * n
     row = dict(workload=workload, params=n, group_size=G, grads=grads_kind, steps=steps, warmup=warmup,
                ms_per_step=wall / steps * 1e3, avg_launch_ms=avg_launch_s * 1e3, params_per_s=n * steps / wall,
@@ -270,7 +273,7 @@ def run_step_config(C, S, torch, dev, workload, G, grads_kind, warmup, steps, st
     finite = bool(torch.isfinite(w[:: max(1, n // (1 << 20))]).all().item())
     if not finite:
         sys.exit("bench.py: non-finite weights after the timed steps (%s)" % workload)
-    if copy_control and not (emit_bf16 or flags.get("bf16_scale")):
+    if copy_control and not (emit_bf16 or flags.get("bf16_scale") or flags.get("bf16_k")):
         # the copy control: the same bytes in the same access pattern without the arithmetic (destroys the state)
         reps = max(steps, 5) + steady_steps
         for i in range(2):
@@ -318,6 +321,7 @@ def main():
     ap.add_argument("--m-plain", action="store_true", help="first moment without dynamic range expansion")
     ap.add_argument("--v-plain", action="store_true", help="second moment without dynamic range expansion")
     ap.add_argument("--bf16-scale", action="store_true", help="per-group scales stored as bf16 (14 + 24/G B/param)")
+    ap.add_argument("--bf16-k", action="store_true", help="per-group exponents stored as bf16 (with --bf16-scale: 14 + 16/G B/param)")
     ap.add_argument("--emit-bf16", action="store_true", help="also write the bf16 copy of the new weights (+2 B/param)")
     ap.add_argument("--multi", action="store_true",
                     help="step the workload as its separate tensors through ONE multi-tensor launch")
@@ -378,7 +382,8 @@ def main():
                           "hbm_gbs": bytes_per_param(G) * n / ms / 1e6, "frac_of_peak": bytes_per_param(G) * n / ms / 1e6 / HBM_PEAK_GBS}))
         return
 
-    flags = dict(m_e5m2=args.m_e5m2, v_e5m2=args.v_e5m2, m_plain=args.m_plain, v_plain=args.v_plain, bf16_scale=args.bf16_scale)
+    flags = dict(m_e5m2=args.m_e5m2, v_e5m2=args.v_e5m2, m_plain=args.m_plain, v_plain=args.v_plain, bf16_scale=args.bf16_scale,
+                 bf16_k=args.bf16_k)
     generic = any(flags.values())
     head = run_step_config(C, S, torch, dev, args.workload, G, grads_kind, args.warmup, args.steps,
                            copy_control=not args.only, flags=flags, emit_bf16=args.emit_bf16, multi=args.multi,
@@ -400,7 +405,7 @@ def main():
         "config": {"workload": "%s: %s, %d params, G=%d, grads %s" % (args.workload, WORKLOAD_TEXT[args.workload], n, G, grads_kind) + (
                     ", m %s%s, v %s%s" % ("E5M2" if args.m_e5m2 else "E4M3", "" if args.m_plain else "+expand",
                                             "E5M2" if args.v_e5m2 else "E4M3", "" if args.v_plain else "+expand")
-                    if generic else "") + (", bf16 weight copy" if args.emit_bf16 else "") + (", bf16 scales" if args.bf16_scale else "") + (
+                    if generic else "") + (", bf16 weight copy" if args.emit_bf16 else "") + (", bf16 scales" if args.bf16_scale else "") + (", bf16 exponents" if args.bf16_k else "") + (
                         ", %d tensors in one multi-tensor launch" % head["tensors"] if args.multi else ""),
             "params": n, "group_size": G, "hbm_gbs": achieved, "hbm_frac_of_peak": achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -244,15 +244,16 @@ int coat_act_quant_group(const uint16_t* x_bf16, uint64_t n, int32_t G,
  *   stage 1  group_amax [ceil(n/G)] (out) = max|x| of every 1xG group,
  *   stage 2  tensor_amax [1] (out) = max over group_amax,
  *   then     tensor_scale [1] (out) = fl32(tensor_amax / 448),  q [n] = E4M3(fl32(x / tensor_scale)).
- * Three launches in stream order on hip_stream.  Stage 2 leaves one partial maximum per workgroup
- * in `workspace` (COAT_ACT_WORKSPACE_FLOATS floats of caller-owned device scratch, 16-byte
- * aligned, contents undefined before and after the call) and the quantizing kernel folds them: no
- * atomics, no memset, so the result is deterministic and the sequence may be captured into a
- * graph.  Calls that share a workspace must not overlap.  tensor_amax and tensor_scale need
- * 4-byte alignment only.  G in {16, 32, 64, 128, 256, 512}; n == 0 touches nothing.  Inputs must
- * be finite.
+ * Two launches in stream order on hip_stream (three for coat_act_quant_tensor_from_group_amax, whose
+ * reduction over the caller's group maxima is a launch of its own).  The reducing launch leaves one
+ * partial maximum per workgroup in `workspace` (COAT_ACT_WORKSPACE_FLOATS floats of caller-owned
+ * device scratch, 16-byte aligned, contents undefined before and after the call) and the quantizing
+ * launch folds them: no atomics, no memset, so the result is deterministic and the sequence may be
+ * captured into a graph.  Calls that share a workspace must not overlap.  tensor_amax and
+ * tensor_scale need 4-byte alignment only.  G in {16, 32, 64, 128, 256, 512}; n == 0 touches
+ * nothing.  Inputs must be finite.
  */
-#define COAT_ACT_WORKSPACE_FLOATS 64
+#define COAT_ACT_WORKSPACE_FLOATS 1024
 int coat_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G,
                           float* group_amax, float* workspace, float* tensor_amax,
                           float* tensor_scale, uint8_t* q, void* hip_stream);
@@ -261,7 +262,7 @@ int coat_act_quant_tensor(const uint16_t* x_bf16, uint64_t n, int32_t G,
  * coat_act_quant_tensor for callers that cannot hand over a workspace and cannot allocate one:
  * code under graph capture, tight serving loops, harnesses that forbid allocation.  Same
  * arguments, results and launches, but the COAT_ACT_WORKSPACE_FLOATS partial maxima live in a
- * device array of the library's own (256 bytes per GPU, held until the process ends) instead of a
+ * device array of the library's own (4 KiB per GPU, held until the process ends) instead of a
  * caller buffer.  The call allocates and frees nothing, on the host or on the device; its first
  * use on a device looks the array's address up (hipGetSymbolAddress) and caches it.
  * Limits and errors: n above 2^46 elements returns COAT_ERR_SIZE (the scratch itself does not grow

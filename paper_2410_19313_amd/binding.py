@@ -16,7 +16,7 @@ FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN, FL
 SUPPORTED_GROUP_SIZES = (32, 64, 128, 256, 512)
 
 ACT_GROUP_SIZES = (16,) + SUPPORTED_GROUP_SIZES
-ACT_WORKSPACE_FLOATS = 64
+ACT_WORKSPACE_FLOATS = 1024
 
 EXPORTS = ("coat_fp8_adamw_step", "coat_fp8_adamw_step_bf16w", "coat_quant_group", "coat_dequant_group",
            "coat_act_quant_group", "coat_act_quant_tensor", "coat_act_quant_tensor_from_group_amax",
@@ -208,8 +208,8 @@ def coat_bench_copy_control(w, grad_bf16, m_q, m_scale, m_k, v_q, v_scale, v_k, 
     ng = n_groups(n, G)
     _check(lib().coat_bench_copy_control(
         _dev_ptr(w, torch.float32), _dev_ptr(grad_bf16, torch.bfloat16, n),
-        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, torch.float32, ng), _dev_ptr(m_k, _k_dtype(hp.flags), ng),
-        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, torch.float32, ng), _dev_ptr(v_k, _k_dtype(hp.flags), ng),
+        _dev_ptr(m_q, torch.uint8, n), _dev_ptr(m_scale, torch.float32, ng), _dev_ptr(m_k, torch.float32, ng),
+        _dev_ptr(v_q, torch.uint8, n), _dev_ptr(v_scale, torch.float32, ng), _dev_ptr(v_k, torch.float32, ng),
         n, G, _stream()))
 
 

@@ -14,8 +14,9 @@ struct ActArgs {
   const uint16_t* x;
   uint8_t* q;
   float* per_group;        // per-group scales (1xG quantizer) or per-group maxima (Group Scaling stage 1)
-  float* partial;          // Group Scaling stage 2: one partial maximum per workgroup (caller's workspace)
-  int n_partial;           // how many of them the stage-2 launch writes (<= kActPartials)
+  float* partial;          // Group Scaling: one partial maximum per workgroup of the reducing launch (caller's workspace)
+  int n_partial;           // how many of them are written (<= COAT_ACT_WORKSPACE_FLOATS)
+  int tail_slot;           // where the ragged last chunk's launch leaves its maximum
   float* tensor_amax;      // max |x| of the tensor
   float* tensor_scale;
   uint64_t n, n_full, n_groups;
@@ -75,12 +76,24 @@ __device__ __forceinline__ void act_load_chunk(const uint16_t* x, uint64_t cb, u
   tile_rows_to_lanes_bf16(tile, lane, rows, v);
 }
 
-// The end of Group Scaling's stage 2: every wavefront folds the (at most 64) per-workgroup partial
-// maxima itself, one per lane; all lanes return the tensor maximum.
-__device__ __forceinline__ float act_fold_partials(const ActArgs& a, int lane) {
-  float hi = lane < a.n_partial ? a.partial[lane] : 0.0f;
+// The end of Group Scaling's reduction: every workgroup of the quantizing launch folds the partial
+// maxima (at most COAT_ACT_WORKSPACE_FLOATS, a few per thread, served by the L2) itself; all threads
+// return the tensor maximum.  part: one LDS word per wavefront of the workgroup.
+__device__ __forceinline__ float act_wave_max(float hi) {
   hi = group_allreduce<32, true>(hi);
   return __builtin_fmaxf(hi, __shfl_xor(hi, 32));
+}
+__device__ __forceinline__ float act_fold_partials(const ActArgs& a, float* part) {
+  float hi = 0.0f;
+  for (int i = threadIdx.x; i < a.n_partial; i += blockDim.x) hi = __builtin_fmaxf(hi, a.partial[i]);
+  hi = act_wave_max(hi);
+  const int waves = blockDim.x / kWave;
+  if (waves == 1) return hi;
+  if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x >> 6] = hi;
+  __syncthreads();
+  hi = part[0];
+  for (int w = 1; w < waves; ++w) hi = __builtin_fmaxf(hi, part[w]);
+  return hi;
 }
 
 // PER_TENSOR = false: the 1xG quantizer (per-group scale).  PER_TENSOR = true: the last step of
@@ -94,7 +107,8 @@ __global__ __launch_bounds__(kBlock) void act_quant_kernel(ActArgs a) {
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
   float tmax = 0.0f;
   if constexpr (PER_TENSOR) {
-    tmax = act_fold_partials(a, lane);
+    __shared__ float part[kWavesPerBlock];
+    tmax = act_fold_partials(a, part);
     if (blockIdx.x == 0 && threadIdx.x == 0) { *a.tensor_amax = tmax; *a.tensor_scale = tmax / 448.0f; }
   }
   for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
@@ -122,7 +136,7 @@ __global__ __launch_bounds__(kWave) void act_quant_tail_kernel(ActArgs a) {
   load_bf16x16_guarded(a.x, base, a.n, x);
   float amax;
   if constexpr (PER_TENSOR) {
-    amax = act_fold_partials(a, lane);
+    amax = act_fold_partials(a, nullptr);            // one wavefront: no LDS needed
     if (lane == 0) { *a.tensor_amax = amax; *a.tensor_scale = amax / 448.0f; }
   } else {
     amax = act_group_amax<G>(x);
@@ -133,19 +147,33 @@ __global__ __launch_bounds__(kWave) void act_quant_tail_kernel(ActArgs a) {
     if (gidx < a.n_groups && (lane % LPG) == 0) a.per_group[gidx] = s;
 }
 
-// Group Scaling stage 1: the maximum of every 1xG group, kept as an intermediate tensor.
+// Group Scaling stage 1: the maximum of every 1xG group, kept as an intermediate tensor.  Every
+// workgroup also leaves the maximum of what it saw in its slot of the workspace, so that the
+// reduction over the intermediate tensor (stage 2) costs no pass and no launch of its own here: the
+// quantizing launch folds the slots.  The grid is capped at the number of slots and loops.
 template <int G>
 __global__ __launch_bounds__(kBlock) void act_group_amax_kernel(ActArgs a) {
   __shared__ u32x4 tile_x[kWavesPerBlock * kTileSlotsG];
+  __shared__ float part[kWavesPerBlock];
   constexpr int LPG = G / kEPL;
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
+  float seen = 0.0f;
   for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
     float x[kEPL];
     act_load_chunk(a.x, chunk * kChunk, tile_x + wv * kTileSlotsG, lane, x);
     const float amax = act_group_amax<G>(x);
     if ((lane % LPG) == 0) a.per_group[chunk * (kChunk / G) + lane / LPG] = amax;
+    seen = __builtin_fmaxf(seen, amax);
+  }
+  seen = act_wave_max(seen);
+  if (lane == 0) part[wv] = seen;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kWavesPerBlock; ++w) seen = __builtin_fmaxf(seen, part[w]);
+    a.partial[blockIdx.x] = seen;
   }
 }
 
@@ -159,11 +187,13 @@ __global__ __launch_bounds__(kWave) void act_group_amax_tail_kernel(ActArgs a) {
   load_bf16x16_guarded(a.x, base, a.n, x);
   const float amax = act_group_amax<G>(x);
   if (gidx < a.n_groups && (lane % LPG) == 0) a.per_group[gidx] = amax;
+  const float seen = act_wave_max(amax);             // lanes beyond n hold zeros
+  if (lane == 0) a.partial[a.tail_slot] = seen;
 }
 
-// Group Scaling stage 2: the maximum of the G-times smaller tensor of group maxima.  At most 64
-// large workgroups each fold a strided share and store one partial maximum; the quantizing kernel
-// that follows folds those in every wavefront.  No atomics (same-address atomic maxima serialize
+// Group Scaling stage 2 for a caller who brings the group maxima (the producing operator wrote
+// them): the maximum of the G-times smaller tensor.  At most 64 large workgroups each fold a strided
+// share and store one partial maximum; the quantizing kernel that follows folds those.  No atomics (same-address atomic maxima serialize
 // at about 11 ns each here, which cost more than the whole reduction), nothing to clear, and the
 // result does not depend on the order in which workgroups finish.
 template <int BLOCK, int UNROLL>

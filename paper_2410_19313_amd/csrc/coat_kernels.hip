@@ -167,10 +167,16 @@ bool act_group_ok(int32_t G) { return G == 16 || group_ok(G); }
   }                                                   \
   COAT_DISPATCH_G(G, CALL)
 
+constexpr unsigned kActTensorMaxGrid = 1024;
 template <int G, bool PER_TENSOR>
 int launch_act_quant(const ActArgs& a, hipStream_t s) {
   if (a.n_full) {
-    hipLaunchKernelGGL((act_quant_kernel<G, PER_TENSOR>), dim3(grid_for(a.n_full)), dim3(kBlock), 0, s, a);
+    // with one scale per tensor every workgroup first folds the workspace slots: few, looping
+    // workgroups pay that once each (8192 x 4096 elements, whole call: uncapped 35.5 us, at most
+    // 4096 / 2048 / 1024 / 768 / 512 workgroups 34.9 / 33.7 / 33.1 / 32.9 / 35.1 us)
+    unsigned grid = grid_for(a.n_full);
+    if (PER_TENSOR && grid > kActTensorMaxGrid) grid = kActTensorMaxGrid;
+    hipLaunchKernelGGL((act_quant_kernel<G, PER_TENSOR>), dim3(grid), dim3(kBlock), 0, s, a);
     if (int rc = launch_status()) return rc;
   }
   if (a.n > a.n_full * kChunk) {
@@ -180,13 +186,22 @@ int launch_act_quant(const ActArgs& a, hipStream_t s) {
   return COAT_OK;
 }
 
+// Stage 1 of Group Scaling; also fills the workspace slots (one per workgroup, one more for the
+// ragged last chunk) and says how many in a.n_partial.
+constexpr unsigned kStage1MaxGrid = COAT_ACT_WORKSPACE_FLOATS - 1;
 template <int G>
-int launch_act_group_amax(const ActArgs& a, hipStream_t s) {
+int launch_act_group_amax(ActArgs& a, hipStream_t s) {
+  unsigned grid = 0;
   if (a.n_full) {
-    hipLaunchKernelGGL((act_group_amax_kernel<G>), dim3(grid_for(a.n_full)), dim3(kBlock), 0, s, a);
+    const uint64_t need = (a.n_full + kWavesPerBlock - 1) / kWavesPerBlock;
+    grid = static_cast<unsigned>(need < kStage1MaxGrid ? need : kStage1MaxGrid);
+    hipLaunchKernelGGL((act_group_amax_kernel<G>), dim3(grid), dim3(kBlock), 0, s, a);
     if (int rc = launch_status()) return rc;
   }
+  a.n_partial = static_cast<int>(grid);
   if (a.n > a.n_full * kChunk) {
+    a.tail_slot = static_cast<int>(grid);
+    a.n_partial = static_cast<int>(grid) + 1;
     hipLaunchKernelGGL((act_group_amax_tail_kernel<G>), dim3(1), dim3(kWave), 0, s, a);
     if (int rc = launch_status()) return rc;
   }
@@ -196,20 +211,19 @@ int launch_act_group_amax(const ActArgs& a, hipStream_t s) {
 int dispatch_act_quant_group(const ActArgs& a, int32_t G, hipStream_t s) {
   COAT_DISPATCH_ACT_G(G, (launch_act_quant<kG, false>(a, s)));
 }
-int dispatch_act_group_amax(const ActArgs& a, int32_t G, hipStream_t s) {
+int dispatch_act_group_amax(ActArgs& a, int32_t G, hipStream_t s) {
   COAT_DISPATCH_ACT_G(G, (launch_act_group_amax<kG>(a, s)));
 }
 
-// stages 2 and 3 of Group Scaling: reduce the group maxima, then quantize with the one scale
-constexpr int kStage2Block = 1024, kStage2Unroll = 4, kStage2MaxGrid = COAT_ACT_WORKSPACE_FLOATS;
-static_assert(kStage2MaxGrid <= kWave, "one partial maximum per lane");
-int launch_act_tensor_rest(ActArgs a, hipStream_t s) {
+// Group Scaling for a caller who brings the group maxima: reduce them (stage 2), then quantize
+constexpr int kStage2Block = 1024, kStage2Unroll = 4, kStage2MaxGrid = 64;
+static_assert(kStage2MaxGrid <= COAT_ACT_WORKSPACE_FLOATS, "one workspace slot per workgroup");
+int launch_act_tensor_amax(ActArgs& a, hipStream_t s) {
   const uint64_t need = (a.n_groups / 4 + kStage2Block * kStage2Unroll - 1) / (kStage2Block * kStage2Unroll);
   const unsigned grid = static_cast<unsigned>(need < 1 ? 1 : (need > kStage2MaxGrid ? kStage2MaxGrid : need));
   a.n_partial = static_cast<int>(grid);
   hipLaunchKernelGGL((act_tensor_amax_kernel<kStage2Block, kStage2Unroll>), dim3(grid), dim3(kStage2Block), 0, s, a);
-  if (int rc = launch_status()) return rc;
-  return launch_act_quant<16, true>(a, s);   // the group size plays no part once the scale is per tensor
+  return launch_status();
 }
 
 constexpr int kMaxDevices = 64;
@@ -238,13 +252,14 @@ int act_quant_tensor_impl(const uint16_t* x, uint64_t n, int32_t G, float* group
   if (n > kMaxElements) return COAT_ERR_SIZE;
   ActArgs a;
   a.x = x; a.q = q; a.per_group = group_amax;
-  a.partial = workspace; a.n_partial = 0; a.tensor_amax = tensor_amax; a.tensor_scale = tensor_scale;
+  a.partial = workspace; a.n_partial = 0; a.tail_slot = 0; a.tensor_amax = tensor_amax; a.tensor_scale = tensor_scale;
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(G) - 1) / static_cast<uint64_t>(G);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (!have_group_amax)
-    if (int rc = dispatch_act_group_amax(a, G, s)) return rc;
-  return launch_act_tensor_rest(a, s);
+  // the reduction to one maximum: from the caller's group maxima in a launch of its own, otherwise
+  // as a by-product of stage 1; either way the quantizing launch folds the workspace slots
+  if (int rc = have_group_amax ? launch_act_tensor_amax(a, s) : dispatch_act_group_amax(a, G, s)) return rc;
+  return launch_act_quant<16, true>(a, s);   // the group size plays no part once the scale is per tensor
 }
 
 template <int G, bool GENERIC>

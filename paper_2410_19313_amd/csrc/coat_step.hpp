@@ -199,8 +199,9 @@ __device__ __forceinline__ void process_chunk(const StepArgs& a, const ModeM& mm
 // owning that chunk may be rewriting the word at the same moment.
 constexpr int kGateSpan = 32;
 // `words`: any array of the operand with a fixed number of 32-bit words per chunk.
+template <int SPAN = kGateSpan>
 __device__ __forceinline__ uint64_t gate_on_neighbourhood(const void* words, uint64_t chunk, int words_per_chunk) {
-  const uint64_t first = chunk & ~static_cast<uint64_t>(kGateSpan - 1);
+  const uint64_t first = chunk & ~static_cast<uint64_t>(SPAN - 1);
   const uint32_t probe = __builtin_amdgcn_readfirstlane(static_cast<const uint32_t*>(words)[first * words_per_chunk]);
   uint32_t lo = static_cast<uint32_t>(chunk);
   asm volatile("" : "+s"(lo) : "s"(probe));

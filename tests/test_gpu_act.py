@@ -155,8 +155,8 @@ def test_full_size_activation_tensor(coat, ref):
     q_g, s_g = coat.coat_act_quant_group(x, 16)
     ws = coat.act_workspace("cuda")
     qt_g, ts_g, ga_g, ta_g = coat.coat_act_quant_tensor(x, 16, workspace=ws)
-    # all 64 stage-2 partial maxima are in use now; a short, small-valued tensor through the same
-    # workspace right after (one partial) must not see the other 63
+    # every slot of the workspace is in use now; a short, small-valued tensor through the same
+    # workspace right after (a few slots) must not see the others
     short = S.f32_to_bf16_bits(S.bf16_bits_to_f32(bits[:70000]) * np.float32(2.0 ** -7))
     qs_g, tss_g, _, _ = coat.coat_act_quant_tensor(dev_bf16(short), 16, workspace=ws)
     torch.cuda.synchronize()

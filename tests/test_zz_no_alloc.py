@@ -49,9 +49,10 @@ def run_both(coat, x_bits, G):
 
 def test_static_scratch_entry_matches_the_workspace_entry(coat, ref):
     G = 16
-    # first call: large enough for the full 64 partial maxima of stage 2, with a ragged tail and a
-    # big maximum; second call: a much smaller tensor (fewer partials) with a smaller maximum
-    big = S.activations(3 * 1024 * 1024 + 1000 + 9, seed=31, hidden=4096)
+    # first call: large enough to use every slot of the scratch (one partial maximum per workgroup of
+    # stage 1 plus the ragged tail's), with a big maximum; second call: a much smaller tensor (a few
+    # slots) with a smaller maximum
+    big = S.activations(5 * 1024 * 1024 + 1000 + 9, seed=31, hidden=4096)
     small = S.activations(5 * 1024 + 77, seed=32, hidden=512, channel_mult=1.0, spike_mult=1.0, sigma=0.01)
     for x_bits in (big, small):
         (q_w, ga_w, ta_w, ts_w), (q_s, ga_s, ta_s, ts_s) = run_both(coat, x_bits, G)
