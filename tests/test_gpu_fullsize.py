@@ -134,6 +134,10 @@ def test_whole_tensor_set_ten_lockstep_steps(coat, ref, G, grads):
         assert bool((g_d.view(torch.int16) == torch.from_numpy(g_bits.view(np.int16)).to(dev)).all())   # read-only
         w_d, st_d = w_ref_d, st_ref_d                        # lock-step: both continue from the oracle's state
     assert tot["bad"] <= allowed_mismatches(20 * n)
+    # floors on what is measured today (rate 4 to 5e-6, no mismatch of more than a step, one to three
+    # groups in 3e7 to 1.3e8 outside the k bar), so that a regression inside the stated bar still shows
+    assert tot["bad"] <= 2e-5 * 20 * n and tot["far"] == 0
+    assert tot["k_out"] <= max(8, int(1e-6 * 20 * n / G))
     print("\n[whole set] G=%d %s: 10 steps x %d elements: %d code mismatches (rate %.2e), %d of more than a step, "
           "%d groups outside the k bar, w worst %.2f x tol" % (G, grads, n, tot["bad"], tot["bad"] / (20.0 * n),
                                                                 tot["far"], tot["k_out"], tot["w"]))
@@ -211,3 +215,55 @@ def test_full_size_sampled(coat, ref, workload, G, grads, flags):
             put(st[k], st_r[k])
     print("\n[sampled] %s %s: 3 steps x %d sampled elements: %d code mismatches, %d of more than a step, %d groups "
           "outside the k bar" % (workload, flags or "", idx.size * G, total["bad"], total["far"], total["k_out"]))
+
+
+# --- (3) free-running drift: informational ---------------------------------------------------------
+
+@pytest.mark.parametrize("workload", ["cfg1", "cfg2"])
+def test_free_running_drift_report(coat, ref, workload):
+    """Ten steps with each side continuing from its OWN state (no lock-step): how far the fp32 path and
+    the fp64 oracle drift apart when their rare one-step code differences feed back.  A report, with
+    loose limits only: per-step parity is what the lock-step tests above assert."""
+    dev = torch.device("cuda:0")
+    G = 128
+    n = S.workload_numel(workload)
+    gen = S.torch_generator(dev, 21)
+    w_host = S.weights(n, 5)
+    st_host = S.zero_state(n, G)
+    w_d = torch.from_numpy(w_host).to(dev)
+    st_d = {k: torch.from_numpy(v).to(dev) for k, v in st_host.items()}
+    g_d = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    lines = []
+    for t in range(1, 11):
+        draw_grads("normal", n, G, dev, gen, g_d)
+        g_bits = g_d.view(torch.int16).cpu().numpy().view(np.uint16)
+        coat.coat_fp8_adamw_step(w_d, g_d, *(st_d[k] for k in STATE_KEYS), coat.make_hparams(step=t, group_size=G, **HP))
+        assert ref.fp8_adamw_step(w_host, g_bits, *(st_host[k] for k in STATE_KEYS),
+                                  ref.make_hparams(step=t, group_size=G, **HP)) == 0
+        torch.cuda.synchronize()
+        if t in (1, 2, 5, 10):
+            w_r = torch.from_numpy(w_host).to(dev).double()
+            dw = (w_d.double() - w_r).abs()
+            outside = (dw > W_RTOL * w_r.abs() + W_ATOL).double().mean().item()
+            row = "step %2d: w outside the lock-step tolerance %.2e of the elements, worst |dw| %.2e (lr = %.0e)" % (
+                t, outside, dw.max().item(), HP["lr"])
+            for name in ("m", "v"):
+                cg, cr = st_d[name + "_q"], torch.from_numpy(st_host[name + "_q"]).to(dev)
+                a, b = cg.int(), cr.int()
+                a = torch.where((a & 0x7F) == 0, 0, a)
+                b = torch.where((b & 0x7F) == 0, 0, b)
+                differ = a != b
+                far = differ & ((((a ^ b) & 0x80) != 0) | (((a & 0x7F) - (b & 0x7F)).abs() > 1)) & ((a & 0x7F) + (b & 0x7F) > 1)
+                kg, kr = st_d[name + "_k"].double(), torch.from_numpy(st_host[name + "_k"]).to(dev).double()
+                row += "; %s codes differ %.2e (more than a step %.1e), k apart by more than 1e-6 in %.2e of the groups" % (
+                    name, differ.double().mean().item(), far.double().mean().item(), ((kg / kr - 1.0).abs() > 1e-6).double().mean().item())
+            lines.append(row)
+            if t == 10:
+                print("\n[free-running drift] %s, %d parameters, G=%d:\n  " % (workload, n, G) + "\n  ".join(lines))
+                # Loose limits only.  The quantized state is a discontinuous function of its inputs: a relative
+                # difference of 1e-7 in a stored scale or exponent, amplified where beta1 m + (1 - beta1) g cancels,
+                # moves the group minimum, with it k, and with k every code of the group; the oracle does the same
+                # to ITSELF when one of its exponents is nudged by an ulp (tests/test_oracle_step.py).  What stays
+                # small is what matters to training: the weights (each differs by a fraction of lr per step at most)
+                # and the second moment, which has no cancellation.
+                assert dw.max().item() < 10 * HP["lr"] and differ.double().mean().item() < 1e-2

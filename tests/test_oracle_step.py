@@ -262,3 +262,31 @@ def test_effect_of_rounding_the_dequantized_moments_to_fp32(ref, capsys):
         print("\n[dequantize to FP32] codes that differ: %d of %d (%.2e); groups with k apart by more than 1e-6: %d of %d; "
               "weights: worst %.3f of the parity tolerance" % (differ, total, differ / total, k_off, groups, worst_w))
     assert worst_w < 0.5 and differ / total < 1e-4 and k_off / groups < 0.05
+
+
+def test_trajectories_are_sensitive_to_one_ulp_of_metadata(ref, capsys):
+    """Why parity is defined in lock-step: the quantized optimizer state is a discontinuous map.  Two runs
+    of the ORACLE that differ by one ulp in the first-moment exponents after the first step drift apart
+    within ten steps (the difference is amplified where beta1 m + (1 - beta1) g cancels, moves group
+    minima, hence k, hence every code of those groups), while the weights stay within a fraction of the
+    learning rate of each other and the second moment, which has no cancellation, hardly moves."""
+    n, G = 256 * 1024, 128
+    w_a = S.weights(n, 6)
+    w_b = w_a.copy()
+    st_a, st_b = S.zero_state(n, G), S.zero_state(n, G)
+    for t in range(1, 11):
+        g = S.grads_normal(n, 6, t, G=G, outlier_frac=0.01)
+        hp = ref.make_hparams(step=t, group_size=G, **HP)
+        for w, st in ((w_a, st_a), (w_b, st_b)):
+            assert ref.fp8_adamw_step(w, g, st["m_q"], st["m_scale"], st["m_k"], st["v_q"], st["v_scale"], st["v_k"], hp) == 0
+        if t == 1:
+            assert all(np.array_equal(st_a[k], st_b[k]) for k in st_a)
+            st_b["m_k"] = np.nextafter(st_b["m_k"], np.float32(np.inf))          # one ulp, 6e-8 relative
+    m_differ = float(np.mean(st_a["m_q"] != st_b["m_q"]))
+    v_differ = float(np.mean(st_a["v_q"] != st_b["v_q"]))
+    dw = float(np.max(np.abs(w_a.astype(np.float64) - w_b)))
+    with capsys.disabled():
+        print("\n[one ulp of k after step 1, ten steps on] first-moment codes that differ: %.3f; second-moment codes: %.1e; "
+              "worst |dw| %.2e (lr %.0e)" % (m_differ, v_differ, dw, HP["lr"]))
+    assert m_differ > 0.05                       # far beyond any per-step parity rate
+    assert v_differ < 1e-2 and dw < HP["lr"]
