@@ -32,6 +32,16 @@ struct StaticMode {
   __device__ __forceinline__ bool scale16() const { return false; }
   __device__ __forceinline__ bool k16() const { return false; }
 };
+// E4M3 with expansion as in the default cell, but with the per-group scales and / or exponents
+// stored as bf16: only the few per-group operations depend on run-time values, the per-element
+// code folds as in StaticMode.
+struct Bf16MetaMode {
+  bool s16, kh;
+  __device__ __forceinline__ bool e5m2() const { return false; }
+  __device__ __forceinline__ bool expand() const { return true; }
+  __device__ __forceinline__ bool scale16() const { return s16; }
+  __device__ __forceinline__ bool k16() const { return kh; }
+};
 struct RuntimeMode {
   bool e5, ex;
   bool s16;   // the per-group scales are stored as bf16 (Sec. 3) instead of fp32
@@ -348,9 +358,9 @@ constexpr float kLn2 = 0.6931471805599453f;
 //   ACCURATE = false: exp2(L * (1/k)), good to about |L/k| * 2^-22 relative;
 //   ACCURATE = true : the rounding of the product and of 1/k is recovered with one fma
 //     (r = L - t*k is the exact residual of t = fl(L * fl(1/k)) against L/k, times k), the
-//     table's own rounding is added from its low word, and exp2(t + d) = exp2(t) * (1 + d ln2).
-//     Used for the first moment, whose update beta1*m + (1-beta1)*g cancels and so amplifies
-//     the error of m into the group minimum that fixes the next exponent k.
+//     table's own rounding is added from its low word, and exp2(t + d) = exp2(t) * (1 + d ln2):
+//     within a few ulp of the fp64 value.  The standalone dequantizer uses it; the fused step does
+//     not need it (what decides there is recomputed exactly, see ExactChain).
 //   SIGNED: carry the code's sign bit into the result.
 template <bool SIGNED, bool ACCURATE>
 __device__ __forceinline__ void inverse_expand16(const Log2Entry* lut, const uint32_t (&c)[4], float k,
@@ -426,13 +436,15 @@ __device__ __forceinline__ GroupQuant group_quant_params(const Mode& md, float a
   const float ax = amax * unit;
   float s = ax * inv_fmax;
   s = __builtin_fmaf(__builtin_fmaf(-fmax, s, ax), inv_fmax, s);
-  float top = amax;                                  // what the group is normalized by, in held units
-  if (md.scale16()) {
-    // BF16 scale: round UP to a bf16 value (every |x| / (fmax*scale) stays <= 1, nothing saturates)
-    // and take the range that has to fit the format against fmax*scale rather than amax
-    s = as_f32((as_u32(s) + 0xFFFFu) & 0xFFFF0000u);
-    top = (fmax * s) / unit;
-  }
+  // BF16 scale: round UP to a bf16 value (every |x| / (fmax*scale) stays <= 1, nothing saturates)
+  // and take the range that has to fit the format against fmax*scale rather than amax.  Written
+  // with selects: a branch here, even a uniform one, cuts the straight-line code that the exact
+  // chain is interleaved with.  (The reciprocal's ulp moves k by 1e-7 / ln R at most.)
+  const float s_up = as_f32((as_u32(s) + 0xFFFFu) & 0xFFFF0000u);
+  const float top_up = (fmax * s_up) * hw_rcp(unit);
+  const bool s16 = md.scale16();
+  s = s16 ? s_up : s;
+  const float top = s16 ? top_up : amax;             // what the group is normalized by, in held units
   float k = 1.0f;
   if (md.expand()) {
     // two hardware reciprocals (1 ulp each) are enough here: k moves by ~2 ulp

@@ -19,7 +19,8 @@
 // Arithmetic (fp32 throughout; transcendentals are the hardware log2/exp2/rcp/sqrt), with fmax
 // the largest finite value of the moment's FP8 format (448 for E4M3, 57344 for E5M2):
 //   inverse expansion  |c/fmax|^(1/k) = exp2( log2|c/fmax| * (1/k) ), the logarithm from a table
-//                      of the 127 code magnitudes (compensated for the first moment);
+//                      of the 127 code magnitudes; the one element per lane that decides a group's
+//                      exponent is recomputed in fp64 (ExactChain);
 //   expansion          fmax * (|x|/a)^k = exp2( k * log2(|x| * (1/a)) + log2 fmax ), the logarithm
 //                      taken of the RATIO so that its magnitude stays below log2(range)/k;
 //   conversion         native fp32 -> OCP FP8 pack instructions (round to nearest even).
@@ -78,25 +79,25 @@ bool resolve_k_bounds(float& k_min, float& k_max) {
 
 int launch_status() { return hipGetLastError() == hipSuccess ? COAT_OK : COAT_ERR_LAUNCH; }
 
-// The step kernel asks for this much dynamic LDS on top of its ~30 KiB of tiles and table, for no
-// other purpose than to hold a CU to three resident blocks (12 wavefronts).  With fewer bytes in
-// flight per CU the HBM controllers see longer same-page runs; three blocks rather than two cover
-// the wait at the admission gate (measured on the 7B set, with the gate: 2 blocks 15.6 ms,
-// 3 blocks 15.05, 4 blocks 15.3, 5 blocks 15.35; without it: 15.85, 16.1, 16.3, 16.3).
+// The step kernel asks for this much dynamic LDS on top of the 37 KiB it declares (tiles, tables,
+// scratch), for no other purpose than to hold a CU to three resident blocks (12 wavefronts).  With
+// fewer bytes in flight per CU the HBM controllers see longer same-page runs; three blocks rather
+// than two cover the wait at the admission gate (measured on the 7B set: 2 blocks 16.4 ms,
+// 3 blocks 14.9, 4 blocks 16.7).
 constexpr size_t kStepLdsPad = 12 * 1024;
 constexpr size_t kStepStaticLds = 37 * 1024;       // what the step kernel declares itself (tiles, tables, scratch)
 constexpr size_t kMultiLdsPad = 12 * 1024;
 
-template <int G, bool GENERIC>
+template <int G, int KIND>
 int launch_step(const StepArgs& a, hipStream_t s) {
   if (a.n_full) {
     const unsigned grid = grid_for(a.n_full);
     size_t lds = kStepLdsPad;
-    hipLaunchKernelGGL((adamw_step_kernel<G, GENERIC>), dim3(grid), dim3(kBlock), lds, s, a);
+    hipLaunchKernelGGL((adamw_step_kernel<G, KIND>), dim3(grid), dim3(kBlock), lds, s, a);
     if (int rc = launch_status()) return rc;
   }
   if (a.n > a.n_full * kChunk) {
-    hipLaunchKernelGGL((adamw_step_tail_kernel<G, GENERIC>), dim3(1), dim3(kWave), 0, s, a);
+    hipLaunchKernelGGL((adamw_step_tail_kernel<G, KIND>), dim3(1), dim3(kWave), 0, s, a);
     if (int rc = launch_status()) return rc;
   }
   return COAT_OK;
@@ -138,9 +139,10 @@ int launch_dequant(const DequantArgs& a, hipStream_t s) {
   }                                         \
   return COAT_ERR_GROUP
 
-int dispatch_step(const StepArgs& a, int32_t G, bool generic, hipStream_t s) {
-  if (!generic) { COAT_DISPATCH_G(G, (launch_step<kG, false>(a, s))); }
-  COAT_DISPATCH_G(G, (launch_step<kG, true>(a, s)));
+int dispatch_step(const StepArgs& a, int32_t G, int kind, hipStream_t s) {
+  if (kind == kKindDefault) { COAT_DISPATCH_G(G, (launch_step<kG, kKindDefault>(a, s))); }
+  if (kind == kKindBf16Meta) { COAT_DISPATCH_G(G, (launch_step<kG, kKindBf16Meta>(a, s))); }
+  COAT_DISPATCH_G(G, (launch_step<kG, kKindGeneric>(a, s)));
 }
 
 template <int G>
@@ -262,17 +264,18 @@ int act_quant_tensor_impl(const uint16_t* x, uint64_t n, int32_t G, float* group
   return launch_act_quant<16, true>(a, s);   // the group size plays no part once the scale is per tensor
 }
 
-template <int G, bool GENERIC>
+template <int G, int KIND>
 int launch_step_multi(const MultiArgs& ma, uint64_t total_records, hipStream_t s) {
   const uint64_t blocks = total_records * (kPlanSpan / kWavesPerBlock);
   size_t lds = kMultiLdsPad;
-  hipLaunchKernelGGL((adamw_step_multi_kernel<G, GENERIC>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), lds, s, ma);
+  hipLaunchKernelGGL((adamw_step_multi_kernel<G, KIND>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), lds, s, ma);
   return launch_status();
 }
 
-int dispatch_step_multi(const MultiArgs& ma, uint64_t total_records, int32_t G, bool generic, hipStream_t s) {
-  if (!generic) { COAT_DISPATCH_G(G, (launch_step_multi<kG, false>(ma, total_records, s))); }
-  COAT_DISPATCH_G(G, (launch_step_multi<kG, true>(ma, total_records, s)));
+int dispatch_step_multi(const MultiArgs& ma, uint64_t total_records, int32_t G, int kind, hipStream_t s) {
+  if (kind == kKindDefault) { COAT_DISPATCH_G(G, (launch_step_multi<kG, kKindDefault>(ma, total_records, s))); }
+  if (kind == kKindBf16Meta) { COAT_DISPATCH_G(G, (launch_step_multi<kG, kKindBf16Meta>(ma, total_records, s))); }
+  COAT_DISPATCH_G(G, (launch_step_multi<kG, kKindGeneric>(ma, total_records, s)));
 }
 
 constexpr uint32_t kStepFlags = COAT_FLAG_EXPAND | COAT_FLAG_M_E5M2 | COAT_FLAG_V_E5M2 | COAT_FLAG_M_PLAIN |
@@ -290,7 +293,7 @@ uint64_t plan_records_of(uint64_t n) {               // spans of 32 chunks a ten
 
 // Validates the hyper-parameters and fills every field of StepArgs that does not depend on the
 // tensor (the pointers, sizes and the decay factor are set by the caller).
-int step_constants(const coat_adamw_hparams* hp, StepArgs& a, bool& generic) {
+int step_constants(const coat_adamw_hparams* hp, StepArgs& a, int& kind) {
   if (!hp) return COAT_ERR_NULL;
   if (!group_ok(hp->group_size)) return COAT_ERR_GROUP;
   if (hp->step < 1) return COAT_ERR_STEP;
@@ -340,7 +343,8 @@ int step_constants(const coat_adamw_hparams* hp, StepArgs& a, bool& generic) {
   a.mode_v.ex = expand && !(hp->flags & COAT_FLAG_V_PLAIN);
   a.mode_m.s16 = a.mode_v.s16 = (hp->flags & COAT_FLAG_BF16_SCALE) != 0;
   a.mode_m.kh = a.mode_v.kh = (hp->flags & COAT_FLAG_BF16_K) != 0;
-  generic = a.mode_m.e5 || a.mode_v.e5 || !a.mode_m.ex || !a.mode_v.ex || a.mode_m.s16 || a.mode_m.kh;
+  const bool default_cell = !a.mode_m.e5 && !a.mode_v.e5 && a.mode_m.ex && a.mode_v.ex;
+  kind = !default_cell ? kKindGeneric : (a.mode_m.s16 || a.mode_m.kh) ? kKindBf16Meta : kKindDefault;
   return COAT_OK;
 }
 
@@ -348,8 +352,8 @@ int step_constants(const coat_adamw_hparams* hp, StepArgs& a, bool& generic) {
 int step_multi_impl(const void* plan_host, const void* plan_device, const coat_adamw_hparams* hp,
                     const coat_step_consts* consts_device, bool want_consts, void* hip_stream) {
   MultiArgs ma;
-  bool generic = false;
-  if (int rc = step_constants(hp, ma.base, generic)) return rc;
+  int kind = kKindDefault;
+  if (int rc = step_constants(hp, ma.base, kind)) return rc;
   if (!plan_host) return COAT_ERR_NULL;
   PlanHeader h;
   __builtin_memcpy(&h, plan_host, sizeof h);
@@ -368,7 +372,7 @@ int step_multi_impl(const void* plan_host, const void* plan_device, const coat_a
   ma.records = reinterpret_cast<const PlanRecord*>(dev + h.record_offset);
   ma.neg_lr = -static_cast<double>(hp->lr);
   ma.consts = reinterpret_cast<const StepConsts*>(consts_device);
-  return dispatch_step_multi(ma, h.total_records, hp->group_size, generic, static_cast<hipStream_t>(hip_stream));
+  return dispatch_step_multi(ma, h.total_records, hp->group_size, kind, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // namespace
@@ -385,8 +389,8 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
                               void* m_scale, void* m_k, uint8_t* v_q, void* v_scale, void* v_k,
                               uint64_t n, const coat_adamw_hparams* hp, void* hip_stream) {
   StepArgs a;
-  bool generic = false;
-  if (int rc = step_constants(hp, a, generic)) return rc;
+  int kind = kKindDefault;
+  if (int rc = step_constants(hp, a, kind)) return rc;
   if (n == 0) return COAT_OK;
   if (!w || !grad_bf16 || !m_q || !m_scale || !m_k || !v_q || !v_scale || !v_k) return COAT_ERR_NULL;
   if (!aligned16(w) || !aligned16(grad_bf16) || !aligned16(m_q) || !aligned16(v_q) ||
@@ -397,7 +401,7 @@ int coat_fp8_adamw_step_bf16w(float* w, uint16_t* w_bf16, const uint16_t* grad_b
   a.n = n; a.n_full = n / kChunk;
   a.n_groups = (n + static_cast<uint64_t>(hp->group_size) - 1) / static_cast<uint64_t>(hp->group_size);
   a.w_keep = static_cast<float>(1.0 - static_cast<double>(hp->lr) * static_cast<double>(hp->weight_decay));
-  return dispatch_step(a, hp->group_size, generic, static_cast<hipStream_t>(hip_stream));
+  return dispatch_step(a, hp->group_size, kind, static_cast<hipStream_t>(hip_stream));
 }
 
 size_t coat_multi_plan_bytes(const coat_tensor_desc* descs, uint32_t count) {
@@ -448,8 +452,8 @@ int coat_multi_plan_build(const coat_tensor_desc* descs, uint32_t count, void* p
 int coat_step_consts_compute(const coat_adamw_hparams* hp, coat_step_consts* out) {
   if (!out) return COAT_ERR_NULL;
   StepArgs a;
-  bool generic = false;
-  if (int rc = step_constants(hp, a, generic)) return rc;
+  int kind = kKindDefault;
+  if (int rc = step_constants(hp, a, kind)) return rc;
   coat_step_consts c = {};
   c.denom_mul = a.denom_mul;
   c.denom_add = a.denom_add;

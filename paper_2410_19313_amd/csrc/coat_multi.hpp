@@ -73,15 +73,15 @@ struct MultiArgs {
   const StepConsts* consts;  // nullptr: the step's constants are the arguments above
 };
 
-template <int G, bool GENERIC>
+template <int G, int KIND>
 __global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) {
-  constexpr int kTables = GENERIC ? 2 : 1;
+  constexpr int kTables = KIND == kKindGeneric ? 2 : 1;
   __shared__ Log2Entry lut[256 * kTables];
   __shared__ double frac[kExp2Frac];
   __shared__ f32x4 tile_w[kWavesPerBlock * kTileSlotsW];
   __shared__ u32x4 tile_g[kWavesPerBlock * kTileSlotsG];
   __shared__ u32x4 code_scratch[kBlock];
-  const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(ma.base), mv = ModesOf<GENERIC>::v(ma.base);
+  const typename ModesOf<KIND>::M mm = ModesOf<KIND>::m(ma.base), mv = ModesOf<KIND>::v(ma.base);
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const StageTiles tiles = {tile_w + wv * kTileSlotsW, tile_g + wv * kTileSlotsG, code_scratch + wv * kWave};

@@ -208,32 +208,41 @@ __device__ __forceinline__ uint64_t gate_on_neighbourhood(const void* words, uin
   return (chunk & 0xffffffff00000000ull) | lo;
 }
 
-template <bool GENERIC> struct ModesOf;
-template <> struct ModesOf<false> {
+// Which kernel serves a call: the default cell folded at compile time, the default cell with bf16
+// metadata, or everything else with the storage modes as run-time values.
+constexpr int kKindDefault = 0, kKindGeneric = 1, kKindBf16Meta = 2;
+template <int KIND> struct ModesOf;
+template <> struct ModesOf<kKindDefault> {
   typedef DefaultMode M;
   __device__ static DefaultMode m(const StepArgs&) { return DefaultMode(); }
   __device__ static DefaultMode v(const StepArgs&) { return DefaultMode(); }
 };
-template <> struct ModesOf<true> {
+template <> struct ModesOf<kKindGeneric> {
   typedef RuntimeMode M;
   __device__ static RuntimeMode m(const StepArgs& a) { return a.mode_m; }
   __device__ static RuntimeMode v(const StepArgs& a) { return a.mode_v; }
+};
+template <> struct ModesOf<kKindBf16Meta> {
+  typedef Bf16MetaMode M;
+  __device__ static Bf16MetaMode m(const StepArgs& a) { return Bf16MetaMode{a.mode_m.s16, a.mode_m.kh}; }
+  __device__ static Bf16MetaMode v(const StepArgs& a) { return Bf16MetaMode{a.mode_v.s16, a.mode_v.kh}; }
 };
 
 // Main kernel: one chunk per wavefront (the loop only runs again for buffers with more chunks
 // than the grid has wavefronts).  Order of the memory requests: the block's table entries, the
 // gate's probe, the chunk's loads (see fill_issue).
-// GENERIC = false: both moments E4M3 with expansion (the method as the paper runs it);
-// GENERIC = true : per-moment format and expansion read from the arguments (Table 1's grid).
-template <int G, bool GENERIC>
+// KIND = default : both moments E4M3 with expansion (the method as the paper runs it);
+// KIND = bf16 meta: the same with scales and / or exponents stored as bf16;
+// KIND = generic : per-moment format and expansion read from the arguments (Table 1's grid).
+template <int G, int KIND>
 __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
-  constexpr int kTables = GENERIC ? 2 : 1;
+  constexpr int kTables = KIND == kKindGeneric ? 2 : 1;
   __shared__ Log2Entry lut[256 * kTables];
   __shared__ double frac[kExp2Frac];
   __shared__ f32x4 tile_w[kWavesPerBlock * kTileSlotsW];
   __shared__ u32x4 tile_g[kWavesPerBlock * kTileSlotsG];
   __shared__ u32x4 code_scratch[kBlock];
-  const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(a), mv = ModesOf<GENERIC>::v(a);
+  const typename ModesOf<KIND>::M mm = ModesOf<KIND>::m(a), mv = ModesOf<KIND>::v(a);
   const int lane = threadIdx.x & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wavefront-uniform
   const StageTiles tiles = {tile_w + wv * kTileSlotsW, tile_g + wv * kTileSlotsG, code_scratch + wv * kWave};
@@ -321,9 +330,9 @@ __device__ __forceinline__ void process_tail_chunk(const StepArgs& a, const Mode
   step_core<G>(a, mm, mv, tb, ls, mc, vc, meta, IO{a, mm, mv, w, g, base, gidx, gvalid && (lane % LPG) == 0});
 }
 
-template <int G, bool GENERIC>
+template <int G, int KIND>
 __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
-  constexpr int kTables = GENERIC ? 2 : 1;
+  constexpr int kTables = KIND == kKindGeneric ? 2 : 1;
   __shared__ Log2Entry lut[256 * kTables];
   __shared__ double frac[kExp2Frac];
   __shared__ u32x4 slots[3 * kWave];
@@ -331,7 +340,7 @@ __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
   fill_issue(fill);
   fill_commit(fill, lut, frac);
   const StepTables tb = {lut, frac};
-  const typename ModesOf<GENERIC>::M mm = ModesOf<GENERIC>::m(a), mv = ModesOf<GENERIC>::v(a);
+  const typename ModesOf<KIND>::M mm = ModesOf<KIND>::m(a), mv = ModesOf<KIND>::v(a);
   process_tail_chunk<G>(a, mm, mv, tb, slots + 3 * threadIdx.x, threadIdx.x);
 }
 

@@ -236,7 +236,7 @@ def test_effect_of_rounding_the_dequantized_moments_to_fp32(ref, capsys):
     function and rounds to fp32 what the method stores or decides on; the other reading also rounds
     the dequantized moments (COAT_REF_FLAG_DQ_FP32).  This measures what separates the two: far less
     than the parity bar on the weights, a few codes in 10^5 and, where the update cancels, the group
-    exponent k.  (A measurement with loose limits; its numbers are recorded in the design notes.)"""
+    exponent k.  (A measurement with loose limits.)"""
     n, G = 512 * 1024, 128
     st_a, st_b = S.zero_state(n, G), S.zero_state(n, G)
     w_a = S.weights(n, 4)
