@@ -412,9 +412,12 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": (read_profile_traffic(args.workload, G)
                                  if not (generic or args.emit_bf16 or args.multi) else None),   # the counters were read for the default kernel
                      "algorithmic_bytes_per_launch": head["algorithmic_bytes_per_launch"], "avg_launch_ms": head["avg_launch_ms"],
+                     "traffic_gbs": None,            # counter bytes over this run's launch time, filled in below
                      "copy_control_gbs": head.get("copy_control_gbs"), "frac_of_copy_control": head.get("frac_of_copy_control"),
                      "kernel": "adamw_step%s_kernel<%d, %s>" % ("_multi" if args.multi else "", G, "generic" if generic else "default")},
     }
+    if out["roofline"]["traffic"]:
+        out["roofline"]["traffic_gbs"] = out["roofline"]["traffic"] / (head["avg_launch_ms"] * 1e-3) / 1e9
     if not args.only and args.workload == "cfg3" and not (generic or args.emit_bf16 or args.multi):
         # the other configurations of the report, each at its stated length and, for the sub-millisecond
         # ones, once more at steady clocks; one row per configuration (cfg4: one per group size)

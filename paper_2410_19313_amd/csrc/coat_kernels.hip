@@ -600,7 +600,7 @@ const char* coat_strerror(int code) {
   return "unknown error code";
 }
 
-int coat_version(void) { return 230; }
+int coat_version(void) { return 240; }
 
 
 }  // extern "C"
