@@ -6,7 +6,8 @@
  *
  * Conventions shared by every entry point
  *   - Every data pointer is caller-owned DEVICE memory on the current HIP device.  The
- *     library allocates nothing, keeps no state between calls and frees nothing.
+ *     library allocates nothing, keeps no state between calls and frees nothing (one entry point,
+ *     coat_act_quant_tensor_static, works in a small device array of the library's own: see there).
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work on that stream; the caller synchronizes.
  *   - A tensor is a flat buffer of n elements.  Every G consecutive elements form one

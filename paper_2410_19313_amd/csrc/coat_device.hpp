@@ -32,16 +32,18 @@ struct StaticMode {
   __device__ __forceinline__ bool scale16() const { return false; }
   __device__ __forceinline__ bool k16() const { return false; }
 };
-// E4M3 with expansion as in the default cell, but with the per-group scales and / or exponents
-// stored as bf16: only the few per-group operations depend on run-time values, the per-element
-// code folds as in StaticMode.
-struct Bf16MetaMode {
+// Format and expansion folded at compile time, the storage of the per-group scales and exponents
+// (fp32 or bf16) as run-time values: only the few per-group operations depend on those, the
+// per-element code folds as in StaticMode.  Bf16MetaMode is the default cell with bf16 metadata.
+template <bool E5M2, bool EXPAND>
+struct FoldedMode {
   bool s16, kh;
-  __device__ __forceinline__ bool e5m2() const { return false; }
-  __device__ __forceinline__ bool expand() const { return true; }
+  __device__ __forceinline__ bool e5m2() const { return E5M2; }
+  __device__ __forceinline__ bool expand() const { return EXPAND; }
   __device__ __forceinline__ bool scale16() const { return s16; }
   __device__ __forceinline__ bool k16() const { return kh; }
 };
+typedef FoldedMode<false, true> Bf16MetaMode;
 struct RuntimeMode {
   bool e5, ex;
   bool s16;   // the per-group scales are stored as bf16 (Sec. 3) instead of fp32
@@ -89,7 +91,7 @@ struct StepArgs {
   float k_min, k_max;
   RuntimeMode mode_m, mode_v;
   // the same first-moment update in fp64, for the one element per lane that is recomputed exactly
-  // (exact_candidate): m_t / (1 - beta1) = m_ratio64 * m + g_coef64 * g, with beta1 the fp32
+  // (ExactChain): m_t / (1 - beta1) = m_ratio64 * m + g_coef64 * g, with beta1 the fp32
   // hyper-parameter taken as a double; g_coef64 = (1 - beta1) / one_minus_beta1 is 1 whenever the
   // fp32 difference 1 - beta1 is exact (beta1 >= 0.5)
   double m_ratio64, g_coef64;
@@ -307,7 +309,7 @@ __device__ __forceinline__ void tile_lanes_to_rows_store_bf16(u32x4* tile, int l
 
 // The tables a step kernel keeps in LDS: the logarithms of the code magnitudes (per format 256
 // entries so that the whole code byte indexes it; the sign bit is ignored) and the fractional
-// powers 2^(j/512) that exp2_f64 looks up.  TABLES = 1 loads E4M3 only, 2 loads E4M3 then E5M2.
+// powers 2^(j/512) that ExactChain looks up.  TABLES = 1 loads E4M3 only, 2 loads E4M3 then E5M2.
 constexpr int kExp2Frac = kExp2FracSize;
 struct StepTables { const Log2Entry* lut; const double* frac; };
 

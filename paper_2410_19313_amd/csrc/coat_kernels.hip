@@ -87,6 +87,7 @@ int launch_status() { return hipGetLastError() == hipSuccess ? COAT_OK : COAT_ER
 constexpr size_t kStepLdsPad = 12 * 1024;
 constexpr size_t kStepStaticLds = 37 * 1024;       // what the step kernel declares itself (tiles, tables, scratch)
 constexpr size_t kMultiLdsPad = 12 * 1024;
+constexpr size_t kQuantLdsPad = 12 * 1024;
 
 template <int G, int KIND>
 int launch_step(const StepArgs& a, hipStream_t s) {
@@ -106,7 +107,9 @@ int launch_step(const StepArgs& a, hipStream_t s) {
 template <int G>
 int launch_quant(const QuantArgs& a, hipStream_t s) {
   if (a.n_full) {
-    hipLaunchKernelGGL((quant_kernel<G>), dim3(grid_for(a.n_full)), dim3(kBlock), 0, s, a);
+    // 12 KiB of dynamic LDS on top of the 18 KiB tile hold a CU to five resident blocks (6.7e9
+    // elements: no request, 7 blocks, 5.68 ms; 6 KiB 5.59; 9 or 12 KiB 5.50; 16 KiB 5.54; 24 KiB 5.81)
+    hipLaunchKernelGGL((quant_kernel<G>), dim3(grid_for(a.n_full)), dim3(kBlock), kQuantLdsPad, s, a);
     if (int rc = launch_status()) return rc;
   }
   if (a.n > a.n_full * kChunk) {
@@ -589,7 +592,7 @@ const char* coat_strerror(int code) {
   switch (code) {
     case COAT_OK: return "ok";
     case COAT_ERR_NULL: return "a required pointer is NULL";
-    case COAT_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
+    case COAT_ERR_ALIGN: return "a base pointer is not aligned as required (16 bytes; 4 for per-group scale and k arrays)";
     case COAT_ERR_GROUP: return "group size must be one of 32, 64, 128, 256, 512 (activation quantizers: also 16)";
     case COAT_ERR_STEP: return "step must be >= 1";
     case COAT_ERR_HPARAM: return "hyper-parameter or flag is non-finite, unsupported or out of its domain";

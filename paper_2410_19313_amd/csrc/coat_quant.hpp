@@ -9,16 +9,28 @@ namespace {
 // ---------------------------------------------------------------------------------------
 
 // quantize one lane's 16 values (cross-lane: the group reductions) and hand back codes + metadata
-template <int G>
-__device__ __forceinline__ GroupQuant quant_core(const QuantArgs& a, const float (&x)[kEPL], uint32_t (&c)[4]) {
+template <int G, class Mode>
+__device__ __forceinline__ GroupQuant quant_core_as(const Mode& md, const QuantArgs& a, const float (&x)[kEPL], uint32_t (&c)[4]) {
   constexpr int LPG = G / kEPL;
   float hi, lo;
   lane_extremes(x, hi, lo);
   hi = group_allreduce<LPG, true>(hi);
   lo = group_allreduce<LPG, false>(lo);
-  const GroupQuant q = group_quant_params(a.mode, hi, lo, a.k_min, a.k_max, 1.0f);
-  quantize16<true>(a.mode, x, q, c, 1.0f);
+  const GroupQuant q = group_quant_params(md, hi, lo, a.k_min, a.k_max, 1.0f);
+  quantize16<true>(md, x, q, c, 1.0f);
   return q;
+}
+// Format and expansion are wavefront-uniform run-time values; one branch per chunk picks the code
+// with both folded (left as per-element selects they compile to a hundred short basic blocks).
+template <int G>
+__device__ __forceinline__ GroupQuant quant_core(const QuantArgs& a, const float (&x)[kEPL], uint32_t (&c)[4]) {
+  const bool s16 = a.mode.scale16(), kh = a.mode.k16();
+  if (a.mode.expand()) {
+    if (a.mode.e5m2()) return quant_core_as<G>(FoldedMode<true, true>{s16, kh}, a, x, c);
+    return quant_core_as<G>(FoldedMode<false, true>{s16, kh}, a, x, c);
+  }
+  if (a.mode.e5m2()) return quant_core_as<G>(FoldedMode<true, false>{s16, kh}, a, x, c);
+  return quant_core_as<G>(FoldedMode<false, false>{s16, kh}, a, x, c);
 }
 
 // full chunks: coalesced streaming row loads of x staged through the LDS tile, one chunk per wavefront
@@ -30,7 +42,8 @@ __global__ __launch_bounds__(kBlock) void quant_kernel(QuantArgs a) {
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kWavesPerBlock;
   for (uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv; chunk < a.n_full; chunk += stride) {
-    chunk = gate_on_neighbourhood(a.x, chunk, kChunk);   // measured: 871 -> 845 us on 2^30 elements
+    // (measured: 871 -> 845 us on 2^30 elements with the gate; spans of 16 / 32 / 64 / 128 chunks alike)
+    chunk = gate_on_neighbourhood(a.x, chunk, kChunk);
     const uint64_t cb = chunk * kChunk, gb = chunk * (kChunk / G);
     const f32x4* xq = reinterpret_cast<const f32x4*>(a.x + cb);
     f32x4 rows[4];
