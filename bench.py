@@ -321,6 +321,7 @@ def main():
     ap.add_argument("--m-plain", action="store_true", help="first moment without dynamic range expansion")
     ap.add_argument("--v-plain", action="store_true", help="second moment without dynamic range expansion")
     ap.add_argument("--bf16-scale", action="store_true", help="per-group scales stored as bf16 (14 + 24/G B/param)")
+    ap.add_argument("--precise-dq", action="store_true", help="the more accurate inverse expansion (COAT_FLAG_PRECISE_DQ)")
     ap.add_argument("--bf16-k", action="store_true", help="per-group exponents stored as bf16 (with --bf16-scale: 14 + 16/G B/param)")
     ap.add_argument("--emit-bf16", action="store_true", help="also write the bf16 copy of the new weights (+2 B/param)")
     ap.add_argument("--multi", action="store_true",
@@ -383,7 +384,7 @@ def main():
         return
 
     flags = dict(m_e5m2=args.m_e5m2, v_e5m2=args.v_e5m2, m_plain=args.m_plain, v_plain=args.v_plain, bf16_scale=args.bf16_scale,
-                 bf16_k=args.bf16_k)
+                 bf16_k=args.bf16_k, precise_dq=args.precise_dq)
     generic = any(flags.values())
     head = run_step_config(C, S, torch, dev, args.workload, G, grads_kind, args.warmup, args.steps,
                            copy_control=not args.only, flags=flags, emit_bf16=args.emit_bf16, multi=args.multi,
@@ -405,7 +406,7 @@ def main():
         "config": {"workload": "%s: %s, %d params, G=%d, grads %s" % (args.workload, WORKLOAD_TEXT[args.workload], n, G, grads_kind) + (
                     ", m %s%s, v %s%s" % ("E5M2" if args.m_e5m2 else "E4M3", "" if args.m_plain else "+expand",
                                             "E5M2" if args.v_e5m2 else "E4M3", "" if args.v_plain else "+expand")
-                    if generic else "") + (", bf16 weight copy" if args.emit_bf16 else "") + (", bf16 scales" if args.bf16_scale else "") + (", bf16 exponents" if args.bf16_k else "") + (
+                    if generic else "") + (", bf16 weight copy" if args.emit_bf16 else "") + (", bf16 scales" if args.bf16_scale else "") + (", bf16 exponents" if args.bf16_k else "") + (", precise dequantization" if args.precise_dq else "") + (
                         ", %d tensors in one multi-tensor launch" % head["tensors"] if args.multi else ""),
             "params": n, "group_size": G, "hbm_gbs": achieved, "hbm_frac_of_peak": achieved / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -12,7 +12,7 @@ import os
 
 from . import build as _build
 
-FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN, FLAG_BF16_SCALE, FLAG_BF16_K = 1, 2, 2, 4, 8, 16, 32, 64
+FLAG_EXPAND, FLAG_M_E5M2, FLAG_E5M2, FLAG_V_E5M2, FLAG_M_PLAIN, FLAG_V_PLAIN, FLAG_BF16_SCALE, FLAG_BF16_K, FLAG_PRECISE_DQ = 1, 2, 2, 4, 8, 16, 32, 64, 128
 SUPPORTED_GROUP_SIZES = (32, 64, 128, 256, 512)
 
 ACT_GROUP_SIZES = (16,) + SUPPORTED_GROUP_SIZES
@@ -68,10 +68,11 @@ class StepConsts(ctypes.Structure):
 
 
 def step_flags(expand=True, m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False,
-               bf16_k=False) -> int:
+               bf16_k=False, precise_dq=False) -> int:
     return ((FLAG_EXPAND if expand else 0) | (FLAG_M_E5M2 if m_e5m2 else 0) | (FLAG_V_E5M2 if v_e5m2 else 0)
             | (FLAG_M_PLAIN if m_plain else 0) | (FLAG_V_PLAIN if v_plain else 0)
-            | (FLAG_BF16_SCALE if bf16_scale else 0) | (FLAG_BF16_K if bf16_k else 0))
+            | (FLAG_BF16_SCALE if bf16_scale else 0) | (FLAG_BF16_K if bf16_k else 0)
+            | (FLAG_PRECISE_DQ if precise_dq else 0))
 
 
 def _scale_dtype(flags: int):
@@ -86,9 +87,10 @@ def _k_dtype(flags: int):
 
 def make_hparams(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1,
                  group_size=128, expand=True, k_min=0.0, k_max=0.0,
-                 m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False, bf16_k=False) -> HParams:
+                 m_e5m2=False, v_e5m2=False, m_plain=False, v_plain=False, bf16_scale=False, bf16_k=False,
+                 precise_dq=False) -> HParams:
     return HParams(lr, beta1, beta2, eps, weight_decay, int(step), int(group_size),
-                   step_flags(expand, m_e5m2, v_e5m2, m_plain, v_plain, bf16_scale, bf16_k), k_min, k_max)
+                   step_flags(expand, m_e5m2, v_e5m2, m_plain, v_plain, bf16_scale, bf16_k, precise_dq), k_min, k_max)
 
 
 _lib = None

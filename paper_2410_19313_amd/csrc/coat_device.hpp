@@ -25,8 +25,11 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // fast path); RuntimeMode carries the two switches as wavefront-uniform values, so one kernel per
 // group size serves the other fifteen combinations.
 // ---------------------------------------------------------------------------------------
-template <bool E5M2, bool EXPAND>
+// kDq: which inverse expansion the fused step uses for this moment (see inverse_expand16): 0 the
+// plain one, 1 with the rounding of the exponent recovered.
+template <bool E5M2, bool EXPAND, int DQ = 0>
 struct StaticMode {
+  static constexpr int kDq = DQ;
   __device__ __forceinline__ bool e5m2() const { return E5M2; }
   __device__ __forceinline__ bool expand() const { return EXPAND; }
   __device__ __forceinline__ bool scale16() const { return false; }
@@ -37,6 +40,7 @@ struct StaticMode {
 // per-element code folds as in StaticMode.  Bf16MetaMode is the default cell with bf16 metadata.
 template <bool E5M2, bool EXPAND>
 struct FoldedMode {
+  static constexpr int kDq = 0;
   bool s16, kh;
   __device__ __forceinline__ bool e5m2() const { return E5M2; }
   __device__ __forceinline__ bool expand() const { return EXPAND; }
@@ -45,6 +49,7 @@ struct FoldedMode {
 };
 typedef FoldedMode<false, true> Bf16MetaMode;
 struct RuntimeMode {
+  static constexpr int kDq = 1;   // the generic kernel always takes the more accurate inverse expansion
   bool e5, ex;
   bool s16;   // the per-group scales are stored as bf16 (Sec. 3) instead of fp32
   bool kh;    // the per-group exponents k are stored as bf16 as well
@@ -54,6 +59,7 @@ struct RuntimeMode {
   __device__ __forceinline__ bool k16() const { return kh; }
 };
 typedef StaticMode<false, true> DefaultMode;
+typedef StaticMode<false, true, 1> PreciseMode;   // the default cell for callers who set COAT_FLAG_PRECISE_DQ
 
 template <class Mode> __device__ __forceinline__ float fmt_max(const Mode& md) { return md.e5m2() ? 57344.0f : 448.0f; }
 template <class Mode> __device__ __forceinline__ float fmt_inv_max(const Mode& md) {
@@ -357,14 +363,18 @@ __device__ __forceinline__ void fill_commit(const FillRegs<TABLES, THREADS>& fr,
 constexpr float kLn2 = 0.6931471805599453f;
 
 // |c/fmax|^(1/k) for 16 codes.
-//   ACCURATE = false: exp2(L * (1/k)), good to about |L/k| * 2^-22 relative;
-//   ACCURATE = true : the rounding of the product and of 1/k is recovered with one fma
-//     (r = L - t*k is the exact residual of t = fl(L * fl(1/k)) against L/k, times k), the
-//     table's own rounding is added from its low word, and exp2(t + d) = exp2(t) * (1 + d ln2):
-//     within a few ulp of the fp64 value.  The standalone dequantizer uses it; the fused step does
-//     not need it (what decides there is recomputed exactly, see ExactChain).
-//   SIGNED: carry the code's sign bit into the result.
-template <bool SIGNED, bool ACCURATE>
+//   ACCURATE = 0: exp2(L * (1/k)), good to about |L/k| * 2^-22 relative;
+//   ACCURATE = 1: the rounding of the product and of 1/k is recovered with one fma
+//     (r = L - t*k is the exact residual of t = fl(L * fl(1/k)) against L/k, times k) and
+//     exp2(t + d) = exp2(t) * (1 + d ln2): three more instructions per element, error about
+//     |L/k| * 2^-24 + 1 ulp.  The fused step uses it on request (COAT_FLAG_PRECISE_DQ): the
+//     weight update m / (sqrt(v) + eps) inherits the moments' relative error, which matters when
+//     the update is a large fraction of the weight (large lr, beta2 close to 1, heavy-tailed
+//     gradients);
+//   ACCURATE = 2: also the table's own rounding, from its low word: within a few ulp of the fp64
+//     value.  The standalone dequantizer uses it.
+// What decides a group's exponent in the fused step is recomputed exactly either way (ExactChain).
+template <bool SIGNED, int ACCURATE>
 __device__ __forceinline__ void inverse_expand16(const Log2Entry* lut, const uint32_t (&c)[4], float k,
                                                  float inv_k, float (&y)[kEPL]) {
   const float inv_k_ln2 = inv_k * kLn2;
@@ -374,10 +384,16 @@ __device__ __forceinline__ void inverse_expand16(const Log2Entry* lut, const uin
     const int sh = 8 * (e & 3);
     const uint32_t code = (d >> sh) & 0xffu;
     float v;
-    if constexpr (ACCURATE) {
+    if constexpr (ACCURATE == 2) {
       const Log2Entry l = lut[code];
       const float t = l.hi * inv_k;
       const float r = __builtin_fmaf(-t, k, l.hi) + l.lo;
+      const float p = hw_exp2(t);
+      v = __builtin_fmaf(p, r * inv_k_ln2, p);
+    } else if constexpr (ACCURATE == 1) {
+      const float hi = lut[code].hi;
+      const float t = hi * inv_k;
+      const float r = __builtin_fmaf(-t, k, hi);
       const float p = hw_exp2(t);
       v = __builtin_fmaf(p, r * inv_k_ln2, p);
     } else {
@@ -410,7 +426,7 @@ __device__ __forceinline__ void decode16(const uint32_t (&c)[4], float (&y)[kEPL
 // Dequantize 16 codes of one moment up to a per-group factor: the stored value is y * factor with
 //   expansion on : y = +-|c/fmax|^(1/k), factor = fmax * scale      (Sec. 4.2, after the DQ of Sec. 3)
 //   expansion off: y = c,               factor = scale              (k is 1 in this mode, not read)
-template <bool SIGNED, bool ACCURATE, class Mode>
+template <bool SIGNED, int ACCURATE, class Mode>
 __device__ __forceinline__ float dequant16(const Mode& md, const Log2Entry* lut, const uint32_t (&c)[4],
                                            float scale, float k, float inv_k, float (&y)[kEPL]) {
   if (md.expand()) {

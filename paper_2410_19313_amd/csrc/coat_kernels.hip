@@ -145,6 +145,7 @@ int launch_dequant(const DequantArgs& a, hipStream_t s) {
 int dispatch_step(const StepArgs& a, int32_t G, int kind, hipStream_t s) {
   if (kind == kKindDefault) { COAT_DISPATCH_G(G, (launch_step<kG, kKindDefault>(a, s))); }
   if (kind == kKindBf16Meta) { COAT_DISPATCH_G(G, (launch_step<kG, kKindBf16Meta>(a, s))); }
+  if (kind == kKindPrecise) { COAT_DISPATCH_G(G, (launch_step<kG, kKindPrecise>(a, s))); }
   COAT_DISPATCH_G(G, (launch_step<kG, kKindGeneric>(a, s)));
 }
 
@@ -278,11 +279,12 @@ int launch_step_multi(const MultiArgs& ma, uint64_t total_records, hipStream_t s
 int dispatch_step_multi(const MultiArgs& ma, uint64_t total_records, int32_t G, int kind, hipStream_t s) {
   if (kind == kKindDefault) { COAT_DISPATCH_G(G, (launch_step_multi<kG, kKindDefault>(ma, total_records, s))); }
   if (kind == kKindBf16Meta) { COAT_DISPATCH_G(G, (launch_step_multi<kG, kKindBf16Meta>(ma, total_records, s))); }
+  if (kind == kKindPrecise) { COAT_DISPATCH_G(G, (launch_step_multi<kG, kKindPrecise>(ma, total_records, s))); }
   COAT_DISPATCH_G(G, (launch_step_multi<kG, kKindGeneric>(ma, total_records, s)));
 }
 
 constexpr uint32_t kStepFlags = COAT_FLAG_EXPAND | COAT_FLAG_M_E5M2 | COAT_FLAG_V_E5M2 | COAT_FLAG_M_PLAIN |
-                                COAT_FLAG_V_PLAIN | COAT_FLAG_BF16_SCALE | COAT_FLAG_BF16_K;
+                                COAT_FLAG_V_PLAIN | COAT_FLAG_BF16_SCALE | COAT_FLAG_BF16_K | COAT_FLAG_PRECISE_DQ;
 
 constexpr uint64_t kPlanRecordOffset = 128;          // records start one cache line into the blob
 // one launch covers all records with kPlanSpan / kWavesPerBlock = 8 workgroups each, and a grid holds
@@ -347,7 +349,11 @@ int step_constants(const coat_adamw_hparams* hp, StepArgs& a, int& kind) {
   a.mode_m.s16 = a.mode_v.s16 = (hp->flags & COAT_FLAG_BF16_SCALE) != 0;
   a.mode_m.kh = a.mode_v.kh = (hp->flags & COAT_FLAG_BF16_K) != 0;
   const bool default_cell = !a.mode_m.e5 && !a.mode_v.e5 && a.mode_m.ex && a.mode_v.ex;
-  kind = !default_cell ? kKindGeneric : (a.mode_m.s16 || a.mode_m.kh) ? kKindBf16Meta : kKindDefault;
+  const bool precise = (hp->flags & COAT_FLAG_PRECISE_DQ) != 0;
+  const bool bf16_meta = a.mode_m.s16 || a.mode_m.kh;
+  // (the generic kernel always takes the more accurate inverse expansion, so it also serves the
+  // request for it in combination with bf16 metadata)
+  kind = (!default_cell || (precise && bf16_meta)) ? kKindGeneric : bf16_meta ? kKindBf16Meta : precise ? kKindPrecise : kKindDefault;
   return COAT_OK;
 }
 

@@ -85,7 +85,7 @@ __device__ __forceinline__ void fill_lut_one(Log2Entry* lut, bool e5m2) {
 __device__ __forceinline__ void dequant_core(const DequantArgs& a, const Log2Entry* lut, const u32x4& ci, float scale,
                                              float k, float (&x)[kEPL]) {
   const uint32_t c[4] = {ci.x, ci.y, ci.z, ci.w};
-  inverse_expand16<true, true>(lut, c, k, hw_rcp(k), x);
+  inverse_expand16<true, 2>(lut, c, k, hw_rcp(k), x);
   const float amag = fmt_max(a.mode) * scale;
 #pragma unroll
   for (int e = 0; e < kEPL; ++e) x[e] *= amag;

@@ -32,8 +32,8 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, co
   float m[kEPL], v[kEPL];
   const float m_inv_k = hw_rcp(meta.m_k);
   // beta/(1-beta) * (magnitude of the decoded unit)
-  const float m_fac = a.beta1_ratio * dequant16<true, false>(mm, tb.lut, mc, meta.m_scale, meta.m_k, m_inv_k, m);
-  const float v_fac = a.beta2_ratio * dequant16<false, false>(mv, tb.lut, vc, meta.v_scale, meta.v_k, hw_rcp(meta.v_k), v);
+  const float m_fac = a.beta1_ratio * dequant16<true, ModeM::kDq>(mm, tb.lut, mc, meta.m_scale, meta.m_k, m_inv_k, m);
+  const float v_fac = a.beta2_ratio * dequant16<false, ModeV::kDq>(mv, tb.lut, vc, meta.v_scale, meta.v_k, hw_rcp(meta.v_k), v);
   __builtin_amdgcn_sched_barrier(0);
   float w[kEPL], g[kEPL];
   io.gradients(g);
@@ -210,7 +210,7 @@ __device__ __forceinline__ uint64_t gate_on_neighbourhood(const void* words, uin
 
 // Which kernel serves a call: the default cell folded at compile time, the default cell with bf16
 // metadata, or everything else with the storage modes as run-time values.
-constexpr int kKindDefault = 0, kKindGeneric = 1, kKindBf16Meta = 2;
+constexpr int kKindDefault = 0, kKindGeneric = 1, kKindBf16Meta = 2, kKindPrecise = 3;
 template <int KIND> struct ModesOf;
 template <> struct ModesOf<kKindDefault> {
   typedef DefaultMode M;
@@ -221,6 +221,11 @@ template <> struct ModesOf<kKindGeneric> {
   typedef RuntimeMode M;
   __device__ static RuntimeMode m(const StepArgs& a) { return a.mode_m; }
   __device__ static RuntimeMode v(const StepArgs& a) { return a.mode_v; }
+};
+template <> struct ModesOf<kKindPrecise> {
+  typedef PreciseMode M;
+  __device__ static PreciseMode m(const StepArgs&) { return PreciseMode(); }
+  __device__ static PreciseMode v(const StepArgs&) { return PreciseMode(); }
 };
 template <> struct ModesOf<kKindBf16Meta> {
   typedef Bf16MetaMode M;
@@ -233,6 +238,7 @@ template <> struct ModesOf<kKindBf16Meta> {
 // gate's probe, the chunk's loads (see fill_issue).
 // KIND = default : both moments E4M3 with expansion (the method as the paper runs it);
 // KIND = bf16 meta: the same with scales and / or exponents stored as bf16;
+// KIND = precise : the default cell with the more accurate inverse expansion;
 // KIND = generic : per-moment format and expansion read from the arguments (Table 1's grid).
 template <int G, int KIND>
 __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {

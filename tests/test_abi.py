@@ -68,7 +68,7 @@ def test_step_rejects_bad_arguments_before_launch(coat):
     assert call(coat.make_hparams(k_min=1e-3, k_max=2.0)) == -5
     assert call(coat.make_hparams(k_min=1.0, k_max=1e6)) == -5
     hp = coat.make_hparams()
-    hp.flags = 1 | 128
+    hp.flags = 1 | 256
     assert call(hp) == -5                               # unknown flag bit
     assert call(coat.make_hparams(), ptrs=[ok, ok, 0, ok, ok, ok, ok, ok]) == -1
     assert call(coat.make_hparams(), ptrs=[ok + 4, ok, ok, ok, ok, ok, ok, ok]) == -2

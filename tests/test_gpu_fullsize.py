@@ -43,7 +43,7 @@ def draw_grads(kind, n, G, dev, gen, out):
 
 # --- (1) whole tensor set, every element, ten lock-step steps ------------------------------------
 
-def compare_on_device(ref, tag, G, w_d, st_d, w_ref_d, st_ref_d, st_old, g_bits, t):
+def compare_on_device(ref, tag, G, w_d, st_d, w_ref_d, st_ref_d, st_old, g_bits, t, hp=HP):
     """The parity bar over every element, evaluated on the device; whatever misses the plain bar is
     gathered and judged on the host by the rules of parity.py.  Returns statistics."""
     n = w_d.numel()
@@ -85,7 +85,7 @@ def compare_on_device(ref, tag, G, w_d, st_d, w_ref_d, st_ref_d, st_old, g_bits,
             # the exception groups, by the full rules, on the host: bound on k and band of codes
             el = (out[:, None] * G + np.arange(G)[None, :]).reshape(-1)
             sub_old = {k: (v[el] if v.size == n else v[out]) for k, v in st_old.items()}
-            m_t, dm, v_t, dv = new_moments(ref, sub_old, g_bits[el], G, {})
+            m_t, dm, v_t, dv = new_moments(ref, sub_old, g_bits[el], G, {k: hp[k] for k in ("beta1", "beta2")})
             x, dx = (m_t, dm) if name == "m" else (v_t, dv)
             k_ref = st_ref_d[name + "_k"][out].cpu().numpy()
             k_gpu = st_d[name + "_k"][out].cpu().numpy()
@@ -101,8 +101,17 @@ def compare_on_device(ref, tag, G, w_d, st_d, w_ref_d, st_ref_d, st_old, g_bits,
     return stats
 
 
-@pytest.mark.parametrize("G,grads", [(128, "normal"), (32, "lognormal"), (128, "lognormal"), (512, "lognormal")])
-def test_whole_tensor_set_ten_lockstep_steps(coat, ref, G, grads):
+# PyTorch's default AdamW hyper-parameters: under log-normal gradients the update reaches a third of
+# the weight, and the weight bar then needs the more accurate inverse expansion (COAT_FLAG_PRECISE_DQ)
+TORCH_DEFAULTS = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+
+
+@pytest.mark.parametrize("G,grads,hp,flags", [
+    (128, "normal", HP, {}), (32, "lognormal", HP, {}), (128, "lognormal", HP, {}), (512, "lognormal", HP, {}),
+    (128, "lognormal", TORCH_DEFAULTS, dict(precise_dq=True)), (512, "lognormal", TORCH_DEFAULTS, dict(precise_dq=True)),
+], ids=["G128-normal", "G32-lognormal", "G128-lognormal", "G512-lognormal", "G128-lognormal-torch-defaults-precise",
+        "G512-lognormal-torch-defaults-precise"])
+def test_whole_tensor_set_ten_lockstep_steps(coat, ref, G, grads, hp, flags):
     dev = torch.device("cuda:0")
     n = S.workload_numel("cfg2")
     assert n % G == 0
@@ -117,16 +126,15 @@ def test_whole_tensor_set_ten_lockstep_steps(coat, ref, G, grads):
     for t in range(1, 11):
         draw_grads(grads, n, G, dev, gen, g_d)
         g_bits = g_d.view(torch.int16).cpu().numpy().view(np.uint16)
-        hp = coat.make_hparams(step=t, group_size=G, **HP)
-        coat.coat_fp8_adamw_step(w_d, g_d, *(st_d[k] for k in STATE_KEYS), hp)
+        coat.coat_fp8_adamw_step(w_d, g_d, *(st_d[k] for k in STATE_KEYS), coat.make_hparams(step=t, group_size=G, **hp, **flags))
         torch.cuda.synchronize()
         st_old = {k: v.copy() for k, v in st_host.items()}      # only the exception groups' rows are ever read
         assert ref.fp8_adamw_step(w_host, g_bits, *(st_host[k] for k in STATE_KEYS),
-                                  ref.make_hparams(step=t, group_size=G, **HP)) == 0
+                                  ref.make_hparams(step=t, group_size=G, **hp)) == 0
         w_ref_d = torch.from_numpy(w_host).to(dev)
         st_ref_d = {k: torch.from_numpy(v).to(dev) for k, v in st_host.items()}
         stats = compare_on_device(ref, "cfg2 set G=%d %s step %d" % (G, grads, t), G, w_d, st_d, w_ref_d, st_ref_d,
-                                  st_old, g_bits, t)
+                                  st_old, g_bits, t, hp)
         tot["w"] = max(tot["w"], stats["w"])
         for name in ("m", "v"):
             for k in ("bad", "far", "k_out"):
@@ -138,8 +146,8 @@ def test_whole_tensor_set_ten_lockstep_steps(coat, ref, G, grads):
     # groups in 3e7 to 1.3e8 outside the k bar), so that a regression inside the stated bar still shows
     assert tot["bad"] <= 2e-5 * 20 * n and tot["far"] == 0
     assert tot["k_out"] <= max(8, int(1e-6 * 20 * n / G))
-    print("\n[whole set] G=%d %s: 10 steps x %d elements: %d code mismatches (rate %.2e), %d of more than a step, "
-          "%d groups outside the k bar, w worst %.2f x tol" % (G, grads, n, tot["bad"], tot["bad"] / (20.0 * n),
+    print("\n[whole set] G=%d %s%s: 10 steps x %d elements: %d code mismatches (rate %.2e), %d of more than a step, "
+          "%d groups outside the k bar, w worst %.2f x tol" % (G, grads, "" if hp is HP else " (torch defaults, precise)", n, tot["bad"], tot["bad"] / (20.0 * n),
                                                                 tot["far"], tot["k_out"], tot["w"]))
 
 
