@@ -58,6 +58,21 @@ struct RuntimeMode {
   __device__ __forceinline__ bool scale16() const { return s16; }
   __device__ __forceinline__ bool k16() const { return kh; }
 };
+// The expansion switch folded at compile time, format and metadata storage at run time: what the
+// generic kernel runs once it has picked one of its four (first moment, second moment) variants.
+// The switch decides between two different per-element programs (logarithm / exponential, or an
+// exact division), which as run-time branches inside the unrolled element loops compile to several
+// hundred basic blocks; the format only selects constants, a table half and a convert.
+template <bool EXPAND>
+struct FormatMode {
+  static constexpr int kDq = 1;
+  bool e5, s16, kh;
+  __device__ __forceinline__ explicit FormatMode(const RuntimeMode& r) : e5(r.e5), s16(r.s16), kh(r.kh) {}
+  __device__ __forceinline__ bool e5m2() const { return e5; }
+  __device__ __forceinline__ bool expand() const { return EXPAND; }
+  __device__ __forceinline__ bool scale16() const { return s16; }
+  __device__ __forceinline__ bool k16() const { return kh; }
+};
 typedef StaticMode<false, true> DefaultMode;
 typedef StaticMode<false, true, 1> PreciseMode;   // the default cell for callers who set COAT_FLAG_PRECISE_DQ
 

@@ -113,8 +113,12 @@ __global__ __launch_bounds__(kBlock) void adamw_step_multi_kernel(MultiArgs ma) 
   if (full) issue_loads<G>(a, mm, mv, chunk, lane, r);
   fill_commit(fill, lut, frac);                      // every wavefront of the block reaches this
   const StepTables tb = {lut, frac};
-  if (full) process_chunk<G>(a, mm, mv, tb, tiles, chunk, lane, r);
-  else if (tail) process_tail_chunk<G>(a, mm, mv, tb, reinterpret_cast<u32x4*>(tiles.w + 4 * lane + (lane >> 1)), lane);
+  if (full)
+    with_folded_modes<KIND>(a, [&](const auto& fm, const auto& fv) { process_chunk<G>(a, fm, fv, tb, tiles, chunk, lane, r); });
+  else if (tail)
+    with_folded_modes<KIND>(a, [&](const auto& fm, const auto& fv) {
+      process_tail_chunk<G>(a, fm, fv, tb, reinterpret_cast<u32x4*>(tiles.w + 4 * lane + (lane >> 1)), lane);
+    });
 }
 
 }  // namespace

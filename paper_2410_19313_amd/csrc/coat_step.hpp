@@ -233,6 +233,24 @@ template <> struct ModesOf<kKindBf16Meta> {
   __device__ static Bf16MetaMode v(const StepArgs& a) { return Bf16MetaMode{a.mode_v.s16, a.mode_v.kh}; }
 };
 
+// Calls f(first-moment mode, second-moment mode) with the modes as far folded as the kind allows.
+// The generic kind branches ONCE here, on the two expansion switches (wavefront-uniform), into one
+// of four instantiations of f.
+template <int KIND, class F>
+__device__ __forceinline__ void with_folded_modes(const StepArgs& a, F&& f) {
+  if constexpr (KIND == kKindGeneric) {
+    if (a.mode_m.ex) {
+      if (a.mode_v.ex) f(FormatMode<true>(a.mode_m), FormatMode<true>(a.mode_v));
+      else f(FormatMode<true>(a.mode_m), FormatMode<false>(a.mode_v));
+    } else {
+      if (a.mode_v.ex) f(FormatMode<false>(a.mode_m), FormatMode<true>(a.mode_v));
+      else f(FormatMode<false>(a.mode_m), FormatMode<false>(a.mode_v));
+    }
+  } else {
+    f(ModesOf<KIND>::m(a), ModesOf<KIND>::v(a));
+  }
+}
+
 // Main kernel: one chunk per wavefront (the loop only runs again for buffers with more chunks
 // than the grid has wavefronts).  Order of the memory requests: the block's table entries, the
 // gate's probe, the chunk's loads (see fill_issue).
@@ -256,17 +274,29 @@ __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
   uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wv;
 
   RawChunk r;
-  const bool have = chunk < a.n_full;
+  bool have = chunk < a.n_full;                      // (only the generic kind's loop updates it)
   FillRegs<kTables, kBlock> fill;
   fill_issue(fill);
   if (have) chunk = gate_on_neighbourhood(a.mk, chunk, mm.k16() ? kChunk / G / 2 : kChunk / G);
   if (have) issue_loads<G>(a, mm, mv, chunk, lane, r);
   fill_commit(fill, lut, frac);                      // every wavefront of the block reaches this
   const StepTables tb = {lut, frac};
-  if (have) process_chunk<G>(a, mm, mv, tb, tiles, chunk, lane, r);
-  for (chunk += stride; chunk < a.n_full; chunk += stride) {
-    issue_loads<G>(a, mm, mv, chunk, lane, r);
-    process_chunk<G>(a, mm, mv, tb, tiles, chunk, lane, r);
+  if constexpr (KIND == kKindGeneric) {
+    // one call site, so that the four variants exist once
+    while (have) {
+      with_folded_modes<KIND>(a, [&](const auto& fm, const auto& fv) { process_chunk<G>(a, fm, fv, tb, tiles, chunk, lane, r); });
+      chunk += stride;
+      have = chunk < a.n_full;
+      if (have) issue_loads<G>(a, mm, mv, chunk, lane, r);
+    }
+  } else {
+    // (this shape of the loop, with the first chunk outside it, measured 1.8 % faster on the 7B set
+    // than the single-call-site form above: 14.89 against 15.16 ms, one process)
+    if (have) process_chunk<G>(a, mm, mv, tb, tiles, chunk, lane, r);
+    for (chunk += stride; chunk < a.n_full; chunk += stride) {
+      issue_loads<G>(a, mm, mv, chunk, lane, r);
+      process_chunk<G>(a, mm, mv, tb, tiles, chunk, lane, r);
+    }
   }
 }
 
@@ -346,8 +376,7 @@ __global__ __launch_bounds__(kWave) void adamw_step_tail_kernel(StepArgs a) {
   fill_issue(fill);
   fill_commit(fill, lut, frac);
   const StepTables tb = {lut, frac};
-  const typename ModesOf<KIND>::M mm = ModesOf<KIND>::m(a), mv = ModesOf<KIND>::v(a);
-  process_tail_chunk<G>(a, mm, mv, tb, slots + 3 * threadIdx.x, threadIdx.x);
+  with_folded_modes<KIND>(a, [&](const auto& fm, const auto& fv) { process_tail_chunk<G>(a, fm, fv, tb, slots + 3 * threadIdx.x, threadIdx.x); });
 }
 
 }  // namespace
