@@ -76,7 +76,8 @@ def raw(t):
 
 @pytest.mark.parametrize("G,flags", [(128, {}), (32, {}), (512, {}), (64, dict(m_e5m2=True, v_plain=True)),
                                      (128, dict(expand=False)), (128, dict(bf16_scale=True)),
-                                     (32, dict(bf16_scale=True, bf16_k=True)), (512, dict(bf16_k=True))])
+                                     (32, dict(bf16_scale=True, bf16_k=True)), (512, dict(bf16_k=True)),
+                                     (128, dict(precise_dq=True)), (64, dict(precise_dq=True, bf16_scale=True))])
 def test_multi_equals_one_call_per_tensor(coat, G, flags):
     host = make_tensors(G, seed=11, with_bf16=(3, 7, 8))
     a = to_device(host, flags.get("bf16_scale", False), flags.get("bf16_k", False))

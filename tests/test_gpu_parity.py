@@ -54,6 +54,7 @@ def gpu_step(coat, w, g_bits, st, G, step, expand=True, **over):
 def ref_step(ref, w, g_bits, st, G, step, expand=True, **over):
     kw = dict(HP)
     kw.update(over)
+    kw.pop("precise_dq", None)                   # a choice of the kernels' arithmetic: the reference is the same
     hp = ref.make_hparams(step=step, group_size=G, expand=expand, **kw)
     w = w.copy()
     st = {k: v.copy() for k, v in st.items()}
@@ -449,6 +450,16 @@ def test_quant_bf16_k(coat, ref, G, kind):
     ok = np.isfinite(xh_r) & (xh_r != 0)
     assert np.all(np.abs(xh_g[ok] / xh_r[ok] - 1.0) <= 8 * 2.0 ** -24)
     assert np.all(xh_g[xh_r == 0] == 0)
+
+
+@pytest.mark.parametrize("G", [32, 128, 512])
+def test_step_precise_dq(coat, ref, G):
+    """The more accurate inverse expansion on request: same bar; under hyper-parameters that make the
+    update a large fraction of the weight it is what keeps the weights inside it (whole-set test)."""
+    n = 96 * 1024 + 3 * G + 5
+    lockstep(coat, ref, n, G, lambda t: S.grads_lognormal(n, 14, t), steps=4, seed=14, precise_dq=True,
+             lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+    lockstep(coat, ref, n, G, lambda t: S.grads_normal(n, 15, t, G=G, outlier_frac=0.02), steps=3, seed=15, precise_dq=True)
 
 
 def test_step_expansion_off(coat, ref):
