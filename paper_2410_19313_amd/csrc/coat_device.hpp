@@ -675,6 +675,35 @@ __device__ __forceinline__ float apply_exact_min(float exact, uint32_t min_key, 
   return have ? res : __builtin_huge_valf();
 }
 
+// A first moment stored in E5M2 WITHOUT expansion: every element that cancelled deeply is recomputed
+// exactly, not only the lane's smallest.  The plain E5M2 code line reaches 2^-32 of the group
+// maximum, so a value that cancelled to 1e-8 of its terms is still a normal code, while the fp32
+// value of m_t = beta1 m + (1 - beta1) g keeps the rounding of beta1 / (1 - beta1) * scale, 6e-8 of
+// the terms.  Such values are not rare right after the start state: there m / (1 - beta1) is a
+// decoded code times a bf16 maximum, the gradients are bf16 as well, and for a code of significand
+// 1.75 (= fmax's) and a maximum whose significand is a multiple of ten the next gradient can equal
+// -beta1 m / (1 - beta1) to the last bit (measured: 1.5e-4 of the elements at step 2, two of them in
+// one lane a few times in 10^7 lanes).  Without expansion the decoded code times the scale is exact
+// in fp64, so the recomputation is three operations.  (Plain E4M3 reaches 2^-17.8 only: there the
+// fp32 error is 1.4 % of the smallest code step and nothing is done.)
+template <class Mode>
+__device__ __forceinline__ void recompute_cancelled_plain(const StepArgs& a, const Mode& md, const LaneScratch& ls,
+                                                          float scale, const float (&g)[kEPL], float (&x)[kEPL]) {
+  bool any = false;
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) any |= __builtin_fabsf(x[e]) < 0x1p-14f * __builtin_fabsf(g[e]);
+  if (__builtin_expect(any, 0)) {
+#pragma unroll
+    for (int e = 0; e < kEPL; ++e) {
+      const uint32_t code = ls.codes[e];
+      const float c = md.e5m2() ? __builtin_amdgcn_cvt_f32_bf8(code, 0) : __builtin_amdgcn_cvt_f32_fp8(code, 0);
+      const double ex = __builtin_fma(a.m_ratio64, static_cast<double>(c) * static_cast<double>(scale),
+                                      a.g_coef64 * static_cast<double>(g[e]));
+      x[e] = __builtin_fabsf(x[e]) < 0x1p-14f * __builtin_fabsf(g[e]) ? static_cast<float>(ex) : x[e];
+    }
+  }
+}
+
 // The lane's largest |m_t| recomputed exactly, for the groups whose maximum FELL: rare path, the
 // chain run back to back.  The fp32 value of m_t = beta1 m + (1 - beta1) g carries the error of the
 // dequantized m, at most about 2.1e-7 of beta1 * (old group maximum) whichever element it is (the

@@ -60,6 +60,7 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, co
   // The rare branches stay outside this stretch of straight-line code.
   float m_max, v_max, v_min;
   uint32_t m_key;
+  if (!mm.expand() && mm.e5m2()) recompute_cancelled_plain(a, mm, ls, meta.m_scale, g, m);
   lane_extremes_keyed(m, g, m_max, m_key);
   lane_extremes(v, v_max, v_min);
   ExactChain<ModeM> chain(a, mm, tb, ls, m_key, meta.m_scale, meta.m_k, m_inv_k);
