@@ -195,9 +195,11 @@ TOTALS = {}     # tag -> accumulated statistics of the lock-step runs, printed a
 
 def lockstep(coat, ref, n, G, grads_fn, steps, seed, expand=True, state=None, update_model=False, **over):
     """update_model: add the fp32 error model of the update itself to the weight tolerance.  Only for
-    cells in which the second moment is stored WITHOUT expansion under log-normal gradients: its small
-    entries flush to zero, the update m / (sqrt(v) + eps) reaches 1e4 times the weight, and 1e-6 of
-    the weight is then below the fp32 resolution of the update."""
+    cells in which the second moment is stored WITHOUT expansion: its small entries flush to zero,
+    the update m / (sqrt(v) + eps) then exceeds the weight (up to 1e4 times under log-normal gradients;
+    under normal ones an element whose stored v is zero and whose next gradient is tiny, one weight in
+    2e8 element-steps was seen at 2.4 times the plain tolerance), and 1e-6 of the weight is below the
+    fp32 resolution of the update."""
     w = S.weights(n, seed)
     st = state if state is not None else S.zero_state(n, G)
     tot = dict(bad=0, far=0, k_out=0, elems=0, groups=0, w=0.0)
@@ -626,7 +628,7 @@ def test_quant_dequant_e5m2(coat, ref, G, expand):
 def test_step_format_grid(coat, ref, m_e5m2, m_plain, v_e5m2, v_plain):
     n, G = 96 * 1024 + 2 * 128 + 5, 128
     lockstep(coat, ref, n, G, lambda t: S.grads_normal(n, 13, t, G=G, outlier_frac=0.01), steps=3, seed=13,
-             m_e5m2=m_e5m2, m_plain=m_plain, v_e5m2=v_e5m2, v_plain=v_plain)
+             update_model=v_plain, m_e5m2=m_e5m2, m_plain=m_plain, v_e5m2=v_e5m2, v_plain=v_plain)
 
 
 @pytest.mark.parametrize("G", [32, 64, 256, 512])
@@ -749,7 +751,7 @@ def test_step_seeded_sweep_of_configurations(coat, ref):
             return S.grads_normal(n, seed, t, sigma=3e-5)
 
         try:
-            lockstep(coat, ref, n, G, grads, steps=2, seed=seed, update_model=bool(kind == 1 and over.get("v_plain")), **over)
+            lockstep(coat, ref, n, G, grads, steps=2, seed=seed, update_model=bool(over.get("v_plain")), **over)
         except AssertionError as e:
             raise AssertionError("case %d: n=%d G=%d %r: %s" % (case, n, G, over, e))
 
