@@ -704,26 +704,36 @@ __device__ __forceinline__ void recompute_cancelled_plain(const StepArgs& a, con
   }
 }
 
-// The lane's largest |m_t| recomputed exactly, for the groups whose maximum FELL: rare path, the
+// The lane's largest |m_t| from exact values, for the groups whose maximum FELL: rare path, the
 // chain run back to back.  The fp32 value of m_t = beta1 m + (1 - beta1) g carries the error of the
 // dequantized m, at most about 2.1e-7 of beta1 * (old group maximum) whichever element it is (the
 // inverse expansion's error grows with |log2(c/fmax) / k| while the element shrinks as 2 to minus
 // that).  Against a new maximum of at least 3/8 of beta1 * (old maximum) that is below 6e-7 and the
-// scale amax / fmax keeps six digits; only a group whose largest elements all cancelled falls below
-// (a few in 10^4 under heavy-tailed gradients), and for those the maximum is taken from exact values.
+// scale amax / fmax keeps six digits; only a group whose largest elements all cancelled (a few in
+// 10^4 under heavy-tailed gradients), or whose codes were all small to begin with, falls below, and
+// for those the maximum is taken from exact values: of EVERY element whose fp32 magnitude is within
+// 2^-20 of beta1 * (old maximum) (m_fac) of the lane's largest -- more than twice the error above,
+// so the exactly largest one is among them whichever of them fp32 happens to rank first.
 template <class Mode>
 __device__ __forceinline__ float exact_lane_max(const StepArgs& a, const Mode& md, const StepTables& tb,
                                                 const LaneScratch& ls, const float (&x)[kEPL], float scale, float k,
-                                                float inv_k) {
-  uint32_t hi = 0u;
+                                                float inv_k, float m_fac) {
+  float hi = 0.0f;
 #pragma unroll
-  for (int e = 0; e < kEPL; ++e) {
-    const uint32_t key = (as_u32(x[e]) & 0x7ffffff0u) | static_cast<uint32_t>(e);
-    hi = key > hi ? key : hi;
+  for (int e = 0; e < kEPL; ++e) hi = __builtin_fmaxf(hi, __builtin_fabsf(x[e]));
+  const float cut = __builtin_fmaf(-0x1p-20f, m_fac, hi);
+  uint32_t candidates = 0u;
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) candidates |= __builtin_fabsf(x[e]) >= cut ? 1u << e : 0u;
+  float best = 0.0f;
+  while (candidates != 0u) {                         // one trip for nearly every lane
+    const uint32_t idx = static_cast<uint32_t>(__builtin_ctz(candidates));
+    candidates &= candidates - 1u;
+    ExactChain<Mode> chain(a, md, tb, ls, idx, scale, k, inv_k);
+    static_for<0, ExactChain<Mode>::kSteps + 1>([&](auto s) { chain.template step<s.value>(); });
+    best = __builtin_fmaxf(best, __builtin_fabsf(chain.exact));
   }
-  ExactChain<Mode> chain(a, md, tb, ls, hi, scale, k, inv_k);
-  static_for<0, ExactChain<Mode>::kSteps + 1>([&](auto s) { chain.template step<s.value>(); });
-  return __builtin_fabsf(chain.exact);
+  return best;
 }
 
 template <bool E5M2>

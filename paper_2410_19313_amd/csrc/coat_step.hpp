@@ -96,7 +96,7 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, co
     // concerned adopt the result, so a group's outcome does not depend on its neighbours.
     const bool fell = m_max < 0.375f * m_fac;
     if (__builtin_expect(__builtin_amdgcn_ballot_w64(fell) != 0ull, 0)) {
-      const float ex = group_allreduce<LPG, true>(exact_lane_max(a, mm, tb, ls, m, meta.m_scale, meta.m_k, m_inv_k));
+      const float ex = group_allreduce<LPG, true>(exact_lane_max(a, mm, tb, ls, m, meta.m_scale, meta.m_k, m_inv_k, m_fac));
       m_max = fell ? ex : m_max;
     }
   }

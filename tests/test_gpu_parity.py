@@ -384,6 +384,42 @@ def test_step_from_arbitrary_state(coat, ref, G):
     check_step(ref, "random state G=%d" % G, w_g, st_g, w_r, st_r, st, g, G, extra_w_tol=extra)
 
 
+@pytest.mark.parametrize("m_e5m2", [False, True])
+def test_step_group_maximum_among_near_ties(coat, ref, m_e5m2):
+    """Groups whose old codes are all small, so that the new maximum is far below beta1 * fmax * scale
+    (the case in which the kernel takes the maximum from exact values), and whose two largest
+    elements have the same old code, sit in ONE lane and differ by their tiny gradients only, a few
+    1e-7 to 1e-6 of their size: whichever of the two fp32 ranks first, the scale must hold 1e-6."""
+    G, ng = 32, 8192
+    n = G * ng
+    st = S.random_state(n, G, seed=31)
+    rng = np.random.default_rng(31)
+    mq = st["m_q"]
+    mq[:] = (mq & 0x80) | np.minimum(mq & 0x7F, 0x50)
+    a_pos, b_pos = np.arange(ng) * G + 3, np.arange(ng) * G + 9       # both among the group's first 16 elements
+    mq[a_pos] = (mq[a_pos] & 0x80) | 0x58
+    mq[b_pos] = (mq[b_pos] & 0x80) | 0x58
+    m_old = ref.dequant_group(mq, st["m_scale"], st["m_k"], G, f64=True, e5m2=m_e5m2)
+    b1 = float(np.float32(HP["beta1"]))
+    gf = np.zeros(n)
+    for pos in (a_pos, b_pos):                      # same sign as the old moment: the magnitudes add
+        gf[pos] = 3e-6 * rng.random(ng) * (b1 / (1 - b1)) * m_old[pos]
+    g = S.f32_to_bf16_bits(gf.astype(np.float32))
+    w = S.weights(n, 31)
+    t = 5
+    over = dict(m_e5m2=True) if m_e5m2 else {}
+    w_g, st_g, _ = gpu_step(coat, w, g, st, G, t, **over)
+    w_r, st_r = ref_step(ref, w, g, st, G, t, **over)
+    # the case is exercised: in many groups the two are closer than 1e-6 and the new maximum is small
+    m_t = b1 * m_old + (1 - b1) * S.bf16_bits_to_f32(g).astype(np.float64)
+    gap = np.abs(np.abs(m_t[a_pos]) / np.abs(m_t[b_pos]) - 1.0)
+    fmax = 57344.0 if m_e5m2 else 448.0
+    fell = np.maximum(np.abs(m_t[a_pos]), np.abs(m_t[b_pos])) < 0.3 * b1 * fmax * st["m_scale"].astype(np.float64)
+    assert int((fell & (gap > 2e-7) & (gap < 2e-6)).sum()) > ng // 8
+    check_step(ref, "near ties at the maximum", w_g, st_g, w_r, st_r, st, g, G,
+               extra_w_tol=update_error_model(ref, st, g, G, t, **over), **over)
+
+
 @pytest.mark.parametrize("G", [32, 128, 512])
 def test_step_bf16_scale(coat, ref, G):
     """Scales stored in BF16 (Sec. 3): lock-step against the oracle's same option."""
