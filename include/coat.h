@@ -24,6 +24,13 @@
  *     0x7F/0xFF are NaN) by default, OCP E5M2 (1-5-2 bits, bias 15, max 57344, min subnormal
  *     2^-16, 0x7C infinity) per moment on request.  Non-finite codes are never produced from
  *     finite inputs.
+ *   - Optimizer state: any finite codes with scales and exponents in range are accepted.  The
+ *     accuracy the tests state (scales and exponents to 1e-6 of a double-precision evaluation)
+ *     is that of states this library writes, in which every non-empty group holds a code of
+ *     magnitude fmax (the next one below at most with bf16 scales).  In a hand-made state whose
+ *     largest second-moment code of a group is far below fmax, the new scale of that group
+ *     inherits the relative error of the inverse expansion at that code (measured: up to 1.3e-6
+ *     when no code exceeds 0x30, 8e-7 for 0x50), unless COAT_FLAG_PRECISE_DQ is set (3.6e-7).
  */
 #ifndef COAT_H
 #define COAT_H
