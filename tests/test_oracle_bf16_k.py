@@ -127,3 +127,26 @@ def test_step_stores_bf16_exponents_for_both_moments(ref):
         assert np.all(st["v_q"] < 0x80)
     # the trajectories stay close: the stored exponent moves a dequantized value by less than its own quantization step
     assert np.max(np.abs(w - w0)) < 1e-4
+
+
+def test_groups_without_gradient_keep_their_exponent(ref):
+    """A group that receives no gradient only decays (m_t = beta1 m, v_t = beta2 v): the range of its
+    dequantized values is the one its stored k made of the format's range, so the exponent computed
+    from it is the stored one again -- a bf16 value, which its floor keeps.  Wherever the group's
+    extremes sat at the format's two ends (code fmax and the smallest subnormal) the exponent must
+    not move over idle steps, and the codes stay as they are."""
+    G, n = 128, 128 * 512
+    keys = ("m_q", "m_scale", "m_k", "v_q", "v_scale", "v_k")
+    w, st = S.weights(n, 5), S.zero_state(n, G)
+    assert ref.fp8_adamw_step(w, S.grads_normal(n, 5, 1), *(st[k] for k in keys),
+                              ref.make_hparams(step=1, group_size=G, bf16_k=True, **HP)) == 0
+    first = {k: v.copy() for k, v in st.items()}
+    idle = np.zeros(n, np.uint16)
+    for t in range(2, 22):
+        assert ref.fp8_adamw_step(w, idle, *(st[k] for k in keys), ref.make_hparams(step=t, group_size=G, bf16_k=True, **HP)) == 0
+    for name in ("m", "v"):
+        mag = (first[name + "_q"] & 0x7F).reshape(-1, G)
+        ends = (mag.max(1) == 0x7E) & (np.where(mag > 0, mag, 0x7F).min(1) == 1)    # both ends of E4M3 in use
+        assert ends.mean() > 0.9
+        assert np.array_equal(st[name + "_k"][ends], first[name + "_k"][ends])
+        assert np.array_equal(st[name + "_q"].reshape(-1, G)[ends], first[name + "_q"].reshape(-1, G)[ends])
