@@ -484,9 +484,15 @@ __device__ __forceinline__ GroupQuant group_quant_params(const Mode& md, float a
     // (the max keeps a ratio that rounds below 1 from turning the huge k negative)
     const float ratio = __builtin_fmaxf(top * hw_rcp(amin), 1.0f);    // R_X
     float kk = fmt_log2_range(md) * hw_rcp(hw_log2(ratio));
-    kk = __builtin_amdgcn_fmed3f(kk, k_min, k_max);
     // BF16-stored exponent: rounded DOWN after the clamp (R_X^k stays within the format's range);
-    // the codes below are computed with the stored value
+    // the codes below are computed with the stored value.  The fp32 value above is good to about
+    // 5e-7 of itself and is moved up by 2^-20 before the rounding: an exponent that IS a bf16 value
+    // (a group that received no gradient: its range is the one its stored k made, so the new
+    // exponent is the stored one) is then stored as that value instead of, every other time, the
+    // next one below, which would take such a group's k down a notch per idle step.  (The range may
+    // exceed the format's by a factor 2^(31.8 * 2^-20): the smallest element still rounds to the
+    // smallest subnormal.)
+    kk = __builtin_amdgcn_fmed3f(md.k16() ? kk * (1.0f + 0x1p-20f) : kk, k_min, k_max);
     if (md.k16()) kk = as_f32(as_u32(kk) & 0xFFFF0000u);
     k = (amax != amin) ? kk : 1.0f;
   }

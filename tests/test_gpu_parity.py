@@ -467,6 +467,36 @@ def test_step_bf16_k(coat, ref, G, bf16_scale):
 
 
 @pytest.mark.parametrize("G", [32, 128, 512])
+def test_idle_groups_keep_their_bf16_exponent(coat, G):
+    """Free-running on the GPU: one step with gradients, then twenty with none.  A group that only
+    decays reproduces the range its stored k made, so its new exponent is the stored bf16 value and
+    must stay there (the oracle's same property is pinned on the CPU); taken one fp32 rounding short
+    of it, the floor would step k down a notch on about every other idle step."""
+    n = 2048 * G
+    hp = dict(HP, bf16_k=True)
+    tw = dev(S.weights(n, 71))
+    z = S.zero_state(n, G)
+    ts = {k: dev(v) for k, v in z.items()}
+    for k in ("m_k", "v_k"):
+        ts[k] = ts[k].to(torch.bfloat16)
+    args = lambda: (ts["m_q"], ts["m_scale"], ts["m_k"], ts["v_q"], ts["v_scale"], ts["v_k"])
+    coat.coat_fp8_adamw_step(tw, dev_bf16(S.grads_normal(n, 71, 1)), *args(), coat.make_hparams(step=1, group_size=G, **hp))
+    first = {k: v.clone() for k, v in ts.items()}
+    idle = dev_bf16(np.zeros(n, np.uint16))
+    for t in range(2, 22):
+        coat.coat_fp8_adamw_step(tw, idle, *args(), coat.make_hparams(step=t, group_size=G, **hp))
+    torch.cuda.synchronize()
+    for name in ("m", "v"):
+        mag = (first[name + "_q"] & 0x7F).view(-1, G)
+        ends = (mag.max(1).values == 0x7E) & (torch.where(mag > 0, mag, 0x7F).min(1).values == 1)
+        assert float(ends.float().mean()) > 0.9
+        assert torch.equal(ts[name + "_k"][ends], first[name + "_k"][ends]), "%s: %d of %d idle groups moved their exponent" % (
+            name, int((ts[name + "_k"][ends] != first[name + "_k"][ends]).sum()), int(ends.sum()))
+        same = (ts[name + "_q"].view(-1, G)[ends] == first[name + "_q"].view(-1, G)[ends]).float().mean()
+        assert float(same) > 0.9999, "%s: idle codes moved (%.6f equal)" % (name, float(same))
+
+
+@pytest.mark.parametrize("G", [32, 128, 512])
 @pytest.mark.parametrize("kind", ["normal", "square", "lognormal", "zeros_mixed"])
 def test_quant_bf16_k(coat, ref, G, kind):
     """Standalone quantizer with BF16 exponents: identical inputs, so the scales are equal to 1e-6 and
