@@ -112,9 +112,12 @@ def check_step(ref, tag, w_g, st_g, w_r, st_r, st_old, g_bits, G, expand=True, e
             assert np.all(sg.view(np.uint32) & 0xFFFF == 0), tag + ": a stored scale is not a bf16 value"
             assert np.array_equal(sg[~near], sr[~near]), tag + " %s scale (bf16)" % name
             assert np.all((sg[near] == lo16[near]) | (sg[near] == hi16[near])), tag + " %s scale near a bf16 boundary" % name
+            # (How many groups sit that near a boundary depends on the data: a few in 10^4 for generic
+            # gradients, but a group whose gradient is all zero has the new maximum beta1 * fmax * (its
+            # old bf16 scale), and 0.9f times a bf16 significand that is a multiple of ten lies within
+            # 3e-8 of a bf16 value: with sparse gradients about one group in a hundred is a coin flip
+            # of the last fp32 rounding, on either side.  So the count is not limited, only where.)
             excused = near & (sg != sr)
-            assert int(excused.sum()) <= int(np.ceil(5e-3 * excused.size)), \
-                tag + ": %d of %d bf16 scale decisions differ" % (int(excused.sum()), excused.size)
             bound = np.where(excused, np.inf, bound)
         else:
             assert_scale(st_g[name + "_scale"], st_r[name + "_scale"], tag + " %s scale" % name)
@@ -382,6 +385,23 @@ def test_step_from_arbitrary_state(coat, ref, G):
     w_r, st_r = ref_step(ref, w, g, st, G, t)
     extra = update_error_model(ref, st, g, G, t)
     check_step(ref, "random state G=%d" % G, w_g, st_g, w_r, st_r, st, g, G, extra_w_tol=extra)
+
+
+def sparse_grads(n, G, seed, t, live=0.1):
+    """Normal gradients in a tenth of the groups, exactly zero in the others (a different tenth every
+    step): what an embedding table sees.  A group without gradient only decays: m_t = beta1 m."""
+    rng = np.random.default_rng([seed, t])
+    x = rng.standard_normal(n) * 1e-3
+    x *= np.repeat(rng.random((n + G - 1) // G) < live, G)[:n]
+    return S.f32_to_bf16_bits(x.astype(np.float32))
+
+
+@pytest.mark.parametrize("G", [32, 128, 512])
+@pytest.mark.parametrize("bf16_meta", [False, True])
+def test_step_sparse_gradients(coat, ref, G, bf16_meta):
+    n = 300 * 1024 + 3 * G + 11
+    over = dict(bf16_scale=True, bf16_k=True) if bf16_meta else {}
+    lockstep(coat, ref, n, G, lambda t: sparse_grads(n, G, 61, t), steps=8, seed=61, **over)
 
 
 @pytest.mark.parametrize("m_e5m2", [False, True])
