@@ -126,16 +126,22 @@ static float bf16_ceil(float s) {
   return cvt.f;
 }
 
-/* Largest bf16 value that is not above k (k > 0 and finite): the exponent "stored in BF16" like the
- * scale.  Rounding DOWN keeps R_X^k <= R_format: the expanded group stays inside the format's range,
- * its smallest element at or above the smallest subnormal (rounding up would put it below). */
-static float bf16_floor(float k) {
+/* The bf16 value nearest to k, ties to the even one (k > 0 and finite): the exponent "stored in BF16"
+ * like the scale, by the conversion that a cast to bf16 performs.  The stored exponent is within
+ * 2^-8 of the exact one (half a bf16 step), so R_X^k exceeds R_format by at most R_format^(2^-8): the
+ * group's smallest element lands at 0.95 (E4M3; E5M2 0.92) of the smallest subnormal or above and still rounds to it.
+ * A group that receives no gradient reproduces the range its stored exponent made, computes that
+ * exponent again and keeps it: rounding to nearest makes the stored value a fixed point (rounding
+ * down does too in exact arithmetic, but any evaluation that lands one rounding short of the bf16
+ * value then steps a notch down per idle step, and with a BF16 scale beside it the exact value is
+ * not a bf16 number and every idle step loses a notch). */
+static float bf16_nearest(float k) {
   /* bf16 keeps 8 significant bits: for k = m * 2^e with 1/2 <= m < 1 its values are the multiples of 2^(e-8) */
   int e;
   double quantum;
   (void)frexp((double)k, &e);
   quantum = ldexp(1.0, e - 8);
-  return (float)(floor((double)k / quantum) * quantum);
+  return (float)(rint((double)k / quantum) * quantum);   /* rint: to nearest, ties to even (default rounding mode) */
 }
 
 static void quant_one_group(const float* x, uint64_t len, int expand, fmt_t f, int scale16, int k16,
@@ -174,7 +180,7 @@ static void quant_one_group(const float* x, uint64_t len, int expand, fmt_t f, i
     if (kd < (double)k_min) kd = (double)k_min;
     if (kd > (double)k_max) kd = (double)k_max;
     k = (float)kd;
-    if (k16) k = bf16_floor(k);                  /* after the clamp; the quantizer below uses the stored value */
+    if (k16) k = bf16_nearest(k);                  /* after the clamp; the quantizer below uses the stored value */
   }
   /* Quantize with the STORED scale and k so that Q and DQ agree.  The expanded group is
    * f(x / a) with a = fmax * scale ~= amax, whose largest element is 1, so the plain

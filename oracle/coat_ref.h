@@ -44,9 +44,9 @@ typedef struct {
                                         stay float here; every value in them is a bf16. */
 #define COAT_REF_FLAG_BF16_K 64u     /* the exponents k are stored in BF16 as well (Sec. 4.2 computes k per group
                                         and step and keeps it beside the scale, whose storage Sec. 3 gives as BF16):
-                                        rounded DOWN to a bf16 value after the clamp, so that R_X^k <= R_format still
-                                        holds (the smallest element stays at or above the smallest subnormal); the
-                                        quantizer uses the stored value.  The arrays stay float here; every value in them is a bf16. */
+                                        rounded to the NEAREST bf16 value (ties to even, as a cast does) after the clamp;
+                                        R_X^k then exceeds R_format by at most R_format^(2^-8) and the smallest element
+                                        still rounds to the smallest subnormal; the quantizer uses the stored value.  The arrays stay float here; every value in them is a bf16. */
 
 #define COAT_REF_FLAG_DQ_FP32 128u   /* step only, NOT the default: round the dequantized moments to fp32 before the
                                         update.  Appendix A says "dequantize to FP32"; the default reading takes the
