@@ -76,11 +76,12 @@ extern "C" {
                                     gradients).  Codes, scales and exponents do not depend on it beyond rounding. */
 #define COAT_FLAG_BF16_K  64u  /* the per-group exponent arrays hold bf16 (uint16_t) values too: Sec. 4.2
                                   computes k per group and step and keeps it beside the scale.  The
-                                  stored k is the clamped exponent rounded DOWN to a bf16 value (so that
-                                  R_X^k <= R_format still holds; the kernels first move their fp32
-                                  exponent up by 2^-20 of itself, twice its error, so that a group which
-                                  received no gradient keeps the bf16 exponent it has) and quantizer and
-                                  dequantizer both use the stored value.  With both flags: 8 + 8/G bytes per parameter. */
+                                  stored k is the clamped exponent rounded to the NEAREST bf16 value
+                                  (ties to even, as a cast does), and quantizer and dequantizer both use
+                                  the stored value.  R_X^k may then exceed R_format by a factor
+                                  R_format^(2^-8); the smallest element still rounds to the smallest
+                                  subnormal.  A group that receives no gradient keeps its exponent.
+                                  With both flags: 8 + 8/G bytes per parameter. */
 
 /* Hyper-parameters of one step: symbols of Sec. 3, Eq. (1). */
 typedef struct {

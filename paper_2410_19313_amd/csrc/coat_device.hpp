@@ -484,16 +484,14 @@ __device__ __forceinline__ GroupQuant group_quant_params(const Mode& md, float a
     // (the max keeps a ratio that rounds below 1 from turning the huge k negative)
     const float ratio = __builtin_fmaxf(top * hw_rcp(amin), 1.0f);    // R_X
     float kk = fmt_log2_range(md) * hw_rcp(hw_log2(ratio));
-    // BF16-stored exponent: rounded DOWN after the clamp (R_X^k stays within the format's range);
-    // the codes below are computed with the stored value.  The fp32 value above is good to about
-    // 5e-7 of itself and is moved up by 2^-20 before the rounding: an exponent that IS a bf16 value
-    // (a group that received no gradient: its range is the one its stored k made, so the new
-    // exponent is the stored one) is then stored as that value instead of, every other time, the
-    // next one below, which would take such a group's k down a notch per idle step.  (The range may
-    // exceed the format's by a factor 2^(31.8 * 2^-20): the smallest element still rounds to the
-    // smallest subnormal.)
-    kk = __builtin_amdgcn_fmed3f(md.k16() ? kk * (1.0f + 0x1p-20f) : kk, k_min, k_max);
-    if (md.k16()) kk = as_f32(as_u32(kk) & 0xFFFF0000u);
+    kk = __builtin_amdgcn_fmed3f(kk, k_min, k_max);
+    // BF16-stored exponent: the clamped value rounded to the nearest bf16, ties to even (what a cast
+    // does); the codes below are computed with the stored value.  A group that received no gradient
+    // reproduces the range its stored k made, computes that bf16 value again to a few 1e-7 and keeps
+    // it.  (R_X^k may exceed the format's range by a factor range^(2^-8): the smallest element still
+    // rounds to the smallest subnormal.)
+    const uint32_t kb = as_u32(kk);
+    if (md.k16()) kk = as_f32((kb + 0x7FFFu + ((kb >> 16) & 1u)) & 0xFFFF0000u);
     k = (amax != amin) ? kk : 1.0f;
   }
   const float inv_a = unit * hw_rcp(md.expand() ? fmax * s : s);
@@ -779,6 +777,29 @@ __device__ __forceinline__ void quantize16(const Mode& md, const float (&x)[kEPL
 #pragma unroll
     for (int b = 0; b < 4; ++b) q[b] = quantize_value<SIGNED>(md, x[4 * d + b], gq, unit);
     c[d] = md.e5m2() ? pack4<true>(q) : pack4<false>(q);
+  }
+}
+
+// BF16-stored exponents only: a group whose stored exponent came out as exactly 1 is quantized
+// linearly, code = FP8(x / scale), and its codes are re-made here with the correctly rounded
+// quotient (the plain quantizer's arithmetic) in place of exp2(k log2 r + log2 fmax).  The two agree
+// to 2^-22, which is all the other exponents need, but a linear map sends short-significand inputs
+// onto exact rounding ties: at the first step from the zero state the inputs are bf16 gradients over
+// a bf16 maximum, and 8 % of such a group's elements then sit exactly half way between two codes
+// (measured), where only the exact quotient rounds the way the definition does.  About one group
+// in 128 of those whose exponent is near 1; a lane-local rare branch.
+template <bool SIGNED, class Mode>
+__device__ __forceinline__ void requantize_linear_group(const Mode& md, const float (&x)[kEPL], const GroupQuant& gq,
+                                                        uint32_t (&c)[4], float unit) {
+  if (!(md.expand() && md.k16())) return;
+  if (__builtin_expect(gq.k == 1.0f && gq.inv_a != 0.0f, 0)) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      float q[4];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) q[b] = (x[4 * d + b] * unit) / gq.scale;     // IEEE division: correctly rounded
+      c[d] = md.e5m2() ? pack4<true>(q) : pack4<false>(q);
+    }
   }
 }
 

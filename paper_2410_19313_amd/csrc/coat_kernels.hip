@@ -94,7 +94,8 @@ int launch_step(const StepArgs& a, hipStream_t s) {
   if (a.n_full) {
     const unsigned grid = grid_for(a.n_full);
     size_t lds = kStepLdsPad;
-    hipLaunchKernelGGL((adamw_step_kernel<G, KIND>), dim3(grid), dim3(kBlock), lds, s, a);
+    if constexpr (KIND == kKindGeneric) hipLaunchKernelGGL((adamw_step_generic_kernel<G>), dim3(grid), dim3(kBlock), lds, s, a);
+    else hipLaunchKernelGGL((adamw_step_kernel<G, KIND>), dim3(grid), dim3(kBlock), lds, s, a);
     if (int rc = launch_status()) return rc;
   }
   if (a.n > a.n_full * kChunk) {

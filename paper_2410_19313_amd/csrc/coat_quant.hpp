@@ -18,6 +18,7 @@ __device__ __forceinline__ GroupQuant quant_core_as(const Mode& md, const QuantA
   lo = group_allreduce<LPG, false>(lo);
   const GroupQuant q = group_quant_params(md, hi, lo, a.k_min, a.k_max, 1.0f);
   quantize16<true>(md, x, q, c, 1.0f);
+  requantize_linear_group<true>(md, x, q, c, 1.0f);
   return q;
 }
 // Format and expansion are wavefront-uniform run-time values; one branch per chunk picks the code

@@ -80,6 +80,7 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, co
     const float q4[4] = {vq[4 * d], vq[4 * d + 1], vq[4 * d + 2], vq[4 * d + 3]};
     vc[d] = mv.e5m2() ? pack4<true>(q4) : pack4<false>(q4);
   }
+  requantize_linear_group<false>(mv, v, qv, vc, a.one_minus_beta2);
   float m_exact = chain.exact;
   // (empty asm: holds the second moment's codes and the exact value at one point of the program, so
   // that the compiler does not sink the quantization above past the rare branch that follows)
@@ -102,6 +103,7 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, co
   }
   const GroupQuant qm = group_quant_params(mm, m_max, m_min, a.k_min, a.k_max, a.one_minus_beta1);
   quantize16<true>(mm, m, qm, mc, a.one_minus_beta1);
+  requantize_linear_group<true>(mm, m, qm, mc, a.one_minus_beta1);
   if (__builtin_expect(m_replace, 0)) requantize_one(mm, m_exact, qm, m_key & 15u, mc, a.one_minus_beta1);
   io.first(mc, qm.scale, qm.k);
 }
@@ -260,7 +262,7 @@ __device__ __forceinline__ void with_folded_modes(const StepArgs& a, F&& f) {
 // KIND = precise : the default cell with the more accurate inverse expansion;
 // KIND = generic : per-moment format and expansion read from the arguments (Table 1's grid).
 template <int G, int KIND>
-__global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
+__device__ __forceinline__ void adamw_step_body(const StepArgs& a) {
   constexpr int kTables = KIND == kKindGeneric ? 2 : 1;
   __shared__ Log2Entry lut[256 * kTables];
   __shared__ double frac[kExp2Frac];
@@ -299,6 +301,19 @@ __global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
       process_chunk<G>(a, mm, mv, tb, tiles, chunk, lane, r);
     }
   }
+}
+template <int G, int KIND>
+__global__ __launch_bounds__(kBlock) void adamw_step_kernel(StepArgs a) {
+  static_assert(KIND != kKindGeneric, "the generic kind has its own entry");
+  adamw_step_body<G, KIND>(a);
+}
+// The generic kind needs 170 to 177 vector registers when the allocator is left alone, a few more
+// than the 168 that let three wavefronts share a SIMD -- and with two the CU holds two workgroups
+// instead of the three the kernel is tuned for (17.7 ms against 15.9 on the 7B set).  Asked for
+// three, the allocator fits it into 168 without spilling a vector register.
+template <int G>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3))) void adamw_step_generic_kernel(StepArgs a) {
+  adamw_step_body<G, kKindGeneric>(a);
 }
 
 // The ragged last chunk (n % 1024 elements): one wavefront, element-wise guarded accesses
