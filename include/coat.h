@@ -70,10 +70,13 @@ extern "C" {
 #define COAT_FLAG_PRECISE_DQ 128u /* dequantize the old moments with the rounding of the exponent log2(c/fmax)/k
                                     recovered (three more instructions per element; about 2.5 % more time on a
                                     7B-parameter step).  The weight update m/(sqrt(v)+eps) inherits the moments'
-                                    relative error (up to 2e-6 without this flag); that stays below 1e-6 of the
+                                    relative error (up to 2e-6 without this); that stays below 1e-6 of the
                                     WEIGHT for lr = 3e-4, beta = 0.9/0.95, but not when the update is a large
-                                    fraction of the weight (lr = 1e-3 with beta2 = 0.999 under heavy-tailed
-                                    gradients).  Codes, scales and exponents do not depend on it beyond rounding. */
+                                    fraction of the weight.  The step therefore takes this path BY ITSELF when
+                                    lr * (1 - beta1) / sqrt(1 - beta2), the largest update Adam can make, is
+                                    2e-4 or more (PyTorch's defaults lr = 1e-3, beta = 0.9/0.999: 3.2e-3); the
+                                    flag asks for it below that.  Codes, scales and exponents do not depend on
+                                    it beyond rounding. */
 #define COAT_FLAG_BF16_K  64u  /* the per-group exponent arrays hold bf16 (uint16_t) values too: Sec. 4.2
                                   computes k per group and step and keeps it beside the scale.  The
                                   stored k is the clamped exponent rounded to the NEAREST bf16 value

@@ -350,7 +350,13 @@ int step_constants(const coat_adamw_hparams* hp, StepArgs& a, int& kind) {
   a.mode_m.s16 = a.mode_v.s16 = (hp->flags & COAT_FLAG_BF16_SCALE) != 0;
   a.mode_m.kh = a.mode_v.kh = (hp->flags & COAT_FLAG_BF16_K) != 0;
   const bool default_cell = !a.mode_m.e5 && !a.mode_v.e5 && a.mode_m.ex && a.mode_v.ex;
-  const bool precise = (hp->flags & COAT_FLAG_PRECISE_DQ) != 0;
+  // The more accurate inverse expansion: on request, and by itself where the step can be large against
+  // the weight.  |m_hat| / sqrt(v_hat) is at most (1 - beta1) / sqrt(1 - beta2), so the update is at
+  // most lr times that; its relative error without the correction (2e-6) stays below 1e-6 of a
+  // weight of a few 1e-2 while that bound is below 2e-4 (lr = 3e-4 with beta = 0.9 / 0.95: 1.3e-4;
+  // PyTorch's defaults lr = 1e-3, beta = 0.9 / 0.999: 3.2e-3).
+  const bool large_steps = static_cast<double>(hp->lr) * omb1 >= 2e-4 * __builtin_sqrt(omb2);
+  const bool precise = (hp->flags & COAT_FLAG_PRECISE_DQ) != 0 || large_steps;
   const bool bf16_meta = a.mode_m.s16 || a.mode_m.kh;
   // (the generic kernel always takes the more accurate inverse expansion, so it also serves the
   // request for it in combination with bf16 metadata)

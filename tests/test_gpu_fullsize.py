@@ -102,19 +102,21 @@ def compare_on_device(ref, tag, G, w_d, st_d, w_ref_d, st_ref_d, st_old, g_bits,
 
 
 # PyTorch's default AdamW hyper-parameters: under log-normal gradients the update reaches a third of
-# the weight, and the weight bar then needs the more accurate inverse expansion (COAT_FLAG_PRECISE_DQ)
+# the weight, and the weight bar then needs the more accurate inverse expansion, which the step
+# takes by itself for such hyper-parameters (lr (1 - beta1) / sqrt(1 - beta2) >= 2e-4) and on
+# request (COAT_FLAG_PRECISE_DQ) otherwise: one case with the flag, one without
 TORCH_DEFAULTS = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
 
 
 @pytest.mark.parametrize("G,grads,hp,flags", [
     (128, "normal", HP, {}), (32, "lognormal", HP, {}), (128, "lognormal", HP, {}), (512, "lognormal", HP, {}),
-    (128, "lognormal", TORCH_DEFAULTS, dict(precise_dq=True)), (512, "lognormal", TORCH_DEFAULTS, dict(precise_dq=True)),
+    (128, "lognormal", TORCH_DEFAULTS, dict(precise_dq=True)), (512, "lognormal", TORCH_DEFAULTS, {}),
     # First moment in E5M2 without expansion: its code line reaches 2^-32 of the group maximum, and at
     # step 2 the bf16 gradients cancel decoded codes times a bf16 maximum to the last bit in 1.5e-4 of
     # the elements, a few tens of times twice in one lane of this set: every one must come out exact.
     (128, "normal", HP, dict(m_e5m2=True, m_plain=True)),
 ], ids=["G128-normal", "G32-lognormal", "G128-lognormal", "G512-lognormal", "G128-lognormal-torch-defaults-precise",
-        "G512-lognormal-torch-defaults-precise", "G128-normal-first-moment-plain-E5M2"])
+        "G512-lognormal-torch-defaults", "G128-normal-first-moment-plain-E5M2"])
 def test_whole_tensor_set_ten_lockstep_steps(coat, ref, G, grads, hp, flags):
     dev = torch.device("cuda:0")
     n = S.workload_numel("cfg2")
@@ -152,7 +154,7 @@ def test_whole_tensor_set_ten_lockstep_steps(coat, ref, G, grads, hp, flags):
     assert tot["bad"] <= 2e-5 * 20 * n and tot["far"] == 0
     assert tot["k_out"] <= max(8, int(1e-6 * 20 * n / G))
     print("\n[whole set] G=%d %s%s: 10 steps x %d elements: %d code mismatches (rate %.2e), %d of more than a step, "
-          "%d groups outside the k bar, w worst %.2f x tol" % (G, grads, " (torch defaults, precise)" if hp is not HP else " %s" % flags if flags else "", n, tot["bad"], tot["bad"] / (20.0 * n),
+          "%d groups outside the k bar, w worst %.2f x tol" % (G, grads, " (torch defaults)" if hp is not HP else " %s" % flags if flags else "", n, tot["bad"], tot["bad"] / (20.0 * n),
                                                                 tot["far"], tot["k_out"], tot["w"]))
 
 
