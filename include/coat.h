@@ -193,8 +193,10 @@ int coat_fp8_adamw_step_multi(const void* plan_host, const void* plan_device,
  * consts_device, a coat_step_consts in device memory (16-byte aligned) that the caller rewrites
  * between replays with what coat_step_consts_compute (pure host code) returns for the new step;
  * hp->lr, hp->step and hp->eps are validated but not used by the kernels, every other field of hp
- * is frozen into the launch as usual.  Results are bit-identical to coat_fp8_adamw_step_multi with
- * the same hyper-parameters.
+ * is frozen into the launch as usual -- the choice of the inverse expansion too: it is made from
+ * hp->lr as given at capture (see COAT_FLAG_PRECISE_DQ), so a schedule that crosses that bound
+ * should set the flag.  Results are bit-identical to coat_fp8_adamw_step_multi called with the
+ * same hyper-parameters and the same choice.
  */
 typedef struct {
   float    denom_mul;     /* sqrt((1 - beta2) / (1 - beta2^t)) / c,  c = -lr (1 - beta1) / (1 - beta1^t) */
