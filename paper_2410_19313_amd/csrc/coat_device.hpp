@@ -823,4 +823,33 @@ __device__ __forceinline__ void requantize_one(const Mode& md, float xv, const G
     c[d] = (idx >> 2) == static_cast<uint32_t>(d) ? ((c[d] & ~(0xffu << sh)) | (code << sh)) : c[d];
 }
 
+// Two elements of one lane that both cancelled deeply: the smaller one is the lane's candidate and
+// is exact (ExactChain); the other keeps its fp32 value, whose error at a depth of 2^-19 and more is
+// a whole code step of the expanded group.  The pair is rare (a few in 10^11 elements) and costs
+// nothing to look for: when the candidate itself came out below 2^-16 of its gradient (one lane in
+// 10^4), the lane's other elements are tested the same way against the gradients kept in LDS, and
+// any that qualifies is recomputed and re-encoded like the candidate.  It does not take part in the
+// group's extremes any more (they are fixed by now): if it was the true minimum the group is one of
+// those whose exponent is off, a case the candidate scheme already has.
+template <class Mode>
+__device__ __forceinline__ void requantize_other_cancelled(const StepArgs& a, const Mode& md, const StepTables& tb,
+                                                           const LaneScratch& ls, const float (&x)[kEPL],
+                                                           const GroupQuant& gq, uint32_t named, float scale, float k,
+                                                           float inv_k, uint32_t (&c)[4], float unit) {
+  uint32_t others = 0u;
+#pragma unroll
+  for (int e = 0; e < kEPL; ++e) {
+    const float ge = as_f32(static_cast<uint32_t>(ls.g[e]) << 16);
+    others |= __builtin_fabsf(x[e]) < 0x1p-16f * __builtin_fabsf(ge) ? 1u << e : 0u;
+  }
+  others &= ~(1u << named);
+  while (others != 0u) {
+    const uint32_t idx = static_cast<uint32_t>(__builtin_ctz(others));
+    others &= others - 1u;
+    ExactChain<Mode> chain(a, md, tb, ls, idx, scale, k, inv_k);
+    static_for<0, ExactChain<Mode>::kSteps + 1>([&](auto s) { chain.template step<s.value>(); });
+    requantize_one(md, chain.exact, gq, idx, c, unit);
+  }
+}
+
 }  // namespace

@@ -105,6 +105,11 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, co
   quantize16<true>(mm, m, qm, mc, a.one_minus_beta1);
   requantize_linear_group<true>(mm, m, qm, mc, a.one_minus_beta1);
   if (__builtin_expect(m_replace, 0)) requantize_one(mm, m_exact, qm, m_key & 15u, mc, a.one_minus_beta1);
+  if (mm.expand()) {
+    const bool deep = m_key != 0xffffffffu && __builtin_fabsf(m_exact) < 0x1p-16f * __builtin_fabsf(chain.g32);
+    if (__builtin_expect(deep, 0))
+      requantize_other_cancelled(a, mm, tb, ls, m, qm, m_key & 15u, meta.m_scale, meta.m_k, m_inv_k, mc, a.one_minus_beta1);
+  }
   io.first(mc, qm.scale, qm.k);
 }
 
