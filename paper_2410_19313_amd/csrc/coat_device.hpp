@@ -656,13 +656,16 @@ __device__ __forceinline__ void static_for(F&& f) {
 // (an exact zero leaves it; another element may now be the smallest) and the caller re-encodes that
 // one element from the exact value (requantize_one), so that its code comes out right, sign
 // included.  x itself is never written: a conditional write to the register array would cost the
-// straight-line path a copy of all sixteen.  amax: the lane's maximum from the fp32 pass (in/out).
-__device__ __forceinline__ float apply_exact_min(float exact, uint32_t min_key, const float (&x)[kEPL], float& amax,
-                                                 bool& replace) {
+// straight-line path a copy of all sixteen.  amax: the lane's maximum from the fp32 pass (in/out);
+// g_named: the gradient of the candidate.
+__device__ __forceinline__ float apply_exact_min(float exact, float g_named, uint32_t min_key, const float (&x)[kEPL],
+                                                 float& amax, bool& replace) {
   float res = __builtin_fabsf(exact);
   const bool have = min_key != 0xffffffffu;          // false: nothing but true zeros in this lane
   const uint32_t seen_bits = min_key & 0x7ffffff0u;  // what the fp32 pass had (low mantissa bits cleared)
-  replace = have && !(__builtin_fabsf(res - as_f32(seen_bits)) <= 0x1p-9f * res);
+  // (the second condition: below 2^-20 of its gradient the fp32 value need not even have the right
+  // sign, and its magnitude can still agree by chance -- seen once in 3e10 elements)
+  replace = have && (!(__builtin_fabsf(res - as_f32(seen_bits)) <= 0x1p-9f * res) || res < 0x1p-20f * __builtin_fabsf(g_named));
   if (__builtin_expect(replace, 0)) {
     uint32_t idx = min_key & 15u;
     asm volatile("" : "+v"(idx));                    // keeps the loop's arithmetic inside this rare block

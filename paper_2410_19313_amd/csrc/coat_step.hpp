@@ -88,7 +88,7 @@ __device__ __forceinline__ void step_core(const StepArgs& a, const ModeM& mm, co
   io.second(vc, qv.scale, qv.k);
   __builtin_amdgcn_sched_barrier(0);
   bool m_replace;
-  float m_min = apply_exact_min(m_exact, m_key, m, m_max, m_replace);
+  float m_min = apply_exact_min(m_exact, chain.g32, m_key, m, m_max, m_replace);
   m_max = group_allreduce<LPG, true>(m_max);
   m_min = group_allreduce<LPG, false>(m_min);
   if (mm.expand()) {

@@ -388,12 +388,15 @@ def test_step_from_arbitrary_state(coat, ref, G):
     check_step(ref, "random state G=%d" % G, w_g, st_g, w_r, st_r, st, g, G, extra_w_tol=extra)
 
 
-def test_step_two_deep_cancellations_in_one_lane(coat, ref):
+@pytest.mark.parametrize("last_bit", [False, True])
+def test_step_two_deep_cancellations_in_one_lane(coat, ref, last_bit):
     """Two elements of one lane whose beta1 m and (1 - beta1) g cancel to about 2^-22 of either term
     (same old code, same gradient, the group's scale tuned to the last bit): fp32 holds no correct
     digit of them.  One is the lane's candidate and is recomputed exactly; the other must come out
-    right as well, not merely the one that is named."""
-    G, ng = 32, 512
+    right as well, not merely the one that is named.  last_bit: the scale NEAREST to exact
+    cancellation, so that the residue is a fraction of the terms' last bit and the fp32 value often
+    has the wrong sign, now and then with the right magnitude."""
+    G, ng = 32, 8192
     n = G * ng
     st = S.random_state(n, G, seed=81)
     rng = np.random.default_rng(81)
@@ -407,17 +410,17 @@ def test_step_two_deep_cancellations_in_one_lane(coat, ref):
     mq[a_pos] = 0x7E
     mq[b_pos] = 0x7E                                                  # +448 * scale
     g0 = -(2.0 ** rng.integers(-12, -6, ng)) * rng.choice([1.0, 1.25, 1.5, 1.75], ng)   # bf16 values
-    depth = np.empty(ng)
-    for i in range(ng):                                               # scale: the fp32 nearest to exact cancellation, then a few ulp off
-        sc = np.float32(-g0[i] / (ratio * 448.0))
+    sc = (-g0 / (ratio * 448.0)).astype(np.float32)                   # the fp32 nearest to exact cancellation
+    if not last_bit:                                                  # ... or a few ulp off
         for _ in range(64):
-            d = (ratio * 448.0 * float(sc) + g0[i]) / abs(g0[i])
-            if 2.0 ** -23.5 <= abs(d) <= 2.0 ** -21:
-                break
-            sc = np.nextafter(sc, np.float32(np.inf))
-        st["m_scale"][i] = sc
-        depth[i] = abs(d)
-    assert np.mean((depth >= 2.0 ** -23.5) & (depth <= 2.0 ** -21)) > 0.9
+            d = np.abs(ratio * 448.0 * sc.astype(np.float64) + g0) / np.abs(g0)
+            sc = np.where(d < 2.0 ** -23.5, np.nextafter(sc, np.float32(np.inf)), sc)
+    depth = np.abs(ratio * 448.0 * sc.astype(np.float64) + g0) / np.abs(g0)
+    if last_bit:
+        assert np.mean(depth < 2.0 ** -24) > 0.5 and np.all(depth < 2.0 ** -22)
+    else:
+        assert np.mean((depth >= 2.0 ** -23.5) & (depth <= 2.0 ** -21)) > 0.9
+    st["m_scale"][:] = sc
     gb = S.f32_to_bf16_bits(g0.astype(np.float32))
     g[a_pos] = gb
     g[b_pos] = gb
@@ -425,7 +428,7 @@ def test_step_two_deep_cancellations_in_one_lane(coat, ref):
     t = 4
     w_g, st_g, _ = gpu_step(coat, w, g, st, G, t)
     w_r, st_r = ref_step(ref, w, g, st, G, t)
-    # (both sides agree on the two elements' codes, which are far from the top and not zero in most groups)
+    # (the two elements' codes are far from the top and not zero in most groups)
     assert np.mean((st_r["m_q"][b_pos] & 0x7F) > 0) > 0.5
     check_step(ref, "two deep cancellations", w_g, st_g, w_r, st_r, st, g, G, extra_w_tol=update_error_model(ref, st, g, G, t))
 
